@@ -1,0 +1,237 @@
+/*
+ * lazyllm.h -- C ABI of the MI355X (gfx950) pruned-prefill library.
+ *
+ * Implements the prefilling stage of LazyLLM (arxiv 2407.14057, Sec. 3.1-3.2):
+ * every decoder layer runs on the surviving prompt tokens only, each token is
+ * scored by the head-averaged attention probability of the last token
+ * attending to it (Eq. 1), pruning layers keep the top-k percentile of the
+ * surviving tokens (Sec. 3.2, "Progressive Token Pruning"), hidden states and
+ * position ids are compacted, and the hidden states of dropped tokens are
+ * parked in an Aux Cache (Sec. 3.2, "Aux Cache").
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller unless said
+ *     otherwise; "host" pointers are ordinary process memory.
+ *   - bf16 tensors are raw 16-bit patterns; matrices are row-major
+ *     [out_features, in_features] (y = x W^T).
+ *   - every call that enqueues work takes a hipStream_t as void*; work is
+ *     asynchronous on that stream and the results are valid once the caller
+ *     has synchronised it.  Nothing here synchronises except model_create.
+ *   - return value 0 is success, negative values are lazyllm_status codes.
+ *     No call throws or aborts.  Argument validation happens before the first
+ *     HIP call, so the error paths can be exercised without a GPU.
+ *   - one GPU, one stream per call.  Calls sharing a workspace or an output
+ *     buffer must be ordered by the caller.
+ */
+#ifndef LAZYLLM_H
+#define LAZYLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LAZYLLM_MAX_LAYERS 128
+
+typedef enum lazyllm_status {
+  LAZYLLM_OK = 0,
+  LAZYLLM_EINVAL = -1, /* bad argument (null pointer, size, schedule, shape) */
+  LAZYLLM_ENOSPC = -2, /* workspace or output buffer too small */
+  LAZYLLM_EHIP = -3,   /* HIP runtime failure; see lazyllm_last_hip_error() */
+  LAZYLLM_ENOMEM = -4  /* host or device allocation failed in model_create */
+} lazyllm_status;
+
+/* Decoder shape (Sec. 3.1: a stack of layers, each multi-head self-attention
+ * followed by an MLP; Llama 2 conventions: pre-norm RMSNorm, rotary position
+ * embedding with half-split pairing, SwiGLU MLP, untied LM head, no biases).
+ * Supported: head_dim 64 or 128, d_model == n_heads * head_dim,
+ * d_model % 64 == 0, 1 <= n_layers <= LAZYLLM_MAX_LAYERS. */
+typedef struct lazyllm_config {
+  int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_theta;
+} lazyllm_config;
+
+/* Device pointers to bf16 weights.  The per-layer members are HOST arrays of
+ * n_layers device pointers. */
+typedef struct lazyllm_weights {
+  const void* embed;              /* [vocab, d_model] */
+  const void* const* attn_norm;   /* [d_model] each */
+  const void* const* wq;          /* [d_model, d_model] */
+  const void* const* wk;
+  const void* const* wv;
+  const void* const* wo;
+  const void* const* ffn_norm;    /* [d_model] */
+  const void* const* w_gate;      /* [d_ffn, d_model] */
+  const void* const* w_up;        /* [d_ffn, d_model] */
+  const void* const* w_down;      /* [d_model, d_ffn] */
+  const void* final_norm;         /* [d_model] */
+  const void* lm_head;            /* [vocab, d_model] */
+} lazyllm_weights;
+
+/* One pruning layer (Sec. 4.2's three knobs: how many pruning layers, where,
+ * how much).  The scores of layer `layer`-1 decide which tokens enter
+ * `layer`; keep_permille/1000 is the fraction kept of the tokens that ran
+ * `layer`-1, counted as max(1, ceil(m * keep_permille / 1000)) in integer
+ * arithmetic; the last token is always kept and is part of that count.
+ * Entries must be sorted by strictly increasing layer, 1 <= layer < n_layers,
+ * 0 < keep_permille <= 1000 (1000 = no pruning at that layer). */
+typedef struct lazyllm_keep {
+  int32_t layer;
+  int32_t keep_permille;
+} lazyllm_keep;
+
+typedef struct lazyllm_model lazyllm_model;
+
+/* Flags for lazyllm_prefill*. */
+#define LAZYLLM_SCORE_ALL_LAYERS 0u   /* default: Eq. 1 scores for every layer */
+#define LAZYLLM_SCORE_ONLY_USED 1u    /* only for layers whose successor prunes;
+                                         result.scores of other layers is NULL */
+
+/* Bits of *lazyllm_result.status (device int32, read after stream sync). */
+#define LAZYLLM_ST_BAD_TOKEN 1       /* a token id was outside [0, vocab); clamped */
+#define LAZYLLM_ST_BAD_CU 2          /* device cu_seqlens disagrees with the host copy */
+
+/* Where the results of one prefill live.  Every pointer is device memory
+ * inside the caller's output buffer and stays valid as long as that buffer.
+ * Rows of all sequences are packed back to back; within a sequence rows are in
+ * ascending original position.  Layers between two pruning layers share one
+ * kept set, so their kept_pos / cu_kept pointers alias the same memory. */
+typedef struct lazyllm_result {
+  int32_t batch, n_layers;
+  int32_t n_tokens[LAZYLLM_MAX_LAYERS]; /* rows that ran layer l, over the batch */
+  float* logits;                        /* fp32 [batch, vocab], last token of each prompt */
+  int32_t* kept_pos[LAZYLLM_MAX_LAYERS];/* int32 [n_tokens[l]] original position in its prompt */
+  int32_t* cu_kept[LAZYLLM_MAX_LAYERS]; /* int32 [batch+1] row offsets per sequence */
+  void* k[LAZYLLM_MAX_LAYERS];          /* bf16 [n_tokens[l], n_heads, head_dim], rotary applied */
+  void* v[LAZYLLM_MAX_LAYERS];          /* bf16 [n_tokens[l], n_heads, head_dim] */
+  float* scores[LAZYLLM_MAX_LAYERS];    /* fp32 [n_tokens[l]]  Eq. 1, or NULL */
+  /* Aux Cache: only for layers that prune (NULL / 0 elsewhere).  Row i is a
+   * token dropped on entry to layer l: its layer-l input hidden state and its
+   * original position. */
+  int32_t n_aux[LAZYLLM_MAX_LAYERS];
+  void* aux_h[LAZYLLM_MAX_LAYERS];      /* bf16 [n_aux[l], d_model] */
+  int32_t* aux_pos[LAZYLLM_MAX_LAYERS]; /* int32 [n_aux[l]] */
+  int32_t* cu_aux[LAZYLLM_MAX_LAYERS];  /* int32 [batch+1] */
+  int32_t* status;                      /* int32 [1] LAZYLLM_ST_* bits */
+} lazyllm_result;
+
+/* ---- host-only helpers (no HIP call) ------------------------------------------------ */
+
+/* Tokens that run each layer for a prompt of n tokens under the schedule
+ * (Sec. 3.2: kept sets are nested, so the counts never grow).
+ * n_per_layer: host int32[n_layers].  EINVAL on a bad schedule or n <= 0. */
+int lazyllm_keep_counts(int32_t n, int32_t n_layers, const lazyllm_keep* sched, int32_t n_sched,
+                        int32_t* n_per_layer);
+
+/* Bytes of scratch a prefill of `total_tokens` rows in `batch` sequences, the
+ * longest `max_seqlen` tokens, needs.  0 on a bad argument. */
+size_t lazyllm_workspace_bytes(const lazyllm_config* cfg, int32_t total_tokens, int32_t batch,
+                               int32_t max_seqlen);
+
+/* Bytes of output buffer for these prompt lengths (host int32[batch]) and
+ * schedule.  0 on a bad argument. */
+size_t lazyllm_output_bytes(const lazyllm_config* cfg, const int32_t* seqlens, int32_t batch,
+                            const lazyllm_keep* sched, int32_t n_sched);
+
+const char* lazyllm_strerror(int status);
+/* hipError_t value of the last failing HIP call on this thread (0 if none). */
+int lazyllm_last_hip_error(void);
+/* Library ABI version, bumped on any signature change. */
+int lazyllm_abi_version(void);
+
+/* ---- model ---------------------------------------------------------------------------- */
+
+/* Copies the weights into the library's own MFMA-friendly layout (fused QKV,
+ * gate/up interleaved in 32-row blocks, d_ffn zero-padded to a multiple of
+ * 128).  Allocates device memory (about the size of the weights), runs the
+ * repack on `hip_stream` and synchronises it: after return the caller's
+ * weight buffers are no longer referenced.  *out is set only on success. */
+int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, void* hip_stream,
+                         lazyllm_model** out);
+void lazyllm_model_destroy(lazyllm_model* m);
+
+/* ---- the prefill (Sec. 3.1 prefilling stage with Sec. 3.2 pruning) -------------------- */
+
+/* One prompt of n tokens.  token_ids: device int32[n].  embed_scale: device
+ * fp32[n] multiplying each token's embedding row, or NULL.  workspace /
+ * out_buf: device, 256-byte aligned, at least lazyllm_workspace_bytes /
+ * lazyllm_output_bytes.  res: host struct filled before return (its pointers
+ * point into out_buf).  Enqueues everything on hip_stream and returns. */
+int lazyllm_prefill(const lazyllm_model* m, const int32_t* token_ids, const float* embed_scale,
+                    int32_t n, const lazyllm_keep* sched, int32_t n_sched, uint32_t flags,
+                    void* workspace, size_t ws_bytes, void* out_buf, size_t out_bytes,
+                    void* hip_stream, lazyllm_result* res);
+
+/* `batch` independent prompts packed back to back; each is pruned on its own
+ * with the same schedule.  cu_seqlens_host: host int32[batch+1], starting at 0,
+ * strictly increasing.  cu_seqlens_dev: the same values in device memory. */
+int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
+                           const float* embed_scale, const int32_t* cu_seqlens_host,
+                           const int32_t* cu_seqlens_dev, int32_t batch, const lazyllm_keep* sched,
+                           int32_t n_sched, uint32_t flags, void* workspace, size_t ws_bytes,
+                           void* out_buf, size_t out_bytes, void* hip_stream, lazyllm_result* res);
+
+/* ---- single steps of the path (used by kernel-level parity tests and roofline
+ *      measurements; all pointers device, all work enqueued on hip_stream) -------------- */
+
+/* C[M,N] = A[M,K] W[N,K]^T in bf16 with fp32 accumulation (the linear layers
+ * of Sec. 3.1's attention and MLP blocks).  lda/ldw/ldc are row strides in
+ * elements.  epilogue 0: C = bf16(acc).  epilogue 1: C = bf16(R + acc) with
+ * R[M,N] (row stride ldc) the residual stream; C may alias R.
+ * epilogue 2 (SwiGLU): W holds gate and up rows interleaved in blocks of 32
+ * (rows 64j..64j+31 gate, 64j+32..64j+63 up), C[M,N/2] = silu(gate) * up.
+ * Requires N % 128 == 0, K % 64 == 0, 16-byte aligned rows. */
+int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,
+                    int32_t K, int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue,
+                    void* hip_stream);
+
+/* x = h * rsqrt(mean(h^2) + eps) * gain, bf16 in and out, rows of width d. */
+int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d,
+                       float eps, void* hip_stream);
+
+/* Splits a fused projection qkv[rows, 3*H*hd] into q, k (rotary applied at
+ * pos[rows], half-split pairing, theta^(-2i/hd)) and v, and writes the
+ * transposed copy vt[H, hd, vt_ld] the attention kernel reads (columns
+ * rows..vt_ld-1 are zeroed; vt_ld % 64 == 0, vt_ld >= rows).
+ * rope_table: device float2 scratch [max_pos+1, hd/2], filled by this call. */
+int lazyllm_op_rope_split(const void* qkv, const int32_t* pos, int32_t max_pos, void* rope_table,
+                          void* q, void* k, void* v, void* vt, int32_t vt_ld, int32_t rows,
+                          int32_t n_heads, int32_t head_dim, float theta, void* hip_stream);
+
+/* Causal multi-head attention over one sequence of `rows` tokens in compacted
+ * order (ascending original position, so compacted-causal = original-causal):
+ * o = softmax(q k^T / sqrt(hd) + causal) v.  q, k: bf16 [rows, H, hd];
+ * vt: bf16 [H, hd, vt_ld]; o: bf16 [rows, H*hd]. */
+int lazyllm_op_attention(const void* q, const void* k, const void* vt, int32_t vt_ld, void* o,
+                         int32_t rows, int32_t n_heads, int32_t head_dim, void* hip_stream);
+
+/* Eq. 1: s[j] = (1/H) sum_h softmax_j(q_last[h] . k[j,h] / sqrt(hd)) over the
+ * `rows` tokens present.  q_last: bf16 [H, hd] (the last token's rotated
+ * query); k: bf16 [rows, H, hd]; s: fp32 [rows].
+ * scratch: device, at least lazyllm_op_score_scratch_bytes(rows, H). */
+size_t lazyllm_op_score_scratch_bytes(int32_t rows, int32_t n_heads);
+int lazyllm_op_score(const void* q_last, const void* k, float* s, void* scratch, int32_t rows,
+                     int32_t n_heads, int32_t head_dim, void* hip_stream);
+
+/* Top-k percentile rule (Sec. 3.2): of m tokens with scores s keep the last
+ * one and the k-1 best others (higher fp32 score first, then lower index).
+ * keep_idx: int32 [k] ascending; prune_idx: int32 [m-k] ascending. */
+int lazyllm_op_select(const float* s, int32_t m, int32_t k, int32_t* keep_idx, int32_t* prune_idx,
+                      void* hip_stream);
+
+/* Compaction and Aux Cache write: h_out[i] = h[keep_idx[i]], pos_out likewise;
+ * aux_h[i] = h[prune_idx[i]], aux_pos likewise.  Rows are bf16 of width d. */
+int lazyllm_op_gather(const void* h, const int32_t* pos, const int32_t* keep_idx, int32_t n_keep,
+                      const int32_t* prune_idx, int32_t n_prune, void* h_out, int32_t* pos_out,
+                      void* aux_h, int32_t* aux_pos, int32_t d, void* hip_stream);
+
+/* logits[V] = rmsnorm(h_last, gain) . W_lm^T, fp32 out; xf: device fp32[d] scratch. */
+int lazyllm_op_lm_head(const void* h_last, const void* gain, const void* w_lm, float* xf,
+                       float* logits, int32_t d, int32_t vocab, float eps, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAZYLLM_H */

@@ -1,0 +1,394 @@
+"""ctypes binding of liblazyllm.so: same names as include/lazyllm.h, argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; torch is used for device
+memory and for the stream handle.  There is no fallback: if the library is missing, the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblazyllm.so")
+MAX_LAYERS = 128
+
+LAZYLLM_OK, LAZYLLM_EINVAL, LAZYLLM_ENOSPC, LAZYLLM_EHIP, LAZYLLM_ENOMEM = 0, -1, -2, -3, -4
+LAZYLLM_SCORE_ALL_LAYERS, LAZYLLM_SCORE_ONLY_USED = 0, 1
+LAZYLLM_ST_BAD_TOKEN, LAZYLLM_ST_BAD_CU = 1, 2
+EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
+
+
+class lazyllm_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class lazyllm_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p),
+                ("attn_norm", C.POINTER(C.c_void_p)), ("wq", C.POINTER(C.c_void_p)),
+                ("wk", C.POINTER(C.c_void_p)), ("wv", C.POINTER(C.c_void_p)),
+                ("wo", C.POINTER(C.c_void_p)), ("ffn_norm", C.POINTER(C.c_void_p)),
+                ("w_gate", C.POINTER(C.c_void_p)), ("w_up", C.POINTER(C.c_void_p)),
+                ("w_down", C.POINTER(C.c_void_p)),
+                ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+class lazyllm_keep(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("keep_permille", C.c_int32)]
+
+
+class lazyllm_result(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_layers", C.c_int32),
+                ("n_tokens", C.c_int32 * MAX_LAYERS),
+                ("logits", C.c_void_p),
+                ("kept_pos", C.c_void_p * MAX_LAYERS), ("cu_kept", C.c_void_p * MAX_LAYERS),
+                ("k", C.c_void_p * MAX_LAYERS), ("v", C.c_void_p * MAX_LAYERS),
+                ("scores", C.c_void_p * MAX_LAYERS),
+                ("n_aux", C.c_int32 * MAX_LAYERS),
+                ("aux_h", C.c_void_p * MAX_LAYERS), ("aux_pos", C.c_void_p * MAX_LAYERS),
+                ("cu_aux", C.c_void_p * MAX_LAYERS),
+                ("status", C.c_void_p)]
+
+
+_lib_handle = None
+
+_SIGNATURES = {
+    "lazyllm_abi_version": (C.c_int, []),
+    "lazyllm_strerror": (C.c_char_p, [C.c_int]),
+    "lazyllm_last_hip_error": (C.c_int, []),
+    "lazyllm_keep_counts": (C.c_int, [C.c_int32, C.c_int32, C.POINTER(lazyllm_keep), C.c_int32,
+                                      C.POINTER(C.c_int32)]),
+    "lazyllm_workspace_bytes": (C.c_size_t, [C.POINTER(lazyllm_config), C.c_int32, C.c_int32,
+                                             C.c_int32]),
+    "lazyllm_output_bytes": (C.c_size_t, [C.POINTER(lazyllm_config), C.POINTER(C.c_int32), C.c_int32,
+                                          C.POINTER(lazyllm_keep), C.c_int32]),
+    "lazyllm_model_create": (C.c_int, [C.POINTER(lazyllm_config), C.POINTER(lazyllm_weights),
+                                       C.c_void_p, C.POINTER(C.c_void_p)]),
+    "lazyllm_model_destroy": (None, [C.c_void_p]),
+    "lazyllm_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.POINTER(lazyllm_keep), C.c_int32, C.c_uint32, C.c_void_p,
+                                  C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p,
+                                  C.POINTER(lazyllm_result)]),
+    "lazyllm_prefill_varlen": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int32),
+                                         C.c_void_p, C.c_int32, C.POINTER(lazyllm_keep), C.c_int32,
+                                         C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
+                                         C.c_void_p, C.POINTER(lazyllm_result)]),
+    "lazyllm_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_void_p]),
+    "lazyllm_op_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                     C.c_float, C.c_void_p]),
+    "lazyllm_op_rope_split": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                        C.c_int32, C.c_int32, C.c_float, C.c_void_p]),
+    "lazyllm_op_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                       C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
+    "lazyllm_op_score_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
+    "lazyllm_op_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                   C.c_int32, C.c_int32, C.c_void_p]),
+    "lazyllm_op_select": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.c_void_p]),
+    "lazyllm_op_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                    C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_int32, C.c_void_p]),
+    "lazyllm_op_lm_head": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_int32, C.c_int32, C.c_float, C.c_void_p]),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib_handle
+    if _lib_handle is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "liblazyllm.so is not built (%s); run `python -m paper_2407_14057_amd.build`. "
+                "There is no fallback path." % LIB_PATH)
+        h = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(h, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib_handle = h
+    return _lib_handle
+
+
+class LazyLLMError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        msg = lib().lazyllm_strerror(status).decode()
+        if status == LAZYLLM_EHIP:
+            msg += " (hipError_t %d)" % lib().lazyllm_last_hip_error()
+        super().__init__("lazyllm: %s (%d)" % (msg, status))
+
+
+def _check(status: int) -> None:
+    if status != LAZYLLM_OK:
+        raise LazyLLMError(status)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous()
+        return t.data_ptr()
+    return int(t)
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def make_config(shape: Dict[str, float]) -> lazyllm_config:
+    return lazyllm_config(int(shape["n_layers"]), int(shape["d_model"]), int(shape["n_heads"]),
+                          int(shape["head_dim"]), int(shape["d_ffn"]), int(shape["vocab"]),
+                          float(shape["rms_eps"]), float(shape["rope_theta"]))
+
+
+def make_schedule(schedule: Sequence[Tuple[int, int]]):
+    arr = (lazyllm_keep * max(1, len(schedule)))()
+    for i, (layer, permille) in enumerate(schedule):
+        arr[i].layer = int(layer)
+        arr[i].keep_permille = int(permille)
+    return arr, len(schedule)
+
+
+# ---------------------------------------------------------------------------- host-only helpers
+
+def lazyllm_keep_counts(n: int, n_layers: int, schedule: Sequence[Tuple[int, int]]) -> List[int]:
+    arr, ns = make_schedule(schedule)
+    out = (C.c_int32 * max(1, n_layers))()
+    _check(lib().lazyllm_keep_counts(n, n_layers, arr, ns, out))
+    return [int(out[i]) for i in range(n_layers)]
+
+
+def lazyllm_workspace_bytes(cfg: lazyllm_config, total_tokens: int, batch: int, max_seqlen: int) -> int:
+    return int(lib().lazyllm_workspace_bytes(C.byref(cfg), total_tokens, batch, max_seqlen))
+
+
+def lazyllm_output_bytes(cfg: lazyllm_config, seqlens: Sequence[int],
+                         schedule: Sequence[Tuple[int, int]]) -> int:
+    arr, ns = make_schedule(schedule)
+    sl = (C.c_int32 * len(seqlens))(*[int(x) for x in seqlens])
+    return int(lib().lazyllm_output_bytes(C.byref(cfg), sl, len(seqlens), arr, ns))
+
+
+# ---------------------------------------------------------------------------- model + prefill
+
+_PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+def lazyllm_model_create(cfg: lazyllm_config, weights: Dict[str, object],
+                         stream: Optional[torch.cuda.Stream] = None) -> int:
+    """weights: {'embed','final_norm','lm_head': bf16 cuda tensors, per-layer names: lists}."""
+    w = lazyllm_weights()
+    keep = []
+    for name in ("embed", "final_norm", "lm_head"):
+        setattr(w, name, _ptr(weights[name]))
+    for name in _PER_LAYER:
+        arr = (C.c_void_p * cfg.n_layers)(*[_ptr(t) for t in weights[name]])
+        keep.append(arr)
+        setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+    out = C.c_void_p()
+    _check(lib().lazyllm_model_create(C.byref(cfg), C.byref(w), _stream_ptr(stream), C.byref(out)))
+    return out.value
+
+
+def lazyllm_model_destroy(model: int) -> None:
+    lib().lazyllm_model_destroy(model)
+
+
+def lazyllm_prefill(model: int, token_ids, embed_scale, n: int, schedule, flags: int, workspace,
+                    out_buf, stream: Optional[torch.cuda.Stream] = None) -> lazyllm_result:
+    arr, ns = make_schedule(schedule)
+    res = lazyllm_result()
+    _check(lib().lazyllm_prefill(model, _ptr(token_ids), _ptr(embed_scale), n, arr, ns, flags,
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _ptr(out_buf), out_buf.numel() * out_buf.element_size(),
+                                 _stream_ptr(stream), C.byref(res)))
+    return res
+
+
+def lazyllm_prefill_varlen(model: int, token_ids, embed_scale, cu_seqlens_host: Sequence[int],
+                           cu_seqlens_dev, schedule, flags: int, workspace, out_buf,
+                           stream: Optional[torch.cuda.Stream] = None) -> lazyllm_result:
+    arr, ns = make_schedule(schedule)
+    res = lazyllm_result()
+    batch = len(cu_seqlens_host) - 1
+    cu = (C.c_int32 * (batch + 1))(*[int(x) for x in cu_seqlens_host])
+    _check(lib().lazyllm_prefill_varlen(model, _ptr(token_ids), _ptr(embed_scale), cu,
+                                        _ptr(cu_seqlens_dev), batch, arr, ns, flags,
+                                        _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                        _ptr(out_buf), out_buf.numel() * out_buf.element_size(),
+                                        _stream_ptr(stream), C.byref(res)))
+    return res
+
+
+# ---------------------------------------------------------------------------- single steps
+
+def lazyllm_op_gemm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, stream=None) -> None:
+    _check(lib().lazyllm_op_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(R), M, N, K, lda, ldw, ldc,
+                                 epilogue, _stream_ptr(stream)))
+
+
+def lazyllm_op_rmsnorm(h, gain, x, rows, d, eps, stream=None) -> None:
+    _check(lib().lazyllm_op_rmsnorm(_ptr(h), _ptr(gain), _ptr(x), rows, d, eps, _stream_ptr(stream)))
+
+
+def lazyllm_op_rope_split(qkv, pos, max_pos, rope_table, q, k, v, vt, vt_ld, rows, n_heads,
+                          head_dim, theta, stream=None) -> None:
+    _check(lib().lazyllm_op_rope_split(_ptr(qkv), _ptr(pos), max_pos, _ptr(rope_table), _ptr(q),
+                                       _ptr(k), _ptr(v), _ptr(vt), vt_ld, rows, n_heads, head_dim,
+                                       theta, _stream_ptr(stream)))
+
+
+def lazyllm_op_attention(q, k, vt, vt_ld, o, rows, n_heads, head_dim, stream=None) -> None:
+    _check(lib().lazyllm_op_attention(_ptr(q), _ptr(k), _ptr(vt), vt_ld, _ptr(o), rows, n_heads,
+                                      head_dim, _stream_ptr(stream)))
+
+
+def lazyllm_op_score_scratch_bytes(rows: int, n_heads: int) -> int:
+    return int(lib().lazyllm_op_score_scratch_bytes(rows, n_heads))
+
+
+def lazyllm_op_score(q_last, k, s, scratch, rows, n_heads, head_dim, stream=None) -> None:
+    _check(lib().lazyllm_op_score(_ptr(q_last), _ptr(k), _ptr(s), _ptr(scratch), rows, n_heads,
+                                  head_dim, _stream_ptr(stream)))
+
+
+def lazyllm_op_select(s, m, k, keep_idx, prune_idx, stream=None) -> None:
+    _check(lib().lazyllm_op_select(_ptr(s), m, k, _ptr(keep_idx), _ptr(prune_idx),
+                                   _stream_ptr(stream)))
+
+
+def lazyllm_op_gather(h, pos, keep_idx, n_keep, prune_idx, n_prune, h_out, pos_out, aux_h, aux_pos,
+                      d, stream=None) -> None:
+    _check(lib().lazyllm_op_gather(_ptr(h), _ptr(pos), _ptr(keep_idx), n_keep, _ptr(prune_idx),
+                                   n_prune, _ptr(h_out), _ptr(pos_out), _ptr(aux_h), _ptr(aux_pos),
+                                   d, _stream_ptr(stream)))
+
+
+def lazyllm_op_lm_head(h_last, gain, w_lm, xf, logits, d, vocab, eps, stream=None) -> None:
+    _check(lib().lazyllm_op_lm_head(_ptr(h_last), _ptr(gain), _ptr(w_lm), _ptr(xf), _ptr(logits), d,
+                                    vocab, eps, _stream_ptr(stream)))
+
+
+# ---------------------------------------------------------------------------- result views
+
+class PrefillOutput:
+    """Zero-copy torch views of a lazyllm_result (all data stays in `out_buf`)."""
+
+    def __init__(self, res: lazyllm_result, out_buf: torch.Tensor, cfg: lazyllm_config):
+        self.res, self.out_buf, self.cfg = res, out_buf, cfg
+        self.batch, self.n_layers = res.batch, res.n_layers
+        self.n_tokens = [int(res.n_tokens[l]) for l in range(res.n_layers)]
+        self.n_aux = [int(res.n_aux[l]) for l in range(res.n_layers)]
+
+    def _view(self, ptr: Optional[int], count: int, dtype: torch.dtype) -> Optional[torch.Tensor]:
+        if not ptr:
+            return None
+        off = ptr - self.out_buf.data_ptr()
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        return self.out_buf[off: off + nbytes].view(dtype)
+
+    @property
+    def logits(self):
+        return self._view(self.res.logits, self.batch * self.cfg.vocab, torch.float32).view(
+            self.batch, self.cfg.vocab)
+
+    @property
+    def status(self) -> int:
+        return int(self._view(self.res.status, 1, torch.int32).item())
+
+    def kept_pos(self, l):
+        return self._view(self.res.kept_pos[l], self.n_tokens[l], torch.int32)
+
+    def cu_kept(self, l):
+        return self._view(self.res.cu_kept[l], self.batch + 1, torch.int32)
+
+    def k(self, l):
+        return self._view(self.res.k[l], self.n_tokens[l] * self.cfg.d_model, torch.bfloat16).view(
+            self.n_tokens[l], self.cfg.n_heads, self.cfg.head_dim)
+
+    def v(self, l):
+        return self._view(self.res.v[l], self.n_tokens[l] * self.cfg.d_model, torch.bfloat16).view(
+            self.n_tokens[l], self.cfg.n_heads, self.cfg.head_dim)
+
+    def scores(self, l):
+        return self._view(self.res.scores[l], self.n_tokens[l], torch.float32)
+
+    def aux_h(self, l):
+        if not self.res.aux_h[l]:
+            return None
+        return self._view(self.res.aux_h[l], self.n_aux[l] * self.cfg.d_model, torch.bfloat16).view(
+            self.n_aux[l], self.cfg.d_model)
+
+    def aux_pos(self, l):
+        if not self.res.aux_pos[l]:
+            return None
+        return self._view(self.res.aux_pos[l], self.n_aux[l], torch.int32)
+
+    def cu_aux(self, l):
+        return self._view(self.res.cu_aux[l], self.batch + 1, torch.int32)
+
+
+class Model:
+    """Owns a lazyllm_model handle and reusable workspace / output buffers."""
+
+    def __init__(self, shape: Dict[str, float], weights: Dict[str, object], device: str = "cuda:0"):
+        self.cfg = make_config(shape)
+        self.device = torch.device(device)
+        with torch.cuda.device(self.device):
+            self.handle = lazyllm_model_create(self.cfg, weights)
+        self._ws = None
+        self._out = None
+
+    def close(self) -> None:
+        if self.handle:
+            lazyllm_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def buffers(self, seqlens: Sequence[int], schedule) -> Tuple[torch.Tensor, torch.Tensor]:
+        total, batch, mx = int(sum(seqlens)), len(seqlens), int(max(seqlens))
+        wsb = lazyllm_workspace_bytes(self.cfg, total, batch, mx)
+        outb = lazyllm_output_bytes(self.cfg, seqlens, schedule)
+        if wsb == 0 or outb == 0:
+            raise LazyLLMError(LAZYLLM_EINVAL)
+        if self._ws is None or self._ws.numel() < wsb:
+            self._ws = torch.empty(wsb, dtype=torch.uint8, device=self.device)
+        if self._out is None or self._out.numel() < outb:
+            self._out = torch.empty(outb, dtype=torch.uint8, device=self.device)
+        return self._ws, self._out
+
+    def prefill(self, token_ids: torch.Tensor, schedule, *, cu_seqlens: Optional[Sequence[int]] = None,
+                embed_scale: Optional[torch.Tensor] = None, flags: int = 0,
+                stream: Optional[torch.cuda.Stream] = None) -> PrefillOutput:
+        """token_ids: int32 cuda tensor (all prompts packed).  Asynchronous on the stream."""
+        if cu_seqlens is None:
+            cu_seqlens = [0, int(token_ids.numel())]
+        seqlens = [int(cu_seqlens[i + 1] - cu_seqlens[i]) for i in range(len(cu_seqlens) - 1)]
+        ws, out = self.buffers(seqlens, schedule)
+        if len(seqlens) == 1:
+            res = lazyllm_prefill(self.handle, token_ids, embed_scale, seqlens[0], schedule, flags,
+                                  ws, out, stream)
+        else:
+            cu_dev = torch.tensor([int(x) for x in cu_seqlens], dtype=torch.int32, device=self.device)
+            self._cu_dev = cu_dev
+            res = lazyllm_prefill_varlen(self.handle, token_ids, embed_scale, cu_seqlens, cu_dev,
+                                         schedule, flags, ws, out, stream)
+        return PrefillOutput(res, out, self.cfg)

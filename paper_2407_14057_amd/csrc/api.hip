@@ -1,0 +1,538 @@
+// Host side of the C ABI: argument validation (before any HIP call), buffer layout, the
+// model's repacked weights, and the per-layer launch sequence of the pruned prefill.
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/lazyllm.h"
+#include "common.h"
+
+using namespace lz;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return LAZYLLM_EHIP;
+}
+#define LZ_HIP(expr)                           \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) return hip_fail(e_); \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+bool config_ok(const lazyllm_config* c) {
+  if (c == nullptr) return false;
+  if (c->n_layers < 1 || c->n_layers > LAZYLLM_MAX_LAYERS) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->n_heads < 1 || c->n_heads > 256) return false;
+  if ((int64_t)c->n_heads * c->head_dim != c->d_model) return false;
+  if (c->d_model % 128 != 0 || c->d_model > 16384) return false;
+  if (c->d_ffn < 1 || c->vocab < 1) return false;
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return false;
+  return true;
+}
+
+inline int ffn_padded(int f) { return (f + 127) / 128 * 128; }
+
+bool schedule_ok(int n_layers, const lazyllm_keep* sched, int n_sched) {
+  if (n_sched < 0 || n_sched > LAZYLLM_MAX_LAYERS) return false;
+  if (n_sched > 0 && sched == nullptr) return false;
+  int prev = 0;
+  for (int i = 0; i < n_sched; ++i) {
+    if (sched[i].layer < 1 || sched[i].layer >= n_layers) return false;   // layer 0 has no prior scores
+    if (sched[i].layer <= prev) return false;                             // sorted, no duplicates
+    if (sched[i].keep_permille <= 0 || sched[i].keep_permille > 1000) return false;
+    prev = sched[i].layer;
+  }
+  return true;
+}
+
+inline int keep_count(int m, int permille) {
+  long long k = ((long long)m * permille + 999) / 1000;
+  return k < 1 ? 1 : (int)k;
+}
+
+// Stage table: stage 0 = the full prompt; every schedule entry with permille < 1000 opens a
+// new stage at its layer.
+struct Stages {
+  int n_stages = 1;                       // including stage 0
+  int first_layer[LAZYLLM_MAX_LAYERS + 1];
+  int permille[LAZYLLM_MAX_LAYERS + 1];
+  int stage_of_layer[LAZYLLM_MAX_LAYERS];
+  long long total[LAZYLLM_MAX_LAYERS + 1];   // rows over the batch
+  int max_rows[LAZYLLM_MAX_LAYERS + 1];      // longest sequence
+  long long vt_ld[LAZYLLM_MAX_LAYERS + 1];   // sum of per-sequence lengths rounded up to 64
+};
+
+void build_stages(int n_layers, const lazyllm_keep* sched, int n_sched, const int32_t* seqlens,
+                  int batch, Stages* st) {
+  st->n_stages = 1;
+  st->first_layer[0] = 0;
+  st->permille[0] = 1000;
+  for (int i = 0; i < n_sched; ++i) {
+    if (sched[i].keep_permille >= 1000) continue;
+    st->first_layer[st->n_stages] = sched[i].layer;
+    st->permille[st->n_stages] = sched[i].keep_permille;
+    st->n_stages++;
+  }
+  int s = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (s + 1 < st->n_stages && st->first_layer[s + 1] == l) ++s;
+    st->stage_of_layer[l] = s;
+  }
+  for (int k = 0; k < st->n_stages; ++k) { st->total[k] = 0; st->max_rows[k] = 0; st->vt_ld[k] = 0; }
+  for (int b = 0; b < batch; ++b) {
+    int n = seqlens[b];
+    for (int k = 0; k < st->n_stages; ++k) {
+      if (k > 0) n = keep_count(n, st->permille[k]);
+      st->total[k] += n;
+      st->vt_ld[k] += (n + 63) / 64 * 64;
+      if (n > st->max_rows[k]) st->max_rows[k] = n;
+    }
+  }
+}
+
+// ---- workspace layout -------------------------------------------------------------------
+struct Workspace {
+  size_t h0, h1, xa, qkv, q, o, vt, act, score, rope, keep_idx, prune_idx, xf, total;
+};
+
+void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_seqlen,
+                      Workspace* w) {
+  const size_t d = c->d_model, fp = ffn_padded(c->d_ffn);
+  const size_t vt_ld = (size_t)T + 64 * (size_t)batch;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  w->h0 = take((size_t)T * d * 2);
+  w->h1 = take((size_t)T * d * 2);
+  w->xa = take((size_t)T * d * 2);
+  w->qkv = take((size_t)T * 3 * d * 2);
+  w->q = take((size_t)T * d * 2);
+  w->o = take((size_t)T * d * 2);
+  w->vt = take(d * vt_ld * 2);
+  w->act = take((size_t)T * fp * 2);
+  w->score = take(score_scratch_bytes((int)T, batch, c->n_heads));
+  w->rope = take((size_t)max_seqlen * (c->head_dim / 2) * sizeof(float2));
+  w->keep_idx = take((size_t)T * 4);
+  w->prune_idx = take((size_t)T * 4);
+  w->xf = take((size_t)batch * d * 4);
+  w->total = off;
+}
+
+// ---- output layout ------------------------------------------------------------------------
+struct Output {
+  size_t status, cu_stage, cu_aux, cu_vt, logits;
+  size_t kept_pos[LAZYLLM_MAX_LAYERS + 1];            // per stage
+  size_t aux_h[LAZYLLM_MAX_LAYERS + 1], aux_pos[LAZYLLM_MAX_LAYERS + 1];
+  size_t k[LAZYLLM_MAX_LAYERS], v[LAZYLLM_MAX_LAYERS], scores[LAZYLLM_MAX_LAYERS];
+  size_t total;
+};
+
+void layout_output(const lazyllm_config* c, const Stages* st, int batch, Output* o) {
+  const size_t d = c->d_model;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
+  o->status = take(4);
+  o->cu_stage = take((size_t)st->n_stages * (batch + 1) * 4);
+  o->cu_aux = take((size_t)st->n_stages * (batch + 1) * 4);
+  o->cu_vt = take((size_t)st->n_stages * (batch + 1) * 4);
+  o->logits = take((size_t)batch * c->vocab * 4);
+  for (int s = 0; s < st->n_stages; ++s) {
+    o->kept_pos[s] = take((size_t)st->total[s] * 4);
+    if (s > 0) {
+      const size_t na = (size_t)(st->total[s - 1] - st->total[s]);
+      o->aux_h[s] = take(na * d * 2);
+      o->aux_pos[s] = take(na * 4);
+    }
+  }
+  for (int l = 0; l < c->n_layers; ++l) {
+    const size_t n = (size_t)st->total[st->stage_of_layer[l]];
+    o->k[l] = take(n * d * 2);
+    o->v[l] = take(n * d * 2);
+    o->scores[l] = take(n * 4);
+  }
+  o->total = off;
+}
+
+}  // namespace
+
+struct lazyllm_model {
+  lazyllm_config cfg;
+  int f_pad;
+  char* blob;                                   // one device allocation holding everything below
+  const void *embed, *final_norm, *lm_head;
+  std::vector<const void*> attn_norm, ffn_norm, wqkv, wo, wgu, wdown;
+};
+
+extern "C" {
+
+int lazyllm_abi_version(void) { return 1; }
+
+const char* lazyllm_strerror(int status) {
+  switch (status) {
+    case LAZYLLM_OK: return "ok";
+    case LAZYLLM_EINVAL: return "invalid argument";
+    case LAZYLLM_ENOSPC: return "workspace or output buffer too small";
+    case LAZYLLM_EHIP: return "HIP runtime failure";
+    case LAZYLLM_ENOMEM: return "allocation failed";
+    default: return "unknown status";
+  }
+}
+
+int lazyllm_last_hip_error(void) { return g_last_hip_error; }
+
+int lazyllm_keep_counts(int32_t n, int32_t n_layers, const lazyllm_keep* sched, int32_t n_sched,
+                        int32_t* n_per_layer) {
+  if (n <= 0 || n_layers < 1 || n_layers > LAZYLLM_MAX_LAYERS || n_per_layer == nullptr)
+    return LAZYLLM_EINVAL;
+  if (!schedule_ok(n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
+  int m = n, i = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (i < n_sched && sched[i].layer == l) { m = keep_count(m, sched[i].keep_permille); ++i; }
+    n_per_layer[l] = m;
+  }
+  return LAZYLLM_OK;
+}
+
+size_t lazyllm_workspace_bytes(const lazyllm_config* cfg, int32_t total_tokens, int32_t batch,
+                               int32_t max_seqlen) {
+  if (!config_ok(cfg) || total_tokens <= 0 || batch <= 0 || max_seqlen <= 0 ||
+      max_seqlen > total_tokens || batch > total_tokens)
+    return 0;
+  Workspace w;
+  layout_workspace(cfg, total_tokens, batch, max_seqlen, &w);
+  return w.total;
+}
+
+size_t lazyllm_output_bytes(const lazyllm_config* cfg, const int32_t* seqlens, int32_t batch,
+                            const lazyllm_keep* sched, int32_t n_sched) {
+  if (!config_ok(cfg) || seqlens == nullptr || batch <= 0) return 0;
+  if (!schedule_ok(cfg->n_layers, sched, n_sched)) return 0;
+  long long total = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seqlens[b] <= 0) return 0;
+    total += seqlens[b];
+  }
+  if (total > 0x7fffffffLL / 4) return 0;
+  Stages st;
+  build_stages(cfg->n_layers, sched, n_sched, seqlens, batch, &st);
+  Output o;
+  layout_output(cfg, &st, batch, &o);
+  return o.total;
+}
+
+// ---- model --------------------------------------------------------------------------------
+
+int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, void* hip_stream,
+                         lazyllm_model** out) {
+  if (!config_ok(cfg) || w == nullptr || out == nullptr) return LAZYLLM_EINVAL;
+  if (!w->embed || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm ||
+      !w->w_gate || !w->w_up || !w->w_down || !w->final_norm || !w->lm_head)
+    return LAZYLLM_EINVAL;
+  const int L = cfg->n_layers;
+  for (int l = 0; l < L; ++l)
+    if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] ||
+        !w->w_gate[l] || !w->w_up[l] || !w->w_down[l])
+      return LAZYLLM_EINVAL;
+
+  lazyllm_model* m = new (std::nothrow) lazyllm_model();
+  if (m == nullptr) return LAZYLLM_ENOMEM;
+  m->cfg = *cfg;
+  m->f_pad = ffn_padded(cfg->d_ffn);
+  const size_t d = cfg->d_model, f = cfg->d_ffn, fp = m->f_pad, V = cfg->vocab;
+  const size_t per_layer = align_up(d * 2) * 2 + align_up(3 * d * d * 2) + align_up(d * d * 2) +
+                           align_up(2 * fp * d * 2) + align_up(d * fp * 2);
+  const size_t bytes = align_up(V * d * 2) * 2 + align_up(d * 2) + per_layer * L;
+  hipError_t e = hipMalloc((void**)&m->blob, bytes);
+  if (e != hipSuccess) {
+    delete m;
+    g_last_hip_error = (int)e;
+    return e == hipErrorOutOfMemory ? LAZYLLM_ENOMEM : LAZYLLM_EHIP;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  size_t off = 0;
+  auto take = [&](size_t b) { char* p = m->blob + off; off += align_up(b); return p; };
+  int rc = LAZYLLM_OK;
+  auto chk = [&](hipError_t err) { if (err != hipSuccess && rc == LAZYLLM_OK) rc = hip_fail(err); };
+
+  char* p = take(V * d * 2);
+  chk(hipMemcpyAsync(p, w->embed, V * d * 2, hipMemcpyDeviceToDevice, st));
+  m->embed = p;
+  p = take(V * d * 2);
+  chk(hipMemcpyAsync(p, w->lm_head, V * d * 2, hipMemcpyDeviceToDevice, st));
+  m->lm_head = p;
+  p = take(d * 2);
+  chk(hipMemcpyAsync(p, w->final_norm, d * 2, hipMemcpyDeviceToDevice, st));
+  m->final_norm = p;
+  for (int l = 0; l < L && rc == LAZYLLM_OK; ++l) {
+    p = take(d * 2);
+    chk(hipMemcpyAsync(p, w->attn_norm[l], d * 2, hipMemcpyDeviceToDevice, st));
+    m->attn_norm.push_back(p);
+    p = take(d * 2);
+    chk(hipMemcpyAsync(p, w->ffn_norm[l], d * 2, hipMemcpyDeviceToDevice, st));
+    m->ffn_norm.push_back(p);
+    p = take(3 * d * d * 2);                       // fused [q; k; v] rows
+    chk(hipMemcpyAsync(p, w->wq[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    chk(hipMemcpyAsync(p + d * d * 2, w->wk[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    chk(hipMemcpyAsync(p + 2 * d * d * 2, w->wv[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    m->wqkv.push_back(p);
+    p = take(d * d * 2);
+    chk(hipMemcpyAsync(p, w->wo[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    m->wo.push_back(p);
+    p = take(2 * fp * d * 2);                      // gate/up interleaved in 32-row blocks
+    chk(launch_interleave_gate_up(w->w_gate[l], w->w_up[l], p, (int)f, (int)fp, (int)d, st));
+    m->wgu.push_back(p);
+    p = take(d * fp * 2);                          // down, K zero-padded to f_pad
+    chk(launch_copy_rows(w->w_down[l], p, (int)d, (int)f, (int)f, (int)fp, st));
+    m->wdown.push_back(p);
+  }
+  if (rc == LAZYLLM_OK) chk(hipStreamSynchronize(st));
+  if (rc != LAZYLLM_OK) {
+    (void)hipFree(m->blob);
+    delete m;
+    return rc;
+  }
+  *out = m;
+  return LAZYLLM_OK;
+}
+
+void lazyllm_model_destroy(lazyllm_model* m) {
+  if (m == nullptr) return;
+  (void)hipFree(m->blob);
+  delete m;
+}
+
+// ---- prefill ------------------------------------------------------------------------------
+
+int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
+                           const float* embed_scale, const int32_t* cu_host,
+                           const int32_t* cu_dev, int32_t batch, const lazyllm_keep* sched,
+                           int32_t n_sched, uint32_t flags, void* workspace, size_t ws_bytes,
+                           void* out_buf, size_t out_bytes, void* hip_stream, lazyllm_result* res) {
+  // ---- validation: nothing below this block is reached with a bad argument, and nothing in
+  // this block touches HIP
+  if (m == nullptr || token_ids == nullptr || cu_host == nullptr || workspace == nullptr ||
+      out_buf == nullptr || res == nullptr || batch <= 0)
+    return LAZYLLM_EINVAL;
+  if (batch > 1 && cu_dev == nullptr) return LAZYLLM_EINVAL;
+  if ((flags & ~1u) != 0) return LAZYLLM_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)out_buf & 255) != 0) return LAZYLLM_EINVAL;
+  const lazyllm_config* c = &m->cfg;
+  if (!schedule_ok(c->n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
+  if (cu_host[0] != 0) return LAZYLLM_EINVAL;
+  std::vector<int32_t> seqlens(batch);
+  int max_seqlen = 0;
+  for (int b = 0; b < batch; ++b) {
+    const long long n = (long long)cu_host[b + 1] - cu_host[b];
+    if (n <= 0 || cu_host[b + 1] > 0x7fffffff / 4) return LAZYLLM_EINVAL;
+    seqlens[b] = (int32_t)n;
+    if (n > max_seqlen) max_seqlen = (int)n;
+  }
+  const int T = cu_host[batch];
+  Stages stg;
+  build_stages(c->n_layers, sched, n_sched, seqlens.data(), batch, &stg);
+  Workspace ws;
+  layout_workspace(c, T, batch, max_seqlen, &ws);
+  Output ob;
+  layout_output(c, &stg, batch, &ob);
+  if (ws_bytes < ws.total || out_bytes < ob.total) return LAZYLLM_ENOSPC;
+
+  // ---- result struct
+  char* W = (char*)workspace;
+  char* O = (char*)out_buf;
+  const int L = c->n_layers, d = c->d_model, H = c->n_heads, hd = c->head_dim, B = batch;
+  const int BW = B + 1;
+  memset(res, 0, sizeof(*res));
+  res->batch = B;
+  res->n_layers = L;
+  res->logits = (float*)(O + ob.logits);
+  res->status = (int32_t*)(O + ob.status);
+  int32_t* cu_stage = (int32_t*)(O + ob.cu_stage);
+  int32_t* cu_aux = (int32_t*)(O + ob.cu_aux);
+  int32_t* cu_vt = (int32_t*)(O + ob.cu_vt);
+  const bool score_all = (flags & LAZYLLM_SCORE_ONLY_USED) == 0;
+  for (int l = 0; l < L; ++l) {
+    const int s = stg.stage_of_layer[l];
+    res->n_tokens[l] = (int32_t)stg.total[s];
+    res->kept_pos[l] = (int32_t*)(O + ob.kept_pos[s]);
+    res->cu_kept[l] = cu_stage + s * BW;
+    res->k[l] = O + ob.k[l];
+    res->v[l] = O + ob.v[l];
+    const bool used = (l + 1 < L) && stg.stage_of_layer[l + 1] != s;
+    res->scores[l] = (score_all || used) ? (float*)(O + ob.scores[l]) : nullptr;
+    if (s > 0 && stg.first_layer[s] == l) {
+      res->n_aux[l] = (int32_t)(stg.total[s - 1] - stg.total[s]);
+      res->aux_h[l] = O + ob.aux_h[s];
+      res->aux_pos[l] = (int32_t*)(O + ob.aux_pos[s]);
+      res->cu_aux[l] = cu_aux + (s - 1) * BW;
+    }
+  }
+
+  // ---- enqueue
+  hipStream_t st = (hipStream_t)hip_stream;
+  PlanArgs plan;
+  memset(&plan, 0, sizeof(plan));
+  plan.n_stages = stg.n_stages - 1;
+  for (int s = 1; s < stg.n_stages; ++s) plan.permille[s - 1] = stg.permille[s];
+  LZ_HIP(launch_plan(cu_dev, seqlens[0], B, T, plan, cu_stage, cu_aux, cu_vt, res->status, st));
+  float2* rope = (float2*)(W + ws.rope);
+  LZ_HIP(launch_rope_table(rope, max_seqlen, hd, c->rope_theta, st));
+  char* hbuf[2] = {W + ws.h0, W + ws.h1};
+  int cur = 0;
+  LZ_HIP(launch_embed(m->embed, token_ids, embed_scale, cu_dev, B, T, d, c->vocab, hbuf[0],
+                      res->kept_pos[0], res->status, st));
+  const int fp = m->f_pad;
+  for (int l = 0; l < L; ++l) {
+    const int s = stg.stage_of_layer[l];
+    const int n = (int)stg.total[s];
+    const int32_t* cu = cu_stage + s * BW;
+    if (s > 0 && stg.first_layer[s] == l) {
+      // Sec. 3.2: the scores of layer l-1 pick the tokens that enter layer l; the others'
+      // hidden states go to this layer's Aux Cache.
+      const int n_prev = (int)stg.total[s - 1];
+      int32_t* keep_idx = (int32_t*)(W + ws.keep_idx);
+      int32_t* prune_idx = (int32_t*)(W + ws.prune_idx);
+      LZ_HIP(launch_select(res->scores[l - 1], cu_stage + (s - 1) * BW, cu, 0, 0, B, keep_idx,
+                           prune_idx, st));
+      LZ_HIP(launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
+                           hbuf[cur ^ 1], res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st));
+      cur ^= 1;
+    }
+    char* h = hbuf[cur];
+    LZ_HIP(launch_rmsnorm(h, m->attn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
+    LZ_HIP(launch_gemm(W + ws.xa, m->wqkv[l], W + ws.qkv, nullptr, n, 3 * d, d, d, d, 3 * d,
+                       EPI_STORE, st));
+    LZ_HIP(launch_rope_split(W + ws.qkv, res->kept_pos[l], rope, W + ws.q, res->k[l], res->v[l],
+                             W + ws.vt, cu, cu_vt + s * BW, 0, B, stg.max_rows[s],
+                             (int)stg.vt_ld[s], H, hd, st));
+    if (res->scores[l] != nullptr)
+      LZ_HIP(launch_score(W + ws.q, res->k[l], res->scores[l], W + ws.score, cu, 0, B, n,
+                          stg.max_rows[s], H, hd, st));
+    LZ_HIP(launch_attention(W + ws.q, res->k[l], W + ws.vt, W + ws.o, cu, cu_vt + s * BW, 0, B,
+                            stg.max_rows[s], (int)stg.vt_ld[s], H, hd, st));
+    LZ_HIP(launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st));
+    LZ_HIP(launch_rmsnorm(h, m->ffn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
+    LZ_HIP(launch_gemm(W + ws.xa, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp,
+                       EPI_SWIGLU, st));
+    LZ_HIP(launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st));
+  }
+  const int s_last = stg.stage_of_layer[L - 1];
+  LZ_HIP(launch_final_norm(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm,
+                           (float*)(W + ws.xf), d, c->rms_eps, st));
+  LZ_HIP(launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, B, d, c->vocab, st));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_prefill(const lazyllm_model* m, const int32_t* token_ids, const float* embed_scale,
+                    int32_t n, const lazyllm_keep* sched, int32_t n_sched, uint32_t flags,
+                    void* workspace, size_t ws_bytes, void* out_buf, size_t out_bytes,
+                    void* hip_stream, lazyllm_result* res) {
+  if (n <= 0) return LAZYLLM_EINVAL;
+  const int32_t cu[2] = {0, n};
+  return lazyllm_prefill_varlen(m, token_ids, embed_scale, cu, nullptr, 1, sched, n_sched, flags,
+                                workspace, ws_bytes, out_buf, out_bytes, hip_stream, res);
+}
+
+// ---- single steps -------------------------------------------------------------------------
+
+int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,
+                    int32_t K, int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue,
+                    void* hip_stream) {
+  if (!A || !W || !C || M < 0 || N <= 0 || K <= 0) return LAZYLLM_EINVAL;
+  if (N % 128 != 0 || K % 64 != 0 || lda % 8 != 0 || ldw % 8 != 0 || ldc % 4 != 0)
+    return LAZYLLM_EINVAL;
+  if (lda < K || ldw < K) return LAZYLLM_EINVAL;
+  if (epilogue < 0 || epilogue > 2 || (epilogue == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
+  if (ldc < (epilogue == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
+  if (M == 0) return LAZYLLM_OK;
+  LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d, float eps,
+                       void* hip_stream) {
+  if (!h || !gain || !x || rows < 0 || d <= 0 || d % 8 != 0 || d > 16384 || !(eps > 0.f))
+    return LAZYLLM_EINVAL;
+  LZ_HIP(launch_rmsnorm(h, gain, x, rows, d, eps, (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_rope_split(const void* qkv, const int32_t* pos, int32_t max_pos, void* rope_table,
+                          void* q, void* k, void* v, void* vt, int32_t vt_ld, int32_t rows,
+                          int32_t n_heads, int32_t head_dim, float theta, void* hip_stream) {
+  if (!qkv || !pos || !rope_table || !q || !k || !v || !vt || rows <= 0 || max_pos < 0 ||
+      n_heads <= 0 || (head_dim != 64 && head_dim != 128) || vt_ld % 64 != 0 || vt_ld < rows ||
+      !(theta > 0.f))
+    return LAZYLLM_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  LZ_HIP(launch_rope_table((float2*)rope_table, max_pos + 1, head_dim, theta, st));
+  LZ_HIP(launch_rope_split(qkv, pos, (const float2*)rope_table, q, k, v, vt, nullptr, nullptr, rows,
+                           1, rows, vt_ld, n_heads, head_dim, st));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_attention(const void* q, const void* k, const void* vt, int32_t vt_ld, void* o,
+                         int32_t rows, int32_t n_heads, int32_t head_dim, void* hip_stream) {
+  if (!q || !k || !vt || !o || rows <= 0 || n_heads <= 0 || (head_dim != 64 && head_dim != 128) ||
+      vt_ld % 64 != 0 || vt_ld < (rows + 63) / 64 * 64)
+    return LAZYLLM_EINVAL;
+  LZ_HIP(launch_attention(q, k, vt, o, nullptr, nullptr, rows, 1, rows, vt_ld, n_heads, head_dim,
+                          (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+size_t lazyllm_op_score_scratch_bytes(int32_t rows, int32_t n_heads) {
+  if (rows <= 0 || n_heads <= 0) return 0;
+  return score_scratch_bytes(rows, 1, n_heads);
+}
+
+int lazyllm_op_score(const void* q_last, const void* k, float* s, void* scratch, int32_t rows,
+                     int32_t n_heads, int32_t head_dim, void* hip_stream) {
+  if (!q_last || !k || !s || !scratch || rows <= 0 || n_heads <= 0 || n_heads > 256 ||
+      (head_dim != 64 && head_dim != 128) || (n_heads * head_dim) % 8 != 0 ||
+      n_heads * head_dim > 8192)
+    return LAZYLLM_EINVAL;
+  // the kernel reads the query from row (rows-1) of a [rows, H*hd] tensor: rebase the pointer
+  const char* qbase = (const char*)q_last - (size_t)(rows - 1) * n_heads * head_dim * 2;
+  LZ_HIP(launch_score(qbase, k, s, scratch, nullptr, rows, 1, rows, rows, n_heads, head_dim,
+                      (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_select(const float* s, int32_t m, int32_t k, int32_t* keep_idx, int32_t* prune_idx,
+                      void* hip_stream) {
+  if (!s || !keep_idx || !prune_idx || m <= 0 || k < 1 || k > m) return LAZYLLM_EINVAL;
+  LZ_HIP(launch_select(s, nullptr, nullptr, m, k, 1, keep_idx, prune_idx, (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_gather(const void* h, const int32_t* pos, const int32_t* keep_idx, int32_t n_keep,
+                      const int32_t* prune_idx, int32_t n_prune, void* h_out, int32_t* pos_out,
+                      void* aux_h, int32_t* aux_pos, int32_t d, void* hip_stream) {
+  if (!h || !pos || n_keep < 0 || n_prune < 0 || d <= 0 || d % 8 != 0) return LAZYLLM_EINVAL;
+  if (n_keep > 0 && (!keep_idx || !h_out || !pos_out)) return LAZYLLM_EINVAL;
+  if (n_prune > 0 && (!prune_idx || !aux_h || !aux_pos)) return LAZYLLM_EINVAL;
+  LZ_HIP(launch_gather(h, pos, keep_idx, n_keep, prune_idx, n_prune, h_out, pos_out, aux_h, aux_pos,
+                       d, (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_lm_head(const void* h_last, const void* gain, const void* w_lm, float* xf,
+                       float* logits, int32_t d, int32_t vocab, float eps, void* hip_stream) {
+  if (!h_last || !gain || !w_lm || !xf || !logits || d <= 0 || d % 8 != 0 || vocab <= 0 ||
+      !(eps > 0.f))
+    return LAZYLLM_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  LZ_HIP(launch_final_norm(h_last, nullptr, 1, 1, gain, xf, d, eps, st));
+  LZ_HIP(launch_lm_head(xf, w_lm, logits, 1, d, vocab, st));
+  return LAZYLLM_OK;
+}
+
+}  // extern "C"

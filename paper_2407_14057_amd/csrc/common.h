@@ -1,0 +1,124 @@
+// Shared device helpers and the host-side launch interface of the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lz {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+
+constexpr int WAVE = 64;
+
+// ---- bf16 <-> fp32 (round to nearest even through v_cvt_pk_bf16_f32) -------------------
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  floatx2_t f = {lo, hi};
+  bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+  return *reinterpret_cast<uint32_t*>(&h);
+}
+__device__ __forceinline__ uint16_t to_bf16(float x) { return (uint16_t)(pack_bf16(x, 0.f) & 0xffffu); }
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_float(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
+
+// 8 bf16 (one 16-byte vector) <-> 8 floats
+__device__ __forceinline__ void unpack8(const uint4& v, float* f) {
+  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+  uint4 v;
+  v.x = pack_bf16(f[0], f[1]); v.y = pack_bf16(f[2], f[3]);
+  v.z = pack_bf16(f[4], f[5]); v.w = pack_bf16(f[6], f[7]);
+  return v;
+}
+
+// ---- wave-level reductions (64 lanes) ---------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- LDS tiles filled straight from global memory ---------------------------------------
+// A tile is ROWS rows of CH 16-byte chunks.  Chunk c of row r is stored at chunk slot
+// c ^ (r & 7), so that the 16-byte operand reads of 8 consecutive rows at one logical
+// chunk fall into 8 different bank groups.  global_load_lds writes lane i of a wave
+// instruction to LDS base + 16*i, so the permutation is applied on the global side.
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+
+__device__ __forceinline__ void g2l16(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds(
+      (const __attribute__((address_space(1))) void*)gsrc,
+      (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// Row range of sequence b: from the offsets cu[batch+1], or [0, n_single) when cu is null
+// (single-sequence calls need no device-side table).
+__device__ __forceinline__ void seq_range(const int32_t* cu, int b, int n_single, int& row0, int& n) {
+  if (cu != nullptr) { row0 = cu[b]; n = cu[b + 1] - row0; }
+  else { row0 = 0; n = n_single; }
+}
+
+// ---- launch interface (host) ------------------------------------------------------------
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+
+hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
+                       int lda, int ldw, int ldc, int epilogue, hipStream_t st);
+
+hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st);
+
+// Batched pieces take per-sequence row offsets cu[batch+1] (device) of the current stage;
+// cu == nullptr means one sequence of n_single rows (cu_vt likewise means offset 0).
+hipError_t launch_embed(const void* embed, const int32_t* ids, const float* scale, const int32_t* cu,
+                        int batch, int total, int d, int vocab, void* h, int32_t* pos,
+                        int32_t* status, hipStream_t st);
+hipError_t launch_rmsnorm(const void* h, const void* gain, void* x, int rows, int d, float eps,
+                          hipStream_t st);
+hipError_t launch_rope_split(const void* qkv, const int32_t* pos, const float2* table, void* q,
+                             void* k, void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
+                             int n_single, int batch, int max_rows, int vt_ld, int n_heads,
+                             int head_dim, hipStream_t st);
+hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
+                            const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
+                            int n_heads, int head_dim, hipStream_t st);
+size_t score_scratch_bytes(int total_rows, int batch, int n_heads);
+hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, const int32_t* cu,
+                        int n_single, int batch, int total_rows, int max_rows, int n_heads,
+                        int head_dim, hipStream_t st);
+hipError_t launch_select(const float* s, const int32_t* cu_prev, const int32_t* cu_new,
+                         int m_single, int k_single, int batch, int32_t* keep_idx,
+                         int32_t* prune_idx, hipStream_t st);
+hipError_t launch_gather(const void* h, const int32_t* pos, const int32_t* keep_idx, int n_keep,
+                         const int32_t* prune_idx, int n_prune, void* h_out, int32_t* pos_out,
+                         void* aux_h, int32_t* aux_pos, int d, hipStream_t st);
+hipError_t launch_final_norm(const void* h, const int32_t* cu, int n_single, int batch,
+                             const void* gain, float* xf, int d, float eps, hipStream_t st);
+hipError_t launch_lm_head(const float* xf, const void* w_lm, float* logits, int batch, int d,
+                          int vocab, hipStream_t st);
+
+struct PlanArgs {
+  int32_t n_stages;                     // pruning stages after stage 0
+  int32_t permille[128];                // keep ratio entering stage s+1
+};
+// cu_stage[(n_stages+1)][batch+1], cu_aux[n_stages][batch+1], cu_vt[(n_stages+1)][batch+1]
+hipError_t launch_plan(const int32_t* cu_dev, int n_single, int batch, int expect_total,
+                       const PlanArgs& plan, int32_t* cu_stage, int32_t* cu_aux, int32_t* cu_vt,
+                       int32_t* status, hipStream_t st);
+
+// Weight repacking (model creation, off the hot path).
+hipError_t launch_copy_rows(const void* src, void* dst, int rows, int cols, int src_ld, int dst_ld,
+                            hipStream_t st);
+hipError_t launch_interleave_gate_up(const void* gate, const void* up, void* dst, int f, int f_pad,
+                                     int d, hipStream_t st);
+
+}  // namespace lz

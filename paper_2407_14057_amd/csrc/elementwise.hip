@@ -1,0 +1,406 @@
+// Glue kernels of the decoder layer: plan, embedding, RMSNorm, rotary split, final norm,
+// LM head, and the weight repack used at model creation.  All bandwidth-bound; 16-byte
+// vectors, one wave per row.
+#include "common.h"
+
+namespace lz {
+
+// ------------------------------------------------------------------------------------------
+// Per-stage row offsets.  Stage 0 is the full prompt; stage s+1 begins at the s-th pruning
+// layer and keeps max(1, ceil(n * permille / 1000)) tokens of every sequence
+// (Sec. 3.2: top-k percentile of the surviving tokens).  Counts do not depend on the data,
+// so the whole table is known before the first layer runs.
+// ------------------------------------------------------------------------------------------
+__global__ void plan_kernel(const int32_t* __restrict__ cu_dev, int n_single, int batch,
+                            int expect_total, PlanArgs plan, int32_t* __restrict__ cu_stage,
+                            int32_t* __restrict__ cu_aux, int32_t* __restrict__ cu_vt,
+                            int32_t* __restrict__ status) {
+  const int S = plan.n_stages + 1, W = batch + 1;
+  if (threadIdx.x == 0) {
+    *status = 0;
+    if (cu_dev != nullptr && (cu_dev[0] != 0 || cu_dev[batch] != expect_total)) *status = 2;
+  }
+  for (int b = threadIdx.x; b < batch; b += blockDim.x) {
+    int n = cu_dev ? (cu_dev[b + 1] - cu_dev[b]) : n_single;
+    if (n < 1) n = 1;
+    cu_stage[0 * W + b + 1] = n;
+    for (int s = 1; s < S; ++s) {
+      long long k = ((long long)n * plan.permille[s - 1] + 999) / 1000;
+      int kk = k < 1 ? 1 : (int)k;
+      cu_aux[(s - 1) * W + b + 1] = n - kk;
+      n = kk;
+      cu_stage[s * W + b + 1] = n;
+    }
+  }
+  __syncthreads();
+  // prefix sums over the batch, one stage per thread
+  for (int s = threadIdx.x; s < S; s += blockDim.x) {
+    int acc = 0, accv = 0;
+    cu_stage[s * W] = 0;
+    cu_vt[s * W] = 0;
+    for (int b = 0; b < batch; ++b) {
+      int n = cu_stage[s * W + b + 1];
+      acc += n;
+      accv += (n + 63) & ~63;
+      cu_stage[s * W + b + 1] = acc;
+      cu_vt[s * W + b + 1] = accv;
+    }
+    if (s >= 1) {
+      int a = 0;
+      cu_aux[(s - 1) * W] = 0;
+      for (int b = 0; b < batch; ++b) {
+        a += cu_aux[(s - 1) * W + b + 1];
+        cu_aux[(s - 1) * W + b + 1] = a;
+      }
+    }
+  }
+}
+
+hipError_t launch_plan(const int32_t* cu_dev, int n_single, int batch, int expect_total,
+                       const PlanArgs& plan, int32_t* cu_stage, int32_t* cu_aux, int32_t* cu_vt,
+                       int32_t* status, hipStream_t st) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, st, cu_dev, n_single, batch, expect_total,
+                     plan, cu_stage, cu_aux, cu_vt, status);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Rotary table: table[p][i] = (cos, sin)(p * theta^(-2i/hd)), angles formed in fp64.
+// ------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(float2* __restrict__ table, int n_pos, int half, double theta) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_pos * half) return;
+  int p = idx / half, i = idx - p * half;
+  double inv_freq = pow(theta, -(double)i / (double)half);
+  double s, c;
+  sincos((double)p * inv_freq, &s, &c);
+  table[idx] = make_float2((float)c, (float)s);
+}
+
+hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st) {
+  int half = head_dim / 2, total = n_pos * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((total + 255) / 256), dim3(256), 0, st, table, n_pos,
+                     half, (double)theta);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding gather (+ optional per-token scale) and position ids.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+embed_kernel(const uint4* __restrict__ embed, const int32_t* __restrict__ ids,
+             const float* __restrict__ scale, const int32_t* __restrict__ cu, int batch, int total,
+             int vec_per_row, int vocab, uint4* __restrict__ h, int32_t* __restrict__ pos,
+             int32_t* __restrict__ status) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= total) return;
+  int id = ids[row];
+  if (id < 0 || id >= vocab) {
+    if (lane == 0) atomicOr(status, 1);
+    id = id < 0 ? 0 : vocab - 1;
+  }
+  if (lane == 0) {
+    int start = 0;
+    if (cu != nullptr) {
+      int lo = 0, hi = batch;                 // largest b with cu[b] <= row
+      while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (cu[mid] <= row) lo = mid; else hi = mid;
+      }
+      start = cu[lo];
+    }
+    pos[row] = row - start;
+  }
+  const uint4* src = embed + (size_t)id * vec_per_row;
+  uint4* dst = h + (size_t)row * vec_per_row;
+  if (scale == nullptr) {
+    for (int v = lane; v < vec_per_row; v += 64) dst[v] = src[v];
+  } else {
+    const float sc = scale[row];
+    for (int v = lane; v < vec_per_row; v += 64) {
+      float f[8];
+      unpack8(src[v], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] *= sc;
+      dst[v] = pack8(f);
+    }
+  }
+}
+
+hipError_t launch_embed(const void* embed, const int32_t* ids, const float* scale, const int32_t* cu,
+                        int batch, int total, int d, int vocab, void* h, int32_t* pos,
+                        int32_t* status, hipStream_t st) {
+  hipLaunchKernelGGL(embed_kernel, dim3((total + 3) / 4), dim3(256), 0, st, (const uint4*)embed, ids,
+                     scale, cu, batch, total, d / 8, vocab, (uint4*)h, pos, status);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm: one wave per row, the row stays in registers between the two passes.
+// ------------------------------------------------------------------------------------------
+template <int NV>
+__global__ void __launch_bounds__(256)
+rmsnorm_kernel(const uint4* __restrict__ h, const uint4* __restrict__ gain, uint4* __restrict__ x,
+               int rows, int vec_per_row, float inv_d, float eps) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;
+  const uint4* src = h + (size_t)row * vec_per_row;
+  uint4 reg[NV];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int v = lane + 64 * i;
+    if (v < vec_per_row) {
+      reg[i] = src[v];
+      float f[8];
+      unpack8(reg[i], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
+  }
+  ss = wave_sum(ss);
+  const float r = rsqrtf(ss * inv_d + eps);
+  uint4* dst = x + (size_t)row * vec_per_row;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    int v = lane + 64 * i;
+    if (v < vec_per_row) {
+      float f[8], g[8];
+      unpack8(reg[i], f);
+      unpack8(gain[v], g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = f[e] * r * g[e];
+      dst[v] = pack8(f);
+    }
+  }
+}
+
+hipError_t launch_rmsnorm(const void* h, const void* gain, void* x, int rows, int d, float eps,
+                          hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  const int vpr = d / 8, nv = (vpr + 63) / 64;
+  dim3 grid((rows + 3) / 4), block(256);
+  const float inv_d = 1.0f / (float)d;
+#define LZ_RMS(NV)                                                                              \
+  hipLaunchKernelGGL(rmsnorm_kernel<NV>, grid, block, 0, st, (const uint4*)h, (const uint4*)gain, \
+                     (uint4*)x, rows, vpr, inv_d, eps)
+  if (nv <= 1) LZ_RMS(1);
+  else if (nv <= 2) LZ_RMS(2);
+  else if (nv <= 4) LZ_RMS(4);
+  else if (nv <= 8) LZ_RMS(8);
+  else if (nv <= 16) LZ_RMS(16);
+  else if (nv <= 32) LZ_RMS(32);
+  else return hipErrorInvalidValue;
+#undef LZ_RMS
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Split the fused projection into q, k (rotary applied), v, and the transposed copy of v.
+// One workgroup = 64 tokens of one head.  vt[h][dim][cu_vt[b] + token] is what the
+// attention kernel's second product reads (keys contiguous); its tail columns up to the
+// next multiple of 64 are zeroed so that masked probabilities never meet a NaN.
+// ------------------------------------------------------------------------------------------
+template <int HD>
+__global__ void __launch_bounds__(256)
+rope_split_kernel(const uint16_t* __restrict__ qkv, const int32_t* __restrict__ pos,
+                  const float2* __restrict__ table, uint16_t* __restrict__ q,
+                  uint16_t* __restrict__ k, uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
+                  const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
+                  int vt_ld, int n_heads) {
+  constexpr int CH = HD / 8;            // 16-byte chunks per head row
+  constexpr int HALF = HD / 2;
+  constexpr int LROW = HD + 2;          // padded LDS row (elements)
+  __shared__ uint16_t tile[64 * LROW];
+  const int b = blockIdx.z, head = blockIdx.y;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const int t0 = blockIdx.x * 64;
+  if (t0 >= n) return;
+  const int d = n_heads * HD;
+  const size_t ld_in = (size_t)3 * d;
+
+  // q and k: thread takes (token, chunk c < CH/2) and rotates it with chunk c + CH/2
+  for (int idx = threadIdx.x; idx < 64 * (CH / 2); idx += 256) {
+    const int t = idx / (CH / 2), c = idx % (CH / 2);
+    if (t0 + t >= n) continue;
+    const size_t row = (size_t)(row0 + t0 + t);
+    const float2* cs = table + (size_t)pos[row] * HALF + c * 8;
+    float cosv[8], sinv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { float2 t2 = cs[e]; cosv[e] = t2.x; sinv[e] = t2.y; }
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      const uint16_t* src = qkv + row * ld_in + (size_t)which * d + head * HD;
+      uint16_t* dst = (which == 0 ? q : k) + row * d + head * HD;
+      float a[8], bb[8], ra[8], rb[8];
+      unpack8(*(const uint4*)(src + c * 8), a);
+      unpack8(*(const uint4*)(src + HALF + c * 8), bb);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        ra[e] = a[e] * cosv[e] - bb[e] * sinv[e];
+        rb[e] = bb[e] * cosv[e] + a[e] * sinv[e];
+      }
+      *(uint4*)(dst + c * 8) = pack8(ra);
+      *(uint4*)(dst + HALF + c * 8) = pack8(rb);
+    }
+  }
+  // v: copy out and stage into LDS
+  for (int idx = threadIdx.x; idx < 64 * CH; idx += 256) {
+    const int t = idx / CH, c = idx % CH;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (t0 + t < n) {
+      const size_t row = (size_t)(row0 + t0 + t);
+      val = *(const uint4*)(qkv + row * ld_in + (size_t)2 * d + head * HD + c * 8);
+      *(uint4*)(v + row * d + head * HD + c * 8) = val;
+    }
+    uint32_t* p = (uint32_t*)(tile + t * LROW + c * 8);   // LROW even: 4-byte aligned
+    p[0] = val.x; p[1] = val.y; p[2] = val.z; p[3] = val.w;
+  }
+  __syncthreads();
+  // transposed write: thread takes (dim, group of 8 tokens)
+  const size_t vt_base = (size_t)head * HD * vt_ld + (cu_vt ? cu_vt[b] : 0) + t0;
+  for (int idx = threadIdx.x; idx < HD * 8; idx += 256) {
+    const int j = idx & 7, dim = idx >> 3;
+    uint16_t e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = tile[(j * 8 + i) * LROW + dim];
+    uint4 o;
+    o.x = e[0] | ((uint32_t)e[1] << 16); o.y = e[2] | ((uint32_t)e[3] << 16);
+    o.z = e[4] | ((uint32_t)e[5] << 16); o.w = e[6] | ((uint32_t)e[7] << 16);
+    *(uint4*)(vt + vt_base + (size_t)dim * vt_ld + j * 8) = o;
+  }
+}
+
+hipError_t launch_rope_split(const void* qkv, const int32_t* pos, const float2* table, void* q,
+                             void* k, void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
+                             int n_single, int batch, int max_rows, int vt_ld, int n_heads,
+                             int head_dim, hipStream_t st) {
+  if (max_rows <= 0) return hipSuccess;
+  dim3 grid((max_rows + 63) / 64, n_heads, batch), block(256);
+  if (head_dim == 128)
+    hipLaunchKernelGGL(rope_split_kernel<128>, grid, block, 0, st, (const uint16_t*)qkv, pos, table,
+                       (uint16_t*)q, (uint16_t*)k, (uint16_t*)v, (uint16_t*)vt, cu, cu_vt, n_single,
+                       vt_ld, n_heads);
+  else if (head_dim == 64)
+    hipLaunchKernelGGL(rope_split_kernel<64>, grid, block, 0, st, (const uint16_t*)qkv, pos, table,
+                       (uint16_t*)q, (uint16_t*)k, (uint16_t*)v, (uint16_t*)vt, cu, cu_vt, n_single,
+                       vt_ld, n_heads);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Final RMSNorm of each sequence's last row -> fp32, then the LM-head GEMV.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+final_norm_kernel(const uint16_t* __restrict__ h, const int32_t* __restrict__ cu, int n_single,
+                  const uint16_t* __restrict__ gain, float* __restrict__ xf, int d, float eps) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const uint16_t* row = h + (size_t)(row0 + n - 1) * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float f = bf16_to_float(row[i]);
+    ss += f * f;
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  ss = red[0] + red[1] + red[2] + red[3];
+  const float r = rsqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256)
+    xf[(size_t)b * d + i] = bf16_to_float(row[i]) * r * bf16_to_float(gain[i]);
+}
+
+hipError_t launch_final_norm(const void* h, const int32_t* cu, int n_single, int batch,
+                             const void* gain, float* xf, int d, float eps, hipStream_t st) {
+  hipLaunchKernelGGL(final_norm_kernel, dim3(batch), dim3(256), 0, st, (const uint16_t*)h, cu,
+                     n_single, (const uint16_t*)gain, xf, d, eps);
+  return hipGetLastError();
+}
+
+// One wave per vocabulary row; the row's 16-byte vectors are read once and reused for
+// every sequence of the batch.  Reads V*d*2 bytes: HBM-bound.
+__global__ void __launch_bounds__(256)
+lm_head_kernel(const float* __restrict__ xf, const uint4* __restrict__ w, float* __restrict__ logits,
+               int batch, int d, int vocab) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int vpr = d / 8;
+  for (int r = 0; r < 4; ++r) {
+    const int row = (blockIdx.x * 4 + wave) * 4 + r;
+    if (row >= vocab) return;
+    const uint4* src = w + (size_t)row * vpr;
+    for (int b = 0; b < batch; ++b) {
+      const float* x = xf + (size_t)b * d;
+      float acc = 0.f;
+      for (int v = lane; v < vpr; v += 64) {
+        float f[8];
+        unpack8(src[v], f);
+        const float4 x0 = *(const float4*)(x + v * 8), x1 = *(const float4*)(x + v * 8 + 4);
+        acc += f[0] * x0.x + f[1] * x0.y + f[2] * x0.z + f[3] * x0.w + f[4] * x1.x + f[5] * x1.y +
+               f[6] * x1.z + f[7] * x1.w;
+      }
+      acc = wave_sum(acc);
+      if (lane == 0) logits[(size_t)b * vocab + row] = acc;
+    }
+  }
+}
+
+hipError_t launch_lm_head(const float* xf, const void* w_lm, float* logits, int batch, int d,
+                          int vocab, hipStream_t st) {
+  hipLaunchKernelGGL(lm_head_kernel, dim3((vocab + 15) / 16), dim3(256), 0, st, xf,
+                     (const uint4*)w_lm, logits, batch, d, vocab);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight repack (model creation only).
+// ------------------------------------------------------------------------------------------
+__global__ void copy_rows_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst,
+                                 int rows, int cols, int src_ld, int dst_ld) {
+  // dst[r][c] = c < cols ? src[r][c] : 0 for c < dst_ld
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)rows * dst_ld;
+  if (idx >= total) return;
+  int r = (int)(idx / dst_ld), c = (int)(idx % dst_ld);
+  dst[idx] = c < cols ? src[(size_t)r * src_ld + c] : (uint16_t)0;
+}
+
+hipError_t launch_copy_rows(const void* src, void* dst, int rows, int cols, int src_ld, int dst_ld,
+                            hipStream_t st) {
+  size_t total = (size_t)rows * dst_ld;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     (const uint16_t*)src, (uint16_t*)dst, rows, cols, src_ld, dst_ld);
+  return hipGetLastError();
+}
+
+__global__ void interleave_gate_up_kernel(const uint16_t* __restrict__ gate,
+                                          const uint16_t* __restrict__ up,
+                                          uint16_t* __restrict__ dst, int f, int f_pad, int d) {
+  // dst row 64*j + i      = gate row 32*j + i   (i < 32)
+  // dst row 64*j + 32 + i = up   row 32*j + i;  rows beyond f are zero
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)2 * f_pad * d;
+  if (idx >= total) return;
+  int r = (int)(idx / d), c = (int)(idx % d);
+  int j = r >> 6, i = r & 63;
+  int srow = 32 * j + (i & 31);
+  const uint16_t* src = (i < 32) ? gate : up;
+  dst[idx] = srow < f ? src[(size_t)srow * d + c] : (uint16_t)0;
+}
+
+hipError_t launch_interleave_gate_up(const void* gate, const void* up, void* dst, int f, int f_pad,
+                                     int d, hipStream_t st) {
+  size_t total = (size_t)2 * f_pad * d;
+  hipLaunchKernelGGL(interleave_gate_up_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
+                     st, (const uint16_t*)gate, (const uint16_t*)up, (uint16_t*)dst, f, f_pad, d);
+  return hipGetLastError();
+}
+
+}  // namespace lz

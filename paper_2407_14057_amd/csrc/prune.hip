@@ -1,0 +1,380 @@
+// The pruning half of the path: Eq. 1 scoring, top-k percentile selection, compaction and
+// Aux Cache write (Sec. 3.2).  Scoring and compaction are HBM-bound; selection works in LDS.
+#include "common.h"
+
+namespace lz {
+
+// ------------------------------------------------------------------------------------------
+// Scoring, pass 1: z[h][j] = q_last[h] . k[j][h] / sqrt(hd) for every token j, plus each
+// workgroup's (max, sum exp) per head.  A wave streams whole token rows (all heads, 16-byte
+// chunks); K is read exactly once.  Lane l owns chunks l + 64*i of the row; one head is HD/8
+// consecutive chunks, so a head's dot product is a reduction over HD/8 adjacent lanes.
+// ------------------------------------------------------------------------------------------
+constexpr int SCORE_TOK = 16;        // tokens per workgroup (4 per wave)
+constexpr int SCORE_MAX_HEADS = 256;
+
+template <int HD, int NV>   // NV = ceil(H*HD/8 / 64): chunks per lane
+__global__ void __launch_bounds__(256)
+score_logits_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                    float* __restrict__ z, float2* __restrict__ part,
+                    const int32_t* __restrict__ cu, int n_single, int n_heads, int z_ld,
+                    float scale) {
+  constexpr int LPH = HD / 8;                   // lanes per head
+  __shared__ float zs[SCORE_TOK][SCORE_MAX_HEADS + 1];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int b = blockIdx.y;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const int t0 = blockIdx.x * SCORE_TOK;
+  if (t0 >= n) return;
+  const int d = n_heads * HD, vpr = d / 8;
+  const uint4* qrow = (const uint4*)(q + (size_t)(row0 + n - 1) * d);
+
+  float qf[NV][8];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int v = lane + 64 * i;
+    if (v < vpr) unpack8(qrow[v], qf[i]);
+    else
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[i][e] = 0.f;
+  }
+
+#pragma unroll
+  for (int pair = 0; pair < 2; ++pair) {
+    const int tl0 = wave * 4 + pair * 2;         // local token index of this pair
+    uint4 kv[2][NV];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      int t = t0 + tl0 + u;
+      if (t >= n) t = n - 1;                     // clamp: result discarded below
+      const uint4* krow = (const uint4*)(k + (size_t)(row0 + t) * d);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int v = lane + 64 * i;
+        kv[u][i] = (v < vpr) ? krow[v] : make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        float kf[8];
+        unpack8(kv[u][i], kf);
+        float p = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p += qf[i][e] * kf[e];
+#pragma unroll
+        for (int o = 1; o < LPH; o <<= 1) p += __shfl_xor(p, o, 64);
+        const int head = (lane + 64 * i) / LPH;
+        if ((lane % LPH) == 0 && head < n_heads) zs[tl0 + u][head] = p * scale;
+      }
+    }
+  }
+  __syncthreads();
+  const int nt = min(SCORE_TOK, n - t0);
+  // coalesced write of z[h][t0 .. t0+nt) and the workgroup's per-head partials
+  for (int idx = threadIdx.x; idx < n_heads * SCORE_TOK; idx += 256) {
+    const int h = idx / SCORE_TOK, t = idx % SCORE_TOK;
+    if (t < nt) z[(size_t)h * z_ld + row0 + t0 + t] = zs[t][h];
+  }
+  for (int h = threadIdx.x; h < n_heads; h += 256) {
+    float mx = -INFINITY;
+    for (int t = 0; t < nt; ++t) mx = fmaxf(mx, zs[t][h]);
+    float sum = 0.f;
+    for (int t = 0; t < nt; ++t) sum += __expf(zs[t][h] - mx);
+    part[((size_t)b * gridDim.x + blockIdx.x) * n_heads + h] = make_float2(mx, sum);
+  }
+}
+
+// Scoring, pass 2: combine the partials into each head's (max, normaliser), then
+// s[j] = (1/H) sum_h exp(z[h][j] - max_h) / Z_h, heads added in a fixed order.
+__global__ void __launch_bounds__(256)
+score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ part,
+                    float* __restrict__ s, const int32_t* __restrict__ cu, int n_single,
+                    int n_heads, int z_ld, int parts_per_seq) {
+  __shared__ float2 grp[256];
+  __shared__ float hmax[SCORE_MAX_HEADS], hinv[SCORE_MAX_HEADS];
+  const int b = blockIdx.y;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const int t0 = blockIdx.x * 256;
+  if (t0 >= n) return;
+  const int nparts = (n + SCORE_TOK - 1) / SCORE_TOK;
+  const int groups = max(1, 256 / n_heads);
+  const float2* p0 = part + (size_t)b * parts_per_seq * n_heads;
+  for (int hb = 0; hb < n_heads; hb += 256) {           // heads in slabs of up to 256
+    const int hcount = min(256, n_heads - hb);
+    const int g = threadIdx.x / hcount, hl = threadIdx.x % hcount;
+    float mx = -INFINITY, sum = 0.f;
+    if (g < groups) {
+      for (int i = g; i < nparts; i += groups) {
+        const float2 pr = p0[(size_t)i * n_heads + hb + hl];
+        const float nm = fmaxf(mx, pr.x);
+        sum = sum * __expf(mx - nm) + pr.y * __expf(pr.x - nm);
+        mx = nm;
+      }
+    }
+    grp[threadIdx.x] = make_float2(mx, sum);
+    __syncthreads();
+    if (threadIdx.x < hcount) {
+      float M = -INFINITY;
+      for (int gg = 0; gg < groups; ++gg) M = fmaxf(M, grp[gg * hcount + threadIdx.x].x);
+      float Z = 0.f;
+      for (int gg = 0; gg < groups; ++gg) {
+        const float2 pr = grp[gg * hcount + threadIdx.x];
+        if (pr.y > 0.f) Z += pr.y * __expf(pr.x - M);
+      }
+      hmax[hb + threadIdx.x] = M;
+      hinv[hb + threadIdx.x] = 1.0f / Z;
+    }
+    __syncthreads();
+  }
+  const int t = t0 + threadIdx.x;
+  if (t < n) {
+    float acc = 0.f;
+    for (int h = 0; h < n_heads; ++h)
+      acc += __expf(z[(size_t)h * z_ld + row0 + t] - hmax[h]) * hinv[h];
+    s[row0 + t] = acc / (float)n_heads;
+  }
+}
+
+size_t score_scratch_bytes(int total_rows, int batch, int n_heads) {
+  // z[H][total_rows] fp32, then partials [batch][ceil(total/16)+1][H] float2 (upper bound)
+  size_t zb = (size_t)n_heads * total_rows * sizeof(float);
+  zb = (zb + 255) & ~(size_t)255;
+  size_t parts = (size_t)batch * ((size_t)(total_rows + SCORE_TOK - 1) / SCORE_TOK + 1);
+  return zb + parts * n_heads * sizeof(float2) + 256;
+}
+
+hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, const int32_t* cu,
+                        int n_single, int batch, int total_rows, int max_rows, int n_heads,
+                        int head_dim, hipStream_t st) {
+  if (max_rows <= 0) return hipSuccess;
+  if (n_heads > SCORE_MAX_HEADS) return hipErrorInvalidValue;
+  float* z = (float*)scratch;
+  size_t zb = (size_t)n_heads * total_rows * sizeof(float);
+  zb = (zb + 255) & ~(size_t)255;
+  float2* part = (float2*)((char*)scratch + zb);
+  const int parts_per_seq = (max_rows + SCORE_TOK - 1) / SCORE_TOK;
+  const int vpr = n_heads * head_dim / 8, nv = (vpr + 63) / 64;
+  const float scale = 1.0f / sqrtf((float)head_dim);
+  dim3 grid(parts_per_seq, batch), block(256);
+#define LZ_SCORE(HD, NV)                                                                        \
+  hipLaunchKernelGGL((score_logits_kernel<HD, NV>), grid, block, 0, st, (const uint16_t*)q,      \
+                     (const uint16_t*)k, z, part, cu, n_single, n_heads, total_rows, scale)
+  if (head_dim == 128) {
+    if (nv <= 1) LZ_SCORE(128, 1);
+    else if (nv <= 2) LZ_SCORE(128, 2);
+    else if (nv <= 4) LZ_SCORE(128, 4);
+    else if (nv <= 8) LZ_SCORE(128, 8);
+    else if (nv <= 16) LZ_SCORE(128, 16);
+    else return hipErrorInvalidValue;
+  } else if (head_dim == 64) {
+    if (nv <= 1) LZ_SCORE(64, 1);
+    else if (nv <= 2) LZ_SCORE(64, 2);
+    else if (nv <= 4) LZ_SCORE(64, 4);
+    else if (nv <= 8) LZ_SCORE(64, 8);
+    else if (nv <= 16) LZ_SCORE(64, 16);
+    else return hipErrorInvalidValue;
+  } else {
+    return hipErrorInvalidValue;
+  }
+#undef LZ_SCORE
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(score_finish_kernel, dim3((max_rows + 255) / 256, batch), dim3(256), 0, st, z,
+                     part, s, cu, n_single, n_heads, total_rows, parts_per_seq);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Selection: keep the last token and the k-1 best of the others (higher score, then lower
+// index).  One 1024-thread workgroup per sequence.  Scores become order-preserving 32-bit
+// keys held in LDS; an MSB-first radix select (4 passes of 8 bits, LDS histogram, one wave
+// scanning the 256 bins) finds the threshold key and how many of its duplicates to take;
+// a final ordered pass emits kept and pruned row indices, ranks coming from wave ballots
+// and a per-wave prefix.
+// ------------------------------------------------------------------------------------------
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_LDS_KEYS = 15360;   // 60 KB of keys; longer sequences re-read global memory
+
+__device__ __forceinline__ uint32_t score_key(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// exclusive rank of this thread among threads with flag set, and the block total.
+// Must be called by all threads.  wsum: LDS [SEL_WAVES].
+__device__ __forceinline__ int block_rank(bool flag, int* wsum, int& total) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const unsigned long long bal = __ballot(flag);
+  const int below = __popcll(bal & ((1ull << lane) - 1ull));
+  if (lane == 0) wsum[wave] = __popcll(bal);
+  __syncthreads();
+  int pre = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < SEL_WAVES; ++w) {
+    const int c = wsum[w];
+    if (w < wave) pre += c;
+    tot += c;
+  }
+  __syncthreads();
+  total = tot;
+  return pre + below;
+}
+
+__global__ void __launch_bounds__(SEL_THREADS)
+select_kernel(const float* __restrict__ s, const int32_t* __restrict__ cu_prev,
+              const int32_t* __restrict__ cu_new, int m_single, int k_single,
+              int32_t* __restrict__ keep_idx, int32_t* __restrict__ prune_idx) {
+  __shared__ uint32_t keys[SEL_LDS_KEYS];
+  __shared__ int hist[256];
+  __shared__ int wsum[SEL_WAVES];
+  __shared__ int sel_bin, sel_need;
+  const int b = blockIdx.x;
+  int r0, m, k0, k;
+  seq_range(cu_prev, b, m_single, r0, m);
+  seq_range(cu_new, b, k_single, k0, k);
+  int32_t* keep_out = keep_idx + k0;
+  int32_t* prune_out = prune_idx + (r0 - k0);
+  const float* sv = s + r0;
+  const bool in_lds = m <= SEL_LDS_KEYS;
+  const int ncand = m - 1;                       // the last token is not a candidate
+
+  if (in_lds) {
+    for (int i = threadIdx.x; i < m; i += SEL_THREADS) keys[i] = score_key(sv[i]);
+    __syncthreads();
+  }
+#define key_at(i) (in_lds ? keys[(i)] : score_key(sv[(i)]))
+
+  uint32_t T;
+  int need_eq;
+  int need = k - 1;
+  if (need <= 0) {
+    T = 0xffffffffu; need_eq = 0;
+  } else if (need >= ncand) {
+    T = 0u; need_eq = m;
+  } else {
+    uint32_t prefix = 0u, mask = 0u;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      for (int i = threadIdx.x; i < 256; i += SEL_THREADS) hist[i] = 0;
+      __syncthreads();
+      for (int i = threadIdx.x; i < ncand; i += SEL_THREADS) {
+        const uint32_t key = key_at(i);
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+      }
+      __syncthreads();
+      if (threadIdx.x < 64) {
+        // lane L owns bins 255-4L .. 252-4L (descending); scan from the top bin down
+        const int lane = threadIdx.x;
+        const int top = 255 - 4 * lane;
+        const int c0 = hist[top], c1 = hist[top - 1], c2 = hist[top - 2], c3 = hist[top - 3];
+        const int local = c0 + c1 + c2 + c3;
+        int incl = local;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int t = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += t;
+        }
+        const int excl = incl - local;
+        if (excl < need && need <= incl) {
+          int acc = excl, bin = top, cnt = c0;
+          if (acc + cnt < need) { acc += cnt; bin = top - 1; cnt = c1;
+            if (acc + cnt < need) { acc += cnt; bin = top - 2; cnt = c2;
+              if (acc + cnt < need) { acc += cnt; bin = top - 3; } } }
+          sel_bin = bin;
+          sel_need = need - acc;              // rank inside the chosen bin, >= 1
+        }
+      }
+      __syncthreads();
+      prefix |= ((uint32_t)sel_bin) << shift;
+      mask |= 255u << shift;
+      need = sel_need;
+      __syncthreads();
+    }
+    T = prefix;
+    need_eq = need;
+  }
+
+  // ordered emission
+  int run_eq = 0, run_keep = 0;
+  for (int base = 0; base < m; base += SEL_THREADS) {
+    const int i = base + threadIdx.x;
+    const bool valid = i < m;
+    const bool last = valid && (i == m - 1);
+    const uint32_t key = (valid && !last) ? key_at(i) : 0u;
+    const bool gt = valid && !last && key > T;
+    const bool eq = valid && !last && key == T;
+    int tot_eq, tot_keep;
+    const int eq_rank = run_eq + block_rank(eq, wsum, tot_eq);
+    const bool keep = last || gt || (eq && eq_rank < need_eq);
+    const int keep_rank = run_keep + block_rank(keep, wsum, tot_keep);
+    if (valid) {
+      if (keep) keep_out[keep_rank] = r0 + i;
+      else prune_out[i - keep_rank] = r0 + i;
+    }
+    run_eq += tot_eq;
+    run_keep += tot_keep;
+  }
+#undef key_at
+}
+
+hipError_t launch_select(const float* s, const int32_t* cu_prev, const int32_t* cu_new,
+                         int m_single, int k_single, int batch, int32_t* keep_idx,
+                         int32_t* prune_idx, hipStream_t st) {
+  hipLaunchKernelGGL(select_kernel, dim3(batch), dim3(SEL_THREADS), 0, st, s, cu_prev, cu_new,
+                     m_single, k_single, keep_idx, prune_idx);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Compaction + Aux Cache write: every input row is read once and written once, either to
+// the compacted hidden states or to the Aux Cache of this pruning layer.  One wave per row.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
+              const int32_t* __restrict__ keep_idx, int n_keep,
+              const int32_t* __restrict__ prune_idx, int n_prune, uint4* __restrict__ h_out,
+              int32_t* __restrict__ pos_out, uint4* __restrict__ aux_h,
+              int32_t* __restrict__ aux_pos, int vpr) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= n_keep + n_prune) return;
+  int src_row;
+  uint4* dst;
+  if (r < n_keep) {
+    src_row = keep_idx[r];
+    dst = h_out + (size_t)r * vpr;
+    if (lane == 0) pos_out[r] = pos[src_row];
+  } else {
+    const int ra = r - n_keep;
+    src_row = prune_idx[ra];
+    dst = aux_h + (size_t)ra * vpr;
+    if (lane == 0) aux_pos[ra] = pos[src_row];
+  }
+  const uint4* src = h + (size_t)src_row * vpr;
+  int v = lane;
+  for (; v + 64 * 7 < vpr; v += 64 * 8) {
+    uint4 t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = src[v + 64 * i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dst[v + 64 * i] = t[i];
+  }
+  for (; v < vpr; v += 64) dst[v] = src[v];
+}
+
+hipError_t launch_gather(const void* h, const int32_t* pos, const int32_t* keep_idx, int n_keep,
+                         const int32_t* prune_idx, int n_prune, void* h_out, int32_t* pos_out,
+                         void* aux_h, int32_t* aux_pos, int d, hipStream_t st) {
+  const int rows = n_keep + n_prune;
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, (const uint4*)h, pos,
+                     keep_idx, n_keep, prune_idx, n_prune, (uint4*)h_out, pos_out, (uint4*)aux_h,
+                     aux_pos, d / 8);
+  return hipGetLastError();
+}
+
+}  // namespace lz

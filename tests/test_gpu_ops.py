@@ -1,0 +1,303 @@
+"""Kernel-level parity: each step of the path, through the C ABI, against the CPU checker on
+the same seeded inputs.  Sizes span several tiles plus a ragged tail; integer and index
+results must be bit-exact, floating point within the tolerance stated at each test."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lazyllm_oracle as O
+from paper_2407_14057_amd import binding as B
+from paper_2407_14057_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _bf16_dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).to(DEV)
+
+
+def _f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def _rand_bf16(rng, shape, std=1.0):
+    return _bf16_dev(rng.normal(0.0, std, size=shape))
+
+
+# bf16 output: half an ulp of the result (2^-9 relative) plus fp32 accumulation noise
+def _assert_bf16_close(got: np.ndarray, ref: np.ndarray, scale: float, what: str):
+    err = np.abs(got - ref)
+    tol = 2.0 ** -8 * np.abs(ref) + 2e-3 * scale
+    bad = err > tol
+    assert not bad.any(), "%s: %d of %d off, worst %.3g (ref %.3g)" % (
+        what, int(bad.sum()), bad.size, float(err.max()), float(np.abs(ref).max()))
+
+
+# ------------------------------------------------------------------------------------ GEMM
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (37, 256, 128), (300, 768, 256), (513, 1536, 704),
+                                   (130, 4096, 4096), (2100, 768, 256), (2100, 6144, 512)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm(M, N, K, epi):
+    rng = np.random.default_rng(M * 7 + N + K + epi)
+    A = _rand_bf16(rng, (M, K))
+    W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    a, w = _f64(A), _f64(W)
+    acc = a @ w.T
+    if epi == B.EPI_SWIGLU:
+        # library layout: rows 64j..64j+31 gate, 64j+32..64j+63 up
+        blocks = acc.reshape(M, N // 64, 2, 32)
+        ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+        Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, epi)
+    elif epi == B.EPI_RESIDUAL:
+        R = _rand_bf16(rng, (M, N))
+        ref = _f64(R) + acc
+        Cout = R.clone()
+        B.lazyllm_op_gemm(A, W, Cout, Cout, M, N, K, K, K, N, epi)      # in place on the residual
+    else:
+        ref = acc
+        Cout = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N, epi)
+    torch.cuda.synchronize()
+    _assert_bf16_close(_f64(Cout), ref, 1.0, "gemm")
+
+
+def test_gemm_strided_and_edge_rows_untouched():
+    rng = np.random.default_rng(5)
+    M, N, K = 70, 256, 128
+    lda, ldw, ldc = K + 64, K + 8, N + 128
+    A = _rand_bf16(rng, (M, lda)); W = _rand_bf16(rng, (N, ldw), 0.1)
+    Cout = torch.full((M + 3, ldc), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, lda, ldw, ldc, B.EPI_STORE)
+    torch.cuda.synchronize()
+    ref = _f64(A)[:, :K] @ _f64(W)[:, :K].T
+    got = _f64(Cout)
+    _assert_bf16_close(got[:M, :N], ref, 1.0, "gemm strided")
+    assert np.all(got[M:, :] == 7.0) and np.all(got[:, N:] == 7.0)     # nothing written outside
+
+
+def test_gemm_full_size_sampled():
+    """The headline shape's first stage (M=3376, QKV projection), checked on sampled outputs."""
+    rng = np.random.default_rng(6)
+    M, N, K = 3376, 12288, 4096
+    A = torch.randn(M, K, device=DEV, dtype=torch.float32, generator=torch.Generator(DEV).manual_seed(1)).to(torch.bfloat16)
+    W = (torch.randn(N, K, device=DEV, dtype=torch.float32, generator=torch.Generator(DEV).manual_seed(2)) * 0.02).to(torch.bfloat16)
+    Cout = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N, B.EPI_STORE)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 255, 256, M - 1, M - 2], rng.integers(0, M, 40)]))
+    cols = np.unique(np.concatenate([[0, 127, 128, 255, 256, N - 1], rng.integers(0, N, 200)]))
+    a = _f64(A[torch.from_numpy(rows).to(DEV)])
+    w = _f64(W[torch.from_numpy(cols).to(DEV)])
+    ref = a @ w.T
+    got = _f64(Cout[torch.from_numpy(rows).to(DEV)][:, torch.from_numpy(cols).to(DEV)])
+    _assert_bf16_close(got, ref, 1.3, "gemm 7B")
+
+
+# ------------------------------------------------------------------------------------ RMSNorm
+
+@pytest.mark.parametrize("rows,d", [(1, 256), (5, 256), (131, 4096), (33, 1024)])
+def test_rmsnorm(rows, d):
+    rng = np.random.default_rng(rows + d)
+    h = _rand_bf16(rng, (rows, d), 2.0)
+    g = _bf16_dev(1.0 + 0.3 * rng.uniform(-1, 1, d))
+    x = torch.empty_like(h)
+    B.lazyllm_op_rmsnorm(h, g, x, rows, d, 1e-5)
+    torch.cuda.synchronize()
+    ref = O.rmsnorm(_f64(h), _f64(g), 1e-5)
+    _assert_bf16_close(_f64(x), ref, 1e-3, "rmsnorm")
+
+
+# ------------------------------------------------------------------------------------ RoPE split
+
+@pytest.mark.parametrize("rows,H,hd", [(1, 4, 64), (130, 4, 64), (200, 2, 128), (64, 32, 128)])
+def test_rope_split(rows, H, hd):
+    rng = np.random.default_rng(rows + H + hd)
+    d = H * hd
+    qkv = _rand_bf16(rng, (rows, 3 * d))
+    pos_np = np.sort(rng.choice(5000, size=rows, replace=False)).astype(np.int32)
+    pos = torch.from_numpy(pos_np).to(DEV)
+    max_pos = int(pos_np.max())
+    table = torch.empty((max_pos + 1) * (hd // 2) * 2, dtype=torch.float32, device=DEV)
+    vt_ld = (rows + 63) // 64 * 64 + 64
+    q = torch.empty(rows, d, dtype=torch.bfloat16, device=DEV)
+    k = torch.empty_like(q); v = torch.empty_like(q)
+    vt = torch.full((d, vt_ld), 5.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_rope_split(qkv, pos, max_pos, table, q, k, v, vt, vt_ld, rows, H, hd, 10000.0)
+    torch.cuda.synchronize()
+    x = _f64(qkv)
+    q_ref = O.rope(x[:, :d].reshape(rows, H, hd), pos_np, 10000.0).reshape(rows, d)
+    k_ref = O.rope(x[:, d:2 * d].reshape(rows, H, hd), pos_np, 10000.0).reshape(rows, d)
+    _assert_bf16_close(_f64(q), q_ref, 1e-3, "q")
+    _assert_bf16_close(_f64(k), k_ref, 1e-3, "k")
+    assert torch.equal(v, qkv[:, 2 * d:])                                  # v is a plain copy
+    vtn = _f64(vt)
+    assert np.array_equal(vtn[:, :rows], x[:, 2 * d:].T)                   # transposed copy
+    pad = (rows + 63) // 64 * 64
+    assert np.all(vtn[:, rows:pad] == 0.0)                                 # tail of the last tile zeroed
+
+
+# ------------------------------------------------------------------------------------ attention
+
+def _attention_case(rows, H, hd, seed):
+    rng = np.random.default_rng(seed)
+    d = H * hd
+    q = _rand_bf16(rng, (rows, d)); k = _rand_bf16(rng, (rows, d)); v = _rand_bf16(rng, (rows, d))
+    pad = (rows + 63) // 64 * 64
+    vt = torch.zeros(d, pad, dtype=torch.bfloat16, device=DEV)
+    vt[:, :rows] = v.t()
+    o = torch.full((rows, d), 9.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_attention(q, k, vt.contiguous(), pad, o, rows, H, hd)
+    torch.cuda.synchronize()
+    sh = (rows, H, hd)
+    o_ref, _ = O.causal_attention(_f64(q).reshape(sh), _f64(k).reshape(sh), _f64(v).reshape(sh))
+    return _f64(o), o_ref.reshape(rows, d)
+
+
+@pytest.mark.parametrize("rows", [1, 2, 31, 63, 64, 65, 127, 128, 129, 200, 515])
+@pytest.mark.parametrize("H,hd", [(4, 64), (2, 128)])
+def test_attention(rows, H, hd):
+    got, ref = _attention_case(rows, H, hd, rows * 3 + hd)
+    # probabilities are rounded to bf16 before the second product: 2^-9 relative per term
+    err = np.abs(got - ref)
+    assert err.max() < 2e-2, "worst %.3g" % err.max()
+    assert np.sqrt((err ** 2).mean()) < 3e-3
+
+
+def test_attention_sharp_rows():
+    """Large logits: the running-max rescale must not lose the dominant key."""
+    rows, H, hd = 300, 2, 128
+    rng = np.random.default_rng(77)
+    d = H * hd
+    q = _rand_bf16(rng, (rows, d), 4.0); k = _rand_bf16(rng, (rows, d), 4.0); v = _rand_bf16(rng, (rows, d))
+    pad = (rows + 63) // 64 * 64
+    vt = torch.zeros(d, pad, dtype=torch.bfloat16, device=DEV); vt[:, :rows] = v.t()
+    o = torch.empty(rows, d, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_attention(q, k, vt.contiguous(), pad, o, rows, H, hd)
+    torch.cuda.synchronize()
+    sh = (rows, H, hd)
+    o_ref, _ = O.causal_attention(_f64(q).reshape(sh), _f64(k).reshape(sh), _f64(v).reshape(sh))
+    assert np.abs(_f64(o) - o_ref.reshape(rows, d)).max() < 3e-2
+
+
+# ------------------------------------------------------------------------------------ Eq. 1 scoring
+
+@pytest.mark.parametrize("rows", [1, 2, 15, 16, 17, 255, 256, 257, 1000, 3376])
+@pytest.mark.parametrize("H,hd", [(4, 64), (32, 128)])
+def test_score(rows, H, hd):
+    rng = np.random.default_rng(rows + H)
+    d = H * hd
+    k = _rand_bf16(rng, (rows, d))
+    q_last = _rand_bf16(rng, (d,), 1.5)
+    s = torch.full((rows,), -1.0, dtype=torch.float32, device=DEV)
+    scratch = torch.empty(B.lazyllm_op_score_scratch_bytes(rows, H), dtype=torch.uint8, device=DEV)
+    B.lazyllm_op_score(q_last, k, s, scratch, rows, H, hd)
+    torch.cuda.synchronize()
+    ref = O.last_row_scores(_f64(q_last).reshape(H, hd), _f64(k).reshape(rows, H, hd))
+    got = s.cpu().numpy().astype(np.float64)
+    # fp32 dot products of exact bf16 products, fast exp: a few 1e-6 relative
+    assert np.allclose(got, ref, rtol=2e-5, atol=1e-9), np.abs(got / ref - 1).max()
+    assert abs(got.sum() - 1.0) < 1e-5
+
+
+def test_score_is_deterministic():
+    rng = np.random.default_rng(9)
+    rows, H, hd = 3376, 32, 128
+    k = _rand_bf16(rng, (rows, H * hd)); q_last = _rand_bf16(rng, (H * hd,))
+    scratch = torch.empty(B.lazyllm_op_score_scratch_bytes(rows, H), dtype=torch.uint8, device=DEV)
+    outs = []
+    for _ in range(3):
+        s = torch.empty(rows, dtype=torch.float32, device=DEV)
+        B.lazyllm_op_score(q_last, k, s, scratch, rows, H, hd)
+        torch.cuda.synchronize()
+        outs.append(s.cpu().numpy().copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+# ------------------------------------------------------------------------------------ selection
+
+def _select(scores: np.ndarray, k: int):
+    m = scores.shape[0]
+    s = torch.from_numpy(scores).to(DEV)
+    keep = torch.full((k,), -1, dtype=torch.int32, device=DEV)
+    prune = torch.full((max(m - k, 1),), -1, dtype=torch.int32, device=DEV)
+    B.lazyllm_op_select(s, m, k, keep, prune)
+    torch.cuda.synchronize()
+    return keep.cpu().numpy(), prune.cpu().numpy()[: m - k]
+
+
+@pytest.mark.parametrize("kind", synth.SCORE_KINDS)
+@pytest.mark.parametrize("m", [1, 2, 63, 64, 65, 1024, 1025, 3376, 8192])
+def test_select_bit_exact(kind, m):
+    s = synth.make_scores(kind, m, 1000 + m)
+    ks = sorted(k for k in {1, 2, max(1, m // 2), max(1, (m * 7 + 9) // 10), max(1, m - 1), m} if k <= m)
+    for k in ks:
+        keep, prune = _select(s, k)
+        rk, rp = O.select_tokens(s, k)
+        assert np.array_equal(keep, rk), (kind, m, k)
+        assert np.array_equal(prune, rp), (kind, m, k)
+
+
+def test_select_long_sequence_uses_global_memory_path():
+    m = 40000                                      # beyond what the kernel keeps in LDS
+    for kind in ("softmax_like", "few_values", "lognormal3"):
+        s = synth.make_scores(kind, m, 4242)
+        for k in (1, 12000, 39999):
+            keep, prune = _select(s, k)
+            rk, rp = O.select_tokens(s, k)
+            assert np.array_equal(keep, rk) and np.array_equal(prune, rp)
+
+
+def test_select_last_token_forced_and_negative_scores():
+    s = np.linspace(1.0, 0.0, 50, dtype=np.float32)     # the last token has the lowest score
+    keep, _ = _select(s, 5)
+    assert list(keep) == [0, 1, 2, 3, 49]
+    s2 = np.array([-1.0, 3.0, -0.5, 2.0, -7.0], np.float32)
+    keep, prune = _select(s2, 3)
+    assert list(keep) == [1, 3, 4] and list(prune) == [0, 2]
+
+
+# ------------------------------------------------------------------------------------ gather
+
+@pytest.mark.parametrize("m,k,d", [(1, 1, 256), (50, 20, 256), (515, 360, 4096), (300, 300, 1024)])
+def test_gather_bit_exact(m, k, d):
+    rng = np.random.default_rng(m + k)
+    h = _rand_bf16(rng, (m, d))
+    pos_np = np.sort(rng.choice(10000, size=m, replace=False)).astype(np.int32)
+    perm = rng.permutation(m)
+    keep_np = np.sort(perm[:k]).astype(np.int32); prune_np = np.sort(perm[k:]).astype(np.int32)
+    pos = torch.from_numpy(pos_np).to(DEV)
+    keep = torch.from_numpy(keep_np).to(DEV)
+    prune = torch.from_numpy(prune_np).to(DEV) if m > k else torch.zeros(1, dtype=torch.int32, device=DEV)
+    h_out = torch.empty(k, d, dtype=torch.bfloat16, device=DEV)
+    pos_out = torch.empty(k, dtype=torch.int32, device=DEV)
+    aux_h = torch.empty(max(m - k, 1), d, dtype=torch.bfloat16, device=DEV)
+    aux_pos = torch.empty(max(m - k, 1), dtype=torch.int32, device=DEV)
+    B.lazyllm_op_gather(h, pos, keep, k, prune, m - k, h_out, pos_out, aux_h, aux_pos, d)
+    torch.cuda.synchronize()
+    hb = h.view(torch.int16).cpu().numpy()
+    assert np.array_equal(h_out.view(torch.int16).cpu().numpy(), hb[keep_np])
+    assert np.array_equal(pos_out.cpu().numpy(), pos_np[keep_np])
+    if m > k:
+        assert np.array_equal(aux_h.view(torch.int16).cpu().numpy()[: m - k], hb[prune_np])
+        assert np.array_equal(aux_pos.cpu().numpy()[: m - k], pos_np[prune_np])
+
+
+# ------------------------------------------------------------------------------------ LM head
+
+@pytest.mark.parametrize("d,V", [(256, 1024), (4096, 32000), (256, 1001)])
+def test_lm_head(d, V):
+    rng = np.random.default_rng(d + V)
+    h = _rand_bf16(rng, (d,), 1.5)
+    g = _bf16_dev(1.0 + 0.2 * rng.uniform(-1, 1, d))
+    w = _rand_bf16(rng, (V, d), 0.02)
+    xf = torch.empty(d, dtype=torch.float32, device=DEV)
+    logits = torch.empty(V, dtype=torch.float32, device=DEV)
+    B.lazyllm_op_lm_head(h, g, w, xf, logits, d, V, 1e-5)
+    torch.cuda.synchronize()
+    ref = _f64(w) @ O.rmsnorm(_f64(h), _f64(g), 1e-5)
+    assert np.allclose(logits.cpu().numpy(), ref, rtol=1e-4, atol=1e-4)

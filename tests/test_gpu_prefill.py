@@ -1,0 +1,238 @@
+"""End-to-end parity of the pruned prefill, through the C ABI, against the CPU checker.
+
+Kept sets: at every pruning layer the checker (run with bf16 activation storage, fed the
+GPU's earlier selections) computes the previous layer's scores; every token whose score is
+further than 1e-3 (relative) from the selection threshold must be kept / dropped exactly as
+the checker says.  Tokens inside that band may differ; from there on the checker is fed
+the GPU's selection.  Logits: max |gpu - checker| <= 2e-2 * (max - min of the checker's
+logits), against the pure fp64 checker."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lazyllm_oracle as O
+from paper_2407_14057_amd import binding as B
+from paper_2407_14057_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _to_dev(w):
+    return {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in w.items()}
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    w = synth.make_weights(synth.TINY, 1001, "cpu", gain_jitter=0.0)
+    model = B.Model(synth.TINY.as_dict(), _to_dev(w), DEV)
+    yield synth.TINY, synth.weights_to_host_bits(w), model
+    model.close()
+
+
+@pytest.fixture(scope="module")
+def tiny_gains():
+    w = synth.make_weights(synth.TINY, 1011, "cpu", gain_jitter=0.3)
+    model = B.Model(synth.TINY.as_dict(), _to_dev(w), DEV)
+    yield synth.TINY, synth.weights_to_host_bits(w), model
+    model.close()
+
+
+def _run(model, ids, schedule, cu=None, scale=None, flags=0):
+    t = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(DEV)
+    sc = None if scale is None else torch.from_numpy(scale).to(DEV)
+    out = model.prefill(t, schedule, cu_seqlens=cu, embed_scale=sc, flags=flags)
+    torch.cuda.synchronize()
+    return out
+
+
+def _np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64) if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+
+def check_against_checker(shape, wb, ids, schedule, out, scale=None, seq=None, verbose=""):
+    """Compares one sequence of a GPU result with the checker; returns a small report."""
+    sd = shape.as_dict()
+    L = shape.n_layers
+    if seq is None:
+        lo = [0] * L
+        hi = list(out.n_tokens)
+        alo = [0] * L
+        ahi = list(out.n_aux)
+    else:
+        lo = [int(out.cu_kept(l)[seq]) for l in range(L)]
+        hi = [int(out.cu_kept(l)[seq + 1]) for l in range(L)]
+        alo = [int(out.cu_aux(l)[seq]) if out.n_aux[l] or out.res.cu_aux[l] else 0 for l in range(L)]
+        ahi = [int(out.cu_aux(l)[seq + 1]) if out.n_aux[l] or out.res.cu_aux[l] else 0 for l in range(L)]
+    kept = [out.kept_pos(l)[lo[l]:hi[l]].cpu().numpy().astype(np.int64) for l in range(L)]
+    counts = O.keep_counts(len(ids), L, schedule)
+    assert [len(k) for k in kept] == counts
+    report = {"undecided": {}, "symdiff": {}}
+    forced = {}
+    prune_layers = [l for l, p in schedule if p < 1000]
+    for p in prune_layers:
+        ref = O.prefill(sd, wb, ids, schedule, bf16_storage=True, forced_keep=forced,
+                        embed_scale=scale, n_layers=p)
+        s_prev = ref.scores[p - 1]
+        tau, decided = O.decision_margin(s_prev, counts[p], rel=1e-3)
+        own_idx, _ = O.select_tokens(s_prev, counts[p])
+        prev_pos = ref.kept_pos[p - 1]
+        want = np.zeros(len(prev_pos), dtype=bool); want[own_idx] = True
+        got = np.isin(prev_pos, kept[p])
+        assert np.array_equal(prev_pos, kept[p - 1])
+        assert got.sum() == counts[p] and np.all(np.isin(kept[p], prev_pos))      # nested
+        mism = decided & (want != got)
+        assert not mism.any(), "layer %d: %d decided tokens differ" % (p, int(mism.sum()))
+        report["undecided"][p] = int((~decided).sum())
+        report["symdiff"][p] = int((want != got).sum())
+        forced[p] = kept[p]
+    ref64 = O.prefill(sd, wb, ids, schedule, forced_keep=forced, embed_scale=scale, keep_hidden=True)
+    ref16 = O.prefill(sd, wb, ids, schedule, bf16_storage=True, forced_keep=forced, embed_scale=scale,
+                      keep_hidden=True)
+    # structure
+    prev = np.arange(len(ids))
+    for l in range(L):
+        assert np.array_equal(kept[l], ref64.kept_pos[l])
+        assert np.all(np.diff(kept[l]) > 0) and kept[l][-1] == len(ids) - 1
+        if l in forced:
+            aux_pos = out.aux_pos(l)[alo[l]:ahi[l]].cpu().numpy()
+            assert np.array_equal(aux_pos, ref64.aux_pos[l])
+            assert np.array_equal(np.sort(np.concatenate([kept[l], aux_pos])), prev)
+            aux_h = _np(out.aux_h(l)[alo[l]:ahi[l]])
+            assert aux_h.shape == ref16.aux_h[l].shape
+            if aux_h.size:
+                assert np.abs(aux_h - ref16.aux_h[l]).max() <= 0.05 * max(1.0, np.abs(ref16.aux_h[l]).max())
+        prev = kept[l]
+    # values
+    worst = {"k": 0.0, "v": 0.0, "s16": 0.0, "s64": 0.0}
+    for l in range(L):
+        for name, got_t, r in (("k", out.k(l), ref16.k[l]), ("v", out.v(l), ref16.v[l])):
+            g = _np(got_t[lo[l]:hi[l]])
+            e = np.abs(g - r).max() / max(np.abs(r).max(), 1e-9)
+            worst[name] = max(worst[name], e)
+        if out.res.scores[l]:
+            s = out.scores(l)[lo[l]:hi[l]].cpu().numpy().astype(np.float64)
+            assert abs(s.sum() - 1.0) < 1e-4
+            worst["s16"] = max(worst["s16"], float(np.abs(s / ref16.scores[l] - 1).max()))
+            worst["s64"] = max(worst["s64"], float(np.abs(s / ref64.scores[l] - 1).max()))
+    b = 0 if seq is None else seq
+    logits = out.logits[b].cpu().numpy().astype(np.float64)
+    rng_ = ref64.logits.max() - ref64.logits.min()
+    report["logit_err"] = float(np.abs(logits - ref64.logits).max() / rng_)
+    report["logit_err16"] = float(np.abs(logits - ref16.logits).max() / rng_)
+    report.update(worst)
+    print(verbose, report)
+    assert worst["k"] < 3e-2 and worst["v"] < 3e-2, worst
+    assert worst["s64"] < 5e-2 and worst["s16"] < 2e-2, worst
+    assert report["logit_err"] <= 2e-2, report
+    return report
+
+
+def test_tiny512_matches_checker(tiny):
+    shape, wb, model = tiny
+    wl = synth.WORKLOADS["tiny512"]
+    inp = synth.make_workload_inputs(wl)
+    out = _run(model, inp["token_ids"], wl.schedule)
+    assert out.status == 0
+    assert out.n_tokens == [512, 512, 359, 180]
+    assert out.n_aux == [0, 0, 153, 179]
+    check_against_checker(shape, wb, inp["token_ids"], list(wl.schedule), out, verbose="tiny512")
+
+
+@pytest.mark.parametrize("n,sched", [(1, []), (2, [(1, 500)]), (65, [(1, 900), (2, 500), (3, 100)]),
+                                     (300, [(3, 1)]), (777, [(1, 300)]), (1030, [(2, 1000), (3, 250)])])
+def test_tiny_shapes_and_schedules(tiny_gains, n, sched):
+    shape, wb, model = tiny_gains
+    ids = synth.make_prompt(n, shape.vocab, 300 + n)
+    out = _run(model, ids, sched)
+    assert out.status == 0
+    check_against_checker(shape, wb, ids, sched, out, verbose="n=%d %s" % (n, sched))
+
+
+def test_keep_everything_equals_dense_bit_for_bit(tiny):
+    shape, wb, model = tiny
+    ids = synth.make_prompt(400, shape.vocab, 41)
+    a = _run(model, ids, [])
+    la = a.logits.clone(); ka = [a.k(l).clone() for l in range(4)]
+    b = _run(model, ids, [(1, 1000), (3, 1000)])
+    assert torch.equal(la, b.logits)
+    assert all(torch.equal(ka[l], b.k(l)) for l in range(4))
+    assert b.n_aux == [0, 0, 0, 0]
+
+
+def test_runs_are_bit_identical(tiny):
+    shape, wb, model = tiny
+    wl = synth.WORKLOADS["tiny512"]
+    ids = synth.make_workload_inputs(wl)["token_ids"]
+    snaps = []
+    for _ in range(3):
+        out = _run(model, ids, wl.schedule)
+        snaps.append((out.logits.clone(), out.kept_pos(3).clone(), out.scores(2).clone(), out.aux_h(3).clone()))
+    for s in snaps[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(snaps[0], s))
+
+
+def test_score_only_used_flag_gives_same_result(tiny):
+    shape, wb, model = tiny
+    wl = synth.WORKLOADS["tiny512"]
+    ids = synth.make_workload_inputs(wl)["token_ids"]
+    a = _run(model, ids, wl.schedule)
+    la, ka = a.logits.clone(), a.kept_pos(3).clone()
+    b = _run(model, ids, wl.schedule, flags=B.LAZYLLM_SCORE_ONLY_USED)
+    assert torch.equal(la, b.logits) and torch.equal(ka, b.kept_pos(3))
+    assert b.scores(0) is None and b.scores(3) is None and b.scores(1) is not None and b.scores(2) is not None
+
+
+def test_batch_of_ragged_prompts(tiny_gains):
+    shape, wb, model = tiny_gains
+    lens = [70, 513, 1, 260]
+    sched = [(1, 800), (3, 400)]
+    ids = np.concatenate([synth.make_prompt(n, shape.vocab, 500 + i) for i, n in enumerate(lens)])
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    out = _run(model, ids, sched, cu=list(cu))
+    assert out.status == 0
+    for b, n in enumerate(lens):
+        check_against_checker(shape, wb, ids[cu[b]:cu[b + 1]], sched, out, seq=b, verbose="batch seq %d" % b)
+    # the packed batch gives the same bits as each prompt on its own
+    snap = [(out.logits[b].clone(), [out.kept_pos(l)[int(out.cu_kept(l)[b]):int(out.cu_kept(l)[b + 1])].clone()
+                                     for l in range(4)]) for b in range(len(lens))]
+    for b, n in enumerate(lens):
+        single = _run(model, ids[cu[b]:cu[b + 1]], sched)
+        assert torch.equal(single.logits[0], snap[b][0])
+        assert all(torch.equal(single.kept_pos(l), snap[b][1][l]) for l in range(4))
+
+
+def test_needle_scale(tiny):
+    shape, wb, model = tiny
+    n = 384
+    ids = synth.make_prompt(n, shape.vocab, 61)
+    scale = synth.make_needle_scale(n, 16, 62)
+    out = _run(model, ids, [(1, 500), (3, 500)], scale=scale)
+    check_against_checker(shape, wb, ids, [(1, 500), (3, 500)], out, scale=scale, verbose="needles")
+
+
+def test_bad_token_id_sets_status_and_is_clamped(tiny):
+    shape, wb, model = tiny
+    ids = synth.make_prompt(100, shape.vocab, 71)
+    ids[17] = shape.vocab + 5
+    out = _run(model, ids, [])
+    assert out.status & B.LAZYLLM_ST_BAD_TOKEN
+    ids[17] = shape.vocab - 1
+    out2_logits = out.logits.clone()
+    out2 = _run(model, ids, [])
+    assert out2.status == 0 and torch.equal(out2.logits, out2_logits)
+
+
+def test_too_small_buffers_are_refused(tiny):
+    shape, wb, model = tiny
+    ids = torch.zeros(256, dtype=torch.int32, device=DEV)
+    ws, ob = model.buffers([256], [])
+    with pytest.raises(B.LazyLLMError) as e:
+        B.lazyllm_prefill(model.handle, ids, None, 256, [], 0, ws[:4096], ob)
+    assert e.value.status == B.LAZYLLM_ENOSPC
+    with pytest.raises(B.LazyLLMError) as e:
+        B.lazyllm_prefill(model.handle, ids, None, 256, [], 0, ws, ob[:4096])
+    assert e.value.status == B.LAZYLLM_ENOSPC
+    with pytest.raises(B.LazyLLMError) as e:
+        B.lazyllm_prefill(model.handle, ids, None, 256, [(0, 500)], 0, ws, ob)
+    assert e.value.status == B.LAZYLLM_EINVAL

@@ -1,0 +1,102 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares,
+and rejects bad arguments before any HIP call."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import lazyllm_oracle as O
+from paper_2407_14057_amd import binding as B
+from paper_2407_14057_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lazyllm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lazyllm_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared_symbols()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(B._SIGNATURES), "binding and header disagree"
+    assert lib.lazyllm_abi_version() == 1
+    assert lib.lazyllm_strerror(-1) == b"invalid argument"
+    assert lib.lazyllm_strerror(-2) == b"workspace or output buffer too small"
+
+
+def test_keep_counts_match_checker():
+    cases = [(512, 4, [(2, 700), (3, 500)]), (3376, 32, [(8, 700), (16, 500), (24, 300)]),
+             (8192, 32, [(8, 600), (16, 400), (24, 200)]), (3376, 32, [(4, 500), (12, 500), (20, 500)]),
+             (10, 3, [(1, 600)]), (1, 5, [(1, 1), (4, 1)]), (7, 4, [(1, 1000), (2, 1)])]
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        L = int(rng.integers(2, 40))
+        layers = sorted(rng.choice(np.arange(1, L), size=min(L - 1, int(rng.integers(1, 5))), replace=False))
+        cases.append((int(rng.integers(1, 100000)), L, [(int(l), int(rng.integers(1, 1001))) for l in layers]))
+    for n, L, sched in cases:
+        assert B.lazyllm_keep_counts(n, L, sched) == O.keep_counts(n, L, sched)
+
+
+def test_bad_schedules_are_rejected():
+    bad = [[(0, 500)],            # layer 0 has no prior scores
+           [(4, 500)],            # layer out of range for L = 4
+           [(2, 500), (1, 500)],  # unsorted
+           [(2, 500), (2, 400)],  # duplicate
+           [(1, 0)], [(1, 1001)], [(1, -5)]]
+    for sched in bad:
+        with pytest.raises(B.LazyLLMError) as e:
+            B.lazyllm_keep_counts(100, 4, sched)
+        assert e.value.status == B.LAZYLLM_EINVAL
+        assert B.lazyllm_output_bytes(B.make_config(synth.TINY.as_dict()), [100], sched) == 0
+    with pytest.raises(B.LazyLLMError):
+        B.lazyllm_keep_counts(0, 4, [])
+
+
+def test_sizes_are_positive_and_monotone():
+    cfg = B.make_config(synth.TINY.as_dict())
+    w1 = B.lazyllm_workspace_bytes(cfg, 512, 1, 512)
+    w2 = B.lazyllm_workspace_bytes(cfg, 1024, 2, 512)
+    assert 0 < w1 < w2
+    o_dense = B.lazyllm_output_bytes(cfg, [512], [])
+    o_pruned = B.lazyllm_output_bytes(cfg, [512], [(2, 700), (3, 500)])
+    assert o_dense > 0 and o_pruned > 0
+    # K/V of layer l hold exactly the tokens that ran it
+    kv = lambda counts: sum(2 * n * cfg.d_model * 2 for n in counts)
+    assert o_dense >= kv([512] * 4) and o_pruned >= kv([512, 512, 359, 180])
+    assert o_pruned < o_dense + 512 * cfg.d_model * 2 + 65536
+    # unsupported shapes
+    bad = dict(synth.TINY.as_dict())
+    bad["head_dim"] = 96
+    assert B.lazyllm_workspace_bytes(B.make_config(bad), 512, 1, 512) == 0
+    bad = dict(synth.TINY.as_dict())
+    bad["n_heads"] = 3
+    assert B.lazyllm_workspace_bytes(B.make_config(bad), 512, 1, 512) == 0
+    assert B.lazyllm_workspace_bytes(cfg, 0, 1, 1) == 0
+    assert B.lazyllm_workspace_bytes(cfg, 10, 1, 11) == 0
+    assert B.lazyllm_output_bytes(cfg, [0], []) == 0
+
+
+def test_null_arguments_return_einval_without_touching_the_gpu():
+    lib = B.lib()
+    res = B.lazyllm_result()
+    import ctypes as C
+    arr, ns = B.make_schedule([(1, 500)])
+    assert lib.lazyllm_prefill(None, None, None, 16, arr, ns, 0, None, 0, None, 0, None, C.byref(res)) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_gemm(None, None, None, None, 1, 128, 64, 64, 64, 128, 0, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 100, 64, 64, 64, 100, 0, None) == B.LAZYLLM_EINVAL   # N % 128
+    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 128, 60, 64, 64, 128, 0, None) == B.LAZYLLM_EINVAL   # K % 64
+    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 128, 64, 64, 64, 128, 1, None) == B.LAZYLLM_EINVAL   # residual w/o R
+    assert lib.lazyllm_op_select(1, 10, 0, 1, 1, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_select(1, 10, 11, 1, 1, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_attention(1, 1, 1, 100, 1, 10, 4, 64, None) == B.LAZYLLM_EINVAL             # vt_ld % 64
+    assert lib.lazyllm_op_attention(1, 1, 1, 128, 1, 10, 4, 96, None) == B.LAZYLLM_EINVAL             # head_dim
+    assert lib.lazyllm_op_score(1, 1, 1, 1, 0, 4, 64, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_score_scratch_bytes(0, 4) == 0
+    assert lib.lazyllm_model_create(None, None, None, None) == B.LAZYLLM_EINVAL
