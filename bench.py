@@ -1,0 +1,157 @@
+"""Benchmark of the pruned prefill: TTFT and prompt tokens/s on one MI355X.
+
+One step = one whole prefill (embedding, 32 pruned decoder layers with scoring / selection /
+compaction / Aux Cache writes, final norm, LM head) of the 7B-shaped model on a 3376-token
+synthetic prompt already resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="7b_3376")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-step time table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the pruned prefill of one prompt is a single-GPU job "
+              "(--gpus %d refused)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2407_14057_amd import binding as B
+    from paper_2407_14057_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    shape = wl.shape
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wdev = "cpu" if shape is synth.TINY else dev
+    weights = synth.make_weights(shape, wl.weight_seed, wdev)
+    if wdev == "cpu":
+        weights = {k: ([t.to(dev) for t in v] if isinstance(v, list) else v.to(dev)) for k, v in weights.items()}
+    layer0_bits = synth.layer_to_host_bits(weights, 0)
+    embed_bits = weights["embed"].cpu().view(torch.int16).numpy().view(np.uint16)
+    model = B.Model(shape.as_dict(), weights, dev)
+    del weights
+    torch.cuda.empty_cache()
+
+    inp = synth.make_workload_inputs(wl)
+    ids = torch.from_numpy(inp["token_ids"]).to(dev)
+    scale = None if inp["embed_scale"] is None else torch.from_numpy(inp["embed_scale"]).to(dev)
+    cu = [int(x) for x in inp["cu_seqlens"]]
+    sched = list(wl.schedule)
+    n_tokens = int(ids.numel())
+
+    def step(schedule):
+        return model.prefill(ids, schedule, cu_seqlens=cu, embed_scale=scale)
+
+    def timed(schedule, steps, warmup):
+        for _ in range(warmup):
+            step(schedule)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            out = step(schedule)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, out
+
+    ms, out = timed(sched, args.steps, args.warmup)
+    assert out.status == 0
+    dense_ms, _ = timed([], max(3, args.steps // 4), 2)
+
+    # ---- per-launch timing (hipEvents on the prefill's stream), same steps again
+    B.lazyllm_profile_begin()
+    for _ in range(args.steps):
+        step(sched)
+    recs = B.lazyllm_profile_end(1 << 20)
+    by_step = {}
+    for r in recs:
+        a = by_step.setdefault(r["step"], [0.0, 0.0, 0])
+        a[0] += r["ms"]; a[1] += r["work"]; a[2] += 1
+    gemm_steps = ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down")
+    dom = max(gemm_steps, key=lambda s: by_step.get(s, [0, 0, 0])[0])
+    dms, dwork, dn = by_step[dom]
+    achieved = dwork / (dms * 1e-3) / 1e12                       # TFLOP/s over this step's launches
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel (%s)" % dom, "achieved": round(achieved, 1),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "avg_launch_ms": round(dms / dn, 5), "flops_per_launch": dwork / dn, "traffic": None}
+    total_prof_ms = sum(v[0] for v in by_step.values()) / args.steps
+    breakdown = {}
+    for s, (tms, work, cnt) in sorted(by_step.items(), key=lambda kv: -kv[1][0]):
+        per = tms / args.steps
+        rate = work / (tms * 1e-3) if tms > 0 else 0.0
+        is_flop = s.startswith("gemm") or s == "attention"
+        breakdown[s] = {"ms_per_step": round(per, 4), "launches_per_step": cnt // args.steps,
+                        ("tflops" if is_flop else "gbs"): round(rate / (1e12 if is_flop else 1e9), 1)}
+    if args.breakdown:
+        print(json.dumps(breakdown, indent=1), file=sys.stderr)
+
+    total_flops = sum(by_step[s][1] for s in gemm_steps + ("attention",) if s in by_step) / args.steps
+
+    # ---- CPU checker on a bounded sample: decoder layer 0 on the full prompt (rank 0, N=1)
+    cpu = None
+    if not args.no_cpu_baseline and len(cu) == 2:
+        from oracle import lazyllm_oracle as O
+        sd = shape.as_dict()
+        h0 = O.bf16_bits_to_float(embed_bits[inp["token_ids"]])
+        if inp["embed_scale"] is not None:
+            h0 = h0 * inp["embed_scale"][:, None].astype(np.float64)
+        lw = O.LayerWeights({k: [v] for k, v in layer0_bits.items()}, 0, np.float64)
+        t0 = time.perf_counter()
+        O.decoder_layer(h0, np.arange(n_tokens), lw, shape.n_heads, shape.head_dim, shape.rms_eps,
+                        shape.rope_theta)
+        t_layer = time.perf_counter() - t0
+        token_layers = sum(B.lazyllm_keep_counts(n_tokens, shape.n_layers, sched))
+        est_total = t_layer * token_layers / n_tokens
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count()
+        env_threads = os.environ.get("OMP_NUM_THREADS")
+        if env_threads:
+            cores = min(cores, int(env_threads))
+        cpu = {"value": round(n_tokens / est_total, 2), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+               "sample": "decoder layer 0 of the same model on the full %d-token prompt in fp64 took %.1f s; "
+                         "scaled by token-layers (%d of %d per layer) to the whole pruned prefill"
+                         % (n_tokens, t_layer, token_layers, n_tokens)}
+
+    line = {
+        "metric": "pruned-prefill TTFT (ms) + prompt tokens/s, 7B shape, 3376-token prompt",
+        "value": round(n_tokens / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "shape": "llama-2-7b (32 layers, d 4096, 32x128 heads, ffn 11008, vocab 32000)"
+                   if shape is synth.LLAMA7B else "tiny", "prompt_tokens": n_tokens, "batch": len(cu) - 1,
+                   "keep_schedule_permille_of_survivors": sched,
+                   "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True)},
+        "ttft_ms": round(ms, 4), "dense_ttft_ms": round(dense_ms, 4),
+        "pruned_vs_dense_speedup": round(dense_ms / ms, 3),
+        "whole_call_tflops": round(total_flops / (ms * 1e-3) / 1e12, 1),
+        "whole_call_mfma_frac": round(total_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "profiled_ms_per_step": round(total_prof_ms, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
+    }
+    print(json.dumps(line))
+    model.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

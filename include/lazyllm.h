@@ -173,6 +173,29 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                            int32_t n_sched, uint32_t flags, void* workspace, size_t ws_bytes,
                            void* out_buf, size_t out_bytes, void* hip_stream, lazyllm_result* res);
 
+/* ---- per-launch timing of the prefill (measurement aid) --------------------------------
+ * Between profile_begin and profile_end every kernel launch of lazyllm_prefill* is
+ * bracketed by hipEvents on the call's stream.  profile_end waits for the recorded work,
+ * then writes up to `capacity` records (launch order) and the total count.  `work` is the
+ * launch's algorithmic work: FLOPs for the GEMM and attention steps (Sec. 4.3: linear layers
+ * grow linearly, attention quadratically with the tokens computed), bytes for the
+ * bandwidth-bound steps.  Not thread-safe; one stream at a time. */
+enum lazyllm_step {
+  LAZYLLM_STEP_PLAN = 0, LAZYLLM_STEP_ROPE_TABLE, LAZYLLM_STEP_EMBED, LAZYLLM_STEP_SELECT,
+  LAZYLLM_STEP_GATHER, LAZYLLM_STEP_RMSNORM, LAZYLLM_STEP_GEMM_QKV, LAZYLLM_STEP_ROPE_SPLIT,
+  LAZYLLM_STEP_SCORE, LAZYLLM_STEP_ATTENTION, LAZYLLM_STEP_GEMM_O, LAZYLLM_STEP_GEMM_GATE_UP,
+  LAZYLLM_STEP_GEMM_DOWN, LAZYLLM_STEP_LM_HEAD, LAZYLLM_STEP_COUNT
+};
+typedef struct lazyllm_profile_record {
+  int32_t step;   /* lazyllm_step */
+  int32_t layer;  /* -1 outside the layer loop */
+  int32_t rows;   /* token rows the launch worked on */
+  float ms;       /* event-to-event time */
+  double work;    /* FLOPs or bytes, see above */
+} lazyllm_profile_record;
+int lazyllm_profile_begin(void);
+int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* n_records);
+
 /* ---- single steps of the path (used by kernel-level parity tests and roofline
  *      measurements; all pointers device, all work enqueued on hip_stream) -------------- */
 

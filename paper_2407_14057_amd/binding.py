@@ -56,6 +56,14 @@ class lazyllm_result(C.Structure):
                 ("status", C.c_void_p)]
 
 
+class lazyllm_profile_record(C.Structure):
+    _fields_ = [("step", C.c_int32), ("layer", C.c_int32), ("rows", C.c_int32), ("ms", C.c_float),
+                ("work", C.c_double)]
+
+
+STEP_NAMES = ("plan", "rope_table", "embed", "select", "gather", "rmsnorm", "gemm_qkv", "rope_split",
+              "score", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lm_head")
+
 _lib_handle = None
 
 _SIGNATURES = {
@@ -79,6 +87,9 @@ _SIGNATURES = {
                                          C.c_void_p, C.c_int32, C.POINTER(lazyllm_keep), C.c_int32,
                                          C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                          C.c_void_p, C.POINTER(lazyllm_result)]),
+    "lazyllm_profile_begin": (C.c_int, []),
+    "lazyllm_profile_end": (C.c_int, [C.POINTER(lazyllm_profile_record), C.c_int32,
+                                      C.POINTER(C.c_int32)]),
     "lazyllm_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_void_p]),
@@ -231,6 +242,18 @@ def lazyllm_prefill_varlen(model: int, token_ids, embed_scale, cu_seqlens_host: 
                                         _ptr(out_buf), out_buf.numel() * out_buf.element_size(),
                                         _stream_ptr(stream), C.byref(res)))
     return res
+
+
+def lazyllm_profile_begin() -> None:
+    _check(lib().lazyllm_profile_begin())
+
+
+def lazyllm_profile_end(capacity: int = 65536) -> List[Dict[str, float]]:
+    buf = (lazyllm_profile_record * capacity)()
+    n = C.c_int32(0)
+    _check(lib().lazyllm_profile_end(buf, capacity, C.byref(n)))
+    return [dict(step=STEP_NAMES[buf[i].step], layer=int(buf[i].layer), rows=int(buf[i].rows),
+                 ms=float(buf[i].ms), work=float(buf[i].work)) for i in range(min(n.value, capacity))]
 
 
 # ---------------------------------------------------------------------------- single steps

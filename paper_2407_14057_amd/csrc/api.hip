@@ -27,6 +27,47 @@ inline int hip_fail(hipError_t e) {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// ---- optional per-launch timing (hipEvents around every launch of a prefill) ---------------
+struct ProfRec {
+  hipEvent_t start, stop;
+  int step, layer, rows;
+  double work;        // algorithmic FLOPs (MFMA steps) or bytes (bandwidth steps)
+};
+struct ProfState {
+  bool on = false;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+};
+ProfState g_prof;
+
+hipEvent_t prof_event() {
+  if (!g_prof.pool.empty()) {
+    hipEvent_t e = g_prof.pool.back();
+    g_prof.pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Runs `expr` (a launch returning hipError_t); with profiling on, brackets it with events.
+#define LZ_RUN(step_, layer_, rows_, work_, expr)                                      \
+  do {                                                                                 \
+    if (g_prof.on) {                                                                   \
+      ProfRec r_;                                                                      \
+      r_.start = prof_event(); r_.stop = prof_event();                                 \
+      r_.step = (step_); r_.layer = (layer_); r_.rows = (rows_); r_.work = (work_);    \
+      if (r_.start == nullptr || r_.stop == nullptr) return hip_fail(hipErrorUnknown); \
+      LZ_HIP(hipEventRecord(r_.start, st));                                            \
+      LZ_HIP(expr);                                                                    \
+      LZ_HIP(hipEventRecord(r_.stop, st));                                             \
+      g_prof.recs.push_back(r_);                                                       \
+    } else {                                                                           \
+      LZ_HIP(expr);                                                                    \
+    }                                                                                  \
+  } while (0)
+
 bool config_ok(const lazyllm_config* c) {
   if (c == nullptr) return false;
   if (c->n_layers < 1 || c->n_layers > LAZYLLM_MAX_LAYERS) return false;
@@ -381,12 +422,16 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   memset(&plan, 0, sizeof(plan));
   plan.n_stages = stg.n_stages - 1;
   for (int s = 1; s < stg.n_stages; ++s) plan.permille[s - 1] = stg.permille[s];
-  LZ_HIP(launch_plan(cu_dev, seqlens[0], B, T, plan, cu_stage, cu_aux, cu_vt, res->status, st));
+  const double dd = (double)d, rowb = dd * 2.0;      // bytes of one bf16 row
+  LZ_RUN(LAZYLLM_STEP_PLAN, -1, T, 0.0,
+         launch_plan(cu_dev, seqlens[0], B, T, plan, cu_stage, cu_aux, cu_vt, res->status, st));
   float2* rope = (float2*)(W + ws.rope);
-  LZ_HIP(launch_rope_table(rope, max_seqlen, hd, c->rope_theta, st));
+  LZ_RUN(LAZYLLM_STEP_ROPE_TABLE, -1, max_seqlen, (double)max_seqlen * (hd / 2) * 8.0,
+         launch_rope_table(rope, max_seqlen, hd, c->rope_theta, st));
   char* hbuf[2] = {W + ws.h0, W + ws.h1};
   int cur = 0;
-  LZ_HIP(launch_embed(m->embed, token_ids, embed_scale, cu_dev, B, T, d, c->vocab, hbuf[0],
+  LZ_RUN(LAZYLLM_STEP_EMBED, -1, T, 2.0 * T * rowb,
+         launch_embed(m->embed, token_ids, embed_scale, cu_dev, B, T, d, c->vocab, hbuf[0],
                       res->kept_pos[0], res->status, st));
   const int fp = m->f_pad;
   for (int l = 0; l < L; ++l) {
@@ -399,34 +444,54 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       const int n_prev = (int)stg.total[s - 1];
       int32_t* keep_idx = (int32_t*)(W + ws.keep_idx);
       int32_t* prune_idx = (int32_t*)(W + ws.prune_idx);
-      LZ_HIP(launch_select(res->scores[l - 1], cu_stage + (s - 1) * BW, cu, 0, 0, B, keep_idx,
+      LZ_RUN(LAZYLLM_STEP_SELECT, l, n_prev, 8.0 * n_prev,
+             launch_select(res->scores[l - 1], cu_stage + (s - 1) * BW, cu, 0, 0, B, keep_idx,
                            prune_idx, st));
-      LZ_HIP(launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
+      LZ_RUN(LAZYLLM_STEP_GATHER, l, n_prev, 2.0 * n_prev * rowb,
+             launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
                            hbuf[cur ^ 1], res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st));
       cur ^= 1;
     }
     char* h = hbuf[cur];
-    LZ_HIP(launch_rmsnorm(h, m->attn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
-    LZ_HIP(launch_gemm(W + ws.xa, m->wqkv[l], W + ws.qkv, nullptr, n, 3 * d, d, d, d, 3 * d,
+    // causal attention: 2 products of 2*hd FLOPs per (query, visible key, head)
+    double att_flops = 0.0;
+    for (int b = 0; b < B; ++b) {
+      int nb = seqlens[b];
+      for (int k = 1; k <= s; ++k) nb = keep_count(nb, stg.permille[k]);
+      att_flops += 2.0 * (double)nb * ((double)nb + 1.0) * dd;
+    }
+    LZ_RUN(LAZYLLM_STEP_RMSNORM, l, n, 2.0 * n * rowb,
+           launch_rmsnorm(h, m->attn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
+    LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * 3.0 * dd * dd,
+           launch_gemm(W + ws.xa, m->wqkv[l], W + ws.qkv, nullptr, n, 3 * d, d, d, d, 3 * d,
                        EPI_STORE, st));
-    LZ_HIP(launch_rope_split(W + ws.qkv, res->kept_pos[l], rope, W + ws.q, res->k[l], res->v[l],
+    LZ_RUN(LAZYLLM_STEP_ROPE_SPLIT, l, n, 7.0 * n * rowb,
+           launch_rope_split(W + ws.qkv, res->kept_pos[l], rope, W + ws.q, res->k[l], res->v[l],
                              W + ws.vt, cu, cu_vt + s * BW, 0, B, stg.max_rows[s],
                              (int)stg.vt_ld[s], H, hd, st));
     if (res->scores[l] != nullptr)
-      LZ_HIP(launch_score(W + ws.q, res->k[l], res->scores[l], W + ws.score, cu, 0, B, n,
+      LZ_RUN(LAZYLLM_STEP_SCORE, l, n, n * rowb + rowb * B + 4.0 * n,
+             launch_score(W + ws.q, res->k[l], res->scores[l], W + ws.score, cu, 0, B, n,
                           stg.max_rows[s], H, hd, st));
-    LZ_HIP(launch_attention(W + ws.q, res->k[l], W + ws.vt, W + ws.o, cu, cu_vt + s * BW, 0, B,
+    LZ_RUN(LAZYLLM_STEP_ATTENTION, l, n, att_flops,
+           launch_attention(W + ws.q, res->k[l], W + ws.vt, W + ws.o, cu, cu_vt + s * BW, 0, B,
                             stg.max_rows[s], (int)stg.vt_ld[s], H, hd, st));
-    LZ_HIP(launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st));
-    LZ_HIP(launch_rmsnorm(h, m->ffn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
-    LZ_HIP(launch_gemm(W + ws.xa, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp,
+    LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
+           launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st));
+    LZ_RUN(LAZYLLM_STEP_RMSNORM, l, n, 2.0 * n * rowb,
+           launch_rmsnorm(h, m->ffn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
+    LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, n, 2.0 * n * 2.0 * (double)c->d_ffn * dd,
+           launch_gemm(W + ws.xa, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp,
                        EPI_SWIGLU, st));
-    LZ_HIP(launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st));
+    LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, n, 2.0 * n * (double)c->d_ffn * dd,
+           launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st));
   }
   const int s_last = stg.stage_of_layer[L - 1];
-  LZ_HIP(launch_final_norm(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm,
+  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, (double)c->vocab * rowb,
+         launch_final_norm(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm,
                            (float*)(W + ws.xf), d, c->rms_eps, st));
-  LZ_HIP(launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, B, d, c->vocab, st));
+  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, 0.0,
+         launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, B, d, c->vocab, st));
   return LAZYLLM_OK;
 }
 
@@ -438,6 +503,35 @@ int lazyllm_prefill(const lazyllm_model* m, const int32_t* token_ids, const floa
   const int32_t cu[2] = {0, n};
   return lazyllm_prefill_varlen(m, token_ids, embed_scale, cu, nullptr, 1, sched, n_sched, flags,
                                 workspace, ws_bytes, out_buf, out_bytes, hip_stream, res);
+}
+
+// ---- per-launch timing ---------------------------------------------------------------------
+
+int lazyllm_profile_begin(void) {
+  for (ProfRec& r : g_prof.recs) { g_prof.pool.push_back(r.start); g_prof.pool.push_back(r.stop); }
+  g_prof.recs.clear();
+  g_prof.on = true;
+  return LAZYLLM_OK;
+}
+
+int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* n_records) {
+  g_prof.on = false;
+  if (n_records == nullptr || capacity < 0 || (capacity > 0 && out == nullptr)) return LAZYLLM_EINVAL;
+  int n = 0;
+  for (ProfRec& r : g_prof.recs) {
+    LZ_HIP(hipEventSynchronize(r.stop));
+    float ms = 0.f;
+    LZ_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+    if (n < capacity) {
+      out[n].step = r.step; out[n].layer = r.layer; out[n].rows = r.rows;
+      out[n].ms = ms; out[n].work = r.work;
+    }
+    ++n;
+  }
+  *n_records = n;
+  for (ProfRec& r : g_prof.recs) { g_prof.pool.push_back(r.start); g_prof.pool.push_back(r.stop); }
+  g_prof.recs.clear();
+  return LAZYLLM_OK;
 }
 
 // ---- single steps -------------------------------------------------------------------------
