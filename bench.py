@@ -25,6 +25,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="7b_3376")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true", help="skip the unpruned comparison run")
     ap.add_argument("--breakdown", action="store_true", help="print the per-step time table to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -73,7 +74,9 @@ def main() -> int:
 
     ms, out = timed(sched, args.steps, args.warmup)
     assert out.status == 0
-    dense_ms, _ = timed([], max(3, args.steps // 4), 2)
+    dense_ms = None
+    if not args.no_dense:
+        dense_ms, _ = timed([], max(3, args.steps // 4), 2)
 
     # ---- per-launch timing (hipEvents on the prefill's stream), same steps again
     B.lazyllm_profile_begin()
@@ -141,8 +144,8 @@ def main() -> int:
                    if shape is synth.LLAMA7B else "tiny", "prompt_tokens": n_tokens, "batch": len(cu) - 1,
                    "keep_schedule_permille_of_survivors": sched,
                    "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True)},
-        "ttft_ms": round(ms, 4), "dense_ttft_ms": round(dense_ms, 4),
-        "pruned_vs_dense_speedup": round(dense_ms / ms, 3),
+        "ttft_ms": round(ms, 4), "dense_ttft_ms": None if dense_ms is None else round(dense_ms, 4),
+        "pruned_vs_dense_speedup": None if dense_ms is None else round(dense_ms / ms, 3),
         "whole_call_tflops": round(total_flops / (ms * 1e-3) / 1e12, 1),
         "whole_call_mfma_frac": round(total_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "profiled_ms_per_step": round(total_prof_ms, 4),

@@ -543,8 +543,9 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
   if (N % 128 != 0 || K % 64 != 0 || lda % 8 != 0 || ldw % 8 != 0 || ldc % 4 != 0)
     return LAZYLLM_EINVAL;
   if (lda < K || ldw < K) return LAZYLLM_EINVAL;
-  if (epilogue < 0 || epilogue > 2 || (epilogue == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
-  if (ldc < (epilogue == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
+  const int epi = epilogue & 0xff;
+  if (epilogue < 0 || epi > 2 || (epi == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
+  if (ldc < (epi == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
   if (M == 0) return LAZYLLM_OK;
   LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream));
   return LAZYLLM_OK;

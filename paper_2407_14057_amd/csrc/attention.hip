@@ -68,7 +68,7 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
     for (int qi = 0; qi < K_INSTR; ++qi) {
       const int slab = wave * K_INSTR + qi;
       const int r = slab * K_ROWS_PER_INSTR + lane / CHK;   // key row inside the tile
-      const int c = (lane % CHK) ^ (r & 7);
+      const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
       int key = k0 + r;
       key = key < n ? key : n - 1;
       g2l16(kbase + (size_t)key * d + c * 8, sk + slab * 1024);
@@ -77,7 +77,7 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
     for (int qi = 0; qi < V_INSTR; ++qi) {
       const int slab = wave * V_INSTR + qi;
       const int r = slab * 8 + (lane >> 3);                 // dim row inside the tile
-      const int c = (lane & 7) ^ (r & 7);
+      const int c = (lane & 7) ^ swz64(r);
       g2l16(vbase + (size_t)r * vt_ld + k0 + c * 8, sv + slab * 1024);
     }
   };
@@ -87,9 +87,9 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   uint32_t k_addr[2];                       // per 32-key block; chunk term added per k-step
 #pragma unroll
   for (int sub = 0; sub < 2; ++sub) k_addr[sub] = (uint32_t)((sub * 32 + kperm) * HD * 2);
-  const int kx = kperm & 7;
+  const int kx = CHK == 16 ? swz128(kperm) : swz64(kperm);
   const uint32_t v_addr = (uint32_t)(K_TILE + l31 * 128);
-  const int vx = l31 & 7;
+  const int vx = swz64(l31);
 
   floatx16_t oacc[HS];
 #pragma unroll

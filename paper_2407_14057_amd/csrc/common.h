@@ -50,11 +50,19 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- LDS tiles filled straight from global memory ---------------------------------------
-// A tile is ROWS rows of CH 16-byte chunks.  Chunk c of row r is stored at chunk slot
-// c ^ (r & 7), so that the 16-byte operand reads of 8 consecutive rows at one logical
-// chunk fall into 8 different bank groups.  global_load_lds writes lane i of a wave
-// instruction to LDS base + 16*i, so the permutation is applied on the global side.
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ (row & 7); }
+// The gfx950 LDS is 64 banks x 4 bytes: a 16-byte-per-lane read is served 16 lanes at a
+// time, and those 16 lanes must touch 16 different 16-byte units of the 256-byte bank line.
+// MFMA operand reads have consecutive lanes on consecutive rows at one logical chunk, so
+// chunk c of row r is stored at slot c ^ swz(r), with swz chosen so that 16 consecutive rows
+// spread over all 16 units:
+//   128-byte rows (2 per bank line): swz64(r) = (r >> 1) & 7
+//    64-byte rows (4 per bank line): swz32(r) = (r >> 2) & 3
+//   256-byte rows (1 per bank line): swz128(r) = r & 15
+// global_load_lds writes lane i of a wave instruction to LDS base + 16*i, so the permutation
+// is applied to the global address each lane fetches.
+__device__ __forceinline__ int swz64(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ int swz32(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int swz128(int row) { return row & 15; }
 
 __device__ __forceinline__ void g2l16(const void* gsrc, void* lds_wave_base) {
   __builtin_amdgcn_global_load_lds(

@@ -13,151 +13,13 @@ namespace lz {
 constexpr int BK = 64;                 // K elements per step = 128 bytes = 8 chunks per row
 constexpr int ROW_BYTES = BK * 2;
 
-template <int WM, int WN, int TM, int TN, int EPI>
-__global__ void __launch_bounds__(WM * WN * 64)
-gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
-            uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K, int lda,
-            int ldw, int ldc, int tiles_m, int tiles_n) {
-  constexpr int NWAVES = WM * WN;
-  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  constexpr int A_INSTR = BM / 8 / NWAVES;      // wave-wide 1 KB copies per wave per step
-  constexpr int W_INSTR = BN / 8 / NWAVES;
-  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
-  static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile/wave mismatch");
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave / WN, wn = wave % WN;
-
-  // ---- workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them,
-  // each with its own L2), so ids are first regrouped per XCD, then walked in bands of
-  // GROUP_M tile rows so that concurrently running tiles share A and W slabs in L2.
-  int tile_m, tile_n;
-  {
-    const int T = tiles_m * tiles_n;
-    const int pid = blockIdx.x;
-    const int xcd = pid & 7, local = pid >> 3;
-    const int per = (T + 7) >> 3;
-    const int tall = (T & 7) == 0 ? 8 : (T & 7);
-    const int np = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    constexpr int GROUP_M = 4;
-    const int width = GROUP_M * tiles_n;
-    const int group = np / width;
-    const int first_m = group * GROUP_M;
-    const int gsz = min(tiles_m - first_m, GROUP_M);
-    const int in_group = np - group * width;
-    tile_m = first_m + in_group % gsz;
-    tile_n = in_group / gsz;
-  }
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  // ---- global -> LDS copy plan.  Lane p of a wave instruction fills LDS bytes
-  // [16p, 16p+16) of an 8-row slab: row p/8, stored chunk p%8, which holds logical
-  // chunk (p%8) ^ (p/8).
-  const int crow = lane >> 3;
-  const int cchunk = (lane & 7) ^ crow;
-  uint32_t a_off[A_INSTR], w_off[W_INSTR];
-#pragma unroll
-  for (int q = 0; q < A_INSTR; ++q) {
-    int r = m0 + (wave * A_INSTR + q) * 8 + crow;
-    r = r < M ? r : M - 1;                       // rows past the edge: re-read the last row
-    a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
-  }
-#pragma unroll
-  for (int q = 0; q < W_INSTR; ++q) {
-    int r = n0 + (wave * W_INSTR + q) * 8 + crow;
-    r = r < N ? r : N - 1;
-    w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
-  }
-
-  auto issue = [&](int stage, int k0) {
-    char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
-    char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
-    const char* ga = (const char*)A + (size_t)k0 * 2;
-    const char* gw = (const char*)W + (size_t)k0 * 2;
-#pragma unroll
-    for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
-#pragma unroll
-    for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], sw + q * 1024);
-  };
-
-  // ---- MFMA operand addresses: row (l & 31) of a 32-row block, chunk 2*ks + (l >> 5)
-  uint32_t koff[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) koff[ks] = (uint32_t)(((ks * 2 + (lane >> 5)) ^ (lane & 7)) * 16);
-  const uint32_t a_row = (uint32_t)((wm * TM * 32 + (lane & 31)) * ROW_BYTES);
-  const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
-
-  floatx16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // ---- main loop.  Operand fragments are double-buffered in registers: the reads for k-step
-  // s+1 are issued before the MFMAs of k-step s.  The single barrier of an iteration sits
-  // before the last k-step, when every wave has pulled its last fragments of the current
-  // stage into registers; the stage is then free to receive the tile two steps ahead, and the
-  // first fragments of the next stage are fetched under the last 16 MFMAs.
-  bf16x8_t af[2][TM], wf[2][TN];
-#define LZ_LOAD_FRAGS(buf, st, ks)                                                            \
-  do {                                                                                        \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
-        af[buf][i] = *(const bf16x8_t*)((st) + a_row + i * 32 * ROW_BYTES + koff[ks]);        \
-    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
-        wf[buf][j] = *(const bf16x8_t*)((st) + w_row + j * 32 * ROW_BYTES + koff[ks]);        \
-  } while (0)
-#define LZ_MFMAS(buf)                                                                         \
-  do {                                                                                        \
-    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
-      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i],           \
-                                                            acc[i][j], 0, 0, 0);              \
-  } while (0)
-  // interleave: one LDS read, then MFMAs, so the reads hide under the matrix pipe
-#define LZ_SCHED()                                                                            \
-  do {                                                                                        \
-    _Pragma("unroll") for (int n = 0; n < TM + TN; ++n) {                                     \
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                      \
-      __builtin_amdgcn_sched_group_barrier(0x008, (TM * TN) / (TM + TN), 0);                  \
-    }                                                                                         \
-  } while (0)
-
-  const int KT = K / BK;
-  issue(0, 0);
-  if (KT > 1) issue(1, BK);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  LZ_LOAD_FRAGS(0, lds, 0);
-  for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = lds + (kt & 1) * STAGE_BYTES;
-    const char* nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
-    LZ_LOAD_FRAGS(1, cur, 1);
-    LZ_MFMAS(0);
-    LZ_SCHED();
-    LZ_LOAD_FRAGS(0, cur, 2);
-    LZ_MFMAS(1);
-    LZ_SCHED();
-    LZ_LOAD_FRAGS(1, cur, 3);
-    LZ_MFMAS(0);
-    LZ_SCHED();
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 2 < KT) issue(kt & 1, (kt + 2) * BK);
-    if (kt + 1 < KT) LZ_LOAD_FRAGS(0, nxt, 0);
-    LZ_MFMAS(1);
-    LZ_SCHED();
-  }
-#undef LZ_LOAD_FRAGS
-#undef LZ_MFMAS
-#undef LZ_SCHED
-
-  // ---- epilogue.  The W rows are the MFMA's row operand, so each 32x32 block holds C
-  // transposed: lane l owns token (l & 31); its register r is output feature
-  // 8*(r/4) + 4*(l>>5) + r%4.  Four consecutive features pack into one 8-byte store.
+// ---- epilogue.  The W rows are the MFMA's row operand, so each 32x32 block holds C
+// transposed: lane l owns token (l & 31); its register r is output feature
+// 8*(r/4) + 4*(l>>5) + r%4.  Four consecutive features pack into one 8-byte store.
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_t* __restrict__ C,
+                                              const uint16_t* __restrict__ R, int M, int ldc,
+                                              int m0, int n0, int wm, int wn, int lane) {
   const int tok_l = lane & 31, feat_l = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -205,9 +67,164 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   }
 }
 
+template <int WM, int WN, int TM, int TN, int EPI>
+__global__ void __launch_bounds__(WM * WN * 64)
+gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+            uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K, int lda,
+            int ldw, int ldc, int tiles_m, int tiles_n, int group_m) {
+  constexpr int NWAVES = WM * WN;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int A_INSTR = BM / 8 / NWAVES;      // wave-wide 1 KB copies per wave per step
+  constexpr int W_INSTR = BN / 8 / NWAVES;
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile/wave mismatch");
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+
+  // ---- workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them,
+  // each with its own L2), so ids are first regrouped per XCD, then walked in bands of
+  // GROUP_M tile rows so that concurrently running tiles share A and W slabs in L2.
+  int tile_m, tile_n;
+  {
+    const int T = tiles_m * tiles_n;
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, local = pid >> 3;
+    const int per = (T + 7) >> 3;
+    const int tall = (T & 7) == 0 ? 8 : (T & 7);
+    const int np = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    const int GROUP_M = group_m;
+    const int width = GROUP_M * tiles_n;
+    const int group = np / width;
+    const int first_m = group * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int in_group = np - group * width;
+    tile_m = first_m + in_group % gsz;
+    tile_n = in_group / gsz;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // ---- global -> LDS copy plan.  Lane p of a wave instruction fills LDS bytes
+  // [16p, 16p+16) of an 8-row slab: row p/8, stored chunk p%8, which holds logical
+  // chunk (p%8) ^ swz64(row).
+  const int crow = lane >> 3;
+  uint32_t a_off[A_INSTR], w_off[W_INSTR];
+#pragma unroll
+  for (int q = 0; q < A_INSTR; ++q) {
+    const int tr = (wave * A_INSTR + q) * 8 + crow;          // row inside the tile
+    const int cchunk = (lane & 7) ^ swz64(tr);
+    int r = m0 + tr;
+    r = r < M ? r : M - 1;                       // rows past the edge: re-read the last row
+    a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
+  }
+#pragma unroll
+  for (int q = 0; q < W_INSTR; ++q) {
+    const int tr = (wave * W_INSTR + q) * 8 + crow;
+    const int cchunk = (lane & 7) ^ swz64(tr);
+    int r = n0 + tr;
+    r = r < N ? r : N - 1;
+    w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
+  }
+
+  auto issue = [&](int stage, int k0) {
+    char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
+    char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
+    const char* ga = (const char*)A + (size_t)k0 * 2;
+    const char* gw = (const char*)W + (size_t)k0 * 2;
+#pragma unroll
+    for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
+#pragma unroll
+    for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], sw + q * 1024);
+  };
+
+  // ---- MFMA operand addresses: row (l & 31) of a 32-row block, chunk 2*ks + (l >> 5)
+  uint32_t koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    koff[ks] = (uint32_t)(((ks * 2 + (lane >> 5)) ^ swz64(lane & 31)) * 16);
+  const uint32_t a_row = (uint32_t)((wm * TM * 32 + (lane & 31)) * ROW_BYTES);
+  const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
+
+  floatx16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // ---- main loop.  Operand fragments are double-buffered in registers: the reads for k-step
+  // s+1 are issued before the MFMAs of k-step s.  The single barrier of an iteration sits
+  // before the last k-step, when every wave has pulled its last fragments of the current
+  // stage into registers; the stage is then free to receive the tile two steps ahead, and the
+  // first fragments of the next stage are fetched under the last 16 MFMAs.
+  bf16x8_t af[2][TM], wf[2][TN];
+#define LZ_LOAD_FRAGS(buf, st, ks)                                                            \
+  do {                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+        af[buf][i] = *(const bf16x8_t*)((st) + a_row + i * 32 * ROW_BYTES + koff[ks]);        \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+        wf[buf][j] = *(const bf16x8_t*)((st) + w_row + j * 32 * ROW_BYTES + koff[ks]);        \
+  } while (0)
+#define LZ_MFMAS(buf)                                                                         \
+  do {                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i],           \
+                                                            acc[i][j], 0, 0, 0);              \
+  } while (0)
+  // Order inside a k-step: the LDS reads of the NEXT k-step go out first, one or two per MFMA,
+  // so that the last of them still has at least half a k-step of MFMAs to land under.
+#define LZ_SCHED()                                                                            \
+  do {                                                                                        \
+    constexpr int NR = TM + TN, NM = TM * TN;                                                 \
+    constexpr int RPG = (NR * 2 > NM) ? 2 : 1;          /* reads per group */                 \
+    constexpr int NG = NR / RPG;                                                              \
+    _Pragma("unroll") for (int n = 0; n < NG; ++n) {                                          \
+      __builtin_amdgcn_sched_group_barrier(0x100, RPG, 0);                                    \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                      \
+    }                                                                                         \
+    __builtin_amdgcn_sched_group_barrier(0x008, NM - NG, 0);                                  \
+  } while (0)
+
+  const int KT = K / BK;
+  issue(0, 0);
+  if (KT > 1) issue(1, BK);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  LZ_LOAD_FRAGS(0, lds, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    const char* cur = lds + (kt & 1) * STAGE_BYTES;
+    const char* nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
+    LZ_LOAD_FRAGS(1, cur, 1);
+    LZ_MFMAS(0);
+    LZ_SCHED();
+    LZ_LOAD_FRAGS(0, cur, 2);
+    LZ_MFMAS(1);
+    LZ_SCHED();
+    LZ_LOAD_FRAGS(1, cur, 3);
+    LZ_MFMAS(0);
+    LZ_SCHED();
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 2 < KT) issue(kt & 1, (kt + 2) * BK);
+    if (kt + 1 < KT) LZ_LOAD_FRAGS(0, nxt, 0);
+    LZ_MFMAS(1);
+    LZ_SCHED();
+  }
+#undef LZ_LOAD_FRAGS
+#undef LZ_MFMAS
+#undef LZ_SCHED
+
+  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane);
+}
+
 template <int WM, int WN, int TM, int TN>
 static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* R, int M, int N,
-                             int K, int lda, int ldw, int ldc, int epi, hipStream_t st) {
+                             int K, int lda, int ldw, int ldc, int epi, int group_m,
+                             hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
@@ -224,7 +241,7 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
     }                                                                                            \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)A, (const uint16_t*)W, \
                        (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc, tiles_m,        \
-                       tiles_n);                                                                 \
+                       tiles_n, group_m);                                                        \
   } while (0)
   if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
@@ -238,12 +255,26 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
                        int lda, int ldw, int ldc, int epilogue, hipStream_t st) {
   if (M <= 0) return hipSuccess;
   if (N % 128 != 0 || K % BK != 0) return hipErrorInvalidValue;
-  // Tile choice: the 256x256 tile has the best reuse; fall back to 128x128 when N is not a
-  // multiple of 256 or when the big tile would leave most of the 256 CUs idle.
-  const long big_tiles = (long)((M + 255) / 256) * (N / 256);
-  if (N % 256 == 0 && big_tiles >= 200)
-    return launch_cfg<2, 2, 4, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, st);
-  return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, st);
+  // Bits 8..15 of `epilogue` force a tile configuration and bits 16..21 a band height (tuning
+  // hook for measurements); 0 = choose here.
+  int cfg = (epilogue >> 8) & 0xff, group_m = (epilogue >> 16) & 0x3f;
+  epilogue &= 0xff;
+  if (group_m == 0) group_m = 4;
+  if (cfg == 0) {
+    // 256x256 tiles on 8 waves (two per SIMD) have the best reuse and hide LDS latency best;
+    // when they would leave much of the 256 CUs idle, 128x128 tiles on 4 waves win.
+    const long big_tiles = (long)((M + 255) / 256) * (N / 256);
+    cfg = (N % 256 == 0 && big_tiles >= 150) ? 3 : 2;
+  }
+  switch (cfg) {
+    case 1: if (N % 256) return hipErrorInvalidValue;   // 256x256, 4 waves of 128x128
+            return launch_cfg<2, 2, 4, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, st);
+    case 2:                                             // 128x128, 4 waves of 64x64
+            return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, st);
+    case 3: if (N % 256) return hipErrorInvalidValue;   // 256x256, 8 waves of 64x128
+            return launch_cfg<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, st);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace lz

@@ -10,8 +10,20 @@ namespace lz {
 // chunks); K is read exactly once.  Lane l owns chunks l + 64*i of the row; one head is HD/8
 // consecutive chunks, so a head's dot product is a reduction over HD/8 adjacent lanes.
 // ------------------------------------------------------------------------------------------
-constexpr int SCORE_TOK = 16;        // tokens per workgroup (4 per wave)
+constexpr int SCORE_TOK = 8;         // tokens per workgroup (2 per wave, both in flight)
 constexpr int SCORE_MAX_HEADS = 256;
+
+// Sum over groups of LPH (8 or 16) adjacent lanes with DPP moves (no LDS traffic); every lane
+// of a group ends up with the group's sum.
+template <int LPH>
+__device__ __forceinline__ float group_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xf, 0xf, true));   // lane ^ 1
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xf, 0xf, true));   // lane ^ 2
+  v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x141, 0xf, 0xf, true));  // mirror in 8
+  if (LPH == 16)
+    v += __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x140, 0xf, 0xf, true)); // mirror in 16
+  return v;
+}
 
 template <int HD, int NV>   // NV = ceil(H*HD/8 / 64): chunks per lane
 __global__ void __launch_bounds__(256)
@@ -40,9 +52,8 @@ score_logits_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
       for (int e = 0; e < 8; ++e) qf[i][e] = 0.f;
   }
 
-#pragma unroll
-  for (int pair = 0; pair < 2; ++pair) {
-    const int tl0 = wave * 4 + pair * 2;         // local token index of this pair
+  {
+    const int tl0 = wave * 2;                    // local token index of this wave's pair
     uint4 kv[2][NV];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -64,8 +75,7 @@ score_logits_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         float p = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) p += qf[i][e] * kf[e];
-#pragma unroll
-        for (int o = 1; o < LPH; o <<= 1) p += __shfl_xor(p, o, 64);
+        p = group_sum<LPH>(p);
         const int head = (lane + 64 * i) / LPH;
         if ((lane % LPH) == 0 && head < n_heads) zs[tl0 + u][head] = p * scale;
       }
@@ -108,10 +118,22 @@ score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ part
     const int g = threadIdx.x / hcount, hl = threadIdx.x % hcount;
     float mx = -INFINITY, sum = 0.f;
     if (g < groups) {
-      for (int i = g; i < nparts; i += groups) {
-        const float2 pr = p0[(size_t)i * n_heads + hb + hl];
-        const float nm = fmaxf(mx, pr.x);
-        sum = sum * __expf(mx - nm) + pr.y * __expf(pr.x - nm);
+      // eight independent loads in flight per round: the combine is latency-bound otherwise
+      for (int i0 = g; i0 < nparts; i0 += 8 * groups) {
+        float2 pr[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = i0 + u * groups;
+          pr[u] = i < nparts ? p0[(size_t)i * n_heads + hb + hl] : make_float2(-INFINITY, 0.f);
+        }
+        float nm = mx;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) nm = fmaxf(nm, pr[u].x);
+        float acc = sum * __expf(mx - nm);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (pr[u].y > 0.f) acc += pr[u].y * __expf(pr[u].x - nm);
+        sum = acc;
         mx = nm;
       }
     }
