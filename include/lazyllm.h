@@ -88,6 +88,8 @@ typedef struct lazyllm_model lazyllm_model;
 #define LAZYLLM_SCORE_ALL_LAYERS 0u   /* default: Eq. 1 scores for every layer */
 #define LAZYLLM_SCORE_ONLY_USED 1u    /* only for layers whose successor prunes;
                                          result.scores of other layers is NULL */
+#define LAZYLLM_KEEP_HIDDEN 2u        /* also return every layer's input hidden states and the
+                                         last layer's output (verification aid; adds copies) */
 
 /* Bits of *lazyllm_result.status (device int32, read after stream sync). */
 #define LAZYLLM_ST_BAD_TOKEN 1       /* a token id was outside [0, vocab); clamped */
@@ -115,6 +117,11 @@ typedef struct lazyllm_result {
   int32_t* aux_pos[LAZYLLM_MAX_LAYERS]; /* int32 [n_aux[l]] */
   int32_t* cu_aux[LAZYLLM_MAX_LAYERS];  /* int32 [batch+1] */
   int32_t* status;                      /* int32 [1] LAZYLLM_ST_* bits */
+  /* Only with LAZYLLM_KEEP_HIDDEN (NULL otherwise): the residual stream entering layer l
+   * (after that layer's compaction), bf16 [n_tokens[l], d_model], and the stream leaving the
+   * last layer, bf16 [n_tokens[n_layers-1], d_model]. */
+  void* hidden_in[LAZYLLM_MAX_LAYERS];
+  void* hidden_out;
 } lazyllm_result;
 
 /* ---- host-only helpers (no HIP call) ------------------------------------------------ */
@@ -130,10 +137,10 @@ int lazyllm_keep_counts(int32_t n, int32_t n_layers, const lazyllm_keep* sched, 
 size_t lazyllm_workspace_bytes(const lazyllm_config* cfg, int32_t total_tokens, int32_t batch,
                                int32_t max_seqlen);
 
-/* Bytes of output buffer for these prompt lengths (host int32[batch]) and
- * schedule.  0 on a bad argument. */
+/* Bytes of output buffer for these prompt lengths (host int32[batch]), schedule
+ * and prefill flags.  0 on a bad argument. */
 size_t lazyllm_output_bytes(const lazyllm_config* cfg, const int32_t* seqlens, int32_t batch,
-                            const lazyllm_keep* sched, int32_t n_sched);
+                            const lazyllm_keep* sched, int32_t n_sched, uint32_t flags);
 
 const char* lazyllm_strerror(int status);
 /* hipError_t value of the last failing HIP call on this thread (0 if none). */
@@ -182,7 +189,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
  * bandwidth-bound steps.  Not thread-safe; one stream at a time. */
 enum lazyllm_step {
   LAZYLLM_STEP_PLAN = 0, LAZYLLM_STEP_ROPE_TABLE, LAZYLLM_STEP_EMBED, LAZYLLM_STEP_SELECT,
-  LAZYLLM_STEP_GATHER, LAZYLLM_STEP_RMSNORM, LAZYLLM_STEP_GEMM_QKV, LAZYLLM_STEP_ROPE_SPLIT,
+  LAZYLLM_STEP_GATHER, LAZYLLM_STEP_RMSNORM, LAZYLLM_STEP_GEMM_QKV, LAZYLLM_STEP_V_TRANSPOSE,
   LAZYLLM_STEP_SCORE, LAZYLLM_STEP_ATTENTION, LAZYLLM_STEP_GEMM_O, LAZYLLM_STEP_GEMM_GATE_UP,
   LAZYLLM_STEP_GEMM_DOWN, LAZYLLM_STEP_LM_HEAD, LAZYLLM_STEP_COUNT
 };
@@ -214,14 +221,19 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
 int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d,
                        float eps, void* hip_stream);
 
-/* Splits a fused projection qkv[rows, 3*H*hd] into q, k (rotary applied at
- * pos[rows], half-split pairing, theta^(-2i/hd)) and v, and writes the
- * transposed copy vt[H, hd, vt_ld] the attention kernel reads (columns
- * rows..vt_ld-1 are zeroed; vt_ld % 64 == 0, vt_ld >= rows).
+/* Fused QKV projection with rotary embedding: [q|k|v] = x Wqkv^T with Wqkv bf16
+ * [3*H*hd, H*hd] (q rows, then k, then v); q and k are rotated at pos[rows]
+ * (original positions; half-split pairing, angle pos * theta^(-2i/hd)) in fp32
+ * and rounded to bf16 once.  x, q, k, v: bf16 [rows, H*hd].
  * rope_table: device float2 scratch [max_pos+1, hd/2], filled by this call. */
-int lazyllm_op_rope_split(const void* qkv, const int32_t* pos, int32_t max_pos, void* rope_table,
-                          void* q, void* k, void* v, void* vt, int32_t vt_ld, int32_t rows,
-                          int32_t n_heads, int32_t head_dim, float theta, void* hip_stream);
+int lazyllm_op_qkv_rope(const void* x, const void* wqkv, const int32_t* pos, int32_t max_pos,
+                        void* rope_table, void* q, void* k, void* v, int32_t rows, int32_t n_heads,
+                        int32_t head_dim, float theta, void* hip_stream);
+
+/* Transposed copy vt[H, hd, vt_ld] of v[rows, H, hd] that the attention kernel
+ * reads (columns rows..roundup(rows,64)-1 are zeroed; vt_ld % 64 == 0). */
+int lazyllm_op_v_transpose(const void* v, void* vt, int32_t vt_ld, int32_t rows, int32_t n_heads,
+                           int32_t head_dim, void* hip_stream);
 
 /* Causal multi-head attention over one sequence of `rows` tokens in compacted
  * order (ascending original position, so compacted-causal = original-causal):

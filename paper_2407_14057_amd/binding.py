@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblazyllm.so")
 MAX_LAYERS = 128
 
 LAZYLLM_OK, LAZYLLM_EINVAL, LAZYLLM_ENOSPC, LAZYLLM_EHIP, LAZYLLM_ENOMEM = 0, -1, -2, -3, -4
-LAZYLLM_SCORE_ALL_LAYERS, LAZYLLM_SCORE_ONLY_USED = 0, 1
+LAZYLLM_SCORE_ALL_LAYERS, LAZYLLM_SCORE_ONLY_USED, LAZYLLM_KEEP_HIDDEN = 0, 1, 2
 LAZYLLM_ST_BAD_TOKEN, LAZYLLM_ST_BAD_CU = 1, 2
 EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
 
@@ -53,7 +53,8 @@ class lazyllm_result(C.Structure):
                 ("n_aux", C.c_int32 * MAX_LAYERS),
                 ("aux_h", C.c_void_p * MAX_LAYERS), ("aux_pos", C.c_void_p * MAX_LAYERS),
                 ("cu_aux", C.c_void_p * MAX_LAYERS),
-                ("status", C.c_void_p)]
+                ("status", C.c_void_p),
+                ("hidden_in", C.c_void_p * MAX_LAYERS), ("hidden_out", C.c_void_p)]
 
 
 class lazyllm_profile_record(C.Structure):
@@ -61,7 +62,7 @@ class lazyllm_profile_record(C.Structure):
                 ("work", C.c_double)]
 
 
-STEP_NAMES = ("plan", "rope_table", "embed", "select", "gather", "rmsnorm", "gemm_qkv", "rope_split",
+STEP_NAMES = ("plan", "rope_table", "embed", "select", "gather", "rmsnorm", "gemm_qkv", "v_transpose",
               "score", "attention", "gemm_o", "gemm_gate_up", "gemm_down", "lm_head")
 
 _lib_handle = None
@@ -75,7 +76,7 @@ _SIGNATURES = {
     "lazyllm_workspace_bytes": (C.c_size_t, [C.POINTER(lazyllm_config), C.c_int32, C.c_int32,
                                              C.c_int32]),
     "lazyllm_output_bytes": (C.c_size_t, [C.POINTER(lazyllm_config), C.POINTER(C.c_int32), C.c_int32,
-                                          C.POINTER(lazyllm_keep), C.c_int32]),
+                                          C.POINTER(lazyllm_keep), C.c_int32, C.c_uint32]),
     "lazyllm_model_create": (C.c_int, [C.POINTER(lazyllm_config), C.POINTER(lazyllm_weights),
                                        C.c_void_p, C.POINTER(C.c_void_p)]),
     "lazyllm_model_destroy": (None, [C.c_void_p]),
@@ -95,9 +96,11 @@ _SIGNATURES = {
                                   C.c_void_p]),
     "lazyllm_op_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_float, C.c_void_p]),
-    "lazyllm_op_rope_split": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
-                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
-                                        C.c_int32, C.c_int32, C.c_float, C.c_void_p]),
+    "lazyllm_op_qkv_rope": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_float, C.c_void_p]),
+    "lazyllm_op_v_transpose": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_int32, C.c_void_p]),
     "lazyllm_op_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                        C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
     "lazyllm_op_score_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
@@ -187,10 +190,10 @@ def lazyllm_workspace_bytes(cfg: lazyllm_config, total_tokens: int, batch: int, 
 
 
 def lazyllm_output_bytes(cfg: lazyllm_config, seqlens: Sequence[int],
-                         schedule: Sequence[Tuple[int, int]]) -> int:
+                         schedule: Sequence[Tuple[int, int]], flags: int = 0) -> int:
     arr, ns = make_schedule(schedule)
     sl = (C.c_int32 * len(seqlens))(*[int(x) for x in seqlens])
-    return int(lib().lazyllm_output_bytes(C.byref(cfg), sl, len(seqlens), arr, ns))
+    return int(lib().lazyllm_output_bytes(C.byref(cfg), sl, len(seqlens), arr, ns, flags))
 
 
 # ---------------------------------------------------------------------------- model + prefill
@@ -267,11 +270,16 @@ def lazyllm_op_rmsnorm(h, gain, x, rows, d, eps, stream=None) -> None:
     _check(lib().lazyllm_op_rmsnorm(_ptr(h), _ptr(gain), _ptr(x), rows, d, eps, _stream_ptr(stream)))
 
 
-def lazyllm_op_rope_split(qkv, pos, max_pos, rope_table, q, k, v, vt, vt_ld, rows, n_heads,
-                          head_dim, theta, stream=None) -> None:
-    _check(lib().lazyllm_op_rope_split(_ptr(qkv), _ptr(pos), max_pos, _ptr(rope_table), _ptr(q),
-                                       _ptr(k), _ptr(v), _ptr(vt), vt_ld, rows, n_heads, head_dim,
-                                       theta, _stream_ptr(stream)))
+def lazyllm_op_qkv_rope(x, wqkv, pos, max_pos, rope_table, q, k, v, rows, n_heads, head_dim, theta,
+                        stream=None) -> None:
+    _check(lib().lazyllm_op_qkv_rope(_ptr(x), _ptr(wqkv), _ptr(pos), max_pos, _ptr(rope_table),
+                                     _ptr(q), _ptr(k), _ptr(v), rows, n_heads, head_dim, theta,
+                                     _stream_ptr(stream)))
+
+
+def lazyllm_op_v_transpose(v, vt, vt_ld, rows, n_heads, head_dim, stream=None) -> None:
+    _check(lib().lazyllm_op_v_transpose(_ptr(v), _ptr(vt), vt_ld, rows, n_heads, head_dim,
+                                        _stream_ptr(stream)))
 
 
 def lazyllm_op_attention(q, k, vt, vt_ld, o, rows, n_heads, head_dim, stream=None) -> None:
@@ -363,6 +371,19 @@ class PrefillOutput:
     def cu_aux(self, l):
         return self._view(self.res.cu_aux[l], self.batch + 1, torch.int32)
 
+    def hidden_in(self, l):
+        if not self.res.hidden_in[l]:
+            return None
+        return self._view(self.res.hidden_in[l], self.n_tokens[l] * self.cfg.d_model,
+                          torch.bfloat16).view(self.n_tokens[l], self.cfg.d_model)
+
+    @property
+    def hidden_out(self):
+        if not self.res.hidden_out:
+            return None
+        n = self.n_tokens[self.n_layers - 1]
+        return self._view(self.res.hidden_out, n * self.cfg.d_model, torch.bfloat16).view(n, self.cfg.d_model)
+
 
 class Model:
     """Owns a lazyllm_model handle and reusable workspace / output buffers."""
@@ -386,10 +407,10 @@ class Model:
         except Exception:
             pass
 
-    def buffers(self, seqlens: Sequence[int], schedule) -> Tuple[torch.Tensor, torch.Tensor]:
+    def buffers(self, seqlens: Sequence[int], schedule, flags: int = 0) -> Tuple[torch.Tensor, torch.Tensor]:
         total, batch, mx = int(sum(seqlens)), len(seqlens), int(max(seqlens))
         wsb = lazyllm_workspace_bytes(self.cfg, total, batch, mx)
-        outb = lazyllm_output_bytes(self.cfg, seqlens, schedule)
+        outb = lazyllm_output_bytes(self.cfg, seqlens, schedule, flags)
         if wsb == 0 or outb == 0:
             raise LazyLLMError(LAZYLLM_EINVAL)
         if self._ws is None or self._ws.numel() < wsb:
@@ -405,7 +426,7 @@ class Model:
         if cu_seqlens is None:
             cu_seqlens = [0, int(token_ids.numel())]
         seqlens = [int(cu_seqlens[i + 1] - cu_seqlens[i]) for i in range(len(cu_seqlens) - 1)]
-        ws, out = self.buffers(seqlens, schedule)
+        ws, out = self.buffers(seqlens, schedule, flags)
         if len(seqlens) == 1:
             res = lazyllm_prefill(self.handle, token_ids, embed_scale, seqlens[0], schedule, flags,
                                   ws, out, stream)

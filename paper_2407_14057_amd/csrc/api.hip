@@ -142,7 +142,7 @@ void build_stages(int n_layers, const lazyllm_keep* sched, int n_sched, const in
 
 // ---- workspace layout -------------------------------------------------------------------
 struct Workspace {
-  size_t h0, h1, xa, qkv, q, o, vt, act, score, rope, keep_idx, prune_idx, xf, total;
+  size_t h0, h1, xa, q, o, vt, act, score, rope, keep_idx, prune_idx, xf, total;
 };
 
 void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_seqlen,
@@ -154,7 +154,6 @@ void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_s
   w->h0 = take((size_t)T * d * 2);
   w->h1 = take((size_t)T * d * 2);
   w->xa = take((size_t)T * d * 2);
-  w->qkv = take((size_t)T * 3 * d * 2);
   w->q = take((size_t)T * d * 2);
   w->o = take((size_t)T * d * 2);
   w->vt = take(d * vt_ld * 2);
@@ -173,10 +172,11 @@ struct Output {
   size_t kept_pos[LAZYLLM_MAX_LAYERS + 1];            // per stage
   size_t aux_h[LAZYLLM_MAX_LAYERS + 1], aux_pos[LAZYLLM_MAX_LAYERS + 1];
   size_t k[LAZYLLM_MAX_LAYERS], v[LAZYLLM_MAX_LAYERS], scores[LAZYLLM_MAX_LAYERS];
+  size_t hidden_in[LAZYLLM_MAX_LAYERS], hidden_out;
   size_t total;
 };
 
-void layout_output(const lazyllm_config* c, const Stages* st, int batch, Output* o) {
+void layout_output(const lazyllm_config* c, const Stages* st, int batch, uint32_t flags, Output* o) {
   const size_t d = c->d_model;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
@@ -198,6 +198,11 @@ void layout_output(const lazyllm_config* c, const Stages* st, int batch, Output*
     o->k[l] = take(n * d * 2);
     o->v[l] = take(n * d * 2);
     o->scores[l] = take(n * 4);
+  }
+  if (flags & LAZYLLM_KEEP_HIDDEN) {
+    for (int l = 0; l < c->n_layers; ++l)
+      o->hidden_in[l] = take((size_t)st->total[st->stage_of_layer[l]] * d * 2);
+    o->hidden_out = take((size_t)st->total[st->stage_of_layer[c->n_layers - 1]] * d * 2);
   }
   o->total = off;
 }
@@ -253,8 +258,8 @@ size_t lazyllm_workspace_bytes(const lazyllm_config* cfg, int32_t total_tokens, 
 }
 
 size_t lazyllm_output_bytes(const lazyllm_config* cfg, const int32_t* seqlens, int32_t batch,
-                            const lazyllm_keep* sched, int32_t n_sched) {
-  if (!config_ok(cfg) || seqlens == nullptr || batch <= 0) return 0;
+                            const lazyllm_keep* sched, int32_t n_sched, uint32_t flags) {
+  if (!config_ok(cfg) || seqlens == nullptr || batch <= 0 || (flags & ~3u) != 0) return 0;
   if (!schedule_ok(cfg->n_layers, sched, n_sched)) return 0;
   long long total = 0;
   for (int b = 0; b < batch; ++b) {
@@ -265,7 +270,7 @@ size_t lazyllm_output_bytes(const lazyllm_config* cfg, const int32_t* seqlens, i
   Stages st;
   build_stages(cfg->n_layers, sched, n_sched, seqlens, batch, &st);
   Output o;
-  layout_output(cfg, &st, batch, &o);
+  layout_output(cfg, &st, batch, flags, &o);
   return o.total;
 }
 
@@ -363,7 +368,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       out_buf == nullptr || res == nullptr || batch <= 0)
     return LAZYLLM_EINVAL;
   if (batch > 1 && cu_dev == nullptr) return LAZYLLM_EINVAL;
-  if ((flags & ~1u) != 0) return LAZYLLM_EINVAL;
+  if ((flags & ~3u) != 0) return LAZYLLM_EINVAL;
   if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)out_buf & 255) != 0) return LAZYLLM_EINVAL;
   const lazyllm_config* c = &m->cfg;
   if (!schedule_ok(c->n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
@@ -382,7 +387,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   Workspace ws;
   layout_workspace(c, T, batch, max_seqlen, &ws);
   Output ob;
-  layout_output(c, &stg, batch, &ob);
+  layout_output(c, &stg, batch, flags, &ob);
   if (ws_bytes < ws.total || out_bytes < ob.total) return LAZYLLM_ENOSPC;
 
   // ---- result struct
@@ -453,6 +458,10 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       cur ^= 1;
     }
     char* h = hbuf[cur];
+    if (flags & LAZYLLM_KEEP_HIDDEN) {
+      res->hidden_in[l] = O + ob.hidden_in[l];
+      LZ_HIP(hipMemcpyAsync(res->hidden_in[l], h, (size_t)n * d * 2, hipMemcpyDeviceToDevice, st));
+    }
     // causal attention: 2 products of 2*hd FLOPs per (query, visible key, head)
     double att_flops = 0.0;
     for (int b = 0; b < B; ++b) {
@@ -462,13 +471,18 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     }
     LZ_RUN(LAZYLLM_STEP_RMSNORM, l, n, 2.0 * n * rowb,
            launch_rmsnorm(h, m->attn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
+    // QKV projection with the rotary embedding (original positions) applied in the epilogue;
+    // K and V land directly in this layer's KV cache.
+    RopeArgs ra;
+    ra.pos = res->kept_pos[l]; ra.table = rope;
+    ra.q = (uint16_t*)(W + ws.q); ra.k = (uint16_t*)res->k[l]; ra.v = (uint16_t*)res->v[l];
+    ra.d_model = d; ra.head_dim = hd;
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * 3.0 * dd * dd,
-           launch_gemm(W + ws.xa, m->wqkv[l], W + ws.qkv, nullptr, n, 3 * d, d, d, d, 3 * d,
-                       EPI_STORE, st));
-    LZ_RUN(LAZYLLM_STEP_ROPE_SPLIT, l, n, 7.0 * n * rowb,
-           launch_rope_split(W + ws.qkv, res->kept_pos[l], rope, W + ws.q, res->k[l], res->v[l],
-                             W + ws.vt, cu, cu_vt + s * BW, 0, B, stg.max_rows[s],
-                             (int)stg.vt_ld[s], H, hd, st));
+           launch_gemm(W + ws.xa, m->wqkv[l], nullptr, nullptr, n, 3 * d, d, d, d, 0,
+                       EPI_QKV_ROPE, st, &ra));
+    LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 2.0 * n * rowb,
+           launch_v_transpose(res->v[l], W + ws.vt, cu, cu_vt + s * BW, 0, B, stg.max_rows[s],
+                              (int)stg.vt_ld[s], H, hd, st));
     if (res->scores[l] != nullptr)
       LZ_RUN(LAZYLLM_STEP_SCORE, l, n, n * rowb + rowb * B + 4.0 * n,
              launch_score(W + ws.q, res->k[l], res->scores[l], W + ws.score, cu, 0, B, n,
@@ -487,6 +501,11 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
            launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st));
   }
   const int s_last = stg.stage_of_layer[L - 1];
+  if (flags & LAZYLLM_KEEP_HIDDEN) {
+    res->hidden_out = O + ob.hidden_out;
+    LZ_HIP(hipMemcpyAsync(res->hidden_out, hbuf[cur], (size_t)stg.total[s_last] * d * 2,
+                          hipMemcpyDeviceToDevice, st));
+  }
   LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, (double)c->vocab * rowb,
          launch_final_norm(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm,
                            (float*)(W + ws.xf), d, c->rms_eps, st));
@@ -559,17 +578,31 @@ int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, i
   return LAZYLLM_OK;
 }
 
-int lazyllm_op_rope_split(const void* qkv, const int32_t* pos, int32_t max_pos, void* rope_table,
-                          void* q, void* k, void* v, void* vt, int32_t vt_ld, int32_t rows,
-                          int32_t n_heads, int32_t head_dim, float theta, void* hip_stream) {
-  if (!qkv || !pos || !rope_table || !q || !k || !v || !vt || rows <= 0 || max_pos < 0 ||
-      n_heads <= 0 || (head_dim != 64 && head_dim != 128) || vt_ld % 64 != 0 || vt_ld < rows ||
+int lazyllm_op_qkv_rope(const void* x, const void* wqkv, const int32_t* pos, int32_t max_pos,
+                        void* rope_table, void* q, void* k, void* v, int32_t rows, int32_t n_heads,
+                        int32_t head_dim, float theta, void* hip_stream) {
+  if (!x || !wqkv || !pos || !rope_table || !q || !k || !v || rows <= 0 || max_pos < 0 ||
+      n_heads <= 0 || (head_dim != 64 && head_dim != 128) || (n_heads * head_dim) % 128 != 0 ||
       !(theta > 0.f))
     return LAZYLLM_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
+  const int d = n_heads * head_dim;
   LZ_HIP(launch_rope_table((float2*)rope_table, max_pos + 1, head_dim, theta, st));
-  LZ_HIP(launch_rope_split(qkv, pos, (const float2*)rope_table, q, k, v, vt, nullptr, nullptr, rows,
-                           1, rows, vt_ld, n_heads, head_dim, st));
+  RopeArgs ra;
+  ra.pos = pos; ra.table = (const float2*)rope_table;
+  ra.q = (uint16_t*)q; ra.k = (uint16_t*)k; ra.v = (uint16_t*)v;
+  ra.d_model = d; ra.head_dim = head_dim;
+  LZ_HIP(launch_gemm(x, wqkv, nullptr, nullptr, rows, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st, &ra));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_v_transpose(const void* v, void* vt, int32_t vt_ld, int32_t rows, int32_t n_heads,
+                           int32_t head_dim, void* hip_stream) {
+  if (!v || !vt || rows <= 0 || n_heads <= 0 || (head_dim != 64 && head_dim != 128) ||
+      vt_ld % 64 != 0 || vt_ld < (rows + 63) / 64 * 64)
+    return LAZYLLM_EINVAL;
+  LZ_HIP(launch_v_transpose(v, vt, nullptr, nullptr, rows, 1, rows, vt_ld, n_heads, head_dim,
+                            (hipStream_t)hip_stream));
   return LAZYLLM_OK;
 }
 

@@ -78,10 +78,22 @@ __device__ __forceinline__ void seq_range(const int32_t* cu, int b, int n_single
 }
 
 // ---- launch interface (host) ------------------------------------------------------------
-enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROPE = 3 };
+
+// Extra operands of the fused QKV + rotary epilogue: q, k, v are [rows, d_model] bf16,
+// table is float2 [positions, head_dim/2] = (cos, sin), pos the original position of each row.
+struct RopeArgs {
+  const int32_t* pos;
+  const float2* table;
+  uint16_t* q;
+  uint16_t* k;
+  uint16_t* v;
+  int d_model, head_dim;
+};
 
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
-                       int lda, int ldw, int ldc, int epilogue, hipStream_t st);
+                       int lda, int ldw, int ldc, int epilogue, hipStream_t st,
+                       const RopeArgs* rope = nullptr);
 
 hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st);
 
@@ -92,10 +104,9 @@ hipError_t launch_embed(const void* embed, const int32_t* ids, const float* scal
                         int32_t* status, hipStream_t st);
 hipError_t launch_rmsnorm(const void* h, const void* gain, void* x, int rows, int d, float eps,
                           hipStream_t st);
-hipError_t launch_rope_split(const void* qkv, const int32_t* pos, const float2* table, void* q,
-                             void* k, void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
-                             int n_single, int batch, int max_rows, int vt_ld, int n_heads,
-                             int head_dim, hipStream_t st);
+hipError_t launch_v_transpose(const void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
+                              int n_single, int batch, int max_rows, int vt_ld, int n_heads,
+                              int head_dim, hipStream_t st);
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
                             int n_heads, int head_dim, hipStream_t st);

@@ -1,4 +1,4 @@
-// Glue kernels of the decoder layer: plan, embedding, RMSNorm, rotary split, final norm,
+// Glue kernels of the decoder layer: plan, embedding, RMSNorm, rotary table, V transpose, final norm,
 // LM head, and the weight repack used at model creation.  All bandwidth-bound; 16-byte
 // vectors, one wave per row.
 #include "common.h"
@@ -198,20 +198,17 @@ hipError_t launch_rmsnorm(const void* h, const void* gain, void* x, int rows, in
 }
 
 // ------------------------------------------------------------------------------------------
-// Split the fused projection into q, k (rotary applied), v, and the transposed copy of v.
-// One workgroup = 64 tokens of one head.  vt[h][dim][cu_vt[b] + token] is what the
-// attention kernel's second product reads (keys contiguous); its tail columns up to the
-// next multiple of 64 are zeroed so that masked probabilities never meet a NaN.
+// Transposed copy of V for the attention kernel's second product: vt[h][dim][cu_vt[b] + token]
+// (keys contiguous).  One workgroup = 64 tokens of one head, through an LDS tile.  The tail
+// columns up to the next multiple of 64 are zeroed so that masked probabilities never meet a
+// NaN.
 // ------------------------------------------------------------------------------------------
 template <int HD>
 __global__ void __launch_bounds__(256)
-rope_split_kernel(const uint16_t* __restrict__ qkv, const int32_t* __restrict__ pos,
-                  const float2* __restrict__ table, uint16_t* __restrict__ q,
-                  uint16_t* __restrict__ k, uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
-                  const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
-                  int vt_ld, int n_heads) {
+v_transpose_kernel(const uint16_t* __restrict__ v, uint16_t* __restrict__ vt,
+                   const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
+                   int vt_ld, int n_heads) {
   constexpr int CH = HD / 8;            // 16-byte chunks per head row
-  constexpr int HALF = HD / 2;
   constexpr int LROW = HD + 2;          // padded LDS row (elements)
   __shared__ uint16_t tile[64 * LROW];
   const int b = blockIdx.z, head = blockIdx.y;
@@ -220,47 +217,15 @@ rope_split_kernel(const uint16_t* __restrict__ qkv, const int32_t* __restrict__ 
   const int t0 = blockIdx.x * 64;
   if (t0 >= n) return;
   const int d = n_heads * HD;
-  const size_t ld_in = (size_t)3 * d;
-
-  // q and k: thread takes (token, chunk c < CH/2) and rotates it with chunk c + CH/2
-  for (int idx = threadIdx.x; idx < 64 * (CH / 2); idx += 256) {
-    const int t = idx / (CH / 2), c = idx % (CH / 2);
-    if (t0 + t >= n) continue;
-    const size_t row = (size_t)(row0 + t0 + t);
-    const float2* cs = table + (size_t)pos[row] * HALF + c * 8;
-    float cosv[8], sinv[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { float2 t2 = cs[e]; cosv[e] = t2.x; sinv[e] = t2.y; }
-#pragma unroll
-    for (int which = 0; which < 2; ++which) {
-      const uint16_t* src = qkv + row * ld_in + (size_t)which * d + head * HD;
-      uint16_t* dst = (which == 0 ? q : k) + row * d + head * HD;
-      float a[8], bb[8], ra[8], rb[8];
-      unpack8(*(const uint4*)(src + c * 8), a);
-      unpack8(*(const uint4*)(src + HALF + c * 8), bb);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        ra[e] = a[e] * cosv[e] - bb[e] * sinv[e];
-        rb[e] = bb[e] * cosv[e] + a[e] * sinv[e];
-      }
-      *(uint4*)(dst + c * 8) = pack8(ra);
-      *(uint4*)(dst + HALF + c * 8) = pack8(rb);
-    }
-  }
-  // v: copy out and stage into LDS
   for (int idx = threadIdx.x; idx < 64 * CH; idx += 256) {
     const int t = idx / CH, c = idx % CH;
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (t0 + t < n) {
-      const size_t row = (size_t)(row0 + t0 + t);
-      val = *(const uint4*)(qkv + row * ld_in + (size_t)2 * d + head * HD + c * 8);
-      *(uint4*)(v + row * d + head * HD + c * 8) = val;
-    }
+    if (t0 + t < n) val = *(const uint4*)(v + (size_t)(row0 + t0 + t) * d + head * HD + c * 8);
     uint32_t* p = (uint32_t*)(tile + t * LROW + c * 8);   // LROW even: 4-byte aligned
     p[0] = val.x; p[1] = val.y; p[2] = val.z; p[3] = val.w;
   }
   __syncthreads();
-  // transposed write: thread takes (dim, group of 8 tokens)
+  // thread takes (dim, group of 8 tokens)
   const size_t vt_base = (size_t)head * HD * vt_ld + (cu_vt ? cu_vt[b] : 0) + t0;
   for (int idx = threadIdx.x; idx < HD * 8; idx += 256) {
     const int j = idx & 7, dim = idx >> 3;
@@ -274,20 +239,17 @@ rope_split_kernel(const uint16_t* __restrict__ qkv, const int32_t* __restrict__ 
   }
 }
 
-hipError_t launch_rope_split(const void* qkv, const int32_t* pos, const float2* table, void* q,
-                             void* k, void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
-                             int n_single, int batch, int max_rows, int vt_ld, int n_heads,
-                             int head_dim, hipStream_t st) {
+hipError_t launch_v_transpose(const void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
+                              int n_single, int batch, int max_rows, int vt_ld, int n_heads,
+                              int head_dim, hipStream_t st) {
   if (max_rows <= 0) return hipSuccess;
   dim3 grid((max_rows + 63) / 64, n_heads, batch), block(256);
   if (head_dim == 128)
-    hipLaunchKernelGGL(rope_split_kernel<128>, grid, block, 0, st, (const uint16_t*)qkv, pos, table,
-                       (uint16_t*)q, (uint16_t*)k, (uint16_t*)v, (uint16_t*)vt, cu, cu_vt, n_single,
-                       vt_ld, n_heads);
+    hipLaunchKernelGGL(v_transpose_kernel<128>, grid, block, 0, st, (const uint16_t*)v, (uint16_t*)vt,
+                       cu, cu_vt, n_single, vt_ld, n_heads);
   else if (head_dim == 64)
-    hipLaunchKernelGGL(rope_split_kernel<64>, grid, block, 0, st, (const uint16_t*)qkv, pos, table,
-                       (uint16_t*)q, (uint16_t*)k, (uint16_t*)v, (uint16_t*)vt, cu, cu_vt, n_single,
-                       vt_ld, n_heads);
+    hipLaunchKernelGGL(v_transpose_kernel<64>, grid, block, 0, st, (const uint16_t*)v, (uint16_t*)vt,
+                       cu, cu_vt, n_single, vt_ld, n_heads);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

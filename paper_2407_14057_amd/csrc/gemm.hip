@@ -16,16 +16,63 @@ constexpr int ROW_BYTES = BK * 2;
 // ---- epilogue.  The W rows are the MFMA's row operand, so each 32x32 block holds C
 // transposed: lane l owns token (l & 31); its register r is output feature
 // 8*(r/4) + 4*(l>>5) + r%4.  Four consecutive features pack into one 8-byte store.
+//
+// EPI_QKV_ROPE: the N axis is [q | k | v] of width d each.  A wave's TN*32 columns hold whole
+// heads, so the rotary partner of dimension i (i + hd/2) is the same register of block j + hd/64:
+// q and k are rotated in fp32 straight out of the accumulator and rounded to bf16 once.
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_t* __restrict__ C,
                                               const uint16_t* __restrict__ R, int M, int ldc,
-                                              int m0, int n0, int wm, int wn, int lane) {
+                                              int m0, int n0, int wm, int wn, int lane,
+                                              const RopeArgs& ra) {
   const int tok_l = lane & 31, feat_l = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + (wm * TM + i) * 32 + tok_l;
     if (row >= M) continue;
-    if (EPI == EPI_SWIGLU) {
+    if (EPI == EPI_QKV_ROPE) {
+      const int d = ra.d_model, hd = ra.head_dim, half = hd >> 1;
+      const int col0 = n0 + wn * TN * 32;              // first column of this wave
+      const int region = col0 / d;                      // 0 q, 1 k, 2 v (uniform per wave)
+      uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)row * d +
+                      (col0 - region * d) + feat_l;
+      if (region == 2) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            uint2 w2;
+            w2.x = pack_bf16(acc[i][j][4 * g], acc[i][j][4 * g + 1]);
+            w2.y = pack_bf16(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            *(uint2*)(dst + j * 32 + 8 * g) = w2;
+          }
+      } else {
+        const int P = hd >> 6;                          // blocks per half head: 1 (hd 64) or 2 (hd 128)
+        const float2* cs = ra.table + (size_t)ra.pos[row] * half + feat_l;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if ((j / P) & 1) continue;                    // second halves are written with their partner
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float2* t = cs + (j % P) * 32 + 8 * g;
+            const float4 t01 = *(const float4*)t, t23 = *(const float4*)(t + 2);
+            const float c[4] = {t01.x, t01.z, t23.x, t23.z}, sn[4] = {t01.y, t01.w, t23.y, t23.w};
+            float lo[4], hi[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float x1 = acc[i][j][4 * g + e], x2 = acc[i][j + P][4 * g + e];
+              lo[e] = x1 * c[e] - x2 * sn[e];
+              hi[e] = x2 * c[e] + x1 * sn[e];
+            }
+            uint2 w2;
+            w2.x = pack_bf16(lo[0], lo[1]); w2.y = pack_bf16(lo[2], lo[3]);
+            *(uint2*)(dst + j * 32 + 8 * g) = w2;
+            w2.x = pack_bf16(hi[0], hi[1]); w2.y = pack_bf16(hi[2], hi[3]);
+            *(uint2*)(dst + (j + P) * 32 + 8 * g) = w2;
+          }
+        }
+      }
+    } else if (EPI == EPI_SWIGLU) {
 #pragma unroll
       for (int j = 0; j < TN; j += 2) {            // block j = gate, block j+1 = up
         uint16_t* cp = C + (size_t)row * ldc + (n0 + (wn * TN + j) * 32) / 2 + feat_l;
@@ -71,7 +118,7 @@ template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
             uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K, int lda,
-            int ldw, int ldc, int tiles_m, int tiles_n, int group_m) {
+            int ldw, int ldc, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
   constexpr int NWAVES = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int A_INSTR = BM / 8 / NWAVES;      // wave-wide 1 KB copies per wave per step
@@ -218,13 +265,13 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #undef LZ_MFMAS
 #undef LZ_SCHED
 
-  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane);
+  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
 }
 
 template <int WM, int WN, int TM, int TN>
 static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* R, int M, int N,
                              int K, int lda, int ldw, int ldc, int epi, int group_m,
-                             hipStream_t st) {
+                             const RopeArgs& ra, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
@@ -241,38 +288,55 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
     }                                                                                            \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)A, (const uint16_t*)W, \
                        (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc, tiles_m,        \
-                       tiles_n, group_m);                                                        \
+                       tiles_n, group_m, ra);                                                    \
   } while (0)
   if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
   else if (epi == EPI_SWIGLU) LZ_GEMM(EPI_SWIGLU);
+  else if (epi == EPI_QKV_ROPE) {
+    if ((TN * 32) % ra.head_dim != 0) return hipErrorInvalidValue;
+    LZ_GEMM(EPI_QKV_ROPE);
+  }
   else return hipErrorInvalidValue;
 #undef LZ_GEMM
   return hipGetLastError();
 }
 
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
-                       int lda, int ldw, int ldc, int epilogue, hipStream_t st) {
+                       int lda, int ldw, int ldc, int epilogue, hipStream_t st, const RopeArgs* rope) {
   if (M <= 0) return hipSuccess;
   if (N % 128 != 0 || K % BK != 0) return hipErrorInvalidValue;
   // Bits 8..15 of `epilogue` force a tile configuration and bits 16..21 a band height (tuning
   // hook for measurements); 0 = choose here.
   int cfg = (epilogue >> 8) & 0xff, group_m = (epilogue >> 16) & 0x3f;
   epilogue &= 0xff;
+  RopeArgs ra{};
+  if (epilogue == EPI_QKV_ROPE) {
+    if (rope == nullptr || (rope->head_dim != 64 && rope->head_dim != 128) ||
+        N != 3 * rope->d_model || rope->d_model % 128 != 0)
+      return hipErrorInvalidValue;
+    ra = *rope;
+  }
   if (group_m == 0) group_m = 4;
   if (cfg == 0) {
     // 256x256 tiles on 8 waves (two per SIMD) have the best reuse and hide LDS latency best;
-    // when they would leave much of the 256 CUs idle, 128x128 tiles on 4 waves win.
+    // when they would leave much of the 256 CUs idle, smaller tiles on 4 waves win.  The
+    // rotary epilogue needs a wave to span a whole head (128 columns for head_dim 128).
     const long big_tiles = (long)((M + 255) / 256) * (N / 256);
-    cfg = (N % 256 == 0 && big_tiles >= 150) ? 3 : 2;
+    if (N % 256 == 0 && big_tiles >= 150) cfg = 3;
+    else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = (N % 256 == 0) ? 4 : 0;
+    else cfg = 2;
+    if (cfg == 0) return hipErrorInvalidValue;
   }
   switch (cfg) {
     case 1: if (N % 256) return hipErrorInvalidValue;   // 256x256, 4 waves of 128x128
-            return launch_cfg<2, 2, 4, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, st);
+            return launch_cfg<2, 2, 4, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 2:                                             // 128x128, 4 waves of 64x64
-            return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, st);
+            return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 3: if (N % 256) return hipErrorInvalidValue;   // 256x256, 8 waves of 64x128
-            return launch_cfg<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, st);
+            return launch_cfg<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
+            return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     default: return hipErrorInvalidValue;
   }
 }

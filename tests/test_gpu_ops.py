@@ -112,33 +112,47 @@ def test_rmsnorm(rows, d):
     _assert_bf16_close(_f64(x), ref, 1e-3, "rmsnorm")
 
 
-# ------------------------------------------------------------------------------------ RoPE split
+# ------------------------------------------------------------------------------------ QKV + RoPE, V^T
 
-@pytest.mark.parametrize("rows,H,hd", [(1, 4, 64), (130, 4, 64), (200, 2, 128), (64, 32, 128)])
-def test_rope_split(rows, H, hd):
+@pytest.mark.parametrize("rows,H,hd", [(1, 4, 64), (130, 4, 64), (200, 2, 128), (300, 32, 128), (2100, 8, 128)])
+def test_qkv_rope(rows, H, hd):
     rng = np.random.default_rng(rows + H + hd)
     d = H * hd
-    qkv = _rand_bf16(rng, (rows, 3 * d))
-    pos_np = np.sort(rng.choice(5000, size=rows, replace=False)).astype(np.int32)
+    x = _rand_bf16(rng, (rows, d))
+    w = _rand_bf16(rng, (3 * d, d), 1.0 / math.sqrt(d))
+    pos_np = np.sort(rng.choice(9000, size=rows, replace=False)).astype(np.int32)
     pos = torch.from_numpy(pos_np).to(DEV)
     max_pos = int(pos_np.max())
     table = torch.empty((max_pos + 1) * (hd // 2) * 2, dtype=torch.float32, device=DEV)
-    vt_ld = (rows + 63) // 64 * 64 + 64
-    q = torch.empty(rows, d, dtype=torch.bfloat16, device=DEV)
-    k = torch.empty_like(q); v = torch.empty_like(q)
-    vt = torch.full((d, vt_ld), 5.0, dtype=torch.bfloat16, device=DEV)
-    B.lazyllm_op_rope_split(qkv, pos, max_pos, table, q, k, v, vt, vt_ld, rows, H, hd, 10000.0)
+    q = torch.full((rows, d), 3.0, dtype=torch.bfloat16, device=DEV)
+    k = torch.full_like(q, 3.0); v = torch.full_like(q, 3.0)
+    B.lazyllm_op_qkv_rope(x, w, pos, max_pos, table, q, k, v, rows, H, hd, 10000.0)
     torch.cuda.synchronize()
-    x = _f64(qkv)
-    q_ref = O.rope(x[:, :d].reshape(rows, H, hd), pos_np, 10000.0).reshape(rows, d)
-    k_ref = O.rope(x[:, d:2 * d].reshape(rows, H, hd), pos_np, 10000.0).reshape(rows, d)
-    _assert_bf16_close(_f64(q), q_ref, 1e-3, "q")
-    _assert_bf16_close(_f64(k), k_ref, 1e-3, "k")
-    assert torch.equal(v, qkv[:, 2 * d:])                                  # v is a plain copy
+    acc = _f64(x) @ _f64(w).T
+    q_ref = O.rope(acc[:, :d].reshape(rows, H, hd), pos_np, 10000.0).reshape(rows, d)
+    k_ref = O.rope(acc[:, d:2 * d].reshape(rows, H, hd), pos_np, 10000.0).reshape(rows, d)
+    _assert_bf16_close(_f64(q), q_ref, 1.0, "q")
+    _assert_bf16_close(_f64(k), k_ref, 1.0, "k")
+    _assert_bf16_close(_f64(v), acc[:, 2 * d:], 1.0, "v")
+    # one rounding only: almost every element is THE nearest bf16 of the fp64 result
+    exact = (_f64(q) == O.round_to_bf16(q_ref)).mean()
+    assert exact > 0.99, exact
+
+
+@pytest.mark.parametrize("rows,H,hd", [(1, 4, 64), (130, 4, 64), (200, 2, 128), (64, 32, 128)])
+def test_v_transpose(rows, H, hd):
+    rng = np.random.default_rng(rows + H + hd + 1)
+    d = H * hd
+    v = _rand_bf16(rng, (rows, d))
+    vt_ld = (rows + 63) // 64 * 64 + 64
+    vt = torch.full((d, vt_ld), 5.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_v_transpose(v, vt, vt_ld, rows, H, hd)
+    torch.cuda.synchronize()
     vtn = _f64(vt)
-    assert np.array_equal(vtn[:, :rows], x[:, 2 * d:].T)                   # transposed copy
+    assert np.array_equal(vtn[:, :rows], _f64(v).T)                        # transposed copy
     pad = (rows + 63) // 64 * 64
     assert np.all(vtn[:, rows:pad] == 0.0)                                 # tail of the last tile zeroed
+    assert np.all(vtn[:, pad:] == 5.0)                                     # nothing beyond
 
 
 # ------------------------------------------------------------------------------------ attention

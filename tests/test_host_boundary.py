@@ -22,7 +22,7 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = B.lib()
     names = _declared_symbols()
-    assert len(names) >= 18
+    assert len(names) >= 20
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(B._SIGNATURES), "binding and header disagree"
