@@ -78,7 +78,9 @@ __device__ __forceinline__ void seq_range(const int32_t* cu, int b, int n_single
 }
 
 // ---- launch interface (host) ------------------------------------------------------------
-enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROPE = 3 };
+// EPI_QKV_ROPE is the caller-facing value; the kernel is instantiated per head size.
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROPE = 3,
+                    EPI_QKV_ROPE64 = 4, EPI_QKV_ROPE128 = 5 };
 
 // Extra operands of the fused QKV + rotary epilogue: q, k, v are [rows, d_model] bf16,
 // table is float2 [positions, head_dim/2] = (cos, sin), pos the original position of each row.

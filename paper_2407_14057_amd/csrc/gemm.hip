@@ -30,8 +30,9 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + (wm * TM + i) * 32 + tok_l;
     if (row >= M) continue;
-    if (EPI == EPI_QKV_ROPE) {
-      const int d = ra.d_model, hd = ra.head_dim, half = hd >> 1;
+    if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
+      constexpr int hd = (EPI == EPI_QKV_ROPE64) ? 64 : 128, half = hd >> 1;
+      const int d = ra.d_model;
       const int col0 = n0 + wn * TN * 32;              // first column of this wave
       const int region = col0 / d;                      // 0 q, 1 k, 2 v (uniform per wave)
       uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)row * d +
@@ -47,11 +48,12 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
             *(uint2*)(dst + j * 32 + 8 * g) = w2;
           }
       } else {
-        const int P = hd >> 6;                          // blocks per half head: 1 (hd 64) or 2 (hd 128)
+        constexpr int P = hd >> 6;                      // blocks per half head: 1 (hd 64) or 2 (hd 128)
         const float2* cs = ra.table + (size_t)ra.pos[row] * half + feat_l;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           if ((j / P) & 1) continue;                    // second halves are written with their partner
+          if (j + P >= TN) continue;
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const float2* t = cs + (j % P) * 32 + 8 * g;
@@ -295,7 +297,9 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
   else if (epi == EPI_SWIGLU) LZ_GEMM(EPI_SWIGLU);
   else if (epi == EPI_QKV_ROPE) {
     if ((TN * 32) % ra.head_dim != 0) return hipErrorInvalidValue;
-    LZ_GEMM(EPI_QKV_ROPE);
+    if (ra.head_dim == 64) LZ_GEMM(EPI_QKV_ROPE64);
+    else if constexpr (TN >= 4) LZ_GEMM(EPI_QKV_ROPE128);
+    else return hipErrorInvalidValue;
   }
   else return hipErrorInvalidValue;
 #undef LZ_GEMM
