@@ -104,6 +104,17 @@ def main() -> int:
                         ("tflops" if is_flop else "gbs"): round(rate / (1e12 if is_flop else 1e9), 1)}
     if args.breakdown:
         print(json.dumps(breakdown, indent=1), file=sys.stderr)
+        by_rows = {}
+        for r in recs:
+            a = by_rows.setdefault((r["step"], r["rows"]), [0.0, 0.0, 0])
+            a[0] += r["ms"]; a[1] += r["work"]; a[2] += 1
+        for (st, rows), (tms, work, cnt) in sorted(by_rows.items()):
+            if st.startswith("gemm") or st == "attention":
+                print("%-14s rows=%6d  avg %8.1f us  %7.1f TFLOP/s" % (st, rows, tms / cnt * 1e3, work / (tms * 1e-3) / 1e12),
+                      file=sys.stderr)
+            else:
+                print("%-14s rows=%6d  avg %8.1f us  %7.1f GB/s" % (st, rows, tms / cnt * 1e3, work / (tms * 1e-3) / 1e9),
+                      file=sys.stderr)
 
     total_flops = sum(by_step[s][1] for s in gemm_steps + ("attention",) if s in by_step) / args.steps
 

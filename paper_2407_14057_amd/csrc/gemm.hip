@@ -306,6 +306,190 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Ping-pong variant of the 256x256x64 tile on 8 waves (4 x 2, each wave 64 x 128).  The two
+// waves that share a SIMD (wave w and w + 4) run the same loop half a step apart: while one
+// is in a COMPUTE phase (16 back-to-back MFMAs, nothing else), the other is in a MEMORY phase
+// (the 12 LDS reads of its next half step, its global -> LDS copies, the waits).  A workgroup
+// barrier closes every phase, so the matrix pipe of each SIMD always has exactly one wave
+// feeding it and that wave's instruction stream is pure MFMA.
+//   phase p:      0      1      2      3      4    ...
+//   waves 0-3:   M(0a)  C(0a)  M(0b)  C(0b)  M(1a) ...       a, b = first / second half of a
+//   waves 4-7:    -     M(0a)  C(0a)  M(0b)  C(0b) ...              64-wide K step
+// The stage of K step t is last read in phase 4t+3, so the copies for step t+1 (issued in
+// M((t+1)... i.e. the M phase that reads (t, a)) land in the other stage; every wave waits for
+// its own copies before the barrier that ends phase 4t+3.
+// ------------------------------------------------------------------------------------------
+template <int EPI>
+__global__ void __launch_bounds__(512)
+gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+               uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K,
+               int lda, int ldw, int ldc, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
+  constexpr int WM = 4, WN = 2, TM = 2, TN = 4, NWAVES = 8;
+  constexpr int BM = 256, BN = 256;
+  constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;    // 4 + 4 copies per wave
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int group = wave >> 2;                    // waves w and w+4 share a SIMD
+
+  int tile_m, tile_n;
+  {
+    const int T = tiles_m * tiles_n;
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, local = pid >> 3;
+    const int per = (T + 7) >> 3;
+    const int tall = (T & 7) == 0 ? 8 : (T & 7);
+    const int np = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    const int width = group_m * tiles_n;
+    const int grp = np / width;
+    const int first_m = grp * group_m;
+    const int gsz = min(tiles_m - first_m, group_m);
+    const int in_group = np - grp * width;
+    tile_m = first_m + in_group % gsz;
+    tile_n = in_group / gsz;
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int crow = lane >> 3;
+  uint32_t a_off[A_INSTR], w_off[W_INSTR];
+#pragma unroll
+  for (int q = 0; q < A_INSTR; ++q) {
+    const int tr = (wave * A_INSTR + q) * 8 + crow;
+    const int cchunk = (lane & 7) ^ swz64(tr);
+    int r = m0 + tr;
+    r = r < M ? r : M - 1;
+    a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
+  }
+#pragma unroll
+  for (int q = 0; q < W_INSTR; ++q) {
+    const int tr = (wave * W_INSTR + q) * 8 + crow;
+    const int cchunk = (lane & 7) ^ swz64(tr);
+    int r = n0 + tr;
+    r = r < N ? r : N - 1;
+    w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
+  }
+  auto issue = [&](int stage, int k0) {
+    char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
+    char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
+    const char* ga = (const char*)A + (size_t)k0 * 2;
+    const char* gw = (const char*)W + (size_t)k0 * 2;
+#pragma unroll
+    for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
+#pragma unroll
+    for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], sw + q * 1024);
+  };
+
+  uint32_t koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    koff[ks] = (uint32_t)(((ks * 2 + (lane >> 5)) ^ swz64(lane & 31)) * 16);
+  const uint32_t a_row = (uint32_t)((wm * TM * 32 + (lane & 31)) * ROW_BYTES);
+  const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
+
+  floatx16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  bf16x8_t af[2][TM], wf[2][TN];
+
+#define LZ_MEM_PHASE(st, h)                                                                    \
+  do {                                                                                         \
+    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2) {                                         \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+        af[k2][i] = *(const bf16x8_t*)((st) + a_row + i * 32 * ROW_BYTES + koff[2 * (h) + k2]); \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+        wf[k2][j] = *(const bf16x8_t*)((st) + w_row + j * 32 * ROW_BYTES + koff[2 * (h) + k2]); \
+    }                                                                                          \
+  } while (0)
+#define LZ_COMPUTE_PHASE()                                                                     \
+  do {                                                                                         \
+    __builtin_amdgcn_s_setprio(1);                                                             \
+    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                           \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                         \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[k2][j], af[k2][i], acc[i][j], \
+                                                              0, 0, 0);                        \
+    __builtin_amdgcn_s_setprio(0);                                                             \
+  } while (0)
+  // End of a phase: nothing may be scheduled across it.  The barrier is the bare instruction:
+  // __syncthreads() would also drain vmcnt, i.e. wait for the copies that were just issued and
+  // have a whole K step to land; the waits that ARE needed are written out at each phase end.
+#define LZ_PHASE_END()                                                                         \
+  do {                                                                                         \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+    asm volatile("s_barrier" ::: "memory");                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  } while (0)
+
+  const int KT = K / BK;
+  issue(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (group == 1) LZ_PHASE_END();                 // the second group starts one phase later
+  for (int kt = 0; kt < KT; ++kt) {
+    const char* cur = lds + (kt & 1) * STAGE_BYTES;
+    // memory phase, first half; the other stage was last read one phase ago
+    LZ_MEM_PHASE(cur, 0);
+    if (kt + 1 < KT) issue((kt + 1) & 1, (kt + 1) * BK);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    LZ_PHASE_END();
+    LZ_COMPUTE_PHASE();
+    LZ_PHASE_END();
+    LZ_MEM_PHASE(cur, 1);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    LZ_PHASE_END();
+    LZ_COMPUTE_PHASE();
+    if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    LZ_PHASE_END();
+  }
+  if (group == 0) LZ_PHASE_END();
+#undef LZ_MEM_PHASE
+#undef LZ_COMPUTE_PHASE
+#undef LZ_PHASE_END
+  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
+}
+
+static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R, int M, int N,
+                            int K, int lda, int ldw, int ldc, int epi, int group_m,
+                            const RopeArgs& ra, hipStream_t st) {
+  constexpr int LDS_BYTES = 2 * (256 + 256) * ROW_BYTES;
+  if (N % 256 != 0) return hipErrorInvalidValue;
+  const int tiles_m = (M + 255) / 256, tiles_n = N / 256;
+  dim3 grid(tiles_m * tiles_n), block(512);
+#define LZ_GEMM(E)                                                                               \
+  do {                                                                                           \
+    auto kern = gemm_pp_kernel<E>;                                                               \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)A, (const uint16_t*)W, \
+                       (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc, tiles_m,        \
+                       tiles_n, group_m, ra);                                                    \
+  } while (0)
+  if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
+  else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
+  else if (epi == EPI_SWIGLU) LZ_GEMM(EPI_SWIGLU);
+  else if (epi == EPI_QKV_ROPE) {
+    if (ra.head_dim == 64) LZ_GEMM(EPI_QKV_ROPE64);
+    else LZ_GEMM(EPI_QKV_ROPE128);
+  }
+  else return hipErrorInvalidValue;
+#undef LZ_GEMM
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
                        int lda, int ldw, int ldc, int epilogue, hipStream_t st, const RopeArgs* rope) {
   if (M <= 0) return hipSuccess;
@@ -323,11 +507,11 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
   }
   if (group_m == 0) group_m = 4;
   if (cfg == 0) {
-    // 256x256 tiles on 8 waves (two per SIMD) have the best reuse and hide LDS latency best;
-    // when they would leave much of the 256 CUs idle, smaller tiles on 4 waves win.  The
+    // 256x256 tiles on 8 waves in ping-pong phases have the best reuse and keep the matrix pipe
+    // fed; when they would leave much of the 256 CUs idle, smaller tiles on 4 waves win.  The
     // rotary epilogue needs a wave to span a whole head (128 columns for head_dim 128).
     const long big_tiles = (long)((M + 255) / 256) * (N / 256);
-    if (N % 256 == 0 && big_tiles >= 150) cfg = 3;
+    if (N % 256 == 0 && big_tiles >= 150) cfg = 5;
     else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = (N % 256 == 0) ? 4 : 0;
     else cfg = 2;
     if (cfg == 0) return hipErrorInvalidValue;
@@ -341,6 +525,8 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_cfg<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 5:                                             // 256x256, 8 waves, ping-pong phases
+            return launch_pp(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     default: return hipErrorInvalidValue;
   }
 }
