@@ -5,13 +5,22 @@
 namespace lz {
 
 // ------------------------------------------------------------------------------------------
-// Scoring, pass 1: z[h][j] = q_last[h] . k[j][h] / sqrt(hd) for every token j, plus each
-// workgroup's (max, sum exp) per head.  A wave streams whole token rows (all heads, 16-byte
-// chunks); K is read exactly once.  Lane l owns chunks l + 64*i of the row; one head is HD/8
-// consecutive chunks, so a head's dot product is a reduction over HD/8 adjacent lanes.
+// Scoring (Eq. 1) in three launches.
+//   1. score_logits: z[h][j] = q_last[h] . k[j][h] / sqrt(hd) for every token j, plus each
+//      workgroup's (max, sum exp) per head.  A wave streams whole token rows (all heads, 16-byte
+//      chunks), two rows in flight; K is read exactly once.  Lane l owns chunks l + 64*i of the
+//      row; one head is HD/8 consecutive chunks, so a head's dot product is a DPP reduction over
+//      HD/8 adjacent lanes.  Tokens per workgroup (8..64) grow with the sequence so that short
+//      sequences still fill the chip and long ones amortise the per-workgroup work.
+//   2. score_stats: one workgroup per sequence folds the partials into (max_h, 1/Z_h), in a
+//      fixed order (deterministic).
+//   3. score_finish: s[j] = (1/H) sum_h exp(z[h][j] - max_h) / Z_h, heads added in order.
 // ------------------------------------------------------------------------------------------
-constexpr int SCORE_TOK = 8;         // tokens per workgroup (2 per wave, both in flight)
 constexpr int SCORE_MAX_HEADS = 256;
+
+__host__ __device__ inline int score_tok_per_wg(int max_rows) {
+  return max_rows >= 65536 ? 64 : max_rows >= 16384 ? 32 : max_rows >= 6144 ? 16 : 8;
+}
 
 // Sum over groups of LPH (8 or 16) adjacent lanes with DPP moves (no LDS traffic); every lane
 // of a group ends up with the group's sum.
@@ -30,14 +39,15 @@ __global__ void __launch_bounds__(256)
 score_logits_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     float* __restrict__ z, float2* __restrict__ part,
                     const int32_t* __restrict__ cu, int n_single, int n_heads, int z_ld,
-                    float scale) {
+                    float scale, int tok) {
   constexpr int LPH = HD / 8;                   // lanes per head
-  __shared__ float zs[SCORE_TOK][SCORE_MAX_HEADS + 1];
+  extern __shared__ float zs[];                 // [tok][n_heads + 1]
+  const int zrow = n_heads + 1;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.y;
   int row0, n;
   seq_range(cu, b, n_single, row0, n);
-  const int t0 = blockIdx.x * SCORE_TOK;
+  const int t0 = blockIdx.x * tok;
   if (t0 >= n) return;
   const int d = n_heads * HD, vpr = d / 8;
   const uint4* qrow = (const uint4*)(q + (size_t)(row0 + n - 1) * d);
@@ -52,8 +62,9 @@ score_logits_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
       for (int e = 0; e < 8; ++e) qf[i][e] = 0.f;
   }
 
-  {
-    const int tl0 = wave * 2;                    // local token index of this wave's pair
+  const int tpw = tok >> 2;                      // tokens per wave, a multiple of 2
+  for (int tl0 = wave * tpw; tl0 < (wave + 1) * tpw; tl0 += 2) {
+    if (t0 + tl0 >= n) break;
     uint4 kv[2][NV];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
@@ -77,48 +88,43 @@ score_logits_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         for (int e = 0; e < 8; ++e) p += qf[i][e] * kf[e];
         p = group_sum<LPH>(p);
         const int head = (lane + 64 * i) / LPH;
-        if ((lane % LPH) == 0 && head < n_heads) zs[tl0 + u][head] = p * scale;
+        if ((lane % LPH) == 0 && head < n_heads) zs[(tl0 + u) * zrow + head] = p * scale;
       }
     }
   }
   __syncthreads();
-  const int nt = min(SCORE_TOK, n - t0);
+  const int nt = min(tok, n - t0);
   // coalesced write of z[h][t0 .. t0+nt) and the workgroup's per-head partials
-  for (int idx = threadIdx.x; idx < n_heads * SCORE_TOK; idx += 256) {
-    const int h = idx / SCORE_TOK, t = idx % SCORE_TOK;
-    if (t < nt) z[(size_t)h * z_ld + row0 + t0 + t] = zs[t][h];
+  for (int idx = threadIdx.x; idx < n_heads * tok; idx += 256) {
+    const int h = idx / tok, t = idx % tok;
+    if (t < nt) z[(size_t)h * z_ld + row0 + t0 + t] = zs[t * zrow + h];
   }
   for (int h = threadIdx.x; h < n_heads; h += 256) {
     float mx = -INFINITY;
-    for (int t = 0; t < nt; ++t) mx = fmaxf(mx, zs[t][h]);
+    for (int t = 0; t < nt; ++t) mx = fmaxf(mx, zs[t * zrow + h]);
     float sum = 0.f;
-    for (int t = 0; t < nt; ++t) sum += __expf(zs[t][h] - mx);
+    for (int t = 0; t < nt; ++t) sum += __expf(zs[t * zrow + h] - mx);
     part[((size_t)b * gridDim.x + blockIdx.x) * n_heads + h] = make_float2(mx, sum);
   }
 }
 
-// Scoring, pass 2: combine the partials into each head's (max, normaliser), then
-// s[j] = (1/H) sum_h exp(z[h][j] - max_h) / Z_h, heads added in a fixed order.
 __global__ void __launch_bounds__(256)
-score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ part,
-                    float* __restrict__ s, const int32_t* __restrict__ cu, int n_single,
-                    int n_heads, int z_ld, int parts_per_seq) {
+score_stats_kernel(const float2* __restrict__ part, float2* __restrict__ hstat,
+                   const int32_t* __restrict__ cu, int n_single, int n_heads, int parts_per_seq,
+                   int tok) {
   __shared__ float2 grp[256];
-  __shared__ float hmax[SCORE_MAX_HEADS], hinv[SCORE_MAX_HEADS];
-  const int b = blockIdx.y;
+  const int b = blockIdx.x;
   int row0, n;
   seq_range(cu, b, n_single, row0, n);
-  const int t0 = blockIdx.x * 256;
-  if (t0 >= n) return;
-  const int nparts = (n + SCORE_TOK - 1) / SCORE_TOK;
-  const int groups = max(1, 256 / n_heads);
+  const int nparts = (n + tok - 1) / tok;
   const float2* p0 = part + (size_t)b * parts_per_seq * n_heads;
   for (int hb = 0; hb < n_heads; hb += 256) {           // heads in slabs of up to 256
     const int hcount = min(256, n_heads - hb);
+    const int groups = max(1, 256 / hcount);
     const int g = threadIdx.x / hcount, hl = threadIdx.x % hcount;
     float mx = -INFINITY, sum = 0.f;
     if (g < groups) {
-      // eight independent loads in flight per round: the combine is latency-bound otherwise
+      // eight independent loads in flight per round: the fold is latency-bound otherwise
       for (int i0 = g; i0 < nparts; i0 += 8 * groups) {
         float2 pr[8];
 #pragma unroll
@@ -147,26 +153,40 @@ score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ part
         const float2 pr = grp[gg * hcount + threadIdx.x];
         if (pr.y > 0.f) Z += pr.y * __expf(pr.x - M);
       }
-      hmax[hb + threadIdx.x] = M;
-      hinv[hb + threadIdx.x] = 1.0f / Z;
+      hstat[(size_t)b * n_heads + hb + threadIdx.x] = make_float2(M, 1.0f / Z);
     }
     __syncthreads();
   }
+}
+
+__global__ void __launch_bounds__(256)
+score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ hstat,
+                    float* __restrict__ s, const int32_t* __restrict__ cu, int n_single,
+                    int n_heads, int z_ld) {
+  __shared__ float2 hs[SCORE_MAX_HEADS];
+  const int b = blockIdx.y;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const int t0 = blockIdx.x * 256;
+  if (t0 >= n) return;
+  for (int h = threadIdx.x; h < n_heads; h += 256) hs[h] = hstat[(size_t)b * n_heads + h];
+  __syncthreads();
   const int t = t0 + threadIdx.x;
   if (t < n) {
     float acc = 0.f;
     for (int h = 0; h < n_heads; ++h)
-      acc += __expf(z[(size_t)h * z_ld + row0 + t] - hmax[h]) * hinv[h];
+      acc += __expf(z[(size_t)h * z_ld + row0 + t] - hs[h].x) * hs[h].y;
     s[row0 + t] = acc / (float)n_heads;
   }
 }
 
+// scratch layout: z[H][total_rows] fp32 | hstat[batch][H] float2 | partials (upper bound)
 size_t score_scratch_bytes(int total_rows, int batch, int n_heads) {
-  // z[H][total_rows] fp32, then partials [batch][ceil(total/16)+1][H] float2 (upper bound)
   size_t zb = (size_t)n_heads * total_rows * sizeof(float);
   zb = (zb + 255) & ~(size_t)255;
-  size_t parts = (size_t)batch * ((size_t)(total_rows + SCORE_TOK - 1) / SCORE_TOK + 1);
-  return zb + parts * n_heads * sizeof(float2) + 256;
+  size_t hb = ((size_t)batch * n_heads * sizeof(float2) + 255) & ~(size_t)255;
+  size_t parts = (size_t)batch * ((size_t)(total_rows + 7) / 8 + 1);
+  return zb + hb + parts * n_heads * sizeof(float2) + 256;
 }
 
 hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, const int32_t* cu,
@@ -177,14 +197,18 @@ hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, c
   float* z = (float*)scratch;
   size_t zb = (size_t)n_heads * total_rows * sizeof(float);
   zb = (zb + 255) & ~(size_t)255;
-  float2* part = (float2*)((char*)scratch + zb);
-  const int parts_per_seq = (max_rows + SCORE_TOK - 1) / SCORE_TOK;
+  float2* hstat = (float2*)((char*)scratch + zb);
+  size_t hb = ((size_t)batch * n_heads * sizeof(float2) + 255) & ~(size_t)255;
+  float2* part = (float2*)((char*)scratch + zb + hb);
+  const int tok = score_tok_per_wg(max_rows);
+  const int parts_per_seq = (max_rows + tok - 1) / tok;
   const int vpr = n_heads * head_dim / 8, nv = (vpr + 63) / 64;
   const float scale = 1.0f / sqrtf((float)head_dim);
+  const size_t lds = (size_t)tok * (n_heads + 1) * sizeof(float);
   dim3 grid(parts_per_seq, batch), block(256);
 #define LZ_SCORE(HD, NV)                                                                        \
-  hipLaunchKernelGGL((score_logits_kernel<HD, NV>), grid, block, 0, st, (const uint16_t*)q,      \
-                     (const uint16_t*)k, z, part, cu, n_single, n_heads, total_rows, scale)
+  hipLaunchKernelGGL((score_logits_kernel<HD, NV>), grid, block, lds, st, (const uint16_t*)q,    \
+                     (const uint16_t*)k, z, part, cu, n_single, n_heads, total_rows, scale, tok)
   if (head_dim == 128) {
     if (nv <= 1) LZ_SCORE(128, 1);
     else if (nv <= 2) LZ_SCORE(128, 2);
@@ -205,8 +229,12 @@ hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, c
 #undef LZ_SCORE
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(score_stats_kernel, dim3(batch), dim3(256), 0, st, part, hstat, cu, n_single,
+                     n_heads, parts_per_seq, tok);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(score_finish_kernel, dim3((max_rows + 255) / 256, batch), dim3(256), 0, st, z,
-                     part, s, cu, n_single, n_heads, total_rows, parts_per_seq);
+                     hstat, s, cu, n_single, n_heads, total_rows);
   return hipGetLastError();
 }
 
