@@ -212,10 +212,14 @@ int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* 
  * R[M,N] (row stride ldc) the residual stream; C may alias R.
  * epilogue 2 (SwiGLU): W holds gate and up rows interleaved in blocks of 32
  * (rows 64j..64j+31 gate, 64j+32..64j+63 up), C[M,N/2] = silu(gate) * up.
- * Requires N % 128 == 0, K % 64 == 0, 16-byte aligned rows. */
+ * Requires N % 128 == 0, K % 64 == 0, 16-byte aligned rows.
+ * workspace: optional device scratch of lazyllm_op_gemm_workspace_bytes() (256-byte
+ * aligned) that lets epilogues 0 and 1 use the stream-K schedule for shapes whose tile
+ * count does not divide over the CUs; NULL = never. */
+size_t lazyllm_op_gemm_workspace_bytes(void);
 int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,
                     int32_t K, int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue,
-                    void* hip_stream);
+                    void* workspace, size_t ws_bytes, void* hip_stream);
 
 /* x = h * rsqrt(mean(h^2) + eps) * gain, bf16 in and out, rows of width d. */
 int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d,

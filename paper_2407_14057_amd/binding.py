@@ -91,9 +91,10 @@ _SIGNATURES = {
     "lazyllm_profile_begin": (C.c_int, []),
     "lazyllm_profile_end": (C.c_int, [C.POINTER(lazyllm_profile_record), C.c_int32,
                                       C.POINTER(C.c_int32)]),
+    "lazyllm_op_gemm_workspace_bytes": (C.c_size_t, []),
     "lazyllm_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                  C.c_void_p]),
+                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "lazyllm_op_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_float, C.c_void_p]),
     "lazyllm_op_qkv_rope": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -261,9 +262,14 @@ def lazyllm_profile_end(capacity: int = 65536) -> List[Dict[str, float]]:
 
 # ---------------------------------------------------------------------------- single steps
 
-def lazyllm_op_gemm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, stream=None) -> None:
+def lazyllm_op_gemm_workspace_bytes() -> int:
+    return int(lib().lazyllm_op_gemm_workspace_bytes())
+
+
+def lazyllm_op_gemm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, stream=None, workspace=None) -> None:
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lazyllm_op_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(R), M, N, K, lda, ldw, ldc,
-                                 epilogue, _stream_ptr(stream)))
+                                 epilogue, _ptr(workspace), wsb, _stream_ptr(stream)))
 
 
 def lazyllm_op_rmsnorm(h, gain, x, rows, d, eps, stream=None) -> None:

@@ -142,7 +142,7 @@ void build_stages(int n_layers, const lazyllm_keep* sched, int n_sched, const in
 
 // ---- workspace layout -------------------------------------------------------------------
 struct Workspace {
-  size_t h0, h1, xa, q, o, vt, act, score, rope, keep_idx, prune_idx, xf, total;
+  size_t h0, h1, xa, q, o, vt, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, total;
 };
 
 void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_seqlen,
@@ -163,6 +163,7 @@ void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_s
   w->keep_idx = take((size_t)T * 4);
   w->prune_idx = take((size_t)T * 4);
   w->xf = take((size_t)batch * d * 4);
+  w->gemm_ws = take(gemm_workspace_bytes());
   w->total = off;
 }
 
@@ -491,14 +492,16 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
            launch_attention(W + ws.q, res->k[l], W + ws.vt, W + ws.o, cu, cu_vt + s * BW, 0, B,
                             stg.max_rows[s], (int)stg.vt_ld[s], H, hd, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
-           launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st));
+           launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st, nullptr,
+                       W + ws.gemm_ws, gemm_workspace_bytes()));
     LZ_RUN(LAZYLLM_STEP_RMSNORM, l, n, 2.0 * n * rowb,
            launch_rmsnorm(h, m->ffn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, n, 2.0 * n * 2.0 * (double)c->d_ffn * dd,
            launch_gemm(W + ws.xa, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp,
                        EPI_SWIGLU, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, n, 2.0 * n * (double)c->d_ffn * dd,
-           launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st));
+           launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st, nullptr,
+                       W + ws.gemm_ws, gemm_workspace_bytes()));
   }
   const int s_last = stg.stage_of_layer[L - 1];
   if (flags & LAZYLLM_KEEP_HIDDEN) {
@@ -555,9 +558,11 @@ int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* 
 
 // ---- single steps -------------------------------------------------------------------------
 
+size_t lazyllm_op_gemm_workspace_bytes(void) { return gemm_workspace_bytes(); }
+
 int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,
                     int32_t K, int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue,
-                    void* hip_stream) {
+                    void* workspace, size_t ws_bytes, void* hip_stream) {
   if (!A || !W || !C || M < 0 || N <= 0 || K <= 0) return LAZYLLM_EINVAL;
   if (N % 128 != 0 || K % 64 != 0 || lda % 8 != 0 || ldw % 8 != 0 || ldc % 4 != 0)
     return LAZYLLM_EINVAL;
@@ -566,7 +571,9 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
   if (epilogue < 0 || epi > 2 || (epi == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
   if (ldc < (epi == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
   if (M == 0) return LAZYLLM_OK;
-  LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream));
+  if (workspace != nullptr && ((uintptr_t)workspace & 255) != 0) return LAZYLLM_EINVAL;
+  LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, nullptr,
+                     workspace, ws_bytes));
   return LAZYLLM_OK;
 }
 

@@ -93,9 +93,11 @@ struct RopeArgs {
   int d_model, head_dim;
 };
 
+// sk_ws: optional scratch of gemm_workspace_bytes() for the stream-K variant (fp32 partial tiles).
+size_t gemm_workspace_bytes();
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
                        int lda, int ldw, int ldc, int epilogue, hipStream_t st,
-                       const RopeArgs* rope = nullptr);
+                       const RopeArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
 
 hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st);
 

@@ -490,8 +490,266 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Stream-K on 128x128 tiles (4 waves of 64x64): for shapes whose tile count does not divide
+// over the 256 CUs.  The (tile, K step) pairs are numbered tile-major and cut into G equal
+// contiguous ranges, one per persistent workgroup (two fit on a CU).  A workgroup finishes
+// every tile it covers completely through the normal epilogue; the at most two tiles it shares
+// with a neighbour are written as fp32 partial sums into slot [g][0] (its first tile) or
+// [g][1] (its last tile), and a second kernel adds the pieces of each shared tile in workgroup
+// order (deterministic) and applies the epilogue.  No workgroup ever waits for another.
+// ------------------------------------------------------------------------------------------
+constexpr int SK_BM = 128, SK_BN = 128, SK_TILE_ELEMS = SK_BM * SK_BN;
+
+__host__ __device__ inline long long sk_begin(int g, long long U, int G) { return (long long)g * U / G; }
+
+template <int EPI>
+__global__ void __launch_bounds__(256)
+gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+               uint16_t* __restrict__ C, const uint16_t* __restrict__ R, float* __restrict__ partial,
+               int M, int N, int K, int lda, int ldw, int ldc, int tiles_m, int tiles_n, int G) {
+  constexpr int WM = 2, WN = 2, TM = 2, TN = 2, NWAVES = 4;
+  constexpr int BM = SK_BM, BN = SK_BN;
+  constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  // consecutive ranges on one XCD (ids are dealt round-robin over the 8 XCDs)
+  const int g = (int)(blockIdx.x & 7) * (G >> 3) + (int)(blockIdx.x >> 3);
+  const int KT = K / BK;
+  const long long U = (long long)tiles_m * tiles_n * KT;
+  const long long u0 = sk_begin(g, U, G), u1 = sk_begin(g + 1, U, G);
+  if (u0 >= u1) return;
+  const int first_tile = (int)(u0 / KT);
+
+  uint32_t koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    koff[ks] = (uint32_t)(((ks * 2 + (lane >> 5)) ^ swz64(lane & 31)) * 16);
+  const uint32_t a_row = (uint32_t)((wm * TM * 32 + (lane & 31)) * ROW_BYTES);
+  const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
+  const int crow = lane >> 3;
+  RopeArgs ra{};
+
+  long long u = u0;
+  while (u < u1) {
+    const int tile = (int)(u / KT);
+    const int ka = (int)(u - (long long)tile * KT);
+    const int kb = (int)min((long long)KT, ka + (u1 - u));
+    const int n_it = kb - ka;
+    const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+    uint32_t a_off[A_INSTR], w_off[W_INSTR];
+#pragma unroll
+    for (int q = 0; q < A_INSTR; ++q) {
+      const int tr = (wave * A_INSTR + q) * 8 + crow;
+      const int cchunk = (lane & 7) ^ swz64(tr);
+      int r = m0 + tr;
+      r = r < M ? r : M - 1;
+      a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
+    }
+#pragma unroll
+    for (int q = 0; q < W_INSTR; ++q) {
+      const int tr = (wave * W_INSTR + q) * 8 + crow;
+      const int cchunk = (lane & 7) ^ swz64(tr);
+      int r = n0 + tr;
+      r = r < N ? r : N - 1;
+      w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
+    }
+    auto issue = [&](int stage, int kt) {
+      char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
+      char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
+      const char* ga = (const char*)A + (size_t)kt * BK * 2;
+      const char* gw = (const char*)W + (size_t)kt * BK * 2;
+#pragma unroll
+      for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
+#pragma unroll
+      for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], sw + q * 1024);
+    };
+
+    floatx16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    bf16x8_t af[2][TM], wf[2][TN];
+#define LZ_LOAD_FRAGS(buf, st, ks)                                                            \
+  do {                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+        af[buf][i] = *(const bf16x8_t*)((st) + a_row + i * 32 * ROW_BYTES + koff[ks]);        \
+    _Pragma("unroll") for (int j = 0; j < TN; ++j)                                            \
+        wf[buf][j] = *(const bf16x8_t*)((st) + w_row + j * 32 * ROW_BYTES + koff[ks]);        \
+  } while (0)
+#define LZ_MFMAS(buf)                                                                         \
+  do {                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i)                                            \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                          \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i],           \
+                                                            acc[i][j], 0, 0, 0);              \
+  } while (0)
+    issue(0, ka);
+    if (n_it > 1) issue(1, ka + 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    LZ_LOAD_FRAGS(0, lds, 0);
+    for (int it = 0; it < n_it; ++it) {
+      const char* cur = lds + (it & 1) * STAGE_BYTES;
+      const char* nxt = lds + ((it + 1) & 1) * STAGE_BYTES;
+      LZ_LOAD_FRAGS(1, cur, 1);
+      LZ_MFMAS(0);
+      LZ_LOAD_FRAGS(0, cur, 2);
+      LZ_MFMAS(1);
+      LZ_LOAD_FRAGS(1, cur, 3);
+      LZ_MFMAS(0);
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (it + 2 < n_it) issue(it & 1, ka + it + 2);
+      if (it + 1 < n_it) LZ_LOAD_FRAGS(0, nxt, 0);
+      LZ_MFMAS(1);
+    }
+#undef LZ_LOAD_FRAGS
+#undef LZ_MFMAS
+    if (ka == 0 && kb == KT) {
+      gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
+    } else {
+      // fp32 partial sums of this piece, tile-local row-major [128][128]
+      float* dst = partial + ((size_t)g * 2 + (tile == first_tile ? 0 : 1)) * SK_TILE_ELEMS;
+      const int tok_l = lane & 31, feat_l = 4 * (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            float4 v = make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2],
+                                   acc[i][j][4 * q4 + 3]);
+            *(float4*)(dst + ((wm * TM + i) * 32 + tok_l) * SK_BN + (wn * TN + j) * 32 + 8 * q4 +
+                       feat_l) = v;
+          }
+    }
+    u += n_it;
+    __syncthreads();            // the next piece refills stage 0: everyone must be done reading
+  }
+}
+
+// Adds the pieces of every tile that more than one workgroup worked on and applies the
+// epilogue.  One workgroup per tile; tiles finished by a single workgroup return at once.
+template <int EPI>
+__global__ void __launch_bounds__(256)
+gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C,
+                     const uint16_t* __restrict__ R, int M, int ldc, int tiles_m, int KT,
+                     long long U, int G) {
+  const int tile = blockIdx.x;
+  const long long ua = (long long)tile * KT, ub = ua + KT - 1;
+  // owner(u) = largest g with sk_begin(g) <= u
+  int g_first = (int)(ua * G / U), g_last = (int)(ub * G / U);
+  while (g_first + 1 < G && sk_begin(g_first + 1, U, G) <= ua) ++g_first;
+  while (g_first > 0 && sk_begin(g_first, U, G) > ua) --g_first;
+  while (g_last + 1 < G && sk_begin(g_last + 1, U, G) <= ub) ++g_last;
+  while (g_last > 0 && sk_begin(g_last, U, G) > ub) --g_last;
+  if (g_first == g_last) return;
+  // piece pointers are worked out by one thread per batch of 64 (the range arithmetic is
+  // 64-bit division); one float4 per thread: blockIdx.y picks an 8-row slab of the tile
+  constexpr int MAX_PIECES = 64;
+  __shared__ const float* piece[MAX_PIECES];
+  __shared__ int n_piece, g_next;
+  const int tile_m = tile % tiles_m, tile_n = tile / tiles_m;
+  const int m0 = tile_m * SK_BM, n0 = tile_n * SK_BN;
+  const int r = blockIdx.y * 8 + (threadIdx.x >> 5), c4 = (threadIdx.x & 31) * 4;
+  const int row = m0 + r;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (threadIdx.x == 0) g_next = g_first;
+  __syncthreads();
+  while (true) {
+    if (threadIdx.x == 0) {
+      int np = 0, g = g_next;
+      for (; g <= g_last && np < MAX_PIECES; ++g) {
+        const long long b0 = sk_begin(g, U, G), b1 = sk_begin(g + 1, U, G);
+        if (b0 >= b1) continue;                                        // empty range
+        const int slot = ((int)(b0 / KT) == tile) ? 0 : 1;
+        piece[np++] = partial + ((size_t)g * 2 + slot) * SK_TILE_ELEMS;
+      }
+      n_piece = np;
+      g_next = g;
+    }
+    __syncthreads();
+    const int np = n_piece;
+    const bool more = g_next <= g_last;
+    if (row < M) {
+      int p = 0;
+      for (; p + 4 <= np; p += 4) {               // four loads in flight, summed in piece order
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *(const float4*)(piece[p + u] + r * SK_BN + c4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+      }
+      for (; p < np; ++p) {
+        const float4 v = *(const float4*)(piece[p] + r * SK_BN + c4);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
+    }
+    __syncthreads();
+    if (!more) break;
+  }
+  if (row < M) {
+    const size_t off = (size_t)row * ldc + n0 + c4;
+    if (EPI == EPI_RESIDUAL) {
+      const uint2 r2 = *(const uint2*)(R + off);
+      acc.x += bf16_lo(r2.x); acc.y += bf16_hi(r2.x);
+      acc.z += bf16_lo(r2.y); acc.w += bf16_hi(r2.y);
+    }
+    uint2 w2;
+    w2.x = pack_bf16(acc.x, acc.y);
+    w2.y = pack_bf16(acc.z, acc.w);
+    *(uint2*)(C + off) = w2;
+  }
+}
+
+constexpr int SK_GRID = 512;
+size_t gemm_workspace_bytes() { return (size_t)SK_GRID * 2 * SK_TILE_ELEMS * sizeof(float); }
+
+static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R, float* partial,
+                            int M, int N, int K, int lda, int ldw, int ldc, int epi,
+                            hipStream_t st) {
+  constexpr int LDS_BYTES = 2 * (SK_BM + SK_BN) * ROW_BYTES;
+  const int tiles_m = (M + SK_BM - 1) / SK_BM, tiles_n = N / SK_BN, KT = K / BK;
+  const long long U = (long long)tiles_m * tiles_n * KT;
+  const int G = SK_GRID;
+#define LZ_GEMM(E)                                                                               \
+  do {                                                                                           \
+    auto kern = gemm_sk_kernel<E>;                                                               \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, dim3(G), dim3(256), LDS_BYTES, st, (const uint16_t*)A,              \
+                       (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, partial, M, N, K,   \
+                       lda, ldw, ldc, tiles_m, tiles_n, G);                                      \
+    hipError_t e = hipGetLastError();                                                            \
+    if (e != hipSuccess) return e;                                                               \
+    hipLaunchKernelGGL(gemm_sk_fixup_kernel<E>, dim3(tiles_m * tiles_n, 16), dim3(256), 0, st,   \
+                       partial, (uint16_t*)C, (const uint16_t*)R, M, ldc, tiles_m, KT, U, G);    \
+  } while (0)
+  if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
+  else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
+  else return hipErrorInvalidValue;
+#undef LZ_GEMM
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
-                       int lda, int ldw, int ldc, int epilogue, hipStream_t st, const RopeArgs* rope) {
+                       int lda, int ldw, int ldc, int epilogue, hipStream_t st, const RopeArgs* rope,
+                       void* sk_ws, size_t sk_ws_bytes) {
   if (M <= 0) return hipSuccess;
   if (N % 128 != 0 || K % BK != 0) return hipErrorInvalidValue;
   // Bits 8..15 of `epilogue` force a tile configuration and bits 16..21 a band height (tuning
@@ -511,7 +769,16 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // fed; when they would leave much of the 256 CUs idle, smaller tiles on 4 waves win.  The
     // rotary epilogue needs a wave to span a whole head (128 columns for head_dim 128).
     const long big_tiles = (long)((M + 255) / 256) * (N / 256);
-    if (N % 256 == 0 && big_tiles >= 150) cfg = 5;
+    // Stream-K pays when the data-parallel grid would leave most CUs idle through a long K
+    // loop (measured at M = 355: O projection 46 -> 40 us, down projection 114 -> 70 us); with
+    // more tiles the 128x128 partial-sum traffic eats the gain (M = 1182: +-5 %).
+    if ((epilogue == EPI_STORE || epilogue == EPI_RESIDUAL) && sk_ws != nullptr &&
+        sk_ws_bytes >= gemm_workspace_bytes()) {
+      const long t128 = (long)((M + 127) / 128) * (N / 128);
+      if (t128 <= 160 && K / BK >= 32) cfg = 6;
+    }
+    if (cfg != 0) {}
+    else if (N % 256 == 0 && big_tiles >= 150) cfg = 5;
     else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = (N % 256 == 0) ? 4 : 0;
     else cfg = 2;
     if (cfg == 0) return hipErrorInvalidValue;
@@ -527,6 +794,9 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 5:                                             // 256x256, 8 waves, ping-pong phases
             return launch_pp(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 6:                                             // 128x128 stream-K + fix-up
+            if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
+            return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -66,6 +66,28 @@ def test_gemm(M, N, K, epi):
     _assert_bf16_close(_f64(Cout), ref, 1.0, "gemm")
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (355, 4096, 4096), (1182, 4096, 1408), (130, 256, 11008),
+                                   (700, 384, 192), (5000, 128, 64)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL])
+def test_gemm_stream_k(M, N, K, epi):
+    """The stream-K schedule (forced) must give the data-parallel kernel's result up to the
+    order of the fp32 partial sums, and the same bits on every run."""
+    rng = np.random.default_rng(M + N + K + epi)
+    A = _rand_bf16(rng, (M, K)); W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    R = _rand_bf16(rng, (M, N))
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    ref = _f64(A) @ _f64(W).T + (_f64(R) if epi == B.EPI_RESIDUAL else 0.0)
+    outs = []
+    for _ in range(2):
+        Cout = R.clone()
+        B.lazyllm_op_gemm(A, W, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N,
+                          epi | (6 << 8), workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(Cout)
+    _assert_bf16_close(_f64(outs[0]), ref, 1.0, "gemm stream-K")
+    assert torch.equal(outs[0], outs[1])
+
+
 def test_gemm_strided_and_edge_rows_untouched():
     rng = np.random.default_rng(5)
     M, N, K = 70, 256, 128

@@ -22,7 +22,8 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = B.lib()
     names = _declared_symbols()
-    assert len(names) >= 20
+    assert len(names) >= 21
+    assert lib.lazyllm_op_gemm_workspace_bytes() > 0
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(B._SIGNATURES), "binding and header disagree"
@@ -89,10 +90,10 @@ def test_null_arguments_return_einval_without_touching_the_gpu():
     import ctypes as C
     arr, ns = B.make_schedule([(1, 500)])
     assert lib.lazyllm_prefill(None, None, None, 16, arr, ns, 0, None, 0, None, 0, None, C.byref(res)) == B.LAZYLLM_EINVAL
-    assert lib.lazyllm_op_gemm(None, None, None, None, 1, 128, 64, 64, 64, 128, 0, None) == B.LAZYLLM_EINVAL
-    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 100, 64, 64, 64, 100, 0, None) == B.LAZYLLM_EINVAL   # N % 128
-    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 128, 60, 64, 64, 128, 0, None) == B.LAZYLLM_EINVAL   # K % 64
-    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 128, 64, 64, 64, 128, 1, None) == B.LAZYLLM_EINVAL   # residual w/o R
+    assert lib.lazyllm_op_gemm(None, None, None, None, 1, 128, 64, 64, 64, 128, 0, None, 0, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 100, 64, 64, 64, 100, 0, None, 0, None) == B.LAZYLLM_EINVAL   # N % 128
+    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 128, 60, 64, 64, 128, 0, None, 0, None) == B.LAZYLLM_EINVAL   # K % 64
+    assert lib.lazyllm_op_gemm(1, 1, 1, None, 4, 128, 64, 64, 64, 128, 1, None, 0, None) == B.LAZYLLM_EINVAL   # residual w/o R
     assert lib.lazyllm_op_select(1, 10, 0, 1, 1, None) == B.LAZYLLM_EINVAL
     assert lib.lazyllm_op_select(1, 10, 11, 1, 1, None) == B.LAZYLLM_EINVAL
     assert lib.lazyllm_op_attention(1, 1, 1, 100, 1, 10, 4, 64, None) == B.LAZYLLM_EINVAL             # vt_ld % 64
