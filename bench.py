@@ -16,6 +16,14 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# Bytes per launch the dominant kernel (gate/up GEMM, SwiGLU epilogue) moves through the L2s'
+# fabric side, averaged over the 32 launches of a 7b_3376 step: rocprofv3 FETCH_SIZE x 2 KiB +
+# WRITE_SIZE x 1 KiB, factors calibrated on a 1 GiB copy (profiles/gemm_attention_7b_3376_pmc.md).
+TRAFFIC_GATE_UP_7B_3376 = 648.05e6 + 40.4e6
+STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<2> (gate/up projection + SiLU*mul)",
+               "gemm_qkv": "gemm_pp_kernel<5> (QKV projection + RoPE)",
+               "gemm_down": "gemm_pp_kernel<1> (down projection + residual)",
+               "gemm_o": "gemm_pp_kernel<1> (O projection + residual)"}
 
 
 def kernel_sweep(args, torch, B) -> int:
@@ -183,9 +191,16 @@ def main() -> int:
     dom = max(gemm_steps, key=lambda s: by_step.get(s, [0, 0, 0])[0])
     dms, dwork, dn = by_step[dom]
     achieved = dwork / (dms * 1e-3) / 1e12                       # TFLOP/s over this step's launches
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel (%s)" % dom, "achieved": round(achieved, 1),
+    traffic = TRAFFIC_GATE_UP_7B_3376 if (dom == "gemm_gate_up" and wl.name == "7b_3376") else None
+    roofline = {"bound": "mfma", "kernel": STEP_KERNEL[dom], "achieved": round(achieved, 1),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "avg_launch_ms": round(dms / dn, 5), "flops_per_launch": dwork / dn, "traffic": None}
+                "avg_launch_ms": round(dms / dn, 5), "flops_per_launch": dwork / dn, "traffic": traffic,
+                "algorithmic_bytes_per_launch": None}
+    if dom == "gemm_gate_up":
+        # operands read once + activation written once, averaged over the step's launches
+        rows_avg = sum(r["rows"] for r in recs if r["step"] == dom) / max(1, dn)
+        roofline["algorithmic_bytes_per_launch"] = round(
+            2.0 * (rows_avg * shape.d_model + 2.0 * shape.d_ffn * shape.d_model + rows_avg * shape.d_ffn))
     total_prof_ms = sum(v[0] for v in by_step.values()) / args.steps
     breakdown = {}
     for s, (tms, work, cnt) in sorted(by_step.items(), key=lambda kv: -kv[1][0]):
