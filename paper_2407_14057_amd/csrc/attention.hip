@@ -1,9 +1,10 @@
 // Causal flash-attention prefill over the compacted token set (tokens are stored in ascending
 // original position, so causality in the compacted order equals causality in the prompt).
 //
-// Workgroup = 4 waves = 128 queries of one head; each wave owns 32 query rows.  Keys advance
-// 64 per step; the K tile [64][HD] and the transposed V tile [HD][64] are copied global -> LDS
-// by global_load_lds into one of two stages.  Both products run on v_mfma_f32_32x32x16_bf16
+// Workgroup = NW waves (4 or 8) = 32*NW queries of one head; each wave owns 32 query rows.
+// Keys advance 64 per step; the K tile [64][HD] and the transposed V tile [HD][64] are copied
+// global -> LDS by global_load_lds into one of NS stages, NS - 1 steps ahead of their use.
+// Both products run on v_mfma_f32_32x32x16_bf16
 // in the transposed orientation, so that every lane owns ONE query column:
 //   S^T[key][q] = K[key][:] . Q[q][:]        A operand = K rows,   B operand = Q rows
 //   O^T[dim][q] = Vt[dim][key] . P^T[key][q]  A operand = Vt rows,  B operand = P^T (registers)
@@ -16,11 +17,15 @@
 
 namespace lz {
 
-constexpr int ATT_BM = 128;   // queries per workgroup
 constexpr int ATT_BN = 64;    // keys per step
 
-template <int HD>
-__global__ void __launch_bounds__(256)
+// Two waves share each SIMD (two 4-wave workgroups per CU, or waves w and w+4 of an 8-wave one).
+// A step is a matrix phase, a vector phase (softmax), a matrix phase; with equal priorities the
+// two waves of a SIMD fall into the same phase and the matrix pipe idles while both do softmax.
+// In the 8-wave form the first four waves run at a higher priority: they proceed as if alone
+// and the other four fill the pipe they leave idle, which puts the pair in opposite phases.
+template <int HD, int NW, int NS>
+__global__ void __launch_bounds__(NW * 64, 2)
 flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                   const uint16_t* __restrict__ vt, uint16_t* __restrict__ o,
                   const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
@@ -30,8 +35,10 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   constexpr int HS = HD / 32;                 // 32-row blocks of O^T
   constexpr int K_TILE = ATT_BN * HD * 2;     // bytes
   constexpr int STAGE = 2 * K_TILE;           // K tile + Vt tile
-  constexpr int K_INSTR = (ATT_BN * CHK / 64) / 4;   // 1 KB copies per wave for the K tile
-  constexpr int V_INSTR = (HD * 8 / 64) / 4;         // ... for the Vt tile
+  constexpr int ATT_BM = 32 * NW;             // queries per workgroup
+  constexpr int K_INSTR = (ATT_BN * CHK / 64) / NW;  // 1 KB copies per wave for the K tile
+  constexpr int V_INSTR = (HD * 8 / 64) / NW;        // ... for the Vt tile
+  static_assert(K_INSTR >= 1 && V_INSTR >= 1, "tile copies must cover every wave");
   constexpr int K_ROWS_PER_INSTR = 64 / CHK;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -42,6 +49,10 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   seq_range(cu, b, n_single, row0, n);
   const int qblocks = (n + ATT_BM - 1) / ATT_BM;
   if ((int)blockIdx.y >= qblocks) return;
+  if (NW == 8) {
+    if (wave < 4) __builtin_amdgcn_s_setprio(1);
+    else __builtin_amdgcn_s_setprio(0);
+  }
   const int qb = qblocks - 1 - blockIdx.y;    // longest blocks first
   const int q0 = qb * ATT_BM;
   const int d = n_heads * HD;
@@ -100,48 +111,86 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
 
   const int q_lo = q0 + wave * 32, q_hi = q_lo + 31;     // this wave's query range
 
-  issue(0, 0);
-  for (int it = 0; it < ntiles; ++it) {
-    const int k0 = it * ATT_BN;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (it + 1 < ntiles) issue((it + 1) & 1, k0 + ATT_BN);
-    if (k0 > q_hi) continue;                 // every key of this tile is in the future
-    const char* st = lds + (it & 1) * STAGE;
-
-    // S^T = K Q^T for the two 32-key blocks
+  // One 64-key step.  The causal mask costs a compare and a select per element, so only steps
+  // that straddle the diagonal of this wave's queries branch into it.  The running
+  // maximum is raised only when a step's maximum exceeds it by more than 2^8 (in the base-2
+  // domain): softmax is invariant to the shift, p stays below 2^8 (fp32 sums and bf16 P keep
+  // their relative precision), and the rescale of the O^T accumulators -- two register-file
+  // moves and a multiply per element -- leaves the common path.  The 1/sqrt(hd) * log2(e) scale
+  // rides in the fused multiply-add that forms the exponent.
+  // LDS reads run one group ahead of the MFMAs that consume them (two buffers of KSTEPS
+  // fragments): the K rows of the second 32-key block are read under the MFMAs of the first,
+  // the first half of the Vt rows under the MFMAs of the second block (they land during the
+  // softmax), the second half under the first half's MFMAs.  The scheduling fences pin that
+  // order; left alone the compiler pairs every MFMA with its own read and waits for it.
+#define LZ_ATT_INTERLEAVE()                                  \
+  _Pragma("unroll") for (int g = 0; g < KSTEPS; ++g) {        \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
+  }
+  auto step = [&](const char* st, int k0, bool masked) {
+    auto kread = [&](int sub, int s) {
+      return *(const bf16x8_t*)(st + k_addr[sub] + (((s * 2 + hi) ^ kx) * 16));
+    };
+    auto vread = [&](int i) {          // i = 4 * h + 2 * sub + t
+      const int chunk = ((i >> 1) & 1) * 4 + (i & 1) * 2 + hi;
+      return *(const bf16x8_t*)(st + v_addr + (i >> 2) * 32 * 128 + ((chunk ^ vx) * 16));
+    };
+    bf16x8_t fa[KSTEPS], fb[KSTEPS];
     floatx16_t sacc[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
 #pragma unroll
-      for (int s = 0; s < KSTEPS; ++s) {
-        const bf16x8_t kf =
-            *(const bf16x8_t*)(st + k_addr[sub] + (((s * 2 + hi) ^ kx) * 16));
-        sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[sub], 0, 0, 0);
-      }
+    for (int s = 0; s < KSTEPS; ++s) fa[s] = kread(0, s);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) fb[s] = kread(1, s);
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s], qf[s], sacc[0], 0, 0, 0);
+    LZ_ATT_INTERLEAVE();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < KSTEPS; ++i) fa[i] = vread(i);
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s], qf[s], sacc[1], 0, 0, 0);
+    LZ_ATT_INTERLEAVE();
+    __builtin_amdgcn_sched_barrier(0);
+    // Register r of block sub is key k0 + 32*sub + 16*(r/8) + 8*hi + r%8.
+    if (masked) {
+      asm volatile("; causal mask" ::: "memory");   // keeps this a real branch
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * sub + 16 * (r / 8) + 8 * hi + (r % 8);
+          if (key > qrow) sacc[sub][r] = -INFINITY;
+        }
     }
-    // scale, causal mask, running max.  Register r of block sub is key
-    // k0 + 32*sub + 16*(r/8) + 8*hi + r%8.
-    const bool need_mask = (k0 + ATT_BN - 1) > q_lo;
-    float mloc = -INFINITY;
+    float mraw = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float sv = sacc[sub][r] * scale_log2e;
-        if (need_mask) {
-          const int key = k0 + 32 * sub + 16 * (r / 8) + 8 * hi + (r % 8);
-          if (key > qrow) sv = -INFINITY;
-        }
-        sacc[sub][r] = sv;
-        mloc = fmaxf(mloc, sv);
+        mraw = fmaxf(mraw, sacc[sub][r]);
       }
+    float mloc = mraw * scale_log2e;
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    const float m_new = fmaxf(m_run, mloc);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.0f) != 0) {
+      // The empty asm keeps this a real branch: the compiler would otherwise run the rescale
+      // every step under a select.
+      const float m_new = fmaxf(m_run, mloc);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+      asm volatile("; raise the running maximum" ::: "memory");
+#pragma unroll
+      for (int h = 0; h < HS; ++h) oacc[h] *= alpha;
+    }
+    const float neg_m = -m_run;
     float psum = 0.f;
     bf16x8_t pf[2][2];
 #pragma unroll
@@ -151,29 +200,52 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
         float p[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          p[j] = __builtin_amdgcn_exp2f(sacc[sub][8 * t + j] - m_new);
+          p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][8 * t + j], scale_log2e, neg_m));
           psum += p[j];
         }
         uint4 packed = pack8(p);
         pf[sub][t] = *reinterpret_cast<bf16x8_t*>(&packed);
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int h = 0; h < HS; ++h)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[h][r] *= alpha;
+    l_run += psum;
     // O^T += Vt P^T
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int h = 0; h < HS; ++h)
+    for (int i = 0; i < KSTEPS; ++i) fb[i] = vread(KSTEPS + i);
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
+    for (int i = 0; i < KSTEPS; ++i)
+      oacc[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], pf[(i >> 1) & 1][i & 1],
+                                                             oacc[i >> 2], 0, 0, 0);
+    LZ_ATT_INTERLEAVE();
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int chunk = sub * 4 + t * 2 + hi;
-          const bf16x8_t vf =
-              *(const bf16x8_t*)(st + v_addr + h * 32 * 128 + ((chunk ^ vx) * 16));
-          oacc[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sub][t], oacc[h], 0, 0, 0);
-        }
+    for (int i = 0; i < KSTEPS; ++i)
+      oacc[HS / 2 + (i >> 2)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+          fb[i], pf[(i >> 1) & 1][i & 1], oacc[HS / 2 + (i >> 2)], 0, 0, 0);
+  };
+#undef LZ_ATT_INTERLEAVE
+
+  // NS stages: the copies of step it + NS - 1 are issued while step it is computed, so a copy
+  // has NS - 1 steps to land.  A bare s_barrier (not __syncthreads, which would make the
+  // compiler wait for every outstanding copy) closes each step: past it, every wave's share
+  // of step it has landed and nobody still reads the stage of step it - 1.
+  constexpr int PER_STEP = K_INSTR + V_INSTR;            // copies one wave issues per step
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < ntiles) issue(t, t * ATT_BN);
+  int stage_c = 0, stage_i = NS - 1;                     // stage computed / stage copied into
+  for (int it = 0; it < ntiles; ++it) {
+    const int k0 = it * ATT_BN;
+    if (it + NS - 1 <= ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    if (it + NS - 1 < ntiles) issue(stage_i, k0 + (NS - 1) * ATT_BN);
+    const char* st = lds + stage_c * STAGE;
+    if (k0 <= q_hi)                          // else every key of this step is in the future
+      step(st, k0, (k0 + ATT_BN - 1) > q_lo);
+    stage_c = stage_c + 1 == NS ? 0 : stage_c + 1;
+    stage_i = stage_i + 1 == NS ? 0 : stage_i + 1;
   }
 
   // ---- normalise and store.  Register r of block h is dim 32h + 8*(r/4) + 4*hi + r%4.
@@ -198,11 +270,14 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
                             int n_heads, int head_dim, hipStream_t st) {
   if (max_rows <= 0) return hipSuccess;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
-  dim3 grid(n_heads, (max_rows + ATT_BM - 1) / ATT_BM, batch), block(256);
-#define LZ_ATT(HD)                                                                               \
+  // 8-wave workgroups (one per CU, four stages) once they fill the chip twice over: they halve
+  // the L2 -> LDS traffic per query.  Otherwise 4-wave ones (two per CU, two stages), which
+  // spread a short sequence over more CUs.
+  const int nw = ((max_rows + 255) / 256) * n_heads * batch >= 512 ? 8 : 4;
+#define LZ_ATT(HD, NW, NS)                                                                       \
   do {                                                                                           \
-    constexpr int LDS_BYTES = 2 * 2 * ATT_BN * HD * 2;                                           \
-    auto kern = flash_attn_kernel<HD>;                                                           \
+    constexpr int LDS_BYTES = NS * 2 * ATT_BN * HD * 2;                                          \
+    auto kern = flash_attn_kernel<HD, NW, NS>;                                                   \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
@@ -210,13 +285,96 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
       if (e != hipSuccess) return e;                                                             \
       attr_set = true;                                                                           \
     }                                                                                            \
+    dim3 grid(n_heads, (max_rows + 32 * NW - 1) / (32 * NW), batch), block(64 * NW);             \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
                        scale_log2e);                                                             \
   } while (0)
-  if (head_dim == 128) LZ_ATT(128);
-  else if (head_dim == 64) LZ_ATT(64);
-  else return hipErrorInvalidValue;
+  if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
+  if (head_dim == 128 && nw == 8) LZ_ATT(128, 8, 4);
+  else if (head_dim == 128) LZ_ATT(128, 4, 2);
+  else if (nw == 8) LZ_ATT(64, 8, 4);
+  else LZ_ATT(64, 4, 2);
+#undef LZ_ATT_INTERLEAVE
+
+  // NS stages: the copies of step it + NS - 1 are issued while step it is computed, so a copy
+  // has NS - 1 steps to land.  A bare s_barrier (not __syncthreads, which would make the
+  // compiler wait for every outstanding copy) closes each step: past it, every wave's share
+  // of step it has landed and nobody still reads the stage of step it - 1.
+  constexpr int PER_STEP = K_INSTR + V_INSTR;            // copies one wave issues per step
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < ntiles) issue(t, t * ATT_BN);
+  int stage_c = 0, stage_i = NS - 1;                     // stage computed / stage copied into
+  for (int it = 0; it < ntiles; ++it) {
+    const int k0 = it * ATT_BN;
+    if (it + NS - 1 <= ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    if (it + NS - 1 < ntiles) issue(stage_i, k0 + (NS - 1) * ATT_BN);
+    const char* st = lds + stage_c * STAGE;
+    if (k0 <= q_hi)                          // else every key of this step is in the future
+      step(st, k0, (k0 + ATT_BN - 1) > q_lo);
+    stage_c = stage_c + 1 == NS ? 0 : stage_c + 1;
+    stage_i = stage_i + 1 == NS ? 0 : stage_i + 1;
+  }
+
+  // ---- normalise and store.  Register r of block h is dim 32h + 8*(r/4) + 4*hi + r%4.
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  if (qrow < n) {
+    uint16_t* op = o + (size_t)(row0 + qrow) * d + head * HD + 4 * hi;
+#pragma unroll
+    for (int h = 0; h < HS; ++h)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w2;
+        w2.x = pack_bf16(oacc[h][4 * g] * inv, oacc[h][4 * g + 1] * inv);
+        w2.y = pack_bf16(oacc[h][4 * g + 2] * inv, oacc[h][4 * g + 3] * inv);
+        *(uint2*)(op + h * 32 + 8 * g) = w2;
+      }
+  }
+}
+
+hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
+                            const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
+                            int n_heads, int head_dim, hipStream_t st) {
+  if (max_rows <= 0) return hipSuccess;
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
+  // 8-wave workgroups (one per CU, four stages) once they fill the chip twice over: they halve
+  // the L2 -> LDS traffic per query.  Otherwise 4-wave ones (two per CU, two stages), which
+  // spread a short sequence over more CUs.
+  const int nw = ((max_rows + 255) / 256) * n_heads * batch >= 512 ? 8 : 4;
+#define LZ_ATT(HD, NW, NS)                                                                       \
+  do {                                                                                           \
+    constexpr int LDS_BYTES = NS * 2 * ATT_BN * HD * 2;                                          \
+    auto kern = flash_attn_kernel<HD, NW, NS>;                                                   \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    dim3 grid(n_heads, (max_rows + 32 * NW - 1) / (32 * NW), batch), block(64 * NW);             \
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, (const uint16_t*)k, \
+                       (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
+                       scale_log2e);                                                             \
+  } while (0)
+  if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
+  const int key = (head_dim == 128 ? 100 : 0) + nw * 10 + ns;
+  switch (key) {
+    case 184: LZ_ATT(128, 8, 4); break;
+    case 183: LZ_ATT(128, 8, 3); break;
+    case 182: LZ_ATT(128, 8, 2); break;
+    case 143: LZ_ATT(128, 4, 3); break;
+    case 142: LZ_ATT(128, 4, 2); break;
+    case 84: LZ_ATT(64, 8, 4); break;
+    case 42: LZ_ATT(64, 4, 2); break;
+    default: return hipErrorInvalidValue;
+  }
 #undef LZ_ATT
   return hipGetLastError();
 }
