@@ -111,142 +111,161 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
 
   const int q_lo = q0 + wave * 32, q_hi = q_lo + 31;     // this wave's query range
 
-  // One 64-key step.  The causal mask costs a compare and a select per element, so only steps
-  // that straddle the diagonal of this wave's queries branch into it.  The running
-  // maximum is raised only when a step's maximum exceeds it by more than 2^8 (in the base-2
-  // domain): softmax is invariant to the shift, p stays below 2^8 (fp32 sums and bf16 P keep
-  // their relative precision), and the rescale of the O^T accumulators -- two register-file
-  // moves and a multiply per element -- leaves the common path.  The 1/sqrt(hd) * log2(e) scale
+  // One 64-key step has five parts, with the LDS reads of each part issued under the MFMAs of
+  // the part before (two buffers fa/fb of KSTEPS fragments, reads and MFMAs interleaved one
+  // for one by scheduling fences; left alone the compiler pairs every MFMA with its own read
+  // and waits for it):
+  //   1  S^T block 0 from fa (read under part 5 of the step before)   reads K block 1 -> fb
+  //   2  S^T block 1 from fb                                          reads Vt half 0 -> fa
+  //   3  softmax of the 64 keys (vector unit; the other wave on the SIMD fills the matrix pipe)
+  //      -- wait for the copies of step it+1, workgroup barrier, issue the copies of step it+NS-1
+  //   4  O^T half 0 from fa                                           reads Vt half 1 -> fb
+  //   5  O^T half 1 from fb                                           reads K block 0 of it+1 -> fa
+  // The barrier sits after the softmax so that the reads of the next step's K rows can start
+  // under part 5: past it every wave's share of step it+1 has landed, and every wave has
+  // finished step it-1, whose stage the new copies overwrite.  A bare s_barrier, not
+  // __syncthreads, which would make the compiler wait for every outstanding copy.
+  //
+  // The causal mask costs a compare and a select per element, so only steps that straddle the
+  // diagonal of this wave's queries branch into it.  The running maximum is raised only when a
+  // step's maximum exceeds it by more than 2^8 (base-2 domain): softmax is invariant to the
+  // shift, p stays below 2^8 (fp32 sums and bf16 P keep their relative precision), and the
+  // rescale of the O^T accumulators leaves the common path.  The 1/sqrt(hd) * log2(e) scale
   // rides in the fused multiply-add that forms the exponent.
-  // LDS reads run one group ahead of the MFMAs that consume them (two buffers of KSTEPS
-  // fragments): the K rows of the second 32-key block are read under the MFMAs of the first,
-  // the first half of the Vt rows under the MFMAs of the second block (they land during the
-  // softmax), the second half under the first half's MFMAs.  The scheduling fences pin that
-  // order; left alone the compiler pairs every MFMA with its own read and waits for it.
 #define LZ_ATT_INTERLEAVE()                                  \
   _Pragma("unroll") for (int g = 0; g < KSTEPS; ++g) {        \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
   }
-  auto step = [&](const char* st, int k0, bool masked) {
-    auto kread = [&](int sub, int s) {
-      return *(const bf16x8_t*)(st + k_addr[sub] + (((s * 2 + hi) ^ kx) * 16));
-    };
-    auto vread = [&](int i) {          // i = 4 * h + 2 * sub + t
-      const int chunk = ((i >> 1) & 1) * 4 + (i & 1) * 2 + hi;
-      return *(const bf16x8_t*)(st + v_addr + (i >> 2) * 32 * 128 + ((chunk ^ vx) * 16));
-    };
-    bf16x8_t fa[KSTEPS], fb[KSTEPS];
-    floatx16_t sacc[2];
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) fa[s] = kread(0, s);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) fb[s] = kread(1, s);
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-      sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s], qf[s], sacc[0], 0, 0, 0);
-    LZ_ATT_INTERLEAVE();
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < KSTEPS; ++i) fa[i] = vread(i);
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-      sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s], qf[s], sacc[1], 0, 0, 0);
-    LZ_ATT_INTERLEAVE();
-    __builtin_amdgcn_sched_barrier(0);
-    // Register r of block sub is key k0 + 32*sub + 16*(r/8) + 8*hi + r%8.
-    if (masked) {
-      asm volatile("; causal mask" ::: "memory");   // keeps this a real branch
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + 32 * sub + 16 * (r / 8) + 8 * hi + (r % 8);
-          if (key > qrow) sacc[sub][r] = -INFINITY;
-        }
-    }
-    float mraw = -INFINITY;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        mraw = fmaxf(mraw, sacc[sub][r]);
-      }
-    float mloc = mraw * scale_log2e;
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.0f) != 0) {
-      // The empty asm keeps this a real branch: the compiler would otherwise run the rescale
-      // every step under a select.
-      const float m_new = fmaxf(m_run, mloc);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      l_run *= alpha;
-      asm volatile("; raise the running maximum" ::: "memory");
-#pragma unroll
-      for (int h = 0; h < HS; ++h) oacc[h] *= alpha;
-    }
-    const float neg_m = -m_run;
-    float psum = 0.f;
-    bf16x8_t pf[2][2];
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        float p[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][8 * t + j], scale_log2e, neg_m));
-          psum += p[j];
-        }
-        uint4 packed = pack8(p);
-        pf[sub][t] = *reinterpret_cast<bf16x8_t*>(&packed);
-      }
-    l_run += psum;
-    // O^T += Vt P^T
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < KSTEPS; ++i) fb[i] = vread(KSTEPS + i);
-#pragma unroll
-    for (int i = 0; i < KSTEPS; ++i)
-      oacc[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], pf[(i >> 1) & 1][i & 1],
-                                                             oacc[i >> 2], 0, 0, 0);
-    LZ_ATT_INTERLEAVE();
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < KSTEPS; ++i)
-      oacc[HS / 2 + (i >> 2)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-          fb[i], pf[(i >> 1) & 1][i & 1], oacc[HS / 2 + (i >> 2)], 0, 0, 0);
-  };
-#undef LZ_ATT_INTERLEAVE
-
-  // NS stages: the copies of step it + NS - 1 are issued while step it is computed, so a copy
-  // has NS - 1 steps to land.  A bare s_barrier (not __syncthreads, which would make the
-  // compiler wait for every outstanding copy) closes each step: past it, every wave's share
-  // of step it has landed and nobody still reads the stage of step it - 1.
   constexpr int PER_STEP = K_INSTR + V_INSTR;            // copies one wave issues per step
+  static_assert(NS >= 3, "the copies of step it+1 must be issued before step it");
+  bf16x8_t fa[KSTEPS], fb[KSTEPS];
+  auto kread = [&](const char* st, int sub, int s) {
+    return *(const bf16x8_t*)(st + k_addr[sub] + (((s * 2 + hi) ^ kx) * 16));
+  };
+  auto vread = [&](const char* st, int i) {          // i = 4 * h + 2 * sub + t
+    const int chunk = ((i >> 1) & 1) * 4 + (i & 1) * 2 + hi;
+    return *(const bf16x8_t*)(st + v_addr + (i >> 2) * 32 * 128 + ((chunk ^ vx) * 16));
+  };
+
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
     if (t < ntiles) issue(t, t * ATT_BN);
+  if (ntiles >= NS - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_barrier" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int s = 0; s < KSTEPS; ++s) fa[s] = kread(lds, 0, s);
+
   int stage_c = 0, stage_i = NS - 1;                     // stage computed / stage copied into
   for (int it = 0; it < ntiles; ++it) {
     const int k0 = it * ATT_BN;
-    if (it + NS - 1 <= ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const char* st = lds + stage_c * STAGE;
+    const int stage_n = stage_c + 1 == NS ? 0 : stage_c + 1;
+    const bool active = k0 <= q_hi;          // else every key of this step is in the future
+    bf16x8_t pf[2][2];
+    if (active) {
+      floatx16_t sacc[2];
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+      // part 1
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) fb[s] = kread(st, 1, s);
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s)
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s], qf[s], sacc[0], 0, 0, 0);
+      LZ_ATT_INTERLEAVE();
+      __builtin_amdgcn_sched_barrier(0);
+      // part 2
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i) fa[i] = vread(st, i);
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s)
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s], qf[s], sacc[1], 0, 0, 0);
+      LZ_ATT_INTERLEAVE();
+      __builtin_amdgcn_sched_barrier(0);
+      // part 3.  Register r of block sub is key k0 + 32*sub + 16*(r/8) + 8*hi + r%8.
+      if ((k0 + ATT_BN - 1) > q_lo) {
+        asm volatile("; causal mask" ::: "memory");   // keeps this a real branch
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + 32 * sub + 16 * (r / 8) + 8 * hi + (r % 8);
+            if (key > qrow) sacc[sub][r] = -INFINITY;
+          }
+      }
+      float mraw = -INFINITY;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mraw = fmaxf(mraw, sacc[sub][r]);
+      float mloc = mraw * scale_log2e;
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.0f) != 0) {
+        // The empty asm keeps this a real branch: the compiler would otherwise run the rescale
+        // every step under a select.
+        const float m_new = fmaxf(m_run, mloc);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+        asm volatile("; raise the running maximum" ::: "memory");
+#pragma unroll
+        for (int h = 0; h < HS; ++h) oacc[h] *= alpha;
+      }
+      const float neg_m = -m_run;
+      float psum = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          float p[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][8 * t + j], scale_log2e, neg_m));
+            psum += p[j];
+          }
+          uint4 packed = pack8(p);
+          pf[sub][t] = *reinterpret_cast<bf16x8_t*>(&packed);
+        }
+      l_run += psum;
+    }
+    // the copies of step it+1 have landed; nobody reads the stage of step it-1 any more
     __builtin_amdgcn_sched_barrier(0);
+    if (it + NS - 1 <= ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * PER_STEP) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
     if (it + NS - 1 < ntiles) issue(stage_i, k0 + (NS - 1) * ATT_BN);
-    const char* st = lds + stage_c * STAGE;
-    if (k0 <= q_hi)                          // else every key of this step is in the future
-      step(st, k0, (k0 + ATT_BN - 1) > q_lo);
-    stage_c = stage_c + 1 == NS ? 0 : stage_c + 1;
+    if (active) {
+      // part 4
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i) fb[i] = vread(st, KSTEPS + i);
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i)
+        oacc[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], pf[(i >> 1) & 1][i & 1],
+                                                               oacc[i >> 2], 0, 0, 0);
+      LZ_ATT_INTERLEAVE();
+      __builtin_amdgcn_sched_barrier(0);
+      // part 5 (the reads past the last step fetch a stage nobody uses; they stay inside LDS)
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) fa[s] = kread(lds + stage_n * STAGE, 0, s);
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i)
+        oacc[HS / 2 + (i >> 2)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            fb[i], pf[(i >> 1) & 1][i & 1], oacc[HS / 2 + (i >> 2)], 0, 0, 0);
+      LZ_ATT_INTERLEAVE();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    stage_c = stage_n;
     stage_i = stage_i + 1 == NS ? 0 : stage_i + 1;
   }
+#undef LZ_ATT_INTERLEAVE
 
   // ---- normalise and store.  Register r of block h is dim 32h + 8*(r/4) + 4*hi + r%4.
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -270,10 +289,10 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
                             int n_heads, int head_dim, hipStream_t st) {
   if (max_rows <= 0) return hipSuccess;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
-  // 8-wave workgroups (one per CU, four stages) once they fill the chip twice over: they halve
-  // the L2 -> LDS traffic per query.  Otherwise 4-wave ones (two per CU, two stages), which
-  // spread a short sequence over more CUs.
-  const int nw = ((max_rows + 255) / 256) * n_heads * batch >= 512 ? 8 : 4;
+  // 8-wave workgroups (one per CU, four stages) when they alone fill the chip: they halve the
+  // L2 -> LDS traffic per query.  Otherwise 4-wave ones, which spread a short sequence over
+  // more CUs.
+  const int nw = ((max_rows + 255) / 256) * n_heads * batch >= 256 ? 8 : 4;
 #define LZ_ATT(HD, NW, NS)                                                                       \
   do {                                                                                           \
     constexpr int LDS_BYTES = NS * 2 * ATT_BN * HD * 2;                                          \
@@ -292,89 +311,9 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
   } while (0)
   if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
   if (head_dim == 128 && nw == 8) LZ_ATT(128, 8, 4);
-  else if (head_dim == 128) LZ_ATT(128, 4, 2);
+  else if (head_dim == 128) LZ_ATT(128, 4, 3);
   else if (nw == 8) LZ_ATT(64, 8, 4);
-  else LZ_ATT(64, 4, 2);
-#undef LZ_ATT_INTERLEAVE
-
-  // NS stages: the copies of step it + NS - 1 are issued while step it is computed, so a copy
-  // has NS - 1 steps to land.  A bare s_barrier (not __syncthreads, which would make the
-  // compiler wait for every outstanding copy) closes each step: past it, every wave's share
-  // of step it has landed and nobody still reads the stage of step it - 1.
-  constexpr int PER_STEP = K_INSTR + V_INSTR;            // copies one wave issues per step
-#pragma unroll
-  for (int t = 0; t < NS - 1; ++t)
-    if (t < ntiles) issue(t, t * ATT_BN);
-  int stage_c = 0, stage_i = NS - 1;                     // stage computed / stage copied into
-  for (int it = 0; it < ntiles; ++it) {
-    const int k0 = it * ATT_BN;
-    if (it + NS - 1 <= ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_barrier" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    if (it + NS - 1 < ntiles) issue(stage_i, k0 + (NS - 1) * ATT_BN);
-    const char* st = lds + stage_c * STAGE;
-    if (k0 <= q_hi)                          // else every key of this step is in the future
-      step(st, k0, (k0 + ATT_BN - 1) > q_lo);
-    stage_c = stage_c + 1 == NS ? 0 : stage_c + 1;
-    stage_i = stage_i + 1 == NS ? 0 : stage_i + 1;
-  }
-
-  // ---- normalise and store.  Register r of block h is dim 32h + 8*(r/4) + 4*hi + r%4.
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = 1.0f / l_tot;
-  if (qrow < n) {
-    uint16_t* op = o + (size_t)(row0 + qrow) * d + head * HD + 4 * hi;
-#pragma unroll
-    for (int h = 0; h < HS; ++h)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 w2;
-        w2.x = pack_bf16(oacc[h][4 * g] * inv, oacc[h][4 * g + 1] * inv);
-        w2.y = pack_bf16(oacc[h][4 * g + 2] * inv, oacc[h][4 * g + 3] * inv);
-        *(uint2*)(op + h * 32 + 8 * g) = w2;
-      }
-  }
-}
-
-hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
-                            const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
-                            int n_heads, int head_dim, hipStream_t st) {
-  if (max_rows <= 0) return hipSuccess;
-  const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
-  // 8-wave workgroups (one per CU, four stages) once they fill the chip twice over: they halve
-  // the L2 -> LDS traffic per query.  Otherwise 4-wave ones (two per CU, two stages), which
-  // spread a short sequence over more CUs.
-  const int nw = ((max_rows + 255) / 256) * n_heads * batch >= 512 ? 8 : 4;
-#define LZ_ATT(HD, NW, NS)                                                                       \
-  do {                                                                                           \
-    constexpr int LDS_BYTES = NS * 2 * ATT_BN * HD * 2;                                          \
-    auto kern = flash_attn_kernel<HD, NW, NS>;                                                   \
-    static bool attr_set = false;                                                                \
-    if (!attr_set) {                                                                             \
-      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
-      if (e != hipSuccess) return e;                                                             \
-      attr_set = true;                                                                           \
-    }                                                                                            \
-    dim3 grid(n_heads, (max_rows + 32 * NW - 1) / (32 * NW), batch), block(64 * NW);             \
-    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, (const uint16_t*)k, \
-                       (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
-                       scale_log2e);                                                             \
-  } while (0)
-  if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
-  const int key = (head_dim == 128 ? 100 : 0) + nw * 10 + ns;
-  switch (key) {
-    case 184: LZ_ATT(128, 8, 4); break;
-    case 183: LZ_ATT(128, 8, 3); break;
-    case 182: LZ_ATT(128, 8, 2); break;
-    case 143: LZ_ATT(128, 4, 3); break;
-    case 142: LZ_ATT(128, 4, 2); break;
-    case 84: LZ_ATT(64, 8, 4); break;
-    case 42: LZ_ATT(64, 4, 2); break;
-    default: return hipErrorInvalidValue;
-  }
+  else LZ_ATT(64, 4, 4);
 #undef LZ_ATT
   return hipGetLastError();
 }
