@@ -246,6 +246,14 @@ int lazyllm_op_v_transpose(const void* v, void* vt, int32_t vt_ld, int32_t rows,
 int lazyllm_op_attention(const void* q, const void* k, const void* vt, int32_t vt_ld, void* o,
                          int32_t rows, int32_t n_heads, int32_t head_dim, void* hip_stream);
 
+/* lazyllm_op_attention plus Eq. 1 in the form the prefill uses: the attention
+ * kernel leaves the last query's logits against every key in `scratch`, and a
+ * second kernel turns them into s[j] = (1/H) sum_h softmax_j(...) (fp32 [rows]).
+ * scratch: device, at least lazyllm_op_score_scratch_bytes(rows, H). */
+int lazyllm_op_attention_score(const void* q, const void* k, const void* vt, int32_t vt_ld, void* o,
+                               float* s, void* scratch, int32_t rows, int32_t n_heads,
+                               int32_t head_dim, void* hip_stream);
+
 /* Eq. 1: s[j] = (1/H) sum_h softmax_j(q_last[h] . k[j,h] / sqrt(hd)) over the
  * `rows` tokens present.  q_last: bf16 [H, hd] (the last token's rotated
  * query); k: bf16 [rows, H, hd]; s: fp32 [rows].

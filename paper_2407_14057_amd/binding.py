@@ -104,6 +104,9 @@ _SIGNATURES = {
                                          C.c_int32, C.c_void_p]),
     "lazyllm_op_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                        C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
+    "lazyllm_op_attention_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_void_p]),
     "lazyllm_op_score_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
     "lazyllm_op_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_void_p]),
@@ -291,6 +294,13 @@ def lazyllm_op_v_transpose(v, vt, vt_ld, rows, n_heads, head_dim, stream=None) -
 def lazyllm_op_attention(q, k, vt, vt_ld, o, rows, n_heads, head_dim, stream=None) -> None:
     _check(lib().lazyllm_op_attention(_ptr(q), _ptr(k), _ptr(vt), vt_ld, _ptr(o), rows, n_heads,
                                       head_dim, _stream_ptr(stream)))
+
+
+def lazyllm_op_attention_score(q, k, vt, vt_ld, o, s, scratch, rows, n_heads, head_dim,
+                               stream=None) -> None:
+    _check(lib().lazyllm_op_attention_score(_ptr(q), _ptr(k), _ptr(vt), vt_ld, _ptr(o), _ptr(s),
+                                            _ptr(scratch), rows, n_heads, head_dim,
+                                            _stream_ptr(stream)))
 
 
 def lazyllm_op_score_scratch_bytes(rows: int, n_heads: int) -> int:

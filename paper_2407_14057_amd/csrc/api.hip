@@ -484,13 +484,20 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 2.0 * n * rowb,
            launch_v_transpose(res->v[l], W + ws.vt, cu, cu_vt + s * BW, 0, B, stg.max_rows[s],
                               (int)stg.vt_ld[s], H, hd, st));
-    if (res->scores[l] != nullptr)
-      LZ_RUN(LAZYLLM_STEP_SCORE, l, n, n * rowb + rowb * B + 4.0 * n,
-             launch_score(W + ws.q, res->k[l], res->scores[l], W + ws.score, cu, 0, B, n,
-                          stg.max_rows[s], H, hd, st));
+    // Eq. 1 needs the last query's logits against every key, which the attention kernel has
+    // in registers anyway: it leaves them in the score scratch, and one small kernel turns
+    // them into the head-averaged probabilities.
+    const bool scored = res->scores[l] != nullptr;
     LZ_RUN(LAZYLLM_STEP_ATTENTION, l, n, att_flops,
            launch_attention(W + ws.q, res->k[l], W + ws.vt, W + ws.o, cu, cu_vt + s * BW, 0, B,
-                            stg.max_rows[s], (int)stg.vt_ld[s], H, hd, st));
+                            stg.max_rows[s], (int)stg.vt_ld[s], H, hd, st,
+                            scored ? score_z(W + ws.score) : nullptr,
+                            scored ? score_zstat(W + ws.score, (int)stg.vt_ld[s], H) : nullptr,
+                            (int)stg.vt_ld[s]));
+    if (scored)
+      LZ_RUN(LAZYLLM_STEP_SCORE, l, n, 4.0 * n * H + 4.0 * n,
+             launch_score_finish(res->scores[l], W + ws.score, cu, cu_vt + s * BW, 0, B,
+                                 (int)stg.vt_ld[s], stg.max_rows[s], H, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
            launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st, nullptr,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -620,6 +627,21 @@ int lazyllm_op_attention(const void* q, const void* k, const void* vt, int32_t v
     return LAZYLLM_EINVAL;
   LZ_HIP(launch_attention(q, k, vt, o, nullptr, nullptr, rows, 1, rows, vt_ld, n_heads, head_dim,
                           (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_attention_score(const void* q, const void* k, const void* vt, int32_t vt_ld, void* o,
+                               float* s, void* scratch, int32_t rows, int32_t n_heads,
+                               int32_t head_dim, void* hip_stream) {
+  if (!q || !k || !vt || !o || !s || !scratch || rows <= 0 || n_heads <= 0 || n_heads > 256 ||
+      (head_dim != 64 && head_dim != 128) || vt_ld % 64 != 0 || vt_ld < (rows + 63) / 64 * 64)
+    return LAZYLLM_EINVAL;
+  const int z_ld = (rows + 63) / 64 * 64;      // the scratch is sized for this padded length
+  LZ_HIP(launch_attention(q, k, vt, o, nullptr, nullptr, rows, 1, rows, vt_ld, n_heads, head_dim,
+                          (hipStream_t)hip_stream, score_z(scratch),
+                          score_zstat(scratch, z_ld, n_heads), z_ld));
+  LZ_HIP(launch_score_finish(s, scratch, nullptr, nullptr, rows, 1, z_ld, rows, n_heads,
+                             (hipStream_t)hip_stream));
   return LAZYLLM_OK;
 }
 

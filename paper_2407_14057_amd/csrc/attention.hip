@@ -29,7 +29,8 @@ __global__ void __launch_bounds__(NW * 64, 2)
 flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                   const uint16_t* __restrict__ vt, uint16_t* __restrict__ o,
                   const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
-                  int vt_ld, int n_heads, float scale_log2e) {
+                  int vt_ld, int n_heads, float scale_log2e, float* __restrict__ z,
+                  float2* __restrict__ zstat, int z_ld) {
   constexpr int CHK = HD / 8;                 // 16-byte chunks per K row
   constexpr int KSTEPS = HD / 16;             // k-steps of the first product
   constexpr int HS = HD / 32;                 // 32-row blocks of O^T
@@ -110,6 +111,7 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   float m_run = -INFINITY, l_run = 0.f;
 
   const int q_lo = q0 + wave * 32, q_hi = q_lo + 31;     // this wave's query range
+  const bool score_wave = z != nullptr && q_lo <= n - 1 && n - 1 <= q_hi;   // owns the last query
 
   // One 64-key step has five parts, with the LDS reads of each part issued under the MFMAs of
   // the part before (two buffers fa/fb of KSTEPS fragments, reads and MFMAs interleaved one
@@ -138,6 +140,8 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
   }
   constexpr int PER_STEP = K_INSTR + V_INSTR;            // copies one wave issues per step
+  constexpr int SCORE_STORES = 8;                        // logit stores per step (score wave)
+  static_assert((NS - 3) * (PER_STEP + SCORE_STORES) + SCORE_STORES < 64, "vmcnt is 6 bits");
   static_assert(NS >= 3, "the copies of step it+1 must be issued before step it");
   bf16x8_t fa[KSTEPS], fb[KSTEPS];
   auto kread = [&](const char* st, int sub, int s) {
@@ -199,6 +203,25 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
             if (key > qrow) sacc[sub][r] = -INFINITY;
           }
       }
+      // Eq. 1 rides along: the lanes that own the sequence's last query already hold its
+      // logits against every key, so they leave them (base-2 domain) for the score kernel.
+      if (score_wave) {
+        asm volatile("; last-query logits" ::: "memory");
+        if (qrow == n - 1) {
+          // 16-byte stores into the padded layout of the Vt buffer (sequences start at multiples
+          // of 64, so the keys past the sequence's end that a step covers still fall inside)
+          float* zr = z + (size_t)head * z_ld + (cu_vt ? cu_vt[b] : 0) + k0 + 8 * hi;
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              float4 v4;
+              v4.x = sacc[sub][4 * g] * scale_log2e;     v4.y = sacc[sub][4 * g + 1] * scale_log2e;
+              v4.z = sacc[sub][4 * g + 2] * scale_log2e; v4.w = sacc[sub][4 * g + 3] * scale_log2e;
+              *(float4*)(zr + 32 * sub + 16 * (g >> 1) + 4 * (g & 1)) = v4;
+            }
+        }
+      }
       float mraw = -INFINITY;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
@@ -236,8 +259,12 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
     }
     // the copies of step it+1 have landed; nobody reads the stage of step it-1 any more
     __builtin_amdgcn_sched_barrier(0);
-    if (it + NS - 1 <= ntiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * PER_STEP) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // (the wave that also stores the last query's logits has SCORE_STORES more operations in
+    // flight per step; they complete in issue order with the copies)
+    if (it + NS - 1 > ntiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (score_wave)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * (PER_STEP + SCORE_STORES) + SCORE_STORES) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * PER_STEP) : "memory");
     asm volatile("s_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
     if (it + NS - 1 < ntiles) issue(stage_i, k0 + (NS - 1) * ATT_BN);
@@ -270,6 +297,8 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   // ---- normalise and store.  Register r of block h is dim 32h + 8*(r/4) + 4*hi + r%4.
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.0f / l_tot;
+  if (score_wave && qrow == n - 1 && hi == 0)            // reference point and 1 / sum for Eq. 1
+    zstat[(size_t)b * n_heads + head] = make_float2(m_run, inv);
   if (qrow < n) {
     uint16_t* op = o + (size_t)(row0 + qrow) * d + head * HD + 4 * hi;
 #pragma unroll
@@ -286,7 +315,8 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
 
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
-                            int n_heads, int head_dim, hipStream_t st) {
+                            int n_heads, int head_dim, hipStream_t st, float* z, void* zstat,
+                            int z_ld) {
   if (max_rows <= 0) return hipSuccess;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
   // 8-wave workgroups (one per CU, four stages) when they alone fill the chip: they halve the
@@ -307,7 +337,7 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
     dim3 grid(n_heads, (max_rows + 32 * NW - 1) / (32 * NW), batch), block(64 * NW);             \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
-                       scale_log2e);                                                             \
+                       scale_log2e, z, (float2*)zstat, z_ld);                                    \
   } while (0)
   if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
   if (head_dim == 128 && nw == 8) LZ_ATT(128, 8, 4);

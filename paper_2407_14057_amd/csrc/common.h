@@ -113,7 +113,15 @@ hipError_t launch_v_transpose(const void* v, void* vt, const int32_t* cu, const 
                               int head_dim, hipStream_t st);
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
-                            int n_heads, int head_dim, hipStream_t st);
+                            int n_heads, int head_dim, hipStream_t st, float* z = nullptr,
+                            void* zstat = nullptr, int z_ld = 0);
+// Eq. 1 from the logits the attention kernel left in `scratch` (z, zstat of launch_attention
+// = score_z(scratch), score_zstat(scratch, z_ld, H); z_ld = vt_ld, sequence b at cu_vt[b]).
+float* score_z(void* scratch);
+void* score_zstat(void* scratch, int z_ld, int n_heads);
+hipError_t launch_score_finish(float* s, void* scratch, const int32_t* cu, const int32_t* cu_z,
+                               int n_single, int batch, int z_ld, int max_rows, int n_heads,
+                               hipStream_t st);
 size_t score_scratch_bytes(int total_rows, int batch, int n_heads);
 hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, const int32_t* cu,
                         int n_single, int batch, int total_rows, int max_rows, int n_heads,

@@ -159,10 +159,11 @@ score_stats_kernel(const float2* __restrict__ part, float2* __restrict__ hstat,
   }
 }
 
+template <bool BASE2>   // logits and reference points in the base-2 domain (attention kernel's)
 __global__ void __launch_bounds__(256)
 score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ hstat,
                     float* __restrict__ s, const int32_t* __restrict__ cu, int n_single,
-                    int n_heads, int z_ld) {
+                    int n_heads, int z_ld, const int32_t* __restrict__ cu_z, bool padded) {
   __shared__ float2 hs[SCORE_MAX_HEADS];
   const int b = blockIdx.y;
   int row0, n;
@@ -174,15 +175,19 @@ score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ hsta
   const int t = t0 + threadIdx.x;
   if (t < n) {
     float acc = 0.f;
-    for (int h = 0; h < n_heads; ++h)
-      acc += __expf(z[(size_t)h * z_ld + row0 + t] - hs[h].x) * hs[h].y;
+    const int zoff = padded ? (cu_z ? cu_z[b] : 0) : row0;   // where this sequence's logits start
+    for (int h = 0; h < n_heads; ++h) {
+      const float dz = z[(size_t)h * z_ld + zoff + t] - hs[h].x;
+      acc += (BASE2 ? __builtin_amdgcn_exp2f(dz) : __expf(dz)) * hs[h].y;
+    }
     s[row0 + t] = acc / (float)n_heads;
   }
 }
 
 // scratch layout: z[H][total_rows] fp32 | hstat[batch][H] float2 | partials (upper bound)
 size_t score_scratch_bytes(int total_rows, int batch, int n_heads) {
-  size_t zb = (size_t)n_heads * total_rows * sizeof(float);
+  // rows padded per sequence to a multiple of 64 (the layout the attention kernel writes)
+  size_t zb = (size_t)n_heads * ((size_t)total_rows + 64 * (size_t)batch) * sizeof(float);
   zb = (zb + 255) & ~(size_t)255;
   size_t hb = ((size_t)batch * n_heads * sizeof(float2) + 255) & ~(size_t)255;
   size_t parts = (size_t)batch * ((size_t)(total_rows + 7) / 8 + 1);
@@ -233,8 +238,29 @@ hipError_t launch_score(const void* q, const void* k, float* s, void* scratch, c
                      n_heads, parts_per_seq, tok);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(score_finish_kernel, dim3((max_rows + 255) / 256, batch), dim3(256), 0, st, z,
-                     hstat, s, cu, n_single, n_heads, total_rows);
+  hipLaunchKernelGGL(score_finish_kernel<false>, dim3((max_rows + 255) / 256, batch), dim3(256), 0,
+                     st, z, hstat, s, cu, n_single, n_heads, total_rows, nullptr, false);
+  return hipGetLastError();
+}
+
+float* score_z(void* scratch) { return (float*)scratch; }
+
+// The attention kernel writes logits in the padded layout of the Vt buffer: row length z_ld
+// (a multiple of 64, at least the padded token count), sequence b at offset cu_z[b].
+void* score_zstat(void* scratch, int z_ld, int n_heads) {
+  size_t zb = (size_t)n_heads * z_ld * sizeof(float);
+  zb = (zb + 255) & ~(size_t)255;
+  return (char*)scratch + zb;
+}
+
+hipError_t launch_score_finish(float* s, void* scratch, const int32_t* cu, const int32_t* cu_z,
+                               int n_single, int batch, int z_ld, int max_rows, int n_heads,
+                               hipStream_t st) {
+  if (max_rows <= 0) return hipSuccess;
+  if (n_heads > SCORE_MAX_HEADS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(score_finish_kernel<true>, dim3((max_rows + 255) / 256, batch), dim3(256), 0,
+                     st, score_z(scratch), (const float2*)score_zstat(scratch, z_ld, n_heads), s,
+                     cu, n_single, n_heads, z_ld, cu_z, true);
   return hipGetLastError();
 }
 

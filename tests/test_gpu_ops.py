@@ -220,6 +220,36 @@ def test_attention_sharp_rows():
     assert np.abs(_f64(o) - o_ref.reshape(rows, d)).max() < 3e-2
 
 
+@pytest.mark.parametrize("rows", [1, 2, 31, 32, 33, 64, 65, 127, 128, 129, 255, 257, 515, 1000, 2364])
+@pytest.mark.parametrize("H,hd", [(4, 64), (2, 128), (32, 128)])
+def test_attention_score(rows, H, hd):
+    """Attention that also leaves Eq. 1's scores (the form the prefill runs)."""
+    if rows > 600 and H < 32:
+        pytest.skip("long case only at the 7B head count")
+    rng = np.random.default_rng(rows * 5 + H)
+    d = H * hd
+    q = _rand_bf16(rng, (rows, d), 1.5); k = _rand_bf16(rng, (rows, d)); v = _rand_bf16(rng, (rows, d))
+    pad = (rows + 63) // 64 * 64
+    vt = torch.zeros(d, pad, dtype=torch.bfloat16, device=DEV); vt[:, :rows] = v.t()
+    o = torch.full((rows, d), 9.0, dtype=torch.bfloat16, device=DEV)
+    o_plain = torch.full((rows, d), 9.0, dtype=torch.bfloat16, device=DEV)
+    s = torch.full((rows,), -1.0, dtype=torch.float32, device=DEV)
+    scratch = torch.empty(B.lazyllm_op_score_scratch_bytes(rows, H), dtype=torch.uint8, device=DEV)
+    B.lazyllm_op_attention_score(q, k, vt.contiguous(), pad, o, s, scratch, rows, H, hd)
+    B.lazyllm_op_attention(q, k, vt.contiguous(), pad, o_plain, rows, H, hd)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o_plain)                       # scoring does not disturb the output
+    ref = O.last_row_scores(_f64(q[rows - 1]).reshape(H, hd), _f64(k).reshape(rows, H, hd))
+    got = s.cpu().numpy().astype(np.float64)
+    assert np.allclose(got, ref, rtol=2e-5, atol=1e-9), np.abs(got / ref - 1).max()
+    assert abs(got.sum() - 1.0) < 1e-5
+    # same scores as the stand-alone scoring kernels, to fp32 rounding
+    s2 = torch.empty(rows, dtype=torch.float32, device=DEV)
+    B.lazyllm_op_score(q[rows - 1].contiguous(), k, s2, scratch, rows, H, hd)
+    torch.cuda.synchronize()
+    assert np.allclose(got, s2.cpu().numpy().astype(np.float64), rtol=2e-5, atol=1e-9)
+
+
 # ------------------------------------------------------------------------------------ Eq. 1 scoring
 
 @pytest.mark.parametrize("rows", [1, 2, 15, 16, 17, 255, 256, 257, 1000, 3376])
