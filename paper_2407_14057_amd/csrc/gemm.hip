@@ -307,7 +307,8 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
 }
 
 // ------------------------------------------------------------------------------------------
-// Ping-pong variant of the 256x256x64 tile on 8 waves (4 x 2, each wave 64 x 128).  The two
+// Ping-pong kernel on 8 waves: the 256x256x64 tile as 4 x 2 waves of 64 x 128, or the 192x256x64
+// tile as 2 x 4 waves of 96 x 64 (the figures below are for the first).  The two
 // waves that share a SIMD (wave w and w + 4) run the same loop half a step apart: while one
 // is in a COMPUTE phase (16 back-to-back MFMAs, nothing else), the other is in a MEMORY phase
 // (the 12 LDS reads of its next half step, its global -> LDS copies, the waits).  A workgroup
@@ -324,14 +325,17 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
 // read in phase 4t+4, so every wave copies its share of step t+1 during C(t a) (phases 4t+1 and
 // 4t+2) and waits for it before the barrier that ends phase 4t+3.
 // ------------------------------------------------------------------------------------------
-template <int EPI>
+template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(512)
 gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K,
                int lda, int ldw, int ldc, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
-  constexpr int WM = 4, WN = 2, TM = 2, TN = 4, NWAVES = 8;
-  constexpr int BM = 256, BN = 256;
-  constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;    // 4 + 4 copies per wave
+  constexpr int NWAVES = 8;
+  static_assert(WM * WN == NWAVES, "eight waves: two per SIMD");
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;    // copies per wave and K step
+  constexpr int NCOPY = A_INSTR + W_INSTR;
+  static_assert(BM % 64 == 0 && BN % 64 == 0 && NCOPY <= 2 * TM * TN, "tile/wave mismatch");
   constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -386,7 +390,7 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #pragma unroll
     for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], sw + q * 1024);
   };
-  // one of the wave's eight copies of a K step (q < 4: A rows, else W rows)
+  // one of the wave's copies of a K step (q < A_INSTR: A rows, else W rows)
   auto issue_one = [&](int stage, int k0, int q) {
     if (q < A_INSTR)
       g2l16((const char*)A + (size_t)k0 * 2 + a_off[q],
@@ -412,7 +416,7 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   bf16x8_t af[2][TM], wf[2][TN];
 
-  // 16 MFMAs with one copy behind each of the first eight
+  // 2*TM*TN MFMAs with one copy behind each of the first NCOPY
 #define LZ_COMPUTE_COPY_PHASE(stage, k0)                                                       \
   do {                                                                                         \
     __builtin_amdgcn_s_setprio(1);                                                             \
@@ -421,13 +425,13 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
         _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                       \
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[k2][j], af[k2][i], acc[i][j], \
                                                               0, 0, 0);                        \
-          if (k2 == 0) issue_one((stage), (k0), i * TN + j);                                   \
+          if ((k2 * TM + i) * TN + j < NCOPY) issue_one((stage), (k0), (k2 * TM + i) * TN + j); \
         }                                                                                      \
-    _Pragma("unroll") for (int n = 0; n < 8; ++n) {                                            \
+    _Pragma("unroll") for (int n = 0; n < NCOPY; ++n) {                                        \
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                       \
       __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);                                       \
     }                                                                                          \
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                         \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * TM * TN - NCOPY, 0);                       \
     __builtin_amdgcn_s_setprio(0);                                                             \
   } while (0)
 
@@ -491,16 +495,18 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
 }
 
+template <int WM, int WN, int TM, int TN>
 static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R, int M, int N,
                             int K, int lda, int ldw, int ldc, int epi, int group_m,
                             const RopeArgs& ra, hipStream_t st) {
-  constexpr int LDS_BYTES = 2 * (256 + 256) * ROW_BYTES;
-  if (N % 256 != 0) return hipErrorInvalidValue;
-  const int tiles_m = (M + 255) / 256, tiles_n = N / 256;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  if (N % BN != 0) return hipErrorInvalidValue;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   dim3 grid(tiles_m * tiles_n), block(512);
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
-    auto kern = gemm_pp_kernel<E>;                                                               \
+    auto kern = gemm_pp_kernel<WM, WN, TM, TN, E>;                                               \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
@@ -517,7 +523,8 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   else if (epi == EPI_SWIGLU) LZ_GEMM(EPI_SWIGLU);
   else if (epi == EPI_QKV_ROPE) {
     if (ra.head_dim == 64) LZ_GEMM(EPI_QKV_ROPE64);
-    else LZ_GEMM(EPI_QKV_ROPE128);
+    else if constexpr (TN >= 4) LZ_GEMM(EPI_QKV_ROPE128);
+    else return hipErrorInvalidValue;
   }
   else return hipErrorInvalidValue;
 #undef LZ_GEMM
@@ -811,7 +818,14 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
       const long t128 = (long)((M + 127) / 128) * (N / 128);
       if (t128 <= 160 && K / BK >= 32) cfg = 6;
     }
+    // Between 150 and 205 tiles of 256 rows a fifth or more of the CUs would sit idle through
+    // the one round; 192-row tiles (wave tile 96x64, no rotary epilogue) make more, shorter
+    // tiles of the same work when those still fit one round (measured at M = 2364: O projection
+    // 104 -> 90 us, down projection 227 -> 211 us; gate/up at M = 355: 88 -> 77 us).
+    const long tiles192 = (long)((M + 191) / 192) * (N / 256);
     if (cfg != 0) {}
+    else if (N % 256 == 0 && big_tiles >= 150 && big_tiles <= 205 && tiles192 <= 256 &&
+             epilogue != EPI_QKV_ROPE) cfg = 7;
     else if (N % 256 == 0 && big_tiles >= 150) cfg = 5;
     else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = (N % 256 == 0) ? 4 : 0;
     else cfg = 2;
@@ -826,8 +840,10 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_cfg<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
-    case 5:                                             // 256x256, 8 waves, ping-pong phases
-            return launch_pp(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 5:                                             // 256x256, 8 waves of 64x128, ping-pong
+            return launch_pp<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 7:                                             // 192x256, 8 waves of 96x64, ping-pong
+            return launch_pp<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 6:                                             // 128x128 stream-K + fix-up
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
             return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, st);
