@@ -3,6 +3,7 @@ path and Eq. 1, closed forms, and the structural facts the paper states
 (nested kept sets, Aux Cache completeness, each token computed at most once
 per layer, cumulative usage bounded by the baseline)."""
 import dataclasses
+import os
 
 import numpy as np
 import pytest
@@ -229,3 +230,23 @@ def test_fp32_variant_tracks_fp64():
     b = O.prefill(SMALL.as_dict(), wb, ids, [(2, 500)], dtype=np.float32, forced_keep={2: a.kept_pos[2]})
     assert b.logits.dtype == np.float32
     assert np.allclose(a.logits, b.logits, atol=2e-5)
+
+
+def test_tiny512_regression_fixture():
+    """The checker still computes what tests/golden/make_golden.py froze (a later edit of its
+    arithmetic must show up here and name, in its commit, the passage that justifies it)."""
+    import json
+    import importlib.util
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "golden", "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    got = mod.compute()
+    with open(os.path.join(here, "golden", "tiny512_oracle.json")) as f:
+        want = json.load(f)
+    for key in ("n_per_layer", "kept_pos_sha256", "kept_pos_layer3_head", "aux_counts", "logits_argmax"):
+        assert got[key] == want[key], key
+    assert want["n_per_layer"] == [512, 512, 359, 180]
+    for key in ("scores_layer1_first8", "scores_layer3_last4", "logits_first8"):
+        assert np.allclose(got[key], want[key], rtol=1e-9, atol=1e-12), key
+    assert abs(got["logits_sum"] - want["logits_sum"]) < 1e-7
