@@ -142,7 +142,7 @@ void build_stages(int n_layers, const lazyllm_keep* sched, int n_sched, const in
 
 // ---- workspace layout -------------------------------------------------------------------
 struct Workspace {
-  size_t h0, h1, xa, q, o, vt, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, total;
+  size_t h0, h1, xa, q, o, vt, vt_col, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, total;
 };
 
 void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_seqlen,
@@ -157,6 +157,7 @@ void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_s
   w->q = take((size_t)T * d * 2);
   w->o = take((size_t)T * d * 2);
   w->vt = take(d * vt_ld * 2);
+  w->vt_col = take((size_t)T * 4);
   w->act = take((size_t)T * fp * 2);
   w->score = take(score_scratch_bytes((int)T, batch, c->n_heads));
   w->rope = take((size_t)max_seqlen * (c->head_dim / 2) * sizeof(float2));
@@ -474,16 +475,20 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
            launch_rmsnorm(h, m->attn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
     // QKV projection with the rotary embedding (original positions) applied in the epilogue;
     // K and V land directly in this layer's KV cache.
-    RopeArgs ra;
+    RopeArgs ra{};
     ra.pos = res->kept_pos[l]; ra.table = rope;
     ra.q = (uint16_t*)(W + ws.q); ra.k = (uint16_t*)res->k[l]; ra.v = (uint16_t*)res->v[l];
     ra.d_model = d; ra.head_dim = hd;
+    // ... and V also transposed into the workspace copy the attention kernel reads
+    ra.vt = (uint16_t*)(W + ws.vt); ra.vt_ld = (int)stg.vt_ld[s];
+    ra.vt_col = B > 1 ? (const int32_t*)(W + ws.vt_col) : nullptr;
+    if (stg.first_layer[s] == l)
+      LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 0.0,
+             launch_vt_stage_setup(W + ws.vt, B > 1 ? (int32_t*)(W + ws.vt_col) : nullptr, cu,
+                                   cu_vt + s * BW, 0, B, (int)stg.vt_ld[s], d, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * 3.0 * dd * dd,
            launch_gemm(W + ws.xa, m->wqkv[l], nullptr, nullptr, n, 3 * d, d, d, d, 0,
                        EPI_QKV_ROPE, st, &ra));
-    LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 2.0 * n * rowb,
-           launch_v_transpose(res->v[l], W + ws.vt, cu, cu_vt + s * BW, 0, B, stg.max_rows[s],
-                              (int)stg.vt_ld[s], H, hd, st));
     // Eq. 1 needs the last query's logits against every key, which the attention kernel has
     // in registers anyway: it leaves them in the score scratch, and one small kernel turns
     // them into the head-averaged probabilities.
@@ -602,7 +607,7 @@ int lazyllm_op_qkv_rope(const void* x, const void* wqkv, const int32_t* pos, int
   hipStream_t st = (hipStream_t)hip_stream;
   const int d = n_heads * head_dim;
   LZ_HIP(launch_rope_table((float2*)rope_table, max_pos + 1, head_dim, theta, st));
-  RopeArgs ra;
+  RopeArgs ra{};
   ra.pos = pos; ra.table = (const float2*)rope_table;
   ra.q = (uint16_t*)q; ra.k = (uint16_t*)k; ra.v = (uint16_t*)v;
   ra.d_model = d; ra.head_dim = head_dim;

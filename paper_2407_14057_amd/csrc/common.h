@@ -91,6 +91,11 @@ struct RopeArgs {
   uint16_t* k;
   uint16_t* v;
   int d_model, head_dim;
+  // optional transposed copy of V for the attention kernel: vt[H*hd][vt_ld], token `row` in column
+  // vt_col[row] (row itself when vt_col is null); vt == nullptr: not written
+  uint16_t* vt;
+  int vt_ld;
+  const int32_t* vt_col;
 };
 
 // sk_ws: optional scratch of gemm_workspace_bytes() for the stream-K variant (fp32 partial tiles).
@@ -111,6 +116,11 @@ hipError_t launch_rmsnorm(const void* h, const void* gain, void* x, int rows, in
 hipError_t launch_v_transpose(const void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
                               int n_single, int batch, int max_rows, int vt_ld, int n_heads,
                               int head_dim, hipStream_t st);
+// Once per pruning stage: zeroes the columns of vt between each sequence's end and the next
+// multiple of 64 (the attention kernel multiplies them by probabilities that are exactly 0,
+// so they must be finite) and, for a packed batch, writes the column of every row.
+hipError_t launch_vt_stage_setup(void* vt, int32_t* vt_col, const int32_t* cu, const int32_t* cu_vt,
+                                 int n_single, int batch, int vt_ld, int n_feat, hipStream_t st);
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
                             int n_heads, int head_dim, hipStream_t st, float* z = nullptr,

@@ -255,6 +255,32 @@ hipError_t launch_v_transpose(const void* v, void* vt, const int32_t* cu, const 
   return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(256)
+vt_stage_setup_kernel(uint16_t* __restrict__ vt, int32_t* __restrict__ vt_col,
+                      const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt,
+                      int n_single, int vt_ld, int n_feat) {
+  const int b = blockIdx.y;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const int col0 = cu_vt ? cu_vt[b] : 0;
+  const int pad = ((n + 63) & ~63) - n;
+  const int f = blockIdx.x * 256 + threadIdx.x;
+  if (f < n_feat) {
+    uint16_t* p = vt + (size_t)f * vt_ld + col0 + n;
+    for (int i = 0; i < pad; ++i) p[i] = 0;
+  }
+  if (vt_col != nullptr)
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < n; t += gridDim.x * 256)
+      vt_col[row0 + t] = col0 + t;
+}
+
+hipError_t launch_vt_stage_setup(void* vt, int32_t* vt_col, const int32_t* cu, const int32_t* cu_vt,
+                                 int n_single, int batch, int vt_ld, int n_feat, hipStream_t st) {
+  hipLaunchKernelGGL(vt_stage_setup_kernel, dim3((n_feat + 255) / 256, batch), dim3(256), 0, st,
+                     (uint16_t*)vt, vt_col, cu, cu_vt, n_single, vt_ld, n_feat);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------
 // Final RMSNorm of each sequence's last row -> fp32, then the LM-head GEMV.
 // ------------------------------------------------------------------------------------------

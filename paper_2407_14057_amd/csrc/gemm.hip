@@ -29,15 +29,34 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + (wm * TM + i) * 32 + tok_l;
-    if (row >= M) continue;
+    const bool valid = row < M;
+    if (EPI != EPI_QKV_ROPE64 && EPI != EPI_QKV_ROPE128 && !valid) continue;
     if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
       constexpr int hd = (EPI == EPI_QKV_ROPE64) ? 64 : 128, half = hd >> 1;
       const int d = ra.d_model;
       const int col0 = n0 + wn * TN * 32;              // first column of this wave
       const int region = col0 / d;                      // 0 q, 1 k, 2 v (uniform per wave)
+      if (region != 2 && !valid) continue;              // (the V branch keeps every lane: lane pairs exchange data)
       uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)row * d +
                       (col0 - region * d) + feat_l;
       if (region == 2) {
+        // V goes to the KV cache row-major and, for the attention kernel's second product,
+        // transposed: a register holds one feature of 32 consecutive tokens across lanes, so
+        // each 2-byte store instruction writes 64 contiguous bytes of a feature row.
+        uint16_t* vtp = nullptr;
+        int vcol = 0;
+        if (ra.vt != nullptr && valid) {
+          vcol = ra.vt_col != nullptr ? ra.vt_col[row] : row;
+          vtp = ra.vt + (size_t)(col0 - region * d + feat_l) * ra.vt_ld + vcol;
+        }
+        // Neighbouring lanes hold neighbouring tokens: lane pairs swap one value each so that an
+        // even lane writes tokens (t, t+1) of one feature and the odd lane (t-1, t) of the next
+        // feature, 4 bytes per lane.  Needs the even lane's column to be even and both tokens
+        // to be in the same sequence and below M; otherwise 2-byte stores.
+        const int partner_col = __shfl_xor(vtp != nullptr ? vcol : -7, 1, 64);
+        const bool odd = lane & 1;
+        const bool paired = vtp != nullptr &&
+                            partner_col == (odd ? vcol - 1 : vcol + 1) && (((odd ? vcol - 1 : vcol) & 1) == 0);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -45,7 +64,28 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
             uint2 w2;
             w2.x = pack_bf16(acc[i][j][4 * g], acc[i][j][4 * g + 1]);
             w2.y = pack_bf16(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            *(uint2*)(dst + j * 32 + 8 * g) = w2;
+            if (valid) *(uint2*)(dst + j * 32 + 8 * g) = w2;
+            // features 8g..8g+3 of this token: w2.x = (f0, f1), w2.y = (f2, f3)
+            // even lane sends (f1, f3), receives partner's (f0, f2); odd lane the other way
+            const uint32_t mine_lo = (w2.x & 0xffff) | (w2.y << 16);        // (f0, f2)
+            const uint32_t mine_hi = (w2.x >> 16) | (w2.y & 0xffff0000u);   // (f1, f3)
+            const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)(odd ? mine_lo : mine_hi),
+                                                                    0xB1, 0xf, 0xf, true);
+            if (paired) {
+              // even lane: features f0, f2 of tokens (t, t+1); odd lane: f1, f3 of (t-1, t)
+              uint16_t* f0 = vtp + (size_t)(j * 32 + 8 * g + (odd ? 1 : 0)) * ra.vt_ld - (odd ? 1 : 0);
+              const uint32_t own = odd ? mine_hi : mine_lo;
+              const uint32_t a = odd ? ((got & 0xffff) | (own << 16)) : ((own & 0xffff) | (got << 16));
+              const uint32_t c = odd ? ((got >> 16) | (own & 0xffff0000u)) : ((own >> 16) | (got & 0xffff0000u));
+              *(uint32_t*)f0 = a;
+              *(uint32_t*)(f0 + 2 * (size_t)ra.vt_ld) = c;
+            } else if (vtp != nullptr) {
+              uint16_t* f0 = vtp + (size_t)(j * 32 + 8 * g) * ra.vt_ld;
+              f0[0] = (uint16_t)(w2.x & 0xffff);
+              f0[(size_t)ra.vt_ld] = (uint16_t)(w2.x >> 16);
+              f0[2 * (size_t)ra.vt_ld] = (uint16_t)(w2.y & 0xffff);
+              f0[3 * (size_t)ra.vt_ld] = (uint16_t)(w2.y >> 16);
+            }
           }
       } else {
         constexpr int P = hd >> 6;                      // blocks per half head: 1 (hd 64) or 2 (hd 128)
