@@ -208,7 +208,9 @@ def decoder_layer(h: np.ndarray, pos: np.ndarray, lw: LayerWeights, n_heads: int
     k, v [m, H, hd] as they enter the KV cache and s the Eq. 1 scores.
     """
     m, d = h.shape
-    x = store(rmsnorm(h, lw.attn_norm, eps))
+    # The normalised activations x and y are not rounding points: the data flow being modelled
+    # folds RMSNorm into the projections and never writes them to memory.
+    x = rmsnorm(h, lw.attn_norm, eps)
     q = (x @ lw.wq.T).reshape(m, n_heads, head_dim)
     k = (x @ lw.wk.T).reshape(m, n_heads, head_dim)
     v = store((x @ lw.wv.T).reshape(m, n_heads, head_dim))
@@ -217,7 +219,7 @@ def decoder_layer(h: np.ndarray, pos: np.ndarray, lw: LayerWeights, n_heads: int
     o, s = causal_attention(q, k, v)
     o = store(o)
     h = store(h + o.reshape(m, d) @ lw.wo.T)
-    y = store(rmsnorm(h, lw.ffn_norm, eps))
+    y = rmsnorm(h, lw.ffn_norm, eps)
     a = store(swiglu(y, lw.w_gate, lw.w_up))
     h = store(h + a @ lw.w_down.T)
     return h, k, v, s

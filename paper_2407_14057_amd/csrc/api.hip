@@ -142,7 +142,7 @@ void build_stages(int n_layers, const lazyllm_keep* sched, int n_sched, const in
 
 // ---- workspace layout -------------------------------------------------------------------
 struct Workspace {
-  size_t h0, h1, xa, q, o, vt, vt_col, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, total;
+  size_t h0, h1, ssq0, ssq1, q, o, vt, vt_col, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, total;
 };
 
 void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_seqlen,
@@ -153,7 +153,8 @@ void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_s
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w->h0 = take((size_t)T * d * 2);
   w->h1 = take((size_t)T * d * 2);
-  w->xa = take((size_t)T * d * 2);
+  w->ssq0 = take((size_t)T * 8);          // per row sum of squares of h (2^-32 fixed point), two roles
+  w->ssq1 = take((size_t)T * 8);
   w->q = take((size_t)T * d * 2);
   w->o = take((size_t)T * d * 2);
   w->vt = take(d * vt_ld * 2);
@@ -330,12 +331,16 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
     chk(hipMemcpyAsync(p, w->wq[l], d * d * 2, hipMemcpyDeviceToDevice, st));
     chk(hipMemcpyAsync(p + d * d * 2, w->wk[l], d * d * 2, hipMemcpyDeviceToDevice, st));
     chk(hipMemcpyAsync(p + 2 * d * d * 2, w->wv[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    // RMSNorm gains ride in the weights: x*g . w = x . (g*w); the 1/rms factor is applied by the
+    // GEMM epilogue (exact for gains of 1, one more bf16 rounding of the weight otherwise)
+    chk(launch_scale_cols(p, w->attn_norm[l], 3 * d, (int)d, st));
     m->wqkv.push_back(p);
     p = take(d * d * 2);
     chk(hipMemcpyAsync(p, w->wo[l], d * d * 2, hipMemcpyDeviceToDevice, st));
     m->wo.push_back(p);
     p = take(2 * fp * d * 2);                      // gate/up interleaved in 32-row blocks
     chk(launch_interleave_gate_up(w->w_gate[l], w->w_up[l], p, (int)f, (int)fp, (int)d, st));
+    chk(launch_scale_cols(p, w->ffn_norm[l], 2 * fp, (int)d, st));
     m->wgu.push_back(p);
     p = take(d * fp * 2);                          // down, K zero-padded to f_pad
     chk(launch_copy_rows(w->w_down[l], p, (int)d, (int)f, (int)f, (int)fp, st));
@@ -439,8 +444,17 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   int cur = 0;
   LZ_RUN(LAZYLLM_STEP_EMBED, -1, T, 2.0 * T * rowb,
          launch_embed(m->embed, token_ids, embed_scale, cu_dev, B, T, d, c->vocab, hbuf[0],
-                      res->kept_pos[0], res->status, st));
+                      res->kept_pos[0], res->status, st, (unsigned long long*)(W + ws.ssq0)));
   const int fp = m->f_pad;
+  // RMSNorm is folded into the projections that consume it (no launch, no normalised copy of
+  // h): whoever writes h also leaves each row's sum of squares -- the embedding and compaction
+  // kernels directly, the two residual GEMMs by integer atomics from their epilogues -- and the
+  // QKV and gate/up GEMMs scale their output rows by 1/rms (gains are folded into their weights).
+  // ssq_attn belongs to the h that enters a layer, ssq_ffn to the h after the attention block;
+  // each is zeroed by the GEMM that runs just before the one that accumulates into it.
+  unsigned long long* ssq_attn = (unsigned long long*)(W + ws.ssq0);
+  unsigned long long* ssq_ffn = (unsigned long long*)(W + ws.ssq1);
+  const float ssq_mul = 1.0f / (4294967296.0f * (float)d);
   for (int l = 0; l < L; ++l) {
     const int s = stg.stage_of_layer[l];
     const int n = (int)stg.total[s];
@@ -456,7 +470,8 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                            prune_idx, st));
       LZ_RUN(LAZYLLM_STEP_GATHER, l, n_prev, 2.0 * n_prev * rowb,
              launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
-                           hbuf[cur ^ 1], res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st));
+                           hbuf[cur ^ 1], res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st,
+                           ssq_attn));
       cur ^= 1;
     }
     char* h = hbuf[cur];
@@ -471,24 +486,23 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       for (int k = 1; k <= s; ++k) nb = keep_count(nb, stg.permille[k]);
       att_flops += 2.0 * (double)nb * ((double)nb + 1.0) * dd;
     }
-    LZ_RUN(LAZYLLM_STEP_RMSNORM, l, n, 2.0 * n * rowb,
-           launch_rmsnorm(h, m->attn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
     // QKV projection with the rotary embedding (original positions) applied in the epilogue;
     // K and V land directly in this layer's KV cache.
-    RopeArgs ra{};
+    EpiArgs ra{};
     ra.pos = res->kept_pos[l]; ra.table = rope;
     ra.q = (uint16_t*)(W + ws.q); ra.k = (uint16_t*)res->k[l]; ra.v = (uint16_t*)res->v[l];
     ra.d_model = d; ra.head_dim = hd;
     // ... and V also transposed into the workspace copy the attention kernel reads
     ra.vt = (uint16_t*)(W + ws.vt); ra.vt_ld = (int)stg.vt_ld[s];
     ra.vt_col = B > 1 ? (const int32_t*)(W + ws.vt_col) : nullptr;
+    ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
     if (stg.first_layer[s] == l)
       LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 0.0,
              launch_vt_stage_setup(W + ws.vt, B > 1 ? (int32_t*)(W + ws.vt_col) : nullptr, cu,
                                    cu_vt + s * BW, 0, B, (int)stg.vt_ld[s], d, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * 3.0 * dd * dd,
-           launch_gemm(W + ws.xa, m->wqkv[l], nullptr, nullptr, n, 3 * d, d, d, d, 0,
-                       EPI_QKV_ROPE, st, &ra));
+           launch_gemm(h, m->wqkv[l], nullptr, nullptr, n, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st,
+                       &ra));
     // Eq. 1 needs the last query's logits against every key, which the attention kernel has
     // in registers anyway: it leaves them in the score scratch, and one small kernel turns
     // them into the head-averaged probabilities.
@@ -503,16 +517,20 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       LZ_RUN(LAZYLLM_STEP_SCORE, l, n, 4.0 * n * H + 4.0 * n,
              launch_score_finish(res->scores[l], W + ws.score, cu, cu_vt + s * BW, 0, B,
                                  (int)stg.vt_ld[s], stg.max_rows[s], H, st));
+    EpiArgs eo{};
+    eo.ssq_out = ssq_ffn;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
-           launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st, nullptr,
+           launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st, &eo,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
-    LZ_RUN(LAZYLLM_STEP_RMSNORM, l, n, 2.0 * n * rowb,
-           launch_rmsnorm(h, m->ffn_norm[l], W + ws.xa, n, d, c->rms_eps, st));
+    EpiArgs eg{};
+    eg.ssq_in = ssq_ffn; eg.ssq_mul = ssq_mul; eg.eps = c->rms_eps; eg.ssq_clear = ssq_attn;
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, n, 2.0 * n * 2.0 * (double)c->d_ffn * dd,
-           launch_gemm(W + ws.xa, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp,
-                       EPI_SWIGLU, st));
+           launch_gemm(h, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp, EPI_SWIGLU, st,
+                       &eg));
+    EpiArgs ed{};
+    ed.ssq_out = ssq_attn;
     LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, n, 2.0 * n * (double)c->d_ffn * dd,
-           launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st, nullptr,
+           launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
   }
   const int s_last = stg.stage_of_layer[L - 1];
@@ -607,7 +625,7 @@ int lazyllm_op_qkv_rope(const void* x, const void* wqkv, const int32_t* pos, int
   hipStream_t st = (hipStream_t)hip_stream;
   const int d = n_heads * head_dim;
   LZ_HIP(launch_rope_table((float2*)rope_table, max_pos + 1, head_dim, theta, st));
-  RopeArgs ra{};
+  EpiArgs ra{};
   ra.pos = pos; ra.table = (const float2*)rope_table;
   ra.q = (uint16_t*)q; ra.k = (uint16_t*)k; ra.v = (uint16_t*)v;
   ra.d_model = d; ra.head_dim = head_dim;

@@ -84,7 +84,8 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROP
 
 // Extra operands of the fused QKV + rotary epilogue: q, k, v are [rows, d_model] bf16,
 // table is float2 [positions, head_dim/2] = (cos, sin), pos the original position of each row.
-struct RopeArgs {
+struct EpiArgs {
+  // EPI_QKV_ROPE: rotary table and the three destinations
   const int32_t* pos;
   const float2* table;
   uint16_t* q;
@@ -96,13 +97,28 @@ struct RopeArgs {
   uint16_t* vt;
   int vt_ld;
   const int32_t* vt_col;
+  // RMSNorm folded into the projections (gains are folded into the weights when the model is
+  // made).  ssq_in: per token row, the sum of squares of the A operand's row as 2^-32 fixed point;
+  // the epilogue multiplies row t of C by rsqrt(ssq_in[t] * ssq_mul + eps), ssq_mul = 2^-32 / K.
+  // ssq_out: EPI_RESIDUAL adds the sum of squares of the (rounded) values it writes, one integer
+  // atomic per wave and row -- integer addition commutes, so the total does not depend on the
+  // order the waves arrive in.  ssq_clear: rows of this tile are zeroed there by the workgroups of
+  // the first tile column (the buffer the next residual GEMM accumulates into).
+  const unsigned long long* ssq_in;
+  float ssq_mul, eps;
+  unsigned long long* ssq_out;
+  unsigned long long* ssq_clear;
 };
+constexpr float SSQ_FIX = 4294967296.0f;      // 2^32
+__device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {
+  return (unsigned long long)(fminf(ss, 1.0e9f) * SSQ_FIX);
+}
 
 // sk_ws: optional scratch of gemm_workspace_bytes() for the stream-K variant (fp32 partial tiles).
 size_t gemm_workspace_bytes();
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
                        int lda, int ldw, int ldc, int epilogue, hipStream_t st,
-                       const RopeArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
+                       const EpiArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
 
 hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st);
 
@@ -110,7 +126,7 @@ hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta
 // cu == nullptr means one sequence of n_single rows (cu_vt likewise means offset 0).
 hipError_t launch_embed(const void* embed, const int32_t* ids, const float* scale, const int32_t* cu,
                         int batch, int total, int d, int vocab, void* h, int32_t* pos,
-                        int32_t* status, hipStream_t st);
+                        int32_t* status, hipStream_t st, unsigned long long* ssq = nullptr);
 hipError_t launch_rmsnorm(const void* h, const void* gain, void* x, int rows, int d, float eps,
                           hipStream_t st);
 hipError_t launch_v_transpose(const void* v, void* vt, const int32_t* cu, const int32_t* cu_vt,
@@ -141,7 +157,8 @@ hipError_t launch_select(const float* s, const int32_t* cu_prev, const int32_t* 
                          int32_t* prune_idx, hipStream_t st);
 hipError_t launch_gather(const void* h, const int32_t* pos, const int32_t* keep_idx, int n_keep,
                          const int32_t* prune_idx, int n_prune, void* h_out, int32_t* pos_out,
-                         void* aux_h, int32_t* aux_pos, int d, hipStream_t st);
+                         void* aux_h, int32_t* aux_pos, int d, hipStream_t st,
+                         unsigned long long* ssq = nullptr);
 hipError_t launch_final_norm(const void* h, const int32_t* cu, int n_single, int batch,
                              const void* gain, float* xf, int d, float eps, hipStream_t st);
 hipError_t launch_lm_head(const float* xf, const void* w_lm, float* logits, int batch, int d,
@@ -159,6 +176,7 @@ hipError_t launch_plan(const int32_t* cu_dev, int n_single, int batch, int expec
 // Weight repacking (model creation, off the hot path).
 hipError_t launch_copy_rows(const void* src, void* dst, int rows, int cols, int src_ld, int dst_ld,
                             hipStream_t st);
+hipError_t launch_scale_cols(void* w, const void* gain, size_t rows, int cols, hipStream_t st);
 hipError_t launch_interleave_gate_up(const void* gate, const void* up, void* dst, int f, int f_pad,
                                      int d, hipStream_t st);
 

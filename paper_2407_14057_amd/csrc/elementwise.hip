@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(256)
 embed_kernel(const uint4* __restrict__ embed, const int32_t* __restrict__ ids,
              const float* __restrict__ scale, const int32_t* __restrict__ cu, int batch, int total,
              int vec_per_row, int vocab, uint4* __restrict__ h, int32_t* __restrict__ pos,
-             int32_t* __restrict__ status) {
+             int32_t* __restrict__ status, unsigned long long* __restrict__ ssq) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + wave;
   if (row >= total) return;
@@ -114,8 +114,16 @@ embed_kernel(const uint4* __restrict__ embed, const int32_t* __restrict__ ids,
   }
   const uint4* src = embed + (size_t)id * vec_per_row;
   uint4* dst = h + (size_t)row * vec_per_row;
+  float ss = 0.f;                       // sum of squares of the row as stored (for the first RMSNorm)
   if (scale == nullptr) {
-    for (int v = lane; v < vec_per_row; v += 64) dst[v] = src[v];
+    for (int v = lane; v < vec_per_row; v += 64) {
+      const uint4 x = src[v];
+      dst[v] = x;
+      float f[8];
+      unpack8(x, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
   } else {
     const float sc = scale[row];
     for (int v = lane; v < vec_per_row; v += 64) {
@@ -123,16 +131,24 @@ embed_kernel(const uint4* __restrict__ embed, const int32_t* __restrict__ ids,
       unpack8(src[v], f);
 #pragma unroll
       for (int e = 0; e < 8; ++e) f[e] *= sc;
-      dst[v] = pack8(f);
+      const uint4 x = pack8(f);
+      dst[v] = x;
+      unpack8(x, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
     }
+  }
+  if (ssq != nullptr) {
+    ss = wave_sum(ss);
+    if (lane == 0) ssq[row] = ssq_to_fixed(ss);
   }
 }
 
 hipError_t launch_embed(const void* embed, const int32_t* ids, const float* scale, const int32_t* cu,
                         int batch, int total, int d, int vocab, void* h, int32_t* pos,
-                        int32_t* status, hipStream_t st) {
+                        int32_t* status, hipStream_t st, unsigned long long* ssq) {
   hipLaunchKernelGGL(embed_kernel, dim3((total + 3) / 4), dim3(256), 0, st, (const uint4*)embed, ids,
-                     scale, cu, batch, total, d / 8, vocab, (uint4*)h, pos, status);
+                     scale, cu, batch, total, d / 8, vocab, (uint4*)h, pos, status, ssq);
   return hipGetLastError();
 }
 
@@ -365,6 +381,22 @@ hipError_t launch_copy_rows(const void* src, void* dst, int rows, int cols, int 
   size_t total = (size_t)rows * dst_ld;
   hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                      (const uint16_t*)src, (uint16_t*)dst, rows, cols, src_ld, dst_ld);
+  return hipGetLastError();
+}
+
+// w[r][c] *= gain[c]: folds an RMSNorm gain into the projection that consumes the normalised row
+// (exact when the gain is 1).
+__global__ void scale_cols_kernel(uint16_t* __restrict__ w, const uint16_t* __restrict__ gain,
+                                  size_t total, int cols) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  w[idx] = to_bf16(bf16_to_float(w[idx]) * bf16_to_float(gain[idx % cols]));
+}
+
+hipError_t launch_scale_cols(void* w, const void* gain, size_t rows, int cols, hipStream_t st) {
+  const size_t total = rows * (size_t)cols;
+  hipLaunchKernelGGL(scale_cols_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                     (uint16_t*)w, (const uint16_t*)gain, total, cols);
   return hipGetLastError();
 }
 

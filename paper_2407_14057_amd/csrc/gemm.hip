@@ -24,12 +24,19 @@ template <int TM, int TN, int EPI>
 __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_t* __restrict__ C,
                                               const uint16_t* __restrict__ R, int M, int ldc,
                                               int m0, int n0, int wm, int wn, int lane,
-                                              const RopeArgs& ra) {
+                                              const EpiArgs& ra) {
   const int tok_l = lane & 31, feat_l = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + (wm * TM + i) * 32 + tok_l;
     const bool valid = row < M;
+    if (ra.ssq_clear != nullptr && n0 == 0 && wn == 0 && lane < 32 && valid) ra.ssq_clear[row] = 0;
+    if (EPI != EPI_RESIDUAL && ra.ssq_in != nullptr) {
+      // RMSNorm of the A operand's row, applied to the product
+      const float rs = valid ? rsqrtf((float)ra.ssq_in[row] * ra.ssq_mul + ra.eps) : 0.f;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] *= rs;
+    }
     if (EPI != EPI_QKV_ROPE64 && EPI != EPI_QKV_ROPE128 && !valid) continue;
     if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
       constexpr int hd = (EPI == EPI_QKV_ROPE64) ? 64 : 128, half = hd >> 1;
@@ -133,6 +140,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
         }
       }
     } else {
+      float ss = 0.f;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const size_t off = (size_t)row * ldc + n0 + (wn * TN + j) * 32 + feat_l;
@@ -150,7 +158,17 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
           w2.x = pack_bf16(v[0], v[1]);
           w2.y = pack_bf16(v[2], v[3]);
           *(uint2*)(C + off + 8 * g) = w2;
+          if (EPI == EPI_RESIDUAL) {
+            const float a = bf16_lo(w2.x), b = bf16_hi(w2.x), c = bf16_lo(w2.y), e = bf16_hi(w2.y);
+            ss += a * a + b * b + c * c + e * e;
+          }
         }
+      }
+      if (EPI == EPI_RESIDUAL && ra.ssq_out != nullptr) {
+        // rows past M left the loop above, so the partner lane (same token, other 4 features of
+        // each group of 8) is active whenever this one is
+        ss += __shfl_xor(ss, 32, 64);
+        if (lane < 32) atomicAdd(ra.ssq_out + row, ssq_to_fixed(ss));
       }
     }
   }
@@ -160,7 +178,7 @@ template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
             uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K, int lda,
-            int ldw, int ldc, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
+            int ldw, int ldc, int tiles_m, int tiles_n, int group_m, EpiArgs ra) {
   constexpr int NWAVES = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int A_INSTR = BM / 8 / NWAVES;      // wave-wide 1 KB copies per wave per step
@@ -313,7 +331,7 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 template <int WM, int WN, int TM, int TN>
 static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* R, int M, int N,
                              int K, int lda, int ldw, int ldc, int epi, int group_m,
-                             const RopeArgs& ra, hipStream_t st) {
+                             const EpiArgs& ra, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
@@ -369,7 +387,7 @@ template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(512)
 gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K,
-               int lda, int ldw, int ldc, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
+               int lda, int ldw, int ldc, int tiles_m, int tiles_n, int group_m, EpiArgs ra) {
   constexpr int NWAVES = 8;
   static_assert(WM * WN == NWAVES, "eight waves: two per SIMD");
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -538,7 +556,7 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 template <int WM, int WN, int TM, int TN>
 static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R, int M, int N,
                             int K, int lda, int ldw, int ldc, int epi, int group_m,
-                            const RopeArgs& ra, hipStream_t st) {
+                            const EpiArgs& ra, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   if (N % BN != 0) return hipErrorInvalidValue;
@@ -588,7 +606,8 @@ template <int EPI>
 __global__ void __launch_bounds__(256)
 gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, float* __restrict__ partial,
-               int M, int N, int K, int lda, int ldw, int ldc, int tiles_m, int tiles_n, int G) {
+               int M, int N, int K, int lda, int ldw, int ldc, int tiles_m, int tiles_n, int G,
+               unsigned long long* __restrict__ ssq_out) {
   constexpr int WM = 2, WN = 2, TM = 2, TN = 2, NWAVES = 4;
   constexpr int BM = SK_BM, BN = SK_BN;
   constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;
@@ -613,7 +632,8 @@ gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   const uint32_t a_row = (uint32_t)((wm * TM * 32 + (lane & 31)) * ROW_BYTES);
   const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
   const int crow = lane >> 3;
-  RopeArgs ra{};
+  EpiArgs ra{};
+  ra.ssq_out = ssq_out;
 
   long long u = u0;
   while (u < u1) {
@@ -725,7 +745,7 @@ template <int EPI>
 __global__ void __launch_bounds__(256)
 gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C,
                      const uint16_t* __restrict__ R, int M, int ldc, int tiles_m, int KT,
-                     long long U, int G) {
+                     long long U, int G, unsigned long long* __restrict__ ssq_out) {
   const int tile = blockIdx.x;
   const long long ua = (long long)tile * KT, ub = ua + KT - 1;
   // owner(u) = largest g with sk_begin(g) <= u
@@ -790,6 +810,14 @@ gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C
     w2.x = pack_bf16(acc.x, acc.y);
     w2.y = pack_bf16(acc.z, acc.w);
     *(uint2*)(C + off) = w2;
+    if (EPI == EPI_RESIDUAL && ssq_out != nullptr) {
+      // a row is 32 consecutive lanes (half a wave, all of them past the row < M test together)
+      const float a = bf16_lo(w2.x), b = bf16_hi(w2.x), c = bf16_lo(w2.y), e = bf16_hi(w2.y);
+      float ss = a * a + b * b + c * c + e * e;
+#pragma unroll
+      for (int sh = 16; sh >= 1; sh >>= 1) ss += __shfl_xor(ss, sh, 64);
+      if ((threadIdx.x & 31) == 0) atomicAdd(ssq_out + row, ssq_to_fixed(ss));
+    }
   }
 }
 
@@ -798,7 +826,7 @@ size_t gemm_workspace_bytes() { return (size_t)SK_GRID * 2 * SK_TILE_ELEMS * siz
 
 static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R, float* partial,
                             int M, int N, int K, int lda, int ldw, int ldc, int epi,
-                            hipStream_t st) {
+                            unsigned long long* ssq_out, hipStream_t st) {
   constexpr int LDS_BYTES = 2 * (SK_BM + SK_BN) * ROW_BYTES;
   const int tiles_m = (M + SK_BM - 1) / SK_BM, tiles_n = N / SK_BN, KT = K / BK;
   const long long U = (long long)tiles_m * tiles_n * KT;
@@ -815,11 +843,12 @@ static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R
     }                                                                                            \
     hipLaunchKernelGGL(kern, dim3(G), dim3(256), LDS_BYTES, st, (const uint16_t*)A,              \
                        (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, partial, M, N, K,   \
-                       lda, ldw, ldc, tiles_m, tiles_n, G);                                      \
+                       lda, ldw, ldc, tiles_m, tiles_n, G, ssq_out);                             \
     hipError_t e = hipGetLastError();                                                            \
     if (e != hipSuccess) return e;                                                               \
     hipLaunchKernelGGL(gemm_sk_fixup_kernel<E>, dim3(tiles_m * tiles_n, 16), dim3(256), 0, st,   \
-                       partial, (uint16_t*)C, (const uint16_t*)R, M, ldc, tiles_m, KT, U, G);    \
+                       partial, (uint16_t*)C, (const uint16_t*)R, M, ldc, tiles_m, KT, U, G,     \
+                       ssq_out);                                                                 \
   } while (0)
   if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
@@ -829,7 +858,7 @@ static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R
 }
 
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
-                       int lda, int ldw, int ldc, int epilogue, hipStream_t st, const RopeArgs* rope,
+                       int lda, int ldw, int ldc, int epilogue, hipStream_t st, const EpiArgs* rope,
                        void* sk_ws, size_t sk_ws_bytes) {
   if (M <= 0) return hipSuccess;
   if (N % 128 != 0 || K % BK != 0) return hipErrorInvalidValue;
@@ -837,12 +866,12 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
   // hook for measurements); 0 = choose here.
   int cfg = (epilogue >> 8) & 0xff, group_m = (epilogue >> 16) & 0x3f;
   epilogue &= 0xff;
-  RopeArgs ra{};
+  EpiArgs ra{};
+  if (rope != nullptr) ra = *rope;
   if (epilogue == EPI_QKV_ROPE) {
     if (rope == nullptr || (rope->head_dim != 64 && rope->head_dim != 128) ||
         N != 3 * rope->d_model || rope->d_model % 128 != 0)
       return hipErrorInvalidValue;
-    ra = *rope;
   }
   if (group_m == 0) group_m = 4;
   if (cfg == 0) {
@@ -886,7 +915,7 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_pp<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 6:                                             // 128x128 stream-K + fix-up
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
-            return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, st);
+            return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out, st);
     default: return hipErrorInvalidValue;
   }
 }

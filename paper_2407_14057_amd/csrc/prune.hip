@@ -414,7 +414,7 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
               const int32_t* __restrict__ keep_idx, int n_keep,
               const int32_t* __restrict__ prune_idx, int n_prune, uint4* __restrict__ h_out,
               int32_t* __restrict__ pos_out, uint4* __restrict__ aux_h,
-              int32_t* __restrict__ aux_pos, int vpr) {
+              int32_t* __restrict__ aux_pos, int vpr, unsigned long long* __restrict__ ssq) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + wave;
   if (r >= n_keep + n_prune) return;
@@ -431,6 +431,8 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
     if (lane == 0) aux_pos[ra] = pos[src_row];
   }
   const uint4* src = h + (size_t)src_row * vpr;
+  const bool want_ssq = ssq != nullptr && r < n_keep;   // kept rows feed the next RMSNorm
+  float ss = 0.f;
   int v = lane;
   for (; v + 64 * 7 < vpr; v += 64 * 8) {
     uint4 t[8];
@@ -438,18 +440,41 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
     for (int i = 0; i < 8; ++i) t[i] = src[v + 64 * i];
 #pragma unroll
     for (int i = 0; i < 8; ++i) dst[v + 64 * i] = t[i];
+    if (want_ssq) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float f[8];
+        unpack8(t[i], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+      }
+    }
   }
-  for (; v < vpr; v += 64) dst[v] = src[v];
+  for (; v < vpr; v += 64) {
+    const uint4 x = src[v];
+    dst[v] = x;
+    if (want_ssq) {
+      float f[8];
+      unpack8(x, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
+  }
+  if (want_ssq) {
+    ss = wave_sum(ss);
+    if (lane == 0) ssq[r] = ssq_to_fixed(ss);
+  }
 }
 
 hipError_t launch_gather(const void* h, const int32_t* pos, const int32_t* keep_idx, int n_keep,
                          const int32_t* prune_idx, int n_prune, void* h_out, int32_t* pos_out,
-                         void* aux_h, int32_t* aux_pos, int d, hipStream_t st) {
+                         void* aux_h, int32_t* aux_pos, int d, hipStream_t st,
+                         unsigned long long* ssq) {
   const int rows = n_keep + n_prune;
   if (rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(gather_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, (const uint4*)h, pos,
                      keep_idx, n_keep, prune_idx, n_prune, (uint4*)h_out, pos_out, (uint4*)aux_h,
-                     aux_pos, d / 8);
+                     aux_pos, d / 8, ssq);
   return hipGetLastError();
 }
 
