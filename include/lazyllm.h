@@ -221,6 +221,22 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
                     int32_t K, int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue,
                     void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* lazyllm_op_gemm with RMSNorm (the pre-norm of Sec. 3.1's Llama blocks) folded in, the form
+ * the prefill runs.  ssq: uint64 [M], a row's sum of squares in 2^-32 fixed point.
+ *  - ssq_in (epilogues 0 and 2): row t of the product is multiplied by
+ *    rsqrt(ssq_in[t] * 2^-32 / K + eps), i.e. C = rmsnorm(A) W^T for a gain of 1 (a gain is
+ *    folded into W's columns by the caller).
+ *  - ssq_out (epilogue 1): the sum of squares of each row of C as written (bf16) is ADDED to
+ *    ssq_out[t] by integer atomics (order-independent); the caller zeroes it beforehand, or
+ *    passes the same buffer as another call's ssq_clear.
+ *  - ssq_clear: rows 0..M-1 of this buffer are set to zero.
+ * Any of the three may be NULL. */
+int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R, int32_t M,
+                            int32_t N, int32_t K, int32_t lda, int32_t ldw, int32_t ldc,
+                            int32_t epilogue, const uint64_t* ssq_in, float eps, uint64_t* ssq_out,
+                            uint64_t* ssq_clear, void* workspace, size_t ws_bytes,
+                            void* hip_stream);
+
 /* x = h * rsqrt(mean(h^2) + eps) * gain, bf16 in and out, rows of width d. */
 int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d,
                        float eps, void* hip_stream);

@@ -95,6 +95,10 @@ _SIGNATURES = {
     "lazyllm_op_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                   C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lazyllm_op_gemm_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                          C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_size_t, C.c_void_p]),
     "lazyllm_op_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_float, C.c_void_p]),
     "lazyllm_op_qkv_rope": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -273,6 +277,14 @@ def lazyllm_op_gemm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, stream=None
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().lazyllm_op_gemm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(R), M, N, K, lda, ldw, ldc,
                                  epilogue, _ptr(workspace), wsb, _stream_ptr(stream)))
+
+
+def lazyllm_op_gemm_rmsnorm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, ssq_in=None, eps=1e-5,
+                            ssq_out=None, ssq_clear=None, stream=None, workspace=None) -> None:
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lazyllm_op_gemm_rmsnorm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(R), M, N, K, lda, ldw, ldc,
+                                         epilogue, _ptr(ssq_in), eps, _ptr(ssq_out), _ptr(ssq_clear),
+                                         _ptr(workspace), wsb, _stream_ptr(stream)))
 
 
 def lazyllm_op_rmsnorm(h, gain, x, rows, d, eps, stream=None) -> None:

@@ -607,6 +607,35 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
   return LAZYLLM_OK;
 }
 
+int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R, int32_t M,
+                            int32_t N, int32_t K, int32_t lda, int32_t ldw, int32_t ldc,
+                            int32_t epilogue, const uint64_t* ssq_in, float eps, uint64_t* ssq_out,
+                            uint64_t* ssq_clear, void* workspace, size_t ws_bytes,
+                            void* hip_stream) {
+  if (!A || !W || !C || M < 0 || N <= 0 || K <= 0) return LAZYLLM_EINVAL;
+  if (N % 128 != 0 || K % 64 != 0 || lda % 8 != 0 || ldw % 8 != 0 || ldc % 4 != 0)
+    return LAZYLLM_EINVAL;
+  if (lda < K || ldw < K) return LAZYLLM_EINVAL;
+  const int epi = epilogue & 0xff;
+  if (epilogue < 0 || epi > 2 || (epi == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
+  if (ldc < (epi == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
+  if ((ssq_in && (epi == EPI_RESIDUAL || !(eps > 0.f))) || (ssq_out && epi != EPI_RESIDUAL))
+    return LAZYLLM_EINVAL;
+  if (M == 0) return LAZYLLM_OK;
+  if (workspace != nullptr && ((uintptr_t)workspace & 255) != 0) return LAZYLLM_EINVAL;
+  EpiArgs ea{};
+  ea.ssq_in = (const unsigned long long*)ssq_in;
+  ea.ssq_mul = 1.0f / (4294967296.0f * (float)K);
+  ea.eps = eps;
+  ea.ssq_out = (unsigned long long*)ssq_out;
+  ea.ssq_clear = (unsigned long long*)ssq_clear;
+  // the stream-K schedule has no row scaling or clearing: only the plain residual form may use it
+  const bool sk_ok = !ssq_in && !ssq_clear;
+  LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, &ea,
+                     sk_ok ? workspace : nullptr, sk_ok ? ws_bytes : 0));
+  return LAZYLLM_OK;
+}
+
 int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d, float eps,
                        void* hip_stream) {
   if (!h || !gain || !x || rows < 0 || d <= 0 || d % 8 != 0 || d > 16384 || !(eps > 0.f))

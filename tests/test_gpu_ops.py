@@ -88,6 +88,64 @@ def test_gemm_stream_k(M, N, K, epi):
     assert torch.equal(outs[0], outs[1])
 
 
+def _ssq_fixed(rows_f64):
+    """Row sums of squares in the library's 2^-32 fixed point (from fp64, for inputs)."""
+    return torch.from_numpy(np.floor((rows_f64 ** 2).sum(axis=1) * 2.0 ** 32).astype(np.uint64).view(np.int64)).to(DEV)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (37, 256, 128), (513, 1536, 704), (355, 4096, 4096),
+                                   (2100, 6144, 512)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_SWIGLU])
+def test_gemm_with_rmsnorm_folded_in(M, N, K, epi):
+    """C = rmsnorm(A) W^T with the 1/rms factor applied to the product's rows (gain 1)."""
+    rng = np.random.default_rng(M + 3 * N + K + epi)
+    A = _rand_bf16(rng, (M, K), 0.7)
+    W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    a, w = _f64(A), _f64(W)
+    eps = 1e-5
+    acc = O.rmsnorm(a, np.ones(K), eps) @ w.T
+    ssq = _ssq_fixed(a)
+    cleared = torch.full((M + 2,), 77, dtype=torch.int64, device=DEV)
+    if epi == B.EPI_SWIGLU:
+        blocks = acc.reshape(M, N // 64, 2, 32)
+        ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+        Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm_rmsnorm(A, W, Cout, None, M, N, K, K, K, N // 2, epi, ssq_in=ssq, eps=eps,
+                                  ssq_clear=cleared)
+    else:
+        ref = acc
+        Cout = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm_rmsnorm(A, W, Cout, None, M, N, K, K, K, N, epi, ssq_in=ssq, eps=eps,
+                                  ssq_clear=cleared)
+    torch.cuda.synchronize()
+    _assert_bf16_close(_f64(Cout), ref, 1.0, "gemm+rmsnorm")
+    c = cleared.cpu().numpy()
+    assert np.all(c[:M] == 0) and np.all(c[M:] == 77)      # exactly rows 0..M-1 are zeroed
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (37, 256, 128), (355, 4096, 4096), (1182, 4096, 1408),
+                                   (2364, 4096, 512), (3376, 4096, 256)])
+def test_gemm_residual_leaves_row_sums_of_squares(M, N, K):
+    """The residual epilogue adds each written row's sum of squares (of the bf16 values it
+    stored) to ssq_out; integer atomics, so the total is the same on every run."""
+    rng = np.random.default_rng(M + N + K)
+    A = _rand_bf16(rng, (M, K)); W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    R = _rand_bf16(rng, (M, N))
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    got = []
+    for _ in range(2):
+        Cout = R.clone()
+        ssq = torch.zeros(M, dtype=torch.int64, device=DEV)
+        B.lazyllm_op_gemm_rmsnorm(A, W, Cout, Cout, M, N, K, K, K, N, B.EPI_RESIDUAL, ssq_out=ssq,
+                                  workspace=ws)
+        torch.cuda.synchronize()
+        got.append((Cout, ssq.cpu().numpy().view(np.uint64).astype(np.float64) / 2.0 ** 32))
+    ref = (_f64(got[0][0]) ** 2).sum(axis=1)                 # of the values actually stored
+    assert np.allclose(got[0][1], ref, rtol=2e-6, atol=1e-6), np.abs(got[0][1] / ref - 1).max()
+    assert np.array_equal(got[0][1], got[1][1]) and torch.equal(got[0][0], got[1][0])
+    _assert_bf16_close(_f64(got[0][0]), _f64(R) + _f64(A) @ _f64(W).T, 1.0, "gemm residual")
+
+
 def test_gemm_strided_and_edge_rows_untouched():
     rng = np.random.default_rng(5)
     M, N, K = 70, 256, 128
