@@ -20,11 +20,24 @@ constexpr int ROW_BYTES = BK * 2;
 // EPI_QKV_ROPE: the N axis is [q | k | v] of width d each.  A wave's TN*32 columns hold whole
 // heads, so the rotary partner of dimension i (i + hd/2) is the same register of block j + hd/64:
 // q and k are rotated in fp32 straight out of the accumulator and rounded to bf16 once.
+// 1/rms of this lane's TM token rows, fetched before the main loop so that the epilogue does not
+// wait for it (rows past M get 0).
+template <int TM>
+__device__ __forceinline__ void load_row_scales(float (&rs)[TM], const EpiArgs& ra, int M, int m0,
+                                                int wm, int lane) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + (wm * TM + i) * 32 + (lane & 31);
+    rs[i] = (ra.ssq_in != nullptr && row < M)
+                ? rsqrtf((float)ra.ssq_in[row] * ra.ssq_mul + ra.eps) : 0.f;
+  }
+}
+
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_t* __restrict__ C,
                                               const uint16_t* __restrict__ R, int M, int ldc,
                                               int m0, int n0, int wm, int wn, int lane,
-                                              const EpiArgs& ra) {
+                                              const EpiArgs& ra, const float* rs_pre = nullptr) {
   const int tok_l = lane & 31, feat_l = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -33,7 +46,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
     if (ra.ssq_clear != nullptr && n0 == 0 && wn == 0 && lane < 32 && valid) ra.ssq_clear[row] = 0;
     if (EPI != EPI_RESIDUAL && ra.ssq_in != nullptr) {
       // RMSNorm of the A operand's row, applied to the product
-      const float rs = valid ? rsqrtf((float)ra.ssq_in[row] * ra.ssq_mul + ra.eps) : 0.f;
+      const float rs = rs_pre != nullptr ? rs_pre[i]
+                       : valid ? rsqrtf((float)ra.ssq_in[row] * ra.ssq_mul + ra.eps) : 0.f;
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[i][j] *= rs;
     }
@@ -299,6 +313,8 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   const int KT = K / BK;
   issue(0, 0);
   if (KT > 1) issue(1, BK);
+  float rs[TM];
+  load_row_scales<TM>(rs, ra, M, m0, wm, lane);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   LZ_LOAD_FRAGS(0, lds, 0);
@@ -325,7 +341,7 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #undef LZ_MFMAS
 #undef LZ_SCHED
 
-  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
+  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
 }
 
 template <int WM, int WN, int TM, int TN>
@@ -524,6 +540,8 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 
   const int KT = K / BK;
   issue(0, 0);
+  float rs[TM];
+  load_row_scales<TM>(rs, ra, M, m0, wm, lane);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (group == 1) LZ_PHASE_END();                 // the second group starts one phase later
@@ -550,7 +568,7 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #undef LZ_COMPUTE_PHASE
 #undef LZ_COMPUTE_COPY_PHASE
 #undef LZ_PHASE_END
-  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
+  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
 }
 
 template <int WM, int WN, int TM, int TN>
@@ -901,12 +919,8 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     if (cfg == 0) return hipErrorInvalidValue;
   }
   switch (cfg) {
-    case 1: if (N % 256) return hipErrorInvalidValue;   // 256x256, 4 waves of 128x128
-            return launch_cfg<2, 2, 4, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 2:                                             // 128x128, 4 waves of 64x64
             return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
-    case 3: if (N % 256) return hipErrorInvalidValue;   // 256x256, 8 waves of 64x128
-            return launch_cfg<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 5:                                             // 256x256, 8 waves of 64x128, ping-pong
