@@ -19,11 +19,11 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch the dominant kernel (gate/up GEMM, SwiGLU epilogue) moves through the L2s'
 # fabric side, averaged over the 32 launches of a 7b_3376 step: rocprofv3 FETCH_SIZE x 2 KiB +
 # WRITE_SIZE x 1 KiB, factors calibrated on a 1 GiB copy (profiles/gemm_attention_7b_3376_pmc.md).
-TRAFFIC_GATE_UP_7B_3376 = 648.05e6 + 40.4e6
-STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<2> (gate/up projection + SiLU*mul)",
-               "gemm_qkv": "gemm_pp_kernel<5> (QKV projection + RoPE)",
-               "gemm_down": "gemm_pp_kernel<1> (down projection + residual)",
-               "gemm_o": "gemm_pp_kernel<1> (O projection + residual)"}
+TRAFFIC_GATE_UP_7B_3376 = 715.95e6
+STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<4,2,2,4,EPI_SWIGLU> (RMSNorm scale + gate/up projection + SiLU*mul)",
+               "gemm_qkv": "gemm_pp_kernel<4,2,2,4,EPI_QKV_ROPE128> (RMSNorm scale + QKV projection + RoPE + V^T)",
+               "gemm_down": "gemm_pp_kernel<4,2,2,4,EPI_RESIDUAL> (down projection + residual + row sums of squares)",
+               "gemm_o": "gemm_pp_kernel<4,2,2,4,EPI_RESIDUAL> (O projection + residual + row sums of squares)"}
 
 
 def kernel_sweep(args, torch, B) -> int:
