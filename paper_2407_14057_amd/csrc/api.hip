@@ -504,8 +504,8 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
            launch_gemm(h, m->wqkv[l], nullptr, nullptr, n, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st,
                        &ra));
     // Eq. 1 needs the last query's logits against every key, which the attention kernel has
-    // in registers anyway: it leaves them in the score scratch, and one small kernel turns
-    // them into the head-averaged probabilities.
+    // in registers anyway: it leaves them in the score scratch (the gate/up launch below turns
+    // them into the head-averaged probabilities).
     const bool scored = res->scores[l] != nullptr;
     LZ_RUN(LAZYLLM_STEP_ATTENTION, l, n, att_flops,
            launch_attention(W + ws.q, res->k[l], W + ws.vt, W + ws.o, cu, cu_vt + s * BW, 0, B,
@@ -513,10 +513,6 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                             scored ? score_z(W + ws.score) : nullptr,
                             scored ? score_zstat(W + ws.score, (int)stg.vt_ld[s], H) : nullptr,
                             (int)stg.vt_ld[s]));
-    if (scored)
-      LZ_RUN(LAZYLLM_STEP_SCORE, l, n, 4.0 * n * H + 4.0 * n,
-             launch_score_finish(res->scores[l], W + ws.score, cu, cu_vt + s * BW, 0, B,
-                                 (int)stg.vt_ld[s], stg.max_rows[s], H, st));
     EpiArgs eo{};
     eo.ssq_out = ssq_ffn;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
@@ -524,6 +520,16 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
     EpiArgs eg{};
     eg.ssq_in = ssq_ffn; eg.ssq_mul = ssq_mul; eg.eps = c->rms_eps; eg.ssq_clear = ssq_attn;
+    if (scored) {
+      // Eq. 1's last step (softmax of the logits the attention kernel left, averaged over heads)
+      // rides in this launch as extra workgroups behind the GEMM's tiles
+      eg.sf_z = score_z(W + ws.score);
+      eg.sf_stat = (const float2*)score_zstat(W + ws.score, (int)stg.vt_ld[s], H);
+      eg.sf_s = res->scores[l];
+      eg.sf_cu = cu; eg.sf_cu_z = cu_vt + s * BW;
+      eg.sf_n_single = 0; eg.sf_heads = H; eg.sf_z_ld = (int)stg.vt_ld[s];
+      eg.sf_max_rows = stg.max_rows[s]; eg.sf_batch = B;
+    }
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, n, 2.0 * n * 2.0 * (double)c->d_ffn * dd,
            launch_gemm(h, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp, EPI_SWIGLU, st,
                        &eg));

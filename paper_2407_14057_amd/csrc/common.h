@@ -77,6 +77,34 @@ __device__ __forceinline__ void seq_range(const int32_t* cu, int b, int n_single
   else { row0 = 0; n = n_single; }
 }
 
+// Eq. 1 for `threads` consecutive tokens of sequence b starting at t0: s_j = (1/H) sum_h
+// exp(z[h][j] - ref_h) / sum_h, heads added in order.  hs: n_heads float2 of LDS.  BASE2: logits and
+// reference points in the base-2 domain (the attention kernel's).  padded: z rows are laid out
+// like the Vt buffer (sequence b at cu_z[b]) instead of packed.
+template <bool BASE2>
+__device__ __forceinline__ void score_finish_block(const float* __restrict__ z,
+                                                   const float2* __restrict__ hstat,
+                                                   float* __restrict__ s, const int32_t* cu,
+                                                   int n_single, int n_heads, int z_ld,
+                                                   const int32_t* cu_z, bool padded, int b, int t0,
+                                                   float2* hs) {
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  if (t0 >= n) return;
+  for (int h = threadIdx.x; h < n_heads; h += blockDim.x) hs[h] = hstat[(size_t)b * n_heads + h];
+  __syncthreads();
+  const int t = t0 + threadIdx.x;
+  if (t < n) {
+    float acc = 0.f;
+    const int zoff = padded ? (cu_z ? cu_z[b] : 0) : row0;   // where this sequence's logits start
+    for (int h = 0; h < n_heads; ++h) {
+      const float dz = z[(size_t)h * z_ld + zoff + t] - hs[h].x;
+      acc += (BASE2 ? __builtin_amdgcn_exp2f(dz) : __expf(dz)) * hs[h].y;
+    }
+    s[row0 + t] = acc / (float)n_heads;
+  }
+}
+
 // ---- launch interface (host) ------------------------------------------------------------
 // EPI_QKV_ROPE is the caller-facing value; the kernel is instantiated per head size.
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_QKV_ROPE = 3,
@@ -108,6 +136,16 @@ struct EpiArgs {
   float ssq_mul, eps;
   unsigned long long* ssq_out;
   unsigned long long* ssq_clear;
+  // Side job for workgroups past the last tile (independent of the GEMM; it rides in this launch
+  // because a launch of its own would cost more than the work): Eq. 1 from the logits the
+  // attention kernel left, see score_finish_block.  sf_z == nullptr: none.
+  const float* sf_z;
+  const float2* sf_stat;
+  float* sf_s;
+  const int32_t* sf_cu;
+  const int32_t* sf_cu_z;
+  int sf_n_single, sf_heads, sf_z_ld, sf_max_rows, sf_batch;
+  int sf_blocks_per_seq;             // filled in by the launcher (depends on the workgroup size)
 };
 constexpr float SSQ_FIX = 4294967296.0f;      // 2^32
 __device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {

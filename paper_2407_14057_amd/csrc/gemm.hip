@@ -200,6 +200,13 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
   static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "tile/wave mismatch");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x >= tiles_m * tiles_n) {     // side job (see EpiArgs): Eq. 1 scores
+    const int sb = (int)blockIdx.x - tiles_m * tiles_n;
+    score_finish_block<true>(ra.sf_z, ra.sf_stat, ra.sf_s, ra.sf_cu, ra.sf_n_single, ra.sf_heads,
+                             ra.sf_z_ld, ra.sf_cu_z, true, sb / ra.sf_blocks_per_seq,
+                             (sb % ra.sf_blocks_per_seq) * (int)blockDim.x, (float2*)lds);
+    return;
+  }
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -351,7 +358,11 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-  dim3 grid(tiles_m * tiles_n), block(WM * WN * 64);
+  const int threads = WM * WN * 64;
+  EpiArgs ea = ra;
+  ea.sf_blocks_per_seq = (ea.sf_max_rows + threads - 1) / threads;
+  const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
+  dim3 grid(tiles_m * tiles_n + side), block(threads);
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
     auto kern = gemm_kernel<WM, WN, TM, TN, E>;                                                  \
@@ -364,7 +375,7 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
     }                                                                                            \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)A, (const uint16_t*)W, \
                        (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc, tiles_m,        \
-                       tiles_n, group_m, ra);                                                    \
+                       tiles_n, group_m, ea);                                                    \
   } while (0)
   if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
@@ -412,6 +423,13 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   static_assert(BM % 64 == 0 && BN % 64 == 0 && NCOPY <= 2 * TM * TN, "tile/wave mismatch");
   constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x >= tiles_m * tiles_n) {     // side job (see EpiArgs): Eq. 1 scores
+    const int sb = (int)blockIdx.x - tiles_m * tiles_n;
+    score_finish_block<true>(ra.sf_z, ra.sf_stat, ra.sf_s, ra.sf_cu, ra.sf_n_single, ra.sf_heads,
+                             ra.sf_z_ld, ra.sf_cu_z, true, sb / ra.sf_blocks_per_seq,
+                             (sb % ra.sf_blocks_per_seq) * (int)blockDim.x, (float2*)lds);
+    return;
+  }
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -579,7 +597,10 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   if (N % BN != 0) return hipErrorInvalidValue;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-  dim3 grid(tiles_m * tiles_n), block(512);
+  EpiArgs ea = ra;
+  ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
+  const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
+  dim3 grid(tiles_m * tiles_n + side), block(512);
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
     auto kern = gemm_pp_kernel<WM, WN, TM, TN, E>;                                               \
@@ -592,7 +613,7 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
     }                                                                                            \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)A, (const uint16_t*)W, \
                        (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc, tiles_m,        \
-                       tiles_n, group_m, ra);                                                    \
+                       tiles_n, group_m, ea);                                                    \
   } while (0)
   if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);

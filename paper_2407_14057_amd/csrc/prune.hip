@@ -165,23 +165,8 @@ score_finish_kernel(const float* __restrict__ z, const float2* __restrict__ hsta
                     float* __restrict__ s, const int32_t* __restrict__ cu, int n_single,
                     int n_heads, int z_ld, const int32_t* __restrict__ cu_z, bool padded) {
   __shared__ float2 hs[SCORE_MAX_HEADS];
-  const int b = blockIdx.y;
-  int row0, n;
-  seq_range(cu, b, n_single, row0, n);
-  const int t0 = blockIdx.x * 256;
-  if (t0 >= n) return;
-  for (int h = threadIdx.x; h < n_heads; h += 256) hs[h] = hstat[(size_t)b * n_heads + h];
-  __syncthreads();
-  const int t = t0 + threadIdx.x;
-  if (t < n) {
-    float acc = 0.f;
-    const int zoff = padded ? (cu_z ? cu_z[b] : 0) : row0;   // where this sequence's logits start
-    for (int h = 0; h < n_heads; ++h) {
-      const float dz = z[(size_t)h * z_ld + zoff + t] - hs[h].x;
-      acc += (BASE2 ? __builtin_amdgcn_exp2f(dz) : __expf(dz)) * hs[h].y;
-    }
-    s[row0 + t] = acc / (float)n_heads;
-  }
+  score_finish_block<BASE2>(z, hstat, s, cu, n_single, n_heads, z_ld, cu_z, padded, blockIdx.y,
+                            blockIdx.x * 256, hs);
 }
 
 // scratch layout: z[H][total_rows] fp32 | hstat[batch][H] float2 | partials (upper bound)
