@@ -563,11 +563,26 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (group == 1) LZ_PHASE_END();                 // the second group starts one phase later
+  const bool idle_wave = m0 + wm * TM * 32 >= M;
   for (int kt = 0; kt < KT; ++kt) {
     const char* cur = lds + (kt & 1) * STAGE_BYTES;
     // The last step copies itself again into the stage nobody reads any more: no branch in
     // the MFMA stream, and the copy is drained by the waits below like any other.
     const int k_next = (kt + 1 < KT ? kt + 1 : kt) * BK;
+    if (idle_wave) {
+      // all of this wave's rows are past M (last tile row): it still copies its share of the
+      // stages and keeps the barriers, but runs no MFMA -- the part is power-limited, and the
+      // matrix work on padding rows would only lower the clock for everybody else
+      LZ_PHASE_END();
+#pragma unroll
+      for (int q = 0; q < NCOPY; ++q) issue_one((kt + 1) & 1, k_next, q);
+      LZ_PHASE_END();
+      if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      LZ_PHASE_END();
+      if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      LZ_PHASE_END();
+      continue;
+    }
     LZ_MEM_PHASE(cur, 0);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     LZ_PHASE_END();
