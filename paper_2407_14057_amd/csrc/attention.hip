@@ -168,7 +168,7 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
     const int k0 = it * ATT_BN;
     const char* st = lds + stage_c * STAGE;
     const int stage_n = stage_c + 1 == NS ? 0 : stage_c + 1;
-    const bool active = k0 <= q_hi;          // else every key of this step is in the future
+    const bool active = k0 <= q_hi && q_lo < n;   // else every key is in the future, or every query past the end
     bf16x8_t pf[2][2];
     if (active) {
       floatx16_t sacc[2];
