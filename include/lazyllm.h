@@ -152,7 +152,9 @@ int lazyllm_abi_version(void);
 
 /* Copies the weights into the library's own MFMA-friendly layout (fused QKV,
  * gate/up interleaved in 32-row blocks, d_ffn zero-padded to a multiple of
- * 128).  Allocates device memory (about the size of the weights), runs the
+ * 128; the RMSNorm gains multiplied into the columns of the QKV and gate/up
+ * matrices, which is exact for gains of 1 and one more bf16 rounding of the
+ * weight otherwise).  Allocates device memory (about the size of the weights), runs the
  * repack on `hip_stream` and synchronises it: after return the caller's
  * weight buffers are no longer referenced.  *out is set only on success. */
 int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, void* hip_stream,
@@ -186,7 +188,10 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
  * then writes up to `capacity` records (launch order) and the total count.  `work` is the
  * launch's algorithmic work: FLOPs for the GEMM and attention steps (Sec. 4.3: linear layers
  * grow linearly, attention quadratically with the tokens computed), bytes for the
- * bandwidth-bound steps.  Not thread-safe; one stream at a time. */
+ * bandwidth-bound steps.  Not thread-safe; one stream at a time.
+ * Steps without a launch of their own never appear: RMSNorm is folded into the QKV and gate/up
+ * GEMMs, Eq. 1's finish rides in the gate/up launch, and V_TRANSPOSE is only the once-per-stage
+ * zeroing of the transposed V buffer's padding (the copy itself is part of the QKV epilogue). */
 enum lazyllm_step {
   LAZYLLM_STEP_PLAN = 0, LAZYLLM_STEP_ROPE_TABLE, LAZYLLM_STEP_EMBED, LAZYLLM_STEP_SELECT,
   LAZYLLM_STEP_GATHER, LAZYLLM_STEP_RMSNORM, LAZYLLM_STEP_GEMM_QKV, LAZYLLM_STEP_V_TRANSPOSE,
