@@ -146,6 +146,7 @@ struct EpiArgs {
   const int32_t* sf_cu_z;
   int sf_n_single, sf_heads, sf_z_ld, sf_max_rows, sf_batch;
   int sf_blocks_per_seq;             // filled in by the launcher (depends on the workgroup size)
+  int stage_out;                     // filled in by the launcher: tile goes out through LDS (see gemm.hip)
 };
 constexpr float SSQ_FIX = 4294967296.0f;      // 2^32
 __device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {

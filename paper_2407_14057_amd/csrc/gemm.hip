@@ -33,11 +33,23 @@ __device__ __forceinline__ void load_row_scales(float (&rs)[TM], const EpiArgs& 
   }
 }
 
-template <int TM, int TN, int EPI>
+// Staged output: the epilogue writes the tile row-major into LDS (free after the K loop) and the
+// workgroup then copies it out with 16-byte stores that cover whole 128-byte lines.  Straight from
+// the MFMA layout a store instruction's 64 lanes hit 64 different rows, i.e. 64 separate lines:
+// that costs 5-11 us per round of 256x256 tiles (measured by leaving the stores out).
+// Layout: rows of NCH 16-byte chunks, chunk c of row r at slot c ^ (r & (NCH-1)): the 32 lanes
+// that write one column block of 32 rows and the lanes that read one row both spread over the banks.
+template <int NCH>
+__device__ __forceinline__ uint32_t stage_off(int r, int c) {      // c: element column, multiple of 4
+  return (uint32_t)(r * (NCH * 16) + (((c >> 3) ^ (r & (NCH - 1))) << 4) + ((c & 7) << 1));
+}
+
+template <int TM, int TN, int EPI, bool STAGED = false, int NCH = 32>
 __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_t* __restrict__ C,
                                               const uint16_t* __restrict__ R, int M, int ldc,
                                               int m0, int n0, int wm, int wn, int lane,
-                                              const EpiArgs& ra, const float* rs_pre = nullptr) {
+                                              const EpiArgs& ra, const float* rs_pre = nullptr,
+                                              char* sl = nullptr) {
   const int tok_l = lane & 31, feat_l = 4 * (lane >> 5);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -85,7 +97,12 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
             uint2 w2;
             w2.x = pack_bf16(acc[i][j][4 * g], acc[i][j][4 * g + 1]);
             w2.y = pack_bf16(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            if (valid) *(uint2*)(dst + j * 32 + 8 * g) = w2;
+            if (STAGED) {
+              *(uint2*)(sl + stage_off<NCH>((wm * TM + i) * 32 + tok_l,
+                                            (wn * TN + j) * 32 + 8 * g + feat_l)) = w2;
+            } else if (valid) {
+              *(uint2*)(dst + j * 32 + 8 * g) = w2;
+            }
             // features 8g..8g+3 of this token: w2.x = (f0, f1), w2.y = (f2, f3)
             // even lane sends (f1, f3), receives partner's (f0, f2); odd lane the other way
             const uint32_t mine_lo = (w2.x & 0xffff) | (w2.y << 16);        // (f0, f2)
@@ -127,11 +144,17 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
               lo[e] = x1 * c[e] - x2 * sn[e];
               hi[e] = x2 * c[e] + x1 * sn[e];
             }
-            uint2 w2;
+            uint2 w2, w3;
             w2.x = pack_bf16(lo[0], lo[1]); w2.y = pack_bf16(lo[2], lo[3]);
-            *(uint2*)(dst + j * 32 + 8 * g) = w2;
-            w2.x = pack_bf16(hi[0], hi[1]); w2.y = pack_bf16(hi[2], hi[3]);
-            *(uint2*)(dst + (j + P) * 32 + 8 * g) = w2;
+            w3.x = pack_bf16(hi[0], hi[1]); w3.y = pack_bf16(hi[2], hi[3]);
+            if (STAGED) {
+              const int rl = (wm * TM + i) * 32 + tok_l, cl = (wn * TN + j) * 32 + 8 * g + feat_l;
+              *(uint2*)(sl + stage_off<NCH>(rl, cl)) = w2;
+              *(uint2*)(sl + stage_off<NCH>(rl, cl + P * 32)) = w3;
+            } else {
+              *(uint2*)(dst + j * 32 + 8 * g) = w2;
+              *(uint2*)(dst + (j + P) * 32 + 8 * g) = w3;
+            }
           }
         }
       }
@@ -150,7 +173,11 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
           uint2 w2;
           w2.x = pack_bf16(v[0], v[1]);
           w2.y = pack_bf16(v[2], v[3]);
-          *(uint2*)(cp + 8 * g) = w2;
+          if (STAGED)
+            *(uint2*)(sl + stage_off<NCH>((wm * TM + i) * 32 + tok_l,
+                                          (wn * TN + j) * 16 + 8 * g + feat_l)) = w2;
+          else
+            *(uint2*)(cp + 8 * g) = w2;
         }
       }
     } else {
@@ -163,15 +190,19 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * g + e];
+          char* sp = STAGED ? sl + stage_off<NCH>((wm * TM + i) * 32 + tok_l,
+                                                  (wn * TN + j) * 32 + 8 * g + feat_l) : nullptr;
           if (EPI == EPI_RESIDUAL) {
-            const uint2 r2 = *(const uint2*)(R + off + 8 * g);
+            // staged: the residual tile was copied into the same LDS slots beforehand
+            const uint2 r2 = STAGED ? *(const uint2*)sp : *(const uint2*)(R + off + 8 * g);
             v[0] += bf16_lo(r2.x); v[1] += bf16_hi(r2.x);
             v[2] += bf16_lo(r2.y); v[3] += bf16_hi(r2.y);
           }
           uint2 w2;
           w2.x = pack_bf16(v[0], v[1]);
           w2.y = pack_bf16(v[2], v[3]);
-          *(uint2*)(C + off + 8 * g) = w2;
+          if (STAGED) *(uint2*)sp = w2;
+          else *(uint2*)(C + off + 8 * g) = w2;
           if (EPI == EPI_RESIDUAL) {
             const float a = bf16_lo(w2.x), b = bf16_hi(w2.x), c = bf16_lo(w2.y), e = bf16_hi(w2.y);
             ss += a * a + b * b + c * c + e * e;
@@ -601,7 +632,50 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #undef LZ_COMPUTE_PHASE
 #undef LZ_COMPUTE_COPY_PHASE
 #undef LZ_PHASE_END
-  gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
+  if (EPI == EPI_SWIGLU || !ra.stage_out) {        // (the launcher never stages the SiLU*mul form)
+    gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
+    return;
+  }
+  // ---- staged output (see stage_off): tile -> LDS in the MFMA layout's order, LDS -> global in
+  // whole rows.  BNO = output columns of the tile, NCH = its 16-byte chunks per row.
+  constexpr int BNO = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int NCH = BNO / 8;
+  static_assert((NCH & (NCH - 1)) == 0 && BM * BNO * 2 <= 2 * STAGE_BYTES, "staged tile must fit the stages");
+  __syncthreads();                                  // every wave is done reading the stages
+  if (EPI == EPI_RESIDUAL) {
+    // the residual tile comes in the same way (whole rows, straight into LDS); a wave
+    // instruction covers 64 / NCH rows
+    constexpr int RPI = 64 / NCH, R_INSTR = BM / RPI / NWAVES;
+#pragma unroll
+    for (int q = 0; q < R_INSTR; ++q) {
+      const int instr = wave * R_INSTR + q;
+      const int rr = instr * RPI + lane / NCH;
+      const int chunk = (lane % NCH) ^ (rr & (NCH - 1));
+      int gr = m0 + rr;
+      gr = gr < M ? gr : M - 1;
+      g2l16(R + (size_t)gr * ldc + n0 + chunk * 8, lds + instr * 1024);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  gemm_epilogue<TM, TN, EPI, true, NCH>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs, lds);
+  __syncthreads();
+  uint16_t* obase;
+  int old;
+  if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
+    const int region = n0 / ra.d_model;             // the tile lies inside q, k or v
+    obase = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (n0 - region * ra.d_model);
+    old = ra.d_model;
+  } else {
+    obase = C + (EPI == EPI_SWIGLU ? n0 / 2 : n0);
+    old = ldc;
+  }
+  for (int idx = threadIdx.x; idx < BM * NCH; idx += NWAVES * 64) {
+    const int r = idx / NCH, ch = idx % NCH;
+    if (m0 + r < M)
+      *(uint4*)(obase + (size_t)(m0 + r) * old + ch * 8) =
+          *(const uint4*)(lds + r * (NCH * 16) + ((ch ^ (r & (NCH - 1))) << 4));
+  }
 }
 
 template <int WM, int WN, int TM, int TN>
@@ -614,6 +688,11 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   EpiArgs ea = ra;
   ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
+  // the tile goes out through LDS when whole 16-byte chunks of every row are addressable
+  // (not for the SiLU*mul epilogue: its tile is half as wide, its GEMM runs several rounds whose
+  // stores already spread out in time, and staging measured 1.6 % slower there)
+  ea.stage_out = (epi == EPI_QKV_ROPE) ? (ra.d_model % BN == 0 && ra.d_model % 8 == 0)
+                 : (epi != EPI_SWIGLU && ldc % 8 == 0 && ((uintptr_t)C & 15) == 0);
   const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
   dim3 grid(tiles_m * tiles_n + side), block(512);
 #define LZ_GEMM(E)                                                                               \
