@@ -112,6 +112,41 @@ def kernel_sweep(args, torch, B) -> int:
     return 0
 
 
+def schedule_sweep(args, wl, shape, n_tokens, timed, B) -> int:
+    """TTFT against the share of token-layers computed, for the schedule families the paper compares: one pruning
+    layer at varying depth and keep ratio (section "Drop Rate in Different Layers"), all pruning at once after the
+    first few layers (the static-pruning baseline of section "Results"), and progressive schedules (section
+    "Inference with LazyLLM").  Accuracy needs trained weights and is not measured; this is the cost axis."""
+    L = shape.n_layers
+    steps, warmup = max(3, args.steps // 4), 2
+    dense_ms, _ = timed([], steps, warmup)
+    grid = [("dense", [])]
+    grid.append(("progressive (workload's own)", list(wl.schedule)))
+    if L >= 32:
+        grid.append(("progressive 90/70/50/30 % at 6/12/18/24", [(6, 900), (12, 778), (18, 714), (24, 600)]))
+        grid.append(("progressive 50 % at 4/12/20", [(4, 500), (12, 500), (20, 500)]))
+    for layer in sorted({max(1, L // 16), max(1, L // 8)}):
+        for permille in (700, 500, 300):
+            grid.append(("static: all pruning at layer %d, keep %d %%" % (layer, permille // 10), [(layer, permille)]))
+    for layer in sorted({max(1, (L * q) // 8) for q in range(2, 8)}):
+        for permille in (900, 700, 500, 300, 100):
+            grid.append(("one pruning layer %d, keep %d %%" % (layer, permille // 10), [(layer, permille)]))
+    rows = []
+    for name, schedule in grid:
+        ms, out = timed(schedule, steps, warmup)
+        assert out.status == 0
+        tl = sum(out.n_tokens)
+        rows.append({"schedule": name, "keep_permille_of_survivors": schedule,
+                     "token_layers_frac": round(tl / (n_tokens * L), 4), "ttft_ms": round(ms, 3),
+                     "speedup_vs_dense": round(dense_ms / ms, 3)})
+    print(json.dumps({"mode": "schedules", "workload": wl.name, "prompt_tokens": n_tokens, "steps": steps,
+                      "dense_ttft_ms": round(dense_ms, 3), "rows": rows}))
+    for r in rows:
+        print("%-48s token-layers %5.1f %%  TTFT %8.3f ms  x%.2f" % (
+            r["schedule"], 100 * r["token_layers_frac"], r["ttft_ms"], r["speedup_vs_dense"]), file=sys.stderr)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +159,10 @@ def main() -> int:
     ap.add_argument("--kernels", action="store_true",
                     help="instead of the prefill, time the bandwidth-bound steps (scoring, selection, "
                          "compaction, LM head) alone over a sweep of token counts with cold caches")
+    ap.add_argument("--schedules", action="store_true",
+                    help="instead of the headline line, time the prefill under a grid of keep schedules: one "
+                         "pruning layer at varying depth and keep ratio (the paper's drop-rate study), pruning "
+                         "all at once after the first few layers (its static-pruning baseline), progressive")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: the pruned prefill of one prompt is a single-GPU job "
@@ -172,6 +211,9 @@ def main() -> int:
             out = step(schedule)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps, out
+
+    if args.schedules:
+        return schedule_sweep(args, wl, shape, n_tokens, timed, B)
 
     ms, out = timed(sched, args.steps, args.warmup)
     assert out.status == 0
