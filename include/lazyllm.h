@@ -94,6 +94,8 @@ typedef struct lazyllm_model lazyllm_model;
 /* Bits of *lazyllm_result.status (device int32, read after stream sync). */
 #define LAZYLLM_ST_BAD_TOKEN 1       /* a token id was outside [0, vocab); clamped */
 #define LAZYLLM_ST_BAD_CU 2          /* device cu_seqlens disagrees with the host copy */
+#define LAZYLLM_ST_NO_STATE 4        /* decoding: a selected token had neither K,V nor an Aux Cache
+                                        entry at a layer (the state buffer was damaged) */
 
 /* Where the results of one prefill live.  Every pointer is device memory
  * inside the caller's output buffer and stays valid as long as that buffer.
@@ -181,6 +183,85 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                            const int32_t* cu_seqlens_dev, int32_t batch, const lazyllm_keep* sched,
                            int32_t n_sched, uint32_t flags, void* workspace, size_t ws_bytes,
                            void* out_buf, size_t out_bytes, void* hip_stream, lazyllm_result* res);
+
+/* ---- decoding steps with the Aux Cache (Sec. 3.2, "Aux Cache") ---------------------------
+ *
+ * After a pruned prefill the KV cache of layer l holds only the tokens that ran layer l.
+ * Every decoding step selects afresh: the new token's attention row gives Eq. 1's scores,
+ * each pruning layer keeps the top-k percentile of the tokens selected at the layer below
+ * (same rule and schedule as the prefill, counted over all tokens so far; the new token is
+ * forced), and a token pruned earlier may be selected again.  A selected token whose K,V
+ * exist at the layer is read from the cache.  One whose K,V are missing is revived: its
+ * layer input is the hidden state it carries out of the layer below in this step, or else the
+ * Aux Cache entry of this layer; it runs the layer like the new token (its attention sees the
+ * selected tokens at or before its own position) and its K,V stay in the cache, so no token
+ * is computed twice in a layer.  A token that carries a state but is not selected at a
+ * pruning layer leaves that state in the layer's Aux Cache.
+ *
+ * The generation state lives in ONE caller-owned device buffer and is indexed by original
+ * position (capacity = prompt length + the most tokens that will be generated):
+ *   per layer   K  bf16 [capacity, d_model]            row p = token at position p
+ *               Vt bf16 [d_model, vt_ld]               column p (V transposed, vt_ld = capacity
+ *                                                      rounded up to 64)
+ *   per pruning layer and the layers up to the next one (they share one set of tokens)
+ *               has_kv  uint8 [capacity]               1 where K,V exist
+ *   per pruning layer
+ *               aux_h   bf16 [capacity, d_model], has_aux uint8 [capacity]
+ * Rows never written are zero.  The schedule is fixed when the state is made. */
+typedef struct lazyllm_generation lazyllm_generation;
+
+typedef struct lazyllm_generation_view {
+  int32_t n_layers, capacity, n_prompt, n_tokens, vt_ld;
+  void* k[LAZYLLM_MAX_LAYERS];
+  void* vt[LAZYLLM_MAX_LAYERS];
+  uint8_t* has_kv[LAZYLLM_MAX_LAYERS];   /* layers of one stage alias the same table */
+  void* aux_h[LAZYLLM_MAX_LAYERS];       /* pruning layers only, NULL elsewhere */
+  uint8_t* has_aux[LAZYLLM_MAX_LAYERS];
+} lazyllm_generation_view;
+
+/* What one step did.  logits and status live in the state buffer; the per-layer
+ * tables live in the step's workspace and are overwritten by the next step. */
+typedef struct lazyllm_step_result {
+  int32_t n_layers;
+  int32_t n_tokens;                           /* tokens so far, this step's included */
+  int32_t position;                           /* original position of this step's token */
+  float* logits;                              /* fp32 [vocab]: distribution of the NEXT token */
+  int32_t n_selected[LAZYLLM_MAX_LAYERS];     /* tokens attended at layer l in this step */
+  int32_t n_ran[LAZYLLM_MAX_LAYERS];          /* tokens that ran layer l (new token + revived) */
+  const uint8_t* selected[LAZYLLM_MAX_LAYERS];/* uint8 [n_tokens] membership by position; NULL = all */
+  const int32_t* ran_pos[LAZYLLM_MAX_LAYERS]; /* int32 [n_ran[l]] ascending; last = new token */
+  float* scores[LAZYLLM_MAX_LAYERS];          /* fp32 [n_tokens] Eq. 1 by position, 0 if not selected */
+  int32_t* status;                            /* int32 [1] LAZYLLM_ST_* bits (accumulates) */
+} lazyllm_step_result;
+
+/* Bytes of the state buffer / of one step's workspace.  0 on a bad argument. */
+size_t lazyllm_generation_state_bytes(const lazyllm_config* cfg, const lazyllm_keep* sched,
+                                      int32_t n_sched, int32_t capacity);
+size_t lazyllm_decode_workspace_bytes(const lazyllm_config* cfg, const lazyllm_keep* sched,
+                                      int32_t n_sched, int32_t capacity);
+
+/* Builds the state from the result of a single-prompt lazyllm_prefill made with the same
+ * schedule: zeroes `state` (device, 256-byte aligned, >= lazyllm_generation_state_bytes),
+ * scatters the packed K, V and Aux Cache rows to their positions.  Enqueued on hip_stream, not
+ * synchronised; the prefill's output buffer may be released once the stream has passed this
+ * work.  Allocates a few bytes of pinned host memory for the handle.  capacity must exceed
+ * the prompt length.  EINVAL if the result does not match model and schedule. */
+int lazyllm_generation_create(const lazyllm_model* m, const lazyllm_keep* sched, int32_t n_sched,
+                              int32_t capacity, const lazyllm_result* prefill, void* state,
+                              size_t state_bytes, void* hip_stream, lazyllm_generation** out);
+void lazyllm_generation_destroy(lazyllm_generation* g);
+/* Pointers into the state buffer (host call, no HIP). */
+int lazyllm_generation_get_view(const lazyllm_generation* g, lazyllm_generation_view* v);
+
+/* One decoding step on the token *token_id (device int32[1]), which takes the next
+ * position.  Returns res->logits for the token after it.  workspace: device, 256-byte
+ * aligned, >= lazyllm_decode_workspace_bytes.  Unlike the prefill this call SYNCHRONISES
+ * hip_stream once per pruning layer: the number of revived tokens is data-dependent and sets
+ * the shape of every launch that follows.  The layers after the last pruning layer are
+ * still in flight at return.  ENOSPC when the capacity is used up.  A failing step leaves
+ * the state undefined. */
+int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* workspace,
+                        size_t ws_bytes, void* hip_stream, lazyllm_step_result* res);
 
 /* ---- per-launch timing of the prefill (measurement aid) --------------------------------
  * Between profile_begin and profile_end every kernel launch of lazyllm_prefill* is

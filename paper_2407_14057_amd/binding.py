@@ -19,7 +19,7 @@ MAX_LAYERS = 128
 
 LAZYLLM_OK, LAZYLLM_EINVAL, LAZYLLM_ENOSPC, LAZYLLM_EHIP, LAZYLLM_ENOMEM = 0, -1, -2, -3, -4
 LAZYLLM_SCORE_ALL_LAYERS, LAZYLLM_SCORE_ONLY_USED, LAZYLLM_KEEP_HIDDEN = 0, 1, 2
-LAZYLLM_ST_BAD_TOKEN, LAZYLLM_ST_BAD_CU = 1, 2
+LAZYLLM_ST_BAD_TOKEN, LAZYLLM_ST_BAD_CU, LAZYLLM_ST_NO_STATE = 1, 2, 4
 EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
 
 
@@ -57,6 +57,22 @@ class lazyllm_result(C.Structure):
                 ("hidden_in", C.c_void_p * MAX_LAYERS), ("hidden_out", C.c_void_p)]
 
 
+class lazyllm_generation_view(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("capacity", C.c_int32), ("n_prompt", C.c_int32),
+                ("n_tokens", C.c_int32), ("vt_ld", C.c_int32),
+                ("k", C.c_void_p * MAX_LAYERS), ("vt", C.c_void_p * MAX_LAYERS),
+                ("has_kv", C.c_void_p * MAX_LAYERS), ("aux_h", C.c_void_p * MAX_LAYERS),
+                ("has_aux", C.c_void_p * MAX_LAYERS)]
+
+
+class lazyllm_step_result(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_tokens", C.c_int32), ("position", C.c_int32),
+                ("logits", C.c_void_p),
+                ("n_selected", C.c_int32 * MAX_LAYERS), ("n_ran", C.c_int32 * MAX_LAYERS),
+                ("selected", C.c_void_p * MAX_LAYERS), ("ran_pos", C.c_void_p * MAX_LAYERS),
+                ("scores", C.c_void_p * MAX_LAYERS), ("status", C.c_void_p)]
+
+
 class lazyllm_profile_record(C.Structure):
     _fields_ = [("step", C.c_int32), ("layer", C.c_int32), ("rows", C.c_int32), ("ms", C.c_float),
                 ("work", C.c_double)]
@@ -88,6 +104,17 @@ _SIGNATURES = {
                                          C.c_void_p, C.c_int32, C.POINTER(lazyllm_keep), C.c_int32,
                                          C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                          C.c_void_p, C.POINTER(lazyllm_result)]),
+    "lazyllm_generation_state_bytes": (C.c_size_t, [C.POINTER(lazyllm_config), C.POINTER(lazyllm_keep),
+                                                    C.c_int32, C.c_int32]),
+    "lazyllm_decode_workspace_bytes": (C.c_size_t, [C.POINTER(lazyllm_config), C.POINTER(lazyllm_keep),
+                                                    C.c_int32, C.c_int32]),
+    "lazyllm_generation_create": (C.c_int, [C.c_void_p, C.POINTER(lazyllm_keep), C.c_int32, C.c_int32,
+                                            C.POINTER(lazyllm_result), C.c_void_p, C.c_size_t,
+                                            C.c_void_p, C.POINTER(C.c_void_p)]),
+    "lazyllm_generation_destroy": (None, [C.c_void_p]),
+    "lazyllm_generation_get_view": (C.c_int, [C.c_void_p, C.POINTER(lazyllm_generation_view)]),
+    "lazyllm_decode_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p,
+                                      C.POINTER(lazyllm_step_result)]),
     "lazyllm_profile_begin": (C.c_int, []),
     "lazyllm_profile_end": (C.c_int, [C.POINTER(lazyllm_profile_record), C.c_int32,
                                       C.POINTER(C.c_int32)]),
@@ -341,6 +368,46 @@ def lazyllm_op_lm_head(h_last, gain, w_lm, xf, logits, d, vocab, eps, stream=Non
                                     vocab, eps, _stream_ptr(stream)))
 
 
+# ---------------------------------------------------------------------------- decoding steps
+
+def lazyllm_generation_state_bytes(cfg: lazyllm_config, schedule, capacity: int) -> int:
+    arr, ns = make_schedule(schedule)
+    return int(lib().lazyllm_generation_state_bytes(C.byref(cfg), arr, ns, capacity))
+
+
+def lazyllm_decode_workspace_bytes(cfg: lazyllm_config, schedule, capacity: int) -> int:
+    arr, ns = make_schedule(schedule)
+    return int(lib().lazyllm_decode_workspace_bytes(C.byref(cfg), arr, ns, capacity))
+
+
+def lazyllm_generation_create(model: int, schedule, capacity: int, prefill: lazyllm_result, state,
+                              stream=None) -> int:
+    arr, ns = make_schedule(schedule)
+    handle = C.c_void_p()
+    _check(lib().lazyllm_generation_create(model, arr, ns, capacity, C.byref(prefill), _ptr(state),
+                                           state.numel() if state is not None else 0,
+                                           _stream_ptr(stream), C.byref(handle)))
+    return handle.value
+
+
+def lazyllm_generation_destroy(handle: int) -> None:
+    lib().lazyllm_generation_destroy(handle)
+
+
+def lazyllm_generation_get_view(handle: int) -> lazyllm_generation_view:
+    v = lazyllm_generation_view()
+    _check(lib().lazyllm_generation_get_view(handle, C.byref(v)))
+    return v
+
+
+def lazyllm_decode_step(handle: int, token_id, workspace, stream=None) -> lazyllm_step_result:
+    res = lazyllm_step_result()
+    _check(lib().lazyllm_decode_step(handle, _ptr(token_id), _ptr(workspace),
+                                     workspace.numel() if workspace is not None else 0,
+                                     _stream_ptr(stream), C.byref(res)))
+    return res
+
+
 # ---------------------------------------------------------------------------- result views
 
 class PrefillOutput:
@@ -464,3 +531,86 @@ class Model:
             res = lazyllm_prefill_varlen(self.handle, token_ids, embed_scale, cu_seqlens, cu_dev,
                                          schedule, flags, ws, out, stream)
         return PrefillOutput(res, out, self.cfg)
+
+
+def _buf_view(buf: torch.Tensor, ptr: Optional[int], count: int, dtype: torch.dtype):
+    if not ptr:
+        return None
+    off = ptr - buf.data_ptr()
+    nbytes = count * torch.empty((), dtype=dtype).element_size()
+    return buf[off: off + nbytes].view(dtype)
+
+
+class StepOutput:
+    """Zero-copy torch views of a lazyllm_step_result."""
+
+    def __init__(self, res: lazyllm_step_result, state: torch.Tensor, ws: torch.Tensor, cfg: lazyllm_config):
+        self.res, self.state, self.ws, self.cfg = res, state, ws, cfg
+        self.n_layers, self.n_tokens, self.position = res.n_layers, res.n_tokens, res.position
+        self.n_selected = [int(res.n_selected[l]) for l in range(res.n_layers)]
+        self.n_ran = [int(res.n_ran[l]) for l in range(res.n_layers)]
+
+    @property
+    def logits(self):
+        return _buf_view(self.state, self.res.logits, self.cfg.vocab, torch.float32)
+
+    @property
+    def status(self) -> int:
+        return int(_buf_view(self.state, self.res.status, 1, torch.int32).item())
+
+    def selected(self, l):
+        """uint8 [n_tokens] membership by position, or None when every token is selected."""
+        return _buf_view(self.ws, self.res.selected[l], self.n_tokens, torch.uint8)
+
+    def ran_pos(self, l):
+        return _buf_view(self.ws, self.res.ran_pos[l], self.n_ran[l], torch.int32)
+
+    def scores(self, l):
+        return _buf_view(self.ws, self.res.scores[l], self.n_tokens, torch.float32)
+
+
+class Generation:
+    """Owns the state buffer, the step workspace and the handle of one sequence's decoding."""
+
+    def __init__(self, model: Model, schedule, prefill: PrefillOutput, capacity: int,
+                 stream: Optional[torch.cuda.Stream] = None):
+        self.model, self.cfg, self.schedule = model, model.cfg, list(schedule)
+        sb = lazyllm_generation_state_bytes(self.cfg, schedule, capacity)
+        wb = lazyllm_decode_workspace_bytes(self.cfg, schedule, capacity)
+        if sb == 0 or wb == 0:
+            raise LazyLLMError(LAZYLLM_EINVAL)
+        self.state = torch.empty(sb, dtype=torch.uint8, device=model.device)
+        self.ws = torch.empty(wb, dtype=torch.uint8, device=model.device)
+        self.handle = lazyllm_generation_create(model.handle, schedule, capacity, prefill.res, self.state,
+                                                stream)
+
+    def close(self) -> None:
+        if self.handle:
+            lazyllm_generation_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step(self, token_id: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> StepOutput:
+        """token_id: int32 cuda tensor with one element."""
+        res = lazyllm_decode_step(self.handle, token_id, self.ws, stream)
+        return StepOutput(res, self.state, self.ws, self.cfg)
+
+    def view(self):
+        """{'k': [..], 'vt': [..], 'has_kv': [..], 'aux_h': [..], 'has_aux': [..]} torch views by layer."""
+        v = lazyllm_generation_get_view(self.handle)
+        cap, d, ld = v.capacity, self.cfg.d_model, v.vt_ld
+        out = {"n_tokens": v.n_tokens, "capacity": cap, "vt_ld": ld, "k": [], "vt": [], "has_kv": [],
+               "aux_h": [], "has_aux": []}
+        for l in range(v.n_layers):
+            out["k"].append(_buf_view(self.state, v.k[l], cap * d, torch.bfloat16).view(cap, d))
+            out["vt"].append(_buf_view(self.state, v.vt[l], d * ld, torch.bfloat16).view(d, ld))
+            out["has_kv"].append(_buf_view(self.state, v.has_kv[l], cap, torch.uint8))
+            a = _buf_view(self.state, v.aux_h[l], cap * d, torch.bfloat16)
+            out["aux_h"].append(None if a is None else a.view(cap, d))
+            out["has_aux"].append(_buf_view(self.state, v.has_aux[l], cap, torch.uint8))
+        return out

@@ -563,6 +563,331 @@ int lazyllm_prefill(const lazyllm_model* m, const int32_t* token_ids, const floa
                                 workspace, ws_bytes, out_buf, out_bytes, hip_stream, res);
 }
 
+// ---- decoding steps with the Aux Cache (Sec. 3.2) ------------------------------------------
+
+}  // extern "C"
+
+namespace {
+
+static_assert(ST_BAD_TOKEN == LAZYLLM_ST_BAD_TOKEN && ST_BAD_CU == LAZYLLM_ST_BAD_CU &&
+              ST_NO_STATE == LAZYLLM_ST_NO_STATE, "status bits");
+
+inline int round_up64(int x) { return (x + 63) / 64 * 64; }
+
+// Generation state inside the caller's buffer (offsets), everything indexed by position.
+struct GenLayout {
+  size_t k[LAZYLLM_MAX_LAYERS], vt[LAZYLLM_MAX_LAYERS];
+  size_t has_kv[LAZYLLM_MAX_LAYERS + 1], aux_h[LAZYLLM_MAX_LAYERS + 1], has_aux[LAZYLLM_MAX_LAYERS + 1];
+  size_t rope, status, logits, total;
+  int vt_ld;
+};
+
+void layout_generation(const lazyllm_config* c, const Stages* st, int cap, GenLayout* g) {
+  const size_t d = c->d_model;
+  g->vt_ld = round_up64(cap);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
+  g->status = take(4);
+  g->logits = take((size_t)c->vocab * 4);
+  g->rope = take((size_t)cap * (c->head_dim / 2) * sizeof(float2));
+  for (int s = 0; s < st->n_stages; ++s) {
+    g->has_kv[s] = take((size_t)cap);
+    g->has_aux[s] = take((size_t)cap);
+    g->aux_h[s] = s > 0 ? take((size_t)cap * d * 2) : 0;
+  }
+  for (int l = 0; l < c->n_layers; ++l) {
+    g->k[l] = take((size_t)cap * d * 2);
+    g->vt[l] = take(d * (size_t)g->vt_ld * 2);
+  }
+  g->total = off;
+}
+
+// Scratch of one step; rows are bounded by the capacity (every token could be revived at once).
+struct GenWorkspace {
+  size_t h0, h1, ssq0, ssq1, q, o, act, score, scores, member, bits, run_pos, live_row, src_row,
+      park_src, park_pos, counts, xf, gemm_ws, total;
+};
+
+void layout_gen_workspace(const lazyllm_config* c, int n_stages, int cap, GenWorkspace* w) {
+  const size_t d = c->d_model, fp = ffn_padded(c->d_ffn), T = (size_t)cap;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  w->h0 = take(T * d * 2);
+  w->h1 = take(T * d * 2);
+  w->ssq0 = take(T * 8);
+  w->ssq1 = take(T * 8);
+  w->q = take(T * d * 2);
+  w->o = take(T * d * 2);
+  w->act = take(T * fp * 2);
+  w->score = take(score_scratch_bytes(cap, 1, c->n_heads));
+  w->scores = take((size_t)c->n_layers * T * 4);
+  w->member = take((size_t)n_stages * T);
+  w->bits = take((size_t)n_stages * (round_up64(cap) / 64) * 8);
+  w->run_pos = take((size_t)n_stages * T * 4);
+  w->live_row = take(T * 4);
+  w->src_row = take(T * 4);
+  w->park_src = take(T * 4);
+  w->park_pos = take(T * 4);
+  w->counts = take((size_t)n_stages * 16);
+  w->xf = take(d * 4);
+  w->gemm_ws = take(gemm_workspace_bytes());
+  w->total = off;
+}
+
+}  // namespace
+
+struct lazyllm_generation {
+  const lazyllm_model* m;
+  Stages stg;               // stage table of the schedule (token counts are per step)
+  GenLayout gl;
+  char* state;
+  int capacity, n_prompt, n_tokens;
+  int32_t* host_counts;     // pinned host memory, [n_stages][4]
+};
+
+extern "C" {
+
+size_t lazyllm_generation_state_bytes(const lazyllm_config* cfg, const lazyllm_keep* sched,
+                                      int32_t n_sched, int32_t capacity) {
+  if (!config_ok(cfg) || capacity <= 0 || capacity > 0x7fffffff / 8) return 0;
+  if (!schedule_ok(cfg->n_layers, sched, n_sched)) return 0;
+  Stages st;
+  const int32_t one = 1;
+  build_stages(cfg->n_layers, sched, n_sched, &one, 1, &st);
+  GenLayout g;
+  layout_generation(cfg, &st, capacity, &g);
+  return g.total;
+}
+
+size_t lazyllm_decode_workspace_bytes(const lazyllm_config* cfg, const lazyllm_keep* sched,
+                                      int32_t n_sched, int32_t capacity) {
+  if (!config_ok(cfg) || capacity <= 0 || capacity > 0x7fffffff / 8) return 0;
+  if (!schedule_ok(cfg->n_layers, sched, n_sched)) return 0;
+  Stages st;
+  const int32_t one = 1;
+  build_stages(cfg->n_layers, sched, n_sched, &one, 1, &st);
+  GenWorkspace w;
+  layout_gen_workspace(cfg, st.n_stages, capacity, &w);
+  return w.total;
+}
+
+int lazyllm_generation_create(const lazyllm_model* m, const lazyllm_keep* sched, int32_t n_sched,
+                              int32_t capacity, const lazyllm_result* prefill, void* state,
+                              size_t state_bytes, void* hip_stream, lazyllm_generation** out) {
+  if (m == nullptr || prefill == nullptr || state == nullptr || out == nullptr) return LAZYLLM_EINVAL;
+  if (((uintptr_t)state & 255) != 0) return LAZYLLM_EINVAL;
+  const lazyllm_config* c = &m->cfg;
+  if (!schedule_ok(c->n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
+  if (prefill->batch != 1 || prefill->n_layers != c->n_layers) return LAZYLLM_EINVAL;
+  const int n_prompt = prefill->n_tokens[0];
+  if (n_prompt <= 0 || capacity <= n_prompt || capacity > 0x7fffffff / 8) return LAZYLLM_EINVAL;
+  Stages stg;
+  build_stages(c->n_layers, sched, n_sched, &n_prompt, 1, &stg);
+  for (int l = 0; l < c->n_layers; ++l) {          // the prefill must be one made with this schedule
+    const int s = stg.stage_of_layer[l];
+    if (prefill->n_tokens[l] != (int32_t)stg.total[s] || prefill->kept_pos[l] == nullptr ||
+        prefill->k[l] == nullptr || prefill->v[l] == nullptr)
+      return LAZYLLM_EINVAL;
+    if (s > 0 && stg.first_layer[s] == l &&
+        (prefill->n_aux[l] != (int32_t)(stg.total[s - 1] - stg.total[s]) ||
+         (prefill->n_aux[l] > 0 && (prefill->aux_h[l] == nullptr || prefill->aux_pos[l] == nullptr))))
+      return LAZYLLM_EINVAL;
+  }
+  GenLayout gl;
+  layout_generation(c, &stg, capacity, &gl);
+  if (state_bytes < gl.total) return LAZYLLM_ENOSPC;
+
+  lazyllm_generation* g = new (std::nothrow) lazyllm_generation();
+  if (g == nullptr) return LAZYLLM_ENOMEM;
+  g->m = m; g->stg = stg; g->gl = gl; g->state = (char*)state;
+  g->capacity = capacity; g->n_prompt = n_prompt; g->n_tokens = n_prompt;
+  g->host_counts = nullptr;
+  hipError_t e = hipHostMalloc((void**)&g->host_counts, (size_t)stg.n_stages * 16, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    delete g;
+    g_last_hip_error = (int)e;
+    return LAZYLLM_ENOMEM;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  int rc = LAZYLLM_OK;
+  auto chk = [&](hipError_t err) { if (err != hipSuccess && rc == LAZYLLM_OK) rc = hip_fail(err); };
+  char* S = g->state;
+  const int d = c->d_model;
+  // entries never written must still be finite: the attention kernel multiplies the V of
+  // masked keys by probabilities that are exactly 0
+  chk(launch_fill_zero(S, gl.total, st));
+  chk(launch_rope_table((float2*)(S + gl.rope), capacity, c->head_dim, c->rope_theta, st));
+  for (int l = 0; l < c->n_layers && rc == LAZYLLM_OK; ++l) {
+    const int s = stg.stage_of_layer[l];
+    const int n = prefill->n_tokens[l];
+    chk(launch_scatter_rows(prefill->k[l], prefill->kept_pos[l], n, S + gl.k[l],
+                            stg.first_layer[s] == l ? (uint8_t*)(S + gl.has_kv[s]) : nullptr, d, st));
+    chk(launch_scatter_vt(prefill->v[l], prefill->kept_pos[l], n, d, S + gl.vt[l], gl.vt_ld, st));
+    if (s > 0 && stg.first_layer[s] == l)
+      chk(launch_scatter_rows(prefill->aux_h[l], prefill->aux_pos[l], prefill->n_aux[l],
+                              S + gl.aux_h[s], (uint8_t*)(S + gl.has_aux[s]), d, st));
+  }
+  if (rc != LAZYLLM_OK) {
+    (void)hipHostFree(g->host_counts);
+    delete g;
+    return rc;
+  }
+  *out = g;
+  return LAZYLLM_OK;
+}
+
+void lazyllm_generation_destroy(lazyllm_generation* g) {
+  if (g == nullptr) return;
+  if (g->host_counts != nullptr) (void)hipHostFree(g->host_counts);
+  delete g;
+}
+
+int lazyllm_generation_get_view(const lazyllm_generation* g, lazyllm_generation_view* v) {
+  if (g == nullptr || v == nullptr) return LAZYLLM_EINVAL;
+  memset(v, 0, sizeof(*v));
+  const lazyllm_config* c = &g->m->cfg;
+  v->n_layers = c->n_layers; v->capacity = g->capacity; v->n_prompt = g->n_prompt;
+  v->n_tokens = g->n_tokens; v->vt_ld = g->gl.vt_ld;
+  char* S = g->state;
+  for (int l = 0; l < c->n_layers; ++l) {
+    const int s = g->stg.stage_of_layer[l];
+    v->k[l] = S + g->gl.k[l];
+    v->vt[l] = S + g->gl.vt[l];
+    v->has_kv[l] = (uint8_t*)(S + g->gl.has_kv[s]);
+    if (s > 0 && g->stg.first_layer[s] == l) {
+      v->aux_h[l] = S + g->gl.aux_h[s];
+      v->has_aux[l] = (uint8_t*)(S + g->gl.has_aux[s]);
+    }
+  }
+  return LAZYLLM_OK;
+}
+
+int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* workspace,
+                        size_t ws_bytes, void* hip_stream, lazyllm_step_result* res) {
+  if (g == nullptr || token_id == nullptr || workspace == nullptr || res == nullptr)
+    return LAZYLLM_EINVAL;
+  if (((uintptr_t)workspace & 255) != 0) return LAZYLLM_EINVAL;
+  if (g->n_tokens >= g->capacity) return LAZYLLM_ENOSPC;
+  const lazyllm_model* m = g->m;
+  const lazyllm_config* c = &m->cfg;
+  const Stages& stg = g->stg;
+  const int NS = stg.n_stages;
+  GenWorkspace ws;
+  layout_gen_workspace(c, NS, g->capacity, &ws);
+  if (ws_bytes < ws.total) return LAZYLLM_ENOSPC;
+
+  const int L = c->n_layers, d = c->d_model, H = c->n_heads, hd = c->head_dim, fp = m->f_pad;
+  const int cap = g->capacity, new_pos = g->n_tokens, n_tot = g->n_tokens + 1;
+  const GenLayout& gl = g->gl;
+  char* S = g->state;
+  char* W = (char*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int sel_count[LAZYLLM_MAX_LAYERS + 1];
+  sel_count[0] = n_tot;
+  for (int s = 1; s < NS; ++s) sel_count[s] = keep_count(sel_count[s - 1], stg.permille[s]);
+
+  memset(res, 0, sizeof(*res));
+  res->n_layers = L; res->n_tokens = n_tot; res->position = new_pos;
+  res->logits = (float*)(S + gl.logits);
+  res->status = (int32_t*)(S + gl.status);
+
+  int32_t* live_row = (int32_t*)(W + ws.live_row);
+  int32_t* src_row = (int32_t*)(W + ws.src_row);
+  int32_t* park_src = (int32_t*)(W + ws.park_src);
+  int32_t* park_pos = (int32_t*)(W + ws.park_pos);
+  auto run_pos_of = [&](int s) { return (int32_t*)(W + ws.run_pos) + (size_t)s * cap; };
+  auto member_of = [&](int s) { return (uint8_t*)(W + ws.member) + (size_t)s * cap; };
+  auto bits_of = [&](int s) { return (unsigned long long*)(W + ws.bits) + (size_t)s * (round_up64(cap) / 64); };
+  auto scores_of = [&](int l) { return (float*)(W + ws.scores) + (size_t)l * cap; };
+  const float2* rope = (const float2*)(S + gl.rope);
+  unsigned long long* ssq_attn = (unsigned long long*)(W + ws.ssq0);
+  unsigned long long* ssq_ffn = (unsigned long long*)(W + ws.ssq1);
+  const float ssq_mul = 1.0f / (4294967296.0f * (float)d);
+  const double dd = (double)d, rowb = dd * 2.0;
+  const int z_ld = gl.vt_ld;
+  char* hbuf[2] = {W + ws.h0, W + ws.h1};
+  int cur = 0, M = 1;
+
+  LZ_RUN(LAZYLLM_STEP_EMBED, -1, 1, 2.0 * rowb,
+         launch_gen_embed(m->embed, token_id, c->vocab, d, new_pos, hbuf[0], ssq_attn, run_pos_of(0),
+                          live_row, (uint8_t*)(S + gl.has_kv[0]), res->status, st));
+  for (int l = 0; l < L; ++l) {
+    const int s = stg.stage_of_layer[l];
+    if (s > 0 && stg.first_layer[s] == l) {
+      // Sec. 3.2: this step's scores of layer l-1 pick the tokens of layer l; selected tokens
+      // without K,V here run the layer (from the state they carry, or revived from this layer's
+      // Aux Cache), unselected tokens that carry a state leave it in the Aux Cache.
+      int32_t* counts_dev = (int32_t*)(W + ws.counts) + 4 * s;
+      LZ_RUN(LAZYLLM_STEP_SELECT, l, n_tot, 8.0 * n_tot,
+             launch_gen_stage(scores_of(l - 1), s > 1 ? member_of(s - 1) : nullptr, n_tot, sel_count[s],
+                              member_of(s), bits_of(s), (uint8_t*)(S + gl.has_kv[s]),
+                              (uint8_t*)(S + gl.has_aux[s]), live_row, run_pos_of(s), src_row,
+                              park_src, park_pos, counts_dev, res->status, st));
+      // how many rows run this stage decides every launch shape below: the one place a step
+      // waits for the GPU
+      LZ_HIP(hipMemcpyAsync(g->host_counts + 4 * s, counts_dev, 16, hipMemcpyDeviceToHost, st));
+      LZ_HIP(hipStreamSynchronize(st));
+      const int rows = g->host_counts[4 * s], parked = g->host_counts[4 * s + 1];
+      if (rows < 1 || rows > sel_count[s] || parked < 0 || parked > M ||
+          g->host_counts[4 * s + 2] != sel_count[s])
+        return hip_fail(hipErrorUnknown);
+      LZ_RUN(LAZYLLM_STEP_GATHER, l, rows + parked, 2.0 * (rows + parked) * rowb,
+             launch_revive_gather(hbuf[cur], S + gl.aux_h[s], run_pos_of(s), src_row, rows, park_src,
+                                  park_pos, parked, hbuf[cur ^ 1], ssq_attn, d, st));
+      cur ^= 1;
+      M = rows;
+    }
+    char* h = hbuf[cur];
+    const int32_t* rpos = run_pos_of(s);
+    res->n_selected[l] = sel_count[s];
+    res->n_ran[l] = M;
+    res->selected[l] = s > 0 ? member_of(s) : nullptr;
+    res->ran_pos[l] = rpos;
+    res->scores[l] = scores_of(l);
+
+    EpiArgs ra{};
+    ra.pos = rpos; ra.table = rope;
+    ra.q = (uint16_t*)(W + ws.q); ra.k = (uint16_t*)(S + gl.k[l]); ra.v = nullptr;
+    ra.k_row = rpos;                                   // K,V land at the rows of their positions
+    ra.d_model = d; ra.head_dim = hd;
+    ra.vt = (uint16_t*)(S + gl.vt[l]); ra.vt_ld = gl.vt_ld; ra.vt_col = rpos;
+    ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
+    LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, M, 2.0 * M * 3.0 * dd * dd,
+           launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st, &ra));
+    LZ_RUN(LAZYLLM_STEP_ATTENTION, l, M, 4.0 * (double)M * (double)sel_count[s] * dd,
+           launch_decode_attention(W + ws.q, rpos, M, S + gl.k[l], S + gl.vt[l], gl.vt_ld,
+                                   s > 0 ? bits_of(s) : nullptr, n_tot, W + ws.o, H, hd, st,
+                                   score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld));
+    EpiArgs eo{};
+    eo.ssq_out = ssq_ffn;
+    LZ_RUN(LAZYLLM_STEP_GEMM_O, l, M, 2.0 * M * dd * dd,
+           launch_gemm(W + ws.o, m->wo[l], h, h, M, d, d, d, d, d, EPI_RESIDUAL, st, &eo,
+                       W + ws.gemm_ws, gemm_workspace_bytes()));
+    EpiArgs eg{};
+    eg.ssq_in = ssq_ffn; eg.ssq_mul = ssq_mul; eg.eps = c->rms_eps; eg.ssq_clear = ssq_attn;
+    eg.sf_z = score_z(W + ws.score);
+    eg.sf_stat = (const float2*)score_zstat(W + ws.score, z_ld, H);
+    eg.sf_s = scores_of(l);
+    eg.sf_cu = nullptr; eg.sf_cu_z = nullptr;
+    eg.sf_n_single = n_tot; eg.sf_heads = H; eg.sf_z_ld = z_ld;
+    eg.sf_max_rows = n_tot; eg.sf_batch = 1;
+    LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, M, 2.0 * M * 2.0 * (double)c->d_ffn * dd,
+           launch_gemm(h, m->wgu[l], W + ws.act, nullptr, M, 2 * fp, d, d, d, fp, EPI_SWIGLU, st, &eg));
+    EpiArgs ed{};
+    ed.ssq_out = ssq_attn;
+    LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, M, 2.0 * M * (double)c->d_ffn * dd,
+           launch_gemm(W + ws.act, m->wdown[l], h, h, M, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
+                       W + ws.gemm_ws, gemm_workspace_bytes()));
+  }
+  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, (double)c->vocab * rowb,
+         launch_final_norm(hbuf[cur], nullptr, M, 1, m->final_norm, (float*)(W + ws.xf), d,
+                           c->rms_eps, st));
+  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, 0.0,
+         launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, 1, d, c->vocab, st));
+  g->n_tokens = n_tot;
+  return LAZYLLM_OK;
+}
+
 // ---- per-launch timing ---------------------------------------------------------------------
 
 int lazyllm_profile_begin(void) {

@@ -125,6 +125,10 @@ struct EpiArgs {
   uint16_t* vt;
   int vt_ld;
   const int32_t* vt_col;
+  // caches indexed by something other than the GEMM's row (decoding: by original position):
+  // token `row` writes its K to row k_row[row] (row itself when null); v == nullptr: the row-major
+  // V is not written at all (only the transposed copy)
+  const int32_t* k_row;
   // RMSNorm folded into the projections (gains are folded into the weights when the model is
   // made).  ssq_in: per token row, the sum of squares of the A operand's row as 2^-32 fixed point;
   // the epilogue multiplies row t of C by rsqrt(ssq_in[t] * ssq_mul + eps), ssq_mul = 2^-32 / K.
@@ -202,6 +206,31 @@ hipError_t launch_final_norm(const void* h, const int32_t* cu, int n_single, int
                              const void* gain, float* xf, int d, float eps, hipStream_t st);
 hipError_t launch_lm_head(const float* xf, const void* w_lm, float* logits, int batch, int d,
                           int vocab, hipStream_t st);
+
+// ---- decoding steps (position-indexed generation state; see decode.hip) -----------------
+// Bits of the device status word (the public header's LAZYLLM_ST_* values).
+constexpr int ST_BAD_TOKEN = 1, ST_BAD_CU = 2, ST_NO_STATE = 4;
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_scatter_rows(const void* src, const int32_t* pos, int n, void* dst, uint8_t* flag,
+                               int d, hipStream_t st);
+hipError_t launch_scatter_vt(const void* v, const int32_t* pos, int n, int d, void* vt, int vt_ld,
+                             hipStream_t st);
+hipError_t launch_gen_embed(const void* embed, const int32_t* token_id, int vocab, int d, int new_pos,
+                            void* h, unsigned long long* ssq, int32_t* run_pos, int32_t* live_row,
+                            uint8_t* has_kv0, int32_t* status, hipStream_t st);
+hipError_t launch_gen_stage(const float* s, const uint8_t* member_prev, int n_tot, int k,
+                            uint8_t* member, unsigned long long* member_bits, uint8_t* has_kv,
+                            uint8_t* has_aux, int32_t* live_row, int32_t* run_pos,
+                            int32_t* src_row, int32_t* park_src, int32_t* park_pos,
+                            int32_t* counts, int32_t* status, hipStream_t st);
+hipError_t launch_revive_gather(const void* h_prev, void* aux, const int32_t* run_pos,
+                                const int32_t* src_row, int n_rows, const int32_t* park_src,
+                                const int32_t* park_pos, int n_park, void* h_new,
+                                unsigned long long* ssq, int d, hipStream_t st);
+hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, const void* k,
+                                   const void* vt, int vt_ld, const unsigned long long* sel_bits,
+                                   int n_keys, void* o, int n_heads, int head_dim, hipStream_t st,
+                                   float* z = nullptr, void* zstat = nullptr, int z_ld = 0);
 
 struct PlanArgs {
   int32_t n_stages;                     // pruning stages after stage 0

@@ -70,7 +70,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
       const int col0 = n0 + wn * TN * 32;              // first column of this wave
       const int region = col0 / d;                      // 0 q, 1 k, 2 v (uniform per wave)
       if (region != 2 && !valid) continue;              // (the V branch keeps every lane: lane pairs exchange data)
-      uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)row * d +
+      const int orow = (region == 1 && ra.k_row != nullptr && valid) ? ra.k_row[row] : row;
+      uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)orow * d +
                       (col0 - region * d) + feat_l;
       if (region == 2) {
         // V goes to the KV cache row-major and, for the attention kernel's second product,
@@ -100,7 +101,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
             if (STAGED) {
               *(uint2*)(sl + stage_off<NCH>((wm * TM + i) * 32 + tok_l,
                                             (wn * TN + j) * 32 + 8 * g + feat_l)) = w2;
-            } else if (valid) {
+            } else if (valid && ra.v != nullptr) {
               *(uint2*)(dst + j * 32 + 8 * g) = w2;
             }
             // features 8g..8g+3 of this token: w2.x = (f0, f1), w2.y = (f2, f3)
@@ -662,19 +663,24 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   __syncthreads();
   uint16_t* obase;
   int old;
+  const int32_t* orow = nullptr;                    // output row of tile row r, if not m0 + r
   if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
     const int region = n0 / ra.d_model;             // the tile lies inside q, k or v
+    if (region == 2 && ra.v == nullptr) return;     // (the transposed copy went out with the epilogue)
     obase = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (n0 - region * ra.d_model);
     old = ra.d_model;
+    if (region == 1) orow = ra.k_row;
   } else {
     obase = C + (EPI == EPI_SWIGLU ? n0 / 2 : n0);
     old = ldc;
   }
   for (int idx = threadIdx.x; idx < BM * NCH; idx += NWAVES * 64) {
     const int r = idx / NCH, ch = idx % NCH;
-    if (m0 + r < M)
-      *(uint4*)(obase + (size_t)(m0 + r) * old + ch * 8) =
+    if (m0 + r < M) {
+      const size_t dr = orow != nullptr ? (size_t)orow[m0 + r] : (size_t)(m0 + r);
+      *(uint4*)(obase + dr * old + ch * 8) =
           *(const uint4*)(lds + r * (NCH * 16) + ((ch ^ (r & (NCH - 1))) << 4));
+    }
   }
 }
 

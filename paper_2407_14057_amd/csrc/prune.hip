@@ -286,33 +286,15 @@ __device__ __forceinline__ int block_rank(bool flag, int* wsum, int& total) {
   return pre + below;
 }
 
-__global__ void __launch_bounds__(SEL_THREADS)
-select_kernel(const float* __restrict__ s, const int32_t* __restrict__ cu_prev,
-              const int32_t* __restrict__ cu_new, int m_single, int k_single,
-              int32_t* __restrict__ keep_idx, int32_t* __restrict__ prune_idx) {
-  __shared__ uint32_t keys[SEL_LDS_KEYS];
-  __shared__ int hist[256];
-  __shared__ int wsum[SEL_WAVES];
-  __shared__ int sel_bin, sel_need;
-  const int b = blockIdx.x;
-  int r0, m, k0, k;
-  seq_range(cu_prev, b, m_single, r0, m);
-  seq_range(cu_new, b, k_single, k0, k);
-  int32_t* keep_out = keep_idx + k0;
-  int32_t* prune_out = prune_idx + (r0 - k0);
-  const float* sv = s + r0;
-  const bool in_lds = m <= SEL_LDS_KEYS;
-  const int ncand = m - 1;                       // the last token is not a candidate
-
-  if (in_lds) {
-    for (int i = threadIdx.x; i < m; i += SEL_THREADS) keys[i] = score_key(sv[i]);
-    __syncthreads();
-  }
-#define key_at(i) (in_lds ? keys[(i)] : score_key(sv[(i)]))
-
-  uint32_t T;
-  int need_eq;
-  int need = k - 1;
+// The key of rank `need` (1-based, descending) among candidates 0..ncand-1 and how many of its
+// duplicates belong to the top `need`: T = that key, need_eq = duplicates to take (in index
+// order).  need <= 0: nothing qualifies (T = max key, need_eq = 0); need >= ncand: everything.
+// MSB-first radix select, 4 passes of 8 bits.  Called by every thread of the workgroup;
+// hist: LDS int[256], sel_bin / sel_need: LDS ints.
+template <class KeyAt>
+__device__ __forceinline__ void select_threshold(KeyAt key_at, int ncand, int m, int need, int* hist,
+                                                 int* sel_bin, int* sel_need, uint32_t& T,
+                                                 int& need_eq) {
   if (need <= 0) {
     T = 0xffffffffu; need_eq = 0;
   } else if (need >= ncand) {
@@ -345,19 +327,48 @@ select_kernel(const float* __restrict__ s, const int32_t* __restrict__ cu_prev,
           if (acc + cnt < need) { acc += cnt; bin = top - 1; cnt = c1;
             if (acc + cnt < need) { acc += cnt; bin = top - 2; cnt = c2;
               if (acc + cnt < need) { acc += cnt; bin = top - 3; } } }
-          sel_bin = bin;
-          sel_need = need - acc;              // rank inside the chosen bin, >= 1
+          *sel_bin = bin;
+          *sel_need = need - acc;              // rank inside the chosen bin, >= 1
         }
       }
       __syncthreads();
-      prefix |= ((uint32_t)sel_bin) << shift;
+      prefix |= ((uint32_t)*sel_bin) << shift;
       mask |= 255u << shift;
-      need = sel_need;
+      need = *sel_need;
       __syncthreads();
     }
     T = prefix;
     need_eq = need;
   }
+}
+
+__global__ void __launch_bounds__(SEL_THREADS)
+select_kernel(const float* __restrict__ s, const int32_t* __restrict__ cu_prev,
+              const int32_t* __restrict__ cu_new, int m_single, int k_single,
+              int32_t* __restrict__ keep_idx, int32_t* __restrict__ prune_idx) {
+  __shared__ uint32_t keys[SEL_LDS_KEYS];
+  __shared__ int hist[256];
+  __shared__ int wsum[SEL_WAVES];
+  __shared__ int sel_bin, sel_need;
+  const int b = blockIdx.x;
+  int r0, m, k0, k;
+  seq_range(cu_prev, b, m_single, r0, m);
+  seq_range(cu_new, b, k_single, k0, k);
+  int32_t* keep_out = keep_idx + k0;
+  int32_t* prune_out = prune_idx + (r0 - k0);
+  const float* sv = s + r0;
+  const bool in_lds = m <= SEL_LDS_KEYS;
+  const int ncand = m - 1;                       // the last token is not a candidate
+
+  if (in_lds) {
+    for (int i = threadIdx.x; i < m; i += SEL_THREADS) keys[i] = score_key(sv[i]);
+    __syncthreads();
+  }
+#define key_at(i) (in_lds ? keys[(i)] : score_key(sv[(i)]))
+
+  uint32_t T;
+  int need_eq;
+  select_threshold([&](int i) { return key_at(i); }, ncand, m, k - 1, hist, &sel_bin, &sel_need, T, need_eq);
 
   // ordered emission
   int run_eq = 0, run_keep = 0;
@@ -387,6 +398,111 @@ hipError_t launch_select(const float* s, const int32_t* cu_prev, const int32_t* 
                          int32_t* prune_idx, hipStream_t st) {
   hipLaunchKernelGGL(select_kernel, dim3(batch), dim3(SEL_THREADS), 0, st, s, cu_prev, cu_new,
                      m_single, k_single, keep_idx, prune_idx);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Decoding, one pruning layer of one generation step (Sec. 3.2, "Aux Cache").  Everything is
+// indexed by original position.  The same top-k rule as above picks k of the tokens selected
+// at the layer below (member_prev; null = all n_tot tokens), by this step's scores of that
+// layer; the new token (position n_tot-1) is forced.  Then every position is classified:
+//   selected, K,V present at this layer        -> read from the KV cache, nothing to do
+//   selected, no K,V                            -> runs the layer: gets the next row (ascending
+//        position); its input is row live_row[] of the states carried out of the layer below in
+//        this step, or else this layer's Aux Cache entry (src_row = -1)
+//   not selected, but carrying a state          -> the state is parked in this layer's Aux Cache
+// Outputs: member bytes and 64-bit words (the attention kernel's key mask), the row lists, the
+// updated has_kv / has_aux / live_row tables, counts = {rows, parked, selected}.
+// One 1024-thread workgroup.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(SEL_THREADS)
+gen_stage_kernel(const float* __restrict__ s, const uint8_t* __restrict__ member_prev, int m, int k,
+                 uint8_t* __restrict__ member, unsigned long long* __restrict__ member_bits,
+                 uint8_t* __restrict__ has_kv, uint8_t* __restrict__ has_aux,
+                 int32_t* __restrict__ live_row, int32_t* __restrict__ run_pos,
+                 int32_t* __restrict__ src_row, int32_t* __restrict__ park_src,
+                 int32_t* __restrict__ park_pos, int32_t* __restrict__ counts,
+                 int32_t* __restrict__ status) {
+  __shared__ uint32_t keys[SEL_LDS_KEYS];
+  __shared__ int hist[256];
+  __shared__ int wsum[SEL_WAVES];
+  __shared__ int sel_bin, sel_need;
+  const bool in_lds = m <= SEL_LDS_KEYS;
+  const int ncand = m - 1;
+  // tokens outside the candidate set get key 0, below every real score's key (scores are >= 0,
+  // so their keys have the top bit set)
+  auto make_key = [&](int i) -> uint32_t {
+    return (member_prev != nullptr && member_prev[i] == 0) ? 0u : score_key(s[i]);
+  };
+  if (in_lds) {
+    for (int i = threadIdx.x; i < m; i += SEL_THREADS) keys[i] = make_key(i);
+    __syncthreads();
+  }
+  auto key_at = [&](int i) -> uint32_t { return in_lds ? keys[i] : make_key(i); };
+  uint32_t T;
+  int need_eq;
+  select_threshold(key_at, ncand, m, k - 1, hist, &sel_bin, &sel_need, T, need_eq);
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int run_eq = 0, run_rows = 0, run_park = 0, run_sel = 0;
+  for (int base = 0; base < m; base += SEL_THREADS) {
+    const int i = base + threadIdx.x;
+    const bool valid = i < m;
+    const bool last = valid && (i == m - 1);
+    const uint32_t key = (valid && !last) ? key_at(i) : 0u;
+    const bool gt = valid && !last && key > T;
+    const bool eq = valid && !last && key == T;
+    int tot_eq, tot_rows, tot_park;
+    const int eq_rank = run_eq + block_rank(eq, wsum, tot_eq);
+    const bool sel = last || gt || (eq && eq_rank < need_eq);
+    const bool kv = valid && has_kv[i] != 0;
+    const int lr = valid ? live_row[i] : -1;
+    const bool runs = sel && !kv;
+    const bool park = valid && !sel && lr >= 0 && !kv;
+    const int row = run_rows + block_rank(runs, wsum, tot_rows);
+    const int pr = run_park + block_rank(park, wsum, tot_park);
+    const unsigned long long word = __ballot(sel);
+    if (valid) {
+      member[i] = sel ? 1 : 0;
+      if (runs) {
+        run_pos[row] = i;
+        src_row[row] = lr;
+        has_kv[i] = 1;
+        if (lr < 0 && has_aux[i] == 0) atomicOr(status, ST_NO_STATE);
+      }
+      live_row[i] = runs ? row : -1;
+      if (park) {
+        park_src[pr] = lr;
+        park_pos[pr] = i;
+        has_aux[i] = 1;
+      }
+    }
+    if (lane == 0 && base + wave * 64 < m) member_bits[(base >> 6) + wave] = word;
+    run_eq += tot_eq;
+    run_rows += tot_rows;
+    run_park += tot_park;
+    run_sel += __popcll(word);          // per wave; summed below
+  }
+  // selected count: add the waves' partial sums
+  if (lane == 0) wsum[wave] = run_sel;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+    for (int w = 0; w < SEL_WAVES; ++w) tot += wsum[w];
+    counts[0] = run_rows;
+    counts[1] = run_park;
+    counts[2] = tot;
+  }
+}
+
+hipError_t launch_gen_stage(const float* s, const uint8_t* member_prev, int n_tot, int k,
+                            uint8_t* member, unsigned long long* member_bits, uint8_t* has_kv,
+                            uint8_t* has_aux, int32_t* live_row, int32_t* run_pos,
+                            int32_t* src_row, int32_t* park_src, int32_t* park_pos,
+                            int32_t* counts, int32_t* status, hipStream_t st) {
+  hipLaunchKernelGGL(gen_stage_kernel, dim3(1), dim3(SEL_THREADS), 0, st, s, member_prev, n_tot, k,
+                     member, member_bits, has_kv, has_aux, live_row, run_pos, src_row, park_src,
+                     park_pos, counts, status);
   return hipGetLastError();
 }
 
