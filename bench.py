@@ -147,6 +147,55 @@ def schedule_sweep(args, wl, shape, n_tokens, timed, B) -> int:
     return 0
 
 
+def decode_bench(args, wl, shape, model, ids, sched, n_tokens, torch, B) -> int:
+    """Decoding steps after the workload's prefill (Sec. 3.2, "Aux Cache"; Sec. 5.3's "% of prompt tokens
+    computed" and generation time), pruned and unpruned.  A step is timed from its launch to the
+    completion of its logits; tokens are chosen greedily on the device (the argmax is not timed)."""
+    steps = args.decode
+    L = shape.n_layers
+    runs = {}
+    for name, schedule in (("lazy", sched), ("dense", [])):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = model.prefill(ids, schedule)
+        torch.cuda.synchronize()
+        prefill_ms = (time.perf_counter() - t0) * 1e3
+        tok = torch.argmax(out.logits[0]).to(torch.int32).reshape(1)
+        gen = B.Generation(model, schedule, out, n_tokens + steps + 1)
+        torch.cuda.synchronize()
+        rows = []
+        for t in range(steps):
+            t0 = time.perf_counter()
+            so = gen.step(tok)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            tok = torch.argmax(so.logits).to(torch.int32).reshape(1)
+            stage_rows = sorted(set(so.n_ran), reverse=True)
+            rows.append({"step": t + 1, "ms": round(ms, 3), "token_layers_run": int(sum(so.n_ran)),
+                         "most_rows_in_a_layer": max(so.n_ran)})
+            assert so.status == 0
+        view = gen.view()
+        computed = float(sum(float(view["has_kv"][l][:n_tokens].float().mean()) for l in range(L)) / L)
+        runs[name] = {"prefill_ms": round(prefill_ms, 3), "steps": rows,
+                      "decode_ms_total": round(sum(r["ms"] for r in rows), 3),
+                      "generation_ms": round(prefill_ms + sum(r["ms"] for r in rows), 3),
+                      "prompt_token_layers_computed": round(computed, 4)}
+        gen.close()
+    lazy, dense = runs["lazy"], runs["dense"]
+    print(json.dumps({"mode": "decode", "workload": wl.name, "prompt_tokens": n_tokens, "new_tokens": steps,
+                      "generation_speedup_vs_dense": round(dense["generation_ms"] / lazy["generation_ms"], 3),
+                      "lazy": lazy, "dense": dense}))
+    for name in ("lazy", "dense"):
+        r = runs[name]
+        print("%-5s prefill %8.3f ms  %d steps %9.3f ms  total %9.3f ms  prompt token-layers computed %5.1f %%" % (
+            name, r["prefill_ms"], steps, r["decode_ms_total"], r["generation_ms"],
+            100 * r["prompt_token_layers_computed"]), file=sys.stderr)
+        for row in r["steps"][:12] + ([r["steps"][-1]] if steps > 12 else []):
+            print("      step %3d  %8.3f ms  token-layers run %6d  most rows in a layer %5d" % (
+                row["step"], row["ms"], row["token_layers_run"], row["most_rows_in_a_layer"]), file=sys.stderr)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,6 +212,10 @@ def main() -> int:
                     help="instead of the headline line, time the prefill under a grid of keep schedules: one "
                          "pruning layer at varying depth and keep ratio (the paper's drop-rate study), pruning "
                          "all at once after the first few layers (its static-pruning baseline), progressive")
+    ap.add_argument("--decode", type=int, default=0, metavar="STEPS",
+                    help="instead of the headline line, run the prefill and then this many decoding steps "
+                         "with Aux Cache revival (greedy tokens), and the same with no pruning; prints the time "
+                         "of every step, the tokens revived and the share of prompt tokens computed")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: the pruned prefill of one prompt is a single-GPU job "
@@ -214,6 +267,8 @@ def main() -> int:
 
     if args.schedules:
         return schedule_sweep(args, wl, shape, n_tokens, timed, B)
+    if args.decode:
+        return decode_bench(args, wl, shape, model, ids, sched, n_tokens, torch, B)
 
     ms, out = timed(sched, args.steps, args.warmup)
     assert out.status == 0

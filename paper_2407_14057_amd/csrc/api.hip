@@ -808,6 +808,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
   char* hbuf[2] = {W + ws.h0, W + ws.h1};
   int cur = 0, M = 1;
 
+  LZ_HIP(launch_gemm_counters_clear(W + ws.gemm_ws, st));
   LZ_RUN(LAZYLLM_STEP_EMBED, -1, 1, 2.0 * rowb,
          launch_gen_embed(m->embed, token_id, c->vocab, d, new_pos, hbuf[0], ssq_attn, run_pos_of(0),
                           live_row, (uint8_t*)(S + gl.has_kv[0]), res->status, st));
@@ -852,14 +853,16 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     ra.d_model = d; ra.head_dim = hd;
     ra.vt = (uint16_t*)(S + gl.vt[l]); ra.vt_ld = gl.vt_ld; ra.vt_col = rpos;
     ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
+    ra.skinny = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, M, 2.0 * M * 3.0 * dd * dd,
-           launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st, &ra));
+           launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st, &ra,
+                       W + ws.gemm_ws, gemm_workspace_bytes()));
     LZ_RUN(LAZYLLM_STEP_ATTENTION, l, M, 4.0 * (double)M * (double)sel_count[s] * dd,
            launch_decode_attention(W + ws.q, rpos, M, S + gl.k[l], S + gl.vt[l], gl.vt_ld,
                                    s > 0 ? bits_of(s) : nullptr, n_tot, W + ws.o, H, hd, st,
                                    score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld));
     EpiArgs eo{};
-    eo.ssq_out = ssq_ffn;
+    eo.ssq_out = ssq_ffn; eo.skinny = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, M, 2.0 * M * dd * dd,
            launch_gemm(W + ws.o, m->wo[l], h, h, M, d, d, d, d, d, EPI_RESIDUAL, st, &eo,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -871,10 +874,12 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     eg.sf_cu = nullptr; eg.sf_cu_z = nullptr;
     eg.sf_n_single = n_tot; eg.sf_heads = H; eg.sf_z_ld = z_ld;
     eg.sf_max_rows = n_tot; eg.sf_batch = 1;
+    eg.skinny = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, M, 2.0 * M * 2.0 * (double)c->d_ffn * dd,
-           launch_gemm(h, m->wgu[l], W + ws.act, nullptr, M, 2 * fp, d, d, d, fp, EPI_SWIGLU, st, &eg));
+           launch_gemm(h, m->wgu[l], W + ws.act, nullptr, M, 2 * fp, d, d, d, fp, EPI_SWIGLU, st, &eg,
+                       W + ws.gemm_ws, gemm_workspace_bytes()));
     EpiArgs ed{};
-    ed.ssq_out = ssq_attn;
+    ed.ssq_out = ssq_attn; ed.skinny = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, M, 2.0 * M * (double)c->d_ffn * dd,
            launch_gemm(W + ws.act, m->wdown[l], h, h, M, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -933,6 +938,11 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
   if (ldc < (epi == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
   if (M == 0) return LAZYLLM_OK;
   if (workspace != nullptr && ((uintptr_t)workspace & 255) != 0) return LAZYLLM_EINVAL;
+  if (((epilogue >> 8) & 0xff) == 8) {
+    // the skinny kernel's tickets live at the end of the workspace and must start at zero
+    if (M > 32 || workspace == nullptr || ws_bytes < gemm_workspace_bytes()) return LAZYLLM_EINVAL;
+    LZ_HIP(launch_gemm_counters_clear(workspace, (hipStream_t)hip_stream));
+  }
   LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, nullptr,
                      workspace, ws_bytes));
   return LAZYLLM_OK;

@@ -151,6 +151,9 @@ struct EpiArgs {
   int sf_n_single, sf_heads, sf_z_ld, sf_max_rows, sf_batch;
   int sf_blocks_per_seq;             // filled in by the launcher (depends on the workgroup size)
   int stage_out;                     // filled in by the launcher: tile goes out through LDS (see gemm.hip)
+  // the caller keeps the ticket counters at the end of the GEMM workspace zeroed
+  // (launch_gemm_counters_clear once before the first use): M <= 32 may take the skinny kernel
+  int skinny;
 };
 constexpr float SSQ_FIX = 4294967296.0f;      // 2^32
 __device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {
@@ -162,6 +165,8 @@ size_t gemm_workspace_bytes();
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
                        int lda, int ldw, int ldc, int epilogue, hipStream_t st,
                        const EpiArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
+
+hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st);
 
 hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st);
 

@@ -961,7 +961,8 @@ gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C
 }
 
 constexpr int SK_GRID = 512;
-size_t gemm_workspace_bytes() { return (size_t)SK_GRID * 2 * SK_TILE_ELEMS * sizeof(float); }
+// (the last 4 KB hold the skinny kernel's tickets, see gemm_skinny_kernel)
+size_t gemm_workspace_bytes() { return (size_t)SK_GRID * 2 * SK_TILE_ELEMS * sizeof(float) + 4096; }
 
 static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R, float* partial,
                             int M, int N, int K, int lda, int ldw, int ldc, int epi,
@@ -994,6 +995,276 @@ static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R
   else return hipErrorInvalidValue;
 #undef LZ_GEMM
   return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Skinny kernel for M <= 32 token rows (decoding steps): the GEMM is then a stream of the
+// weight matrix through the chip and is bound by HBM, not by the matrix pipe, so the job is to
+// have every CU pull bytes all the time.  A WAVE owns 128 output features and a range of K and
+// runs its own pipeline, with no workgroup barrier in the loop: it copies 128 x 32 slices of W
+// (8 KB, whole 64-byte row pieces, global -> LDS) into a private two-slot ring, reads them
+// back as MFMA operand fragments, and multiplies them with the 32 token rows (B operand; their
+// slice of A rides in the same ring slot, rows past M repeat row M-1; the A matrix is tiny and
+// L2-resident).  Everything arrives by global -> LDS copies counted by hand: operands loaded
+// into registers across the loop's back edge make the compiler wait for ALL outstanding copies
+// before their first use, which serialises the ring (measured: 2 TB/s instead of 5).
+// The 4 waves of a workgroup take consecutive K ranges of the same 128 features and add their
+// partial sums through LDS in wave order; when K is also split over `ks` workgroups, each leaves
+// its partial tile (valid token rows only) in the workspace and takes a ticket from a
+// per-column-group counter: whoever draws the last ticket adds all partial tiles in split order
+// -- a fixed order, so results do not depend on arrival order -- applies the epilogue and resets
+// the counter.  Nobody waits for anybody.  `counters` must be zero on entry.
+// ------------------------------------------------------------------------------------------
+constexpr int SKN_TN = 4;                         // 32-column blocks per wave: 128 features
+constexpr int SKN_TILE = 64 * SKN_TN * 16;        // floats of one partial tile (lane-major)
+constexpr int SKN_BK = 32;                        // K elements per pipeline step
+constexpr int SKN_WSLOT = SKN_TN * 32 * SKN_BK * 2;       // 8 KB of W
+constexpr int SKN_DMA = SKN_WSLOT / 1024;                 // wave-wide copies of W per slot
+// a slot = the W slice + the token rows' slice of A (AR = 16 or 32 rows of 64 bytes); 4 waves x 2
+// slots = 72 or 80 KB per workgroup.  Two workgroups must fit a CU's 160 KB.
+constexpr int skn_slot(int ar) { return SKN_WSLOT + ar * SKN_BK * 2; }
+constexpr int skn_lds(int ar) { return 4 * 2 * skn_slot(ar); }
+static_assert(3 * SKN_TILE * 4 <= skn_lds(16), "the reduction reuses the rings");
+
+template <int EPI, int AR>
+__global__ void __launch_bounds__(256, 2)
+gemm_skinny_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                   uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int K, int lda,
+                   int ldw, int ldc, int n_groups, int ks, int steps_per_wave,
+                   float* __restrict__ part, unsigned* __restrict__ counters, EpiArgs ra) {
+  constexpr int SKN_SLOT = skn_slot(AR);
+  constexpr int SKN_OPS = SKN_DMA + AR / 16;       // vector-memory operations per step
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x >= n_groups * ks) {          // side job (see EpiArgs): Eq. 1 scores
+    const int sb = (int)blockIdx.x - n_groups * ks;
+    score_finish_block<true>(ra.sf_z, ra.sf_stat, ra.sf_s, ra.sf_cu, ra.sf_n_single, ra.sf_heads,
+                             ra.sf_z_ld, ra.sf_cu_z, true, sb / ra.sf_blocks_per_seq,
+                             (sb % ra.sf_blocks_per_seq) * (int)blockDim.x, (float2*)lds);
+    return;
+  }
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int hi = lane >> 5, l31 = lane & 31;
+  const int cg = blockIdx.x / ks, split = blockIdx.x % ks;
+  const int n0 = cg * (SKN_TN * 32);
+  const int ksteps = K / SKN_BK;
+  const int s_begin = min((split * 4 + wave) * steps_per_wave, ksteps);
+  const int n = min(s_begin + steps_per_wave, ksteps) - s_begin;      // steps of this wave
+
+  floatx16_t acc[1][SKN_TN];
+#pragma unroll
+  for (int j = 0; j < SKN_TN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][j][r] = 0.f;
+
+  // copy plan: instruction t fills rows 16t..16t+15 of the slot, lane p row p/4, stored chunk
+  // p%4 = logical chunk (p%4) ^ swz32(row)
+  char* ring = lds + wave * 2 * SKN_SLOT;
+  uint32_t w_off[SKN_DMA];
+#pragma unroll
+  for (int t = 0; t < SKN_DMA; ++t) {
+    const int tr = t * 16 + (lane >> 2);
+    w_off[t] = (uint32_t)(((size_t)(n0 + tr) * ldw + (((lane & 3) ^ swz32(tr)) * 8)) * 2);
+  }
+  const char* gw = (const char*)W + (size_t)s_begin * SKN_BK * 2;
+  auto issue = [&](int slot, int step) {           // step counted from s_begin
+#pragma unroll
+    for (int t = 0; t < SKN_DMA; ++t)
+      g2l16(gw + (size_t)step * SKN_BK * 2 + w_off[t], ring + slot * SKN_SLOT + t * 1024);
+  };
+  // the A slice: one or two more instructions, 16 token rows each
+  uint32_t a_off[AR / 16];
+#pragma unroll
+  for (int u = 0; u < AR / 16; ++u) {
+    const int tr = u * 16 + (lane >> 2);
+    const int row = tr < M ? tr : M - 1;
+    a_off[u] = (uint32_t)(((size_t)row * lda + (((lane & 3) ^ swz32(tr)) * 8)) * 2);
+  }
+  const char* ga = (const char*)A + (size_t)s_begin * SKN_BK * 2;
+  auto issue_all = [&](int slot, int step) {       // step counted from s_begin
+    issue(slot, step);
+#pragma unroll
+    for (int u = 0; u < AR / 16; ++u)
+      g2l16(ga + (size_t)step * SKN_BK * 2 + a_off[u], ring + slot * SKN_SLOT + SKN_WSLOT + u * 1024);
+  };
+  // operand fragments: row j*32 + l31 of the slot (token row l31 of the A part), logical chunk 2q + hi
+  // (with 16 token rows in the slot, lanes of tokens 16..31 -- past M -- re-read rows 0..15)
+  uint32_t f_off[2], fa_off[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    f_off[q] = (uint32_t)(l31 * 64 + (((q * 2 + hi) ^ swz32(l31)) * 16));
+    const int ta = l31 & (AR - 1);
+    fa_off[q] = (uint32_t)(ta * 64 + (((q * 2 + hi) ^ swz32(ta)) * 16));
+  }
+
+  bf16x8_t af[2], wf[SKN_TN][2];
+#define LZ_SKN_STEP(SLOT, NEXT_ISSUED, REFILL)                                                \
+  do {                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    if (NEXT_ISSUED) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(SKN_OPS) : "memory");           \
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    _Pragma("unroll") for (int q = 0; q < 2; ++q)                                             \
+      af[q] = *(const bf16x8_t*)(ring + (SLOT) * SKN_SLOT + SKN_WSLOT + fa_off[q]);           \
+    _Pragma("unroll") for (int j = 0; j < SKN_TN; ++j)                                        \
+      _Pragma("unroll") for (int q = 0; q < 2; ++q)                                           \
+        wf[j][q] = *(const bf16x8_t*)(ring + (SLOT) * SKN_SLOT + j * 32 * 64 + f_off[q]);     \
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    if ((REFILL) < n) issue_all(SLOT, REFILL);                                                \
+    _Pragma("unroll") for (int q = 0; q < 2; ++q)                                             \
+      _Pragma("unroll") for (int j = 0; j < SKN_TN; ++j)                                      \
+        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j][q], af[q], acc[0][j], 0, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+  } while (0)
+  if (n > 0) issue_all(0, 0);
+  if (n > 1) issue_all(1, 1);
+  for (int i = 0; i < n; i += 2) {
+    LZ_SKN_STEP(0, i + 1 < n, i + 2);
+    if (i + 1 < n) LZ_SKN_STEP(1, i + 2 < n, i + 3);
+  }
+#undef LZ_SKN_STEP
+
+  // ---- the four waves' partial sums, added in wave order (the rings are free now)
+  __syncthreads();
+  float* red = (float*)lds;
+  if (wave > 0) {
+    float* my = red + (wave - 1) * SKN_TILE;
+#pragma unroll
+    for (int j = 0; j < SKN_TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) my[(j * 16 + r) * 64 + lane] = acc[0][j][r];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+#pragma unroll
+      for (int j = 0; j < SKN_TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][j][r] += red[w * SKN_TILE + (j * 16 + r) * 64 + lane];
+  }
+  if (ks == 1) {
+    if (wave != 0) return;
+  } else {
+    // ---- K split over workgroups.  Partial tiles go to the workspace as [token][128 features]
+    // (valid tokens only); the workgroup that draws the last ticket adds them in split order,
+    // all 256 threads at once (one element each per pass, its `ks` loads in flight together:
+    // the fix-up costs one trip to memory, not `ks`), and hands the sums back to wave 0.
+    __shared__ unsigned last_flag;
+    __syncthreads();                                 // (everyone is done reading `red`)
+    if (wave == 0) {
+      // Agent-scope atomic stores go straight to the level of the memory system that every CU
+      // sees; once they have completed (vmcnt) the ticket may be drawn.  A release fence here
+      // instead would write back the whole L2's dirty lines, once per workgroup, hundreds of
+      // them at the same moment: that alone cost 20-40 us per launch.  The adding threads below
+      // read with agent-scope atomic loads, which bypass the non-coherent caches likewise.
+      float* slot = part + ((size_t)cg * ks + split) * SKN_TILE;
+      if (l31 < M) {
+#pragma unroll
+        for (int j = 0; j < SKN_TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            __hip_atomic_store(slot + l31 * 128 + j * 32 + 8 * (r / 4) + 4 * hi + (r % 4), acc[0][j][r],
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (lane == 0)
+        last_flag = __hip_atomic_fetch_add(counters + cg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                            (unsigned)(ks - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (last_flag == 0) return;
+    const float* base = part + (size_t)cg * ks * SKN_TILE;
+    for (int e = threadIdx.x; e < M * 128; e += 256) {
+      float sum = 0.f;
+      for (int sp = 0; sp < ks; sp += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          v[u] = sp + u < ks ? __hip_atomic_load(base + (size_t)(sp + u) * SKN_TILE + e, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT)
+                             : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += v[u];
+      }
+      red[e] = sum;
+    }
+    if (threadIdx.x == 0) counters[cg] = 0;          // ready for the next launch
+    __syncthreads();
+    if (wave != 0) return;
+    if (l31 < M) {
+#pragma unroll
+      for (int j = 0; j < SKN_TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 v4 = *(const float4*)(red + l31 * 128 + j * 32 + 8 * g + 4 * hi);
+          acc[0][j][4 * g] = v4.x; acc[0][j][4 * g + 1] = v4.y; acc[0][j][4 * g + 2] = v4.z; acc[0][j][4 * g + 3] = v4.w;
+        }
+    }
+  }
+  gemm_epilogue<1, SKN_TN, EPI>(acc, C, R, M, ldc, 0, n0, 0, 0, lane, ra);
+}
+
+constexpr size_t SKN_COUNTER_BYTES = 4096;         // one counter per 128 output features
+
+static hipError_t launch_skinny(const void* A, const void* W, void* C, const void* R, int M, int N,
+                                int K, int lda, int ldw, int ldc, int epi, const EpiArgs& ra,
+                                void* ws, hipStream_t st) {
+  if (M > 32 || N % (SKN_TN * 32) != 0 || (size_t)(N / 128) * 4 > SKN_COUNTER_BYTES)
+    return hipErrorInvalidValue;
+  if ((lda % 8) != 0 || (ldw % 8) != 0 || ((uintptr_t)A & 15) != 0 || ((uintptr_t)W & 15) != 0)
+    return hipErrorInvalidValue;
+  const int n_groups = N / (SKN_TN * 32), ksteps = K / SKN_BK;
+  // two workgroups per CU are resident (80 KB of LDS each); split K so that the grid is about
+  // one such round, with at least four steps per wave
+  int ks = (512 + n_groups / 2) / n_groups;
+  if (ks < 1) ks = 1;
+  const int max_ks = (ksteps + 15) / 16;
+  if (ks > max_ks) ks = max_ks;
+  const size_t part_bytes = gemm_workspace_bytes() - SKN_COUNTER_BYTES;
+  while (ks > 1 && (size_t)n_groups * ks * SKN_TILE * sizeof(float) > part_bytes) --ks;
+  const int steps = (ksteps + 4 * ks - 1) / (4 * ks);
+  EpiArgs ea = ra;
+  ea.sf_blocks_per_seq = (ea.sf_max_rows + 255) / 256;
+  ea.stage_out = 0;
+  const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
+  float* part = (float*)ws;
+  unsigned* counters = (unsigned*)((char*)ws + part_bytes);
+#define LZ_GEMM2(E, AR)                                                                          \
+  do {                                                                                           \
+    auto kern = gemm_skinny_kernel<E, AR>;                                                       \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, skn_lds(AR)); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    hipLaunchKernelGGL(kern, dim3(n_groups * ks + side), dim3(256), skn_lds(AR), st,             \
+                       (const uint16_t*)A, (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, \
+                       M, K, lda, ldw, ldc, n_groups, ks, steps, part, counters, ea);            \
+  } while (0)
+#define LZ_GEMM(E)                                                                               \
+  do {                                                                                           \
+    if (M <= 16) LZ_GEMM2(E, 16);                                                                \
+    else LZ_GEMM2(E, 32);                                                                        \
+  } while (0)
+  if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
+  else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
+  else if (epi == EPI_SWIGLU) LZ_GEMM(EPI_SWIGLU);
+  else if (epi == EPI_QKV_ROPE) {
+    if (ra.head_dim == 64) LZ_GEMM(EPI_QKV_ROPE64);
+    else LZ_GEMM(EPI_QKV_ROPE128);
+  }
+  else return hipErrorInvalidValue;
+#undef LZ_GEMM
+#undef LZ_GEMM2
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st) {
+  return launch_fill_zero((char*)sk_ws + gemm_workspace_bytes() - SKN_COUNTER_BYTES, SKN_COUNTER_BYTES, st);
 }
 
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
@@ -1031,6 +1302,11 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // tiles of the same work when those still fit one round (measured at M = 2364: O projection
     // 104 -> 90 us, down projection 227 -> 211 us; gate/up at M = 355: 88 -> 77 us).
     const long tiles192 = (long)((M + 191) / 192) * (N / 256);
+    // a handful of token rows (decoding): stream the weights, see gemm_skinny_kernel.  Only for
+    // callers that keep the ticket counters of the workspace zeroed (ra.skinny).
+    if (ra.skinny && M <= 32 && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
+        N % 128 == 0 && lda % 8 == 0 && ldw % 8 == 0)
+      cfg = 8;
     if (cfg != 0) {}
     else if (N % 256 == 0 && big_tiles >= 150 && big_tiles <= 205 && tiles192 <= 256 &&
              epilogue != EPI_QKV_ROPE) cfg = 7;
@@ -1051,6 +1327,9 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     case 6:                                             // 128x128 stream-K + fix-up
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
             return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out, st);
+    case 8:                                             // M <= 32: weight streaming
+            if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
+            return launch_skinny(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, ra, sk_ws, st);
     default: return hipErrorInvalidValue;
   }
 }

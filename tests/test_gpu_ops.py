@@ -66,6 +66,49 @@ def test_gemm(M, N, K, epi):
     _assert_bf16_close(_f64(Cout), ref, 1.0, "gemm")
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (1, 4096, 4096), (2, 12288, 4096), (7, 4096, 11008), (31, 768, 256),
+                                   (32, 22016, 4096), (17, 1536, 704)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_skinny(M, N, K, epi):
+    """The weight-streaming kernel for a handful of token rows (K split over waves and workgroups,
+    partial sums added in a fixed order): values, and bit-identical results from run to run."""
+    rng = np.random.default_rng(M * 11 + N + K + epi)
+    A = _rand_bf16(rng, (M, K))
+    W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    acc = _f64(A) @ _f64(W).T
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    e = epi | (8 << 8)
+    outs = []
+    for _ in range(2):
+        if epi == B.EPI_SWIGLU:
+            blocks = acc.reshape(M, N // 64, 2, 32)
+            ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, e, workspace=ws)
+        elif epi == B.EPI_RESIDUAL:
+            R = _rand_bf16(np.random.default_rng(5), (M, N))
+            ref = _f64(R) + acc
+            Cout = R.clone()
+            B.lazyllm_op_gemm(A, W, Cout, Cout, M, N, K, K, K, N, e, workspace=ws)
+        else:
+            ref = acc
+            Cout = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N, e, workspace=ws)
+        torch.cuda.synchronize()
+        _assert_bf16_close(_f64(Cout), ref, 1.0, "skinny gemm")
+        outs.append(Cout.clone())
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_gemm_skinny_refuses_more_than_32_rows():
+    A = torch.zeros(33, 64, dtype=torch.bfloat16, device=DEV)
+    W = torch.zeros(128, 64, dtype=torch.bfloat16, device=DEV)
+    Cout = torch.zeros(33, 128, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.LazyLLMError):
+        B.lazyllm_op_gemm(A, W, Cout, None, 33, 128, 64, 64, 64, 128, B.EPI_STORE | (8 << 8), workspace=ws)
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 128, 64), (355, 4096, 4096), (1182, 4096, 1408), (130, 256, 11008),
                                    (700, 384, 192), (5000, 128, 64)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL])
