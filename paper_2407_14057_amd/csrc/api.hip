@@ -605,7 +605,7 @@ void layout_generation(const lazyllm_config* c, const Stages* st, int cap, GenLa
 // Scratch of one step; rows are bounded by the capacity (every token could be revived at once).
 struct GenWorkspace {
   size_t h0, h1, ssq0, ssq1, q, o, act, score, scores, member, bits, run_pos, live_row, src_row,
-      park_src, park_pos, counts, xf, gemm_ws, total;
+      park_src, park_pos, counts, xf, att_ws, gemm_ws, total;
 };
 
 void layout_gen_workspace(const lazyllm_config* c, int n_stages, int cap, GenWorkspace* w) {
@@ -630,6 +630,7 @@ void layout_gen_workspace(const lazyllm_config* c, int n_stages, int cap, GenWor
   w->park_pos = take(T * 4);
   w->counts = take((size_t)n_stages * 16);
   w->xf = take(d * 4);
+  w->att_ws = take(decode_attention_workspace_bytes(c->d_model, c->n_heads));
   w->gemm_ws = take(gemm_workspace_bytes());
   w->total = off;
 }
@@ -860,7 +861,8 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     LZ_RUN(LAZYLLM_STEP_ATTENTION, l, M, 4.0 * (double)M * (double)sel_count[s] * dd,
            launch_decode_attention(W + ws.q, rpos, M, S + gl.k[l], S + gl.vt[l], gl.vt_ld,
                                    s > 0 ? bits_of(s) : nullptr, n_tot, W + ws.o, H, hd, st,
-                                   score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld));
+                                   score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld,
+                                   W + ws.att_ws, decode_attention_workspace_bytes(d, H)));
     EpiArgs eo{};
     eo.ssq_out = ssq_ffn; eo.skinny = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, M, 2.0 * M * dd * dd,

@@ -235,7 +235,9 @@ hipError_t launch_revive_gather(const void* h_prev, void* aux, const int32_t* ru
 hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, const void* k,
                                    const void* vt, int vt_ld, const unsigned long long* sel_bits,
                                    int n_keys, void* o, int n_heads, int head_dim, hipStream_t st,
-                                   float* z = nullptr, void* zstat = nullptr, int z_ld = 0);
+                                   float* z = nullptr, void* zstat = nullptr, int z_ld = 0,
+                                   void* split_ws = nullptr, size_t split_ws_bytes = 0);
+size_t decode_attention_workspace_bytes(int d_model, int n_heads);
 
 struct PlanArgs {
   int32_t n_stages;                     // pruning stages after stage 0

@@ -211,7 +211,8 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
                    const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt, int vt_ld,
                    const unsigned long long* __restrict__ sel_bits, int n_keys,
                    uint16_t* __restrict__ o, int n_heads, float scale_log2e, float* __restrict__ z,
-                   float2* __restrict__ zstat, int z_ld) {
+                   float2* __restrict__ zstat, int z_ld, int n_splits, float* __restrict__ po,
+                   float2* __restrict__ pml) {
   constexpr int NW = 4, BN = 64;
   constexpr int CHK = HD / 8, KSTEPS = HD / 16, HS = HD / 32;
   constexpr int K_TILE = BN * HD * 2, STAGE = 2 * K_TILE;
@@ -229,7 +230,13 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
   const int qrow_c = qrow < M ? qrow : M - 1;
   const int my_pos = qpos[qrow_c];
   const int blk_last = (q0 + 32 * NW < M ? q0 + 32 * NW : M) - 1;
-  const int ntiles = qpos[blk_last] / BN + 1;               // keys 0 .. the block's last position
+  const int ntiles_blk = qpos[blk_last] / BN + 1;           // keys 0 .. the block's last position
+  // with few queries the keys are split over blockIdx.z: each split leaves (max, sum, unnormalised
+  // output) per query and a second kernel merges them
+  const int sp = blockIdx.z;
+  const int per_split = (ntiles_blk + n_splits - 1) / n_splits;
+  const int t_lo = sp * per_split;
+  const int t_hi = min(t_lo + per_split, ntiles_blk);
   const int w_first = q0 + wave * 32;
   const int w_last = w_first + 31 < M ? w_first + 31 : M - 1;
   const int wave_max_pos = w_first < M ? qpos[w_last] : -1; // -1: this wave has no query
@@ -287,14 +294,14 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
   float m_run = -INFINITY, l_run = 0.f;
   const bool score_lane = z != nullptr && qrow == M - 1;
 
-  issue(0, 0);
-  for (int it = 0; it < ntiles; ++it) {
+  if (t_lo < t_hi) issue(0, t_lo * BN);
+  for (int it = t_lo; it < t_hi; ++it) {
     const int k0 = it * BN;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();           // tile `it` has landed for every wave; everyone is done with tile it-1
-    if (it + 1 < ntiles) issue((it + 1) & 1, k0 + BN);
+    if (it + 1 < t_hi) issue((it + 1 - t_lo) & 1, k0 + BN);
     if (k0 > wave_max_pos) continue;                        // (uniform per wave; barriers stay matched)
-    const char* st = lds + (it & 1) * STAGE;
+    const char* st = lds + ((it - t_lo) & 1) * STAGE;
     floatx16_t sacc[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -369,6 +376,20 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (n_splits > 1) {
+    if (qrow < M) {
+      if (hi == 0) pml[((size_t)sp * M + qrow) * n_heads + head] = make_float2(m_run, l_tot);
+      float* pp = po + ((size_t)sp * M + qrow) * d + head * HD + 4 * hi;
+#pragma unroll
+      for (int h = 0; h < HS; ++h)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float4 v4 = {oacc[h][4 * g], oacc[h][4 * g + 1], oacc[h][4 * g + 2], oacc[h][4 * g + 3]};
+          *(float4*)(pp + h * 32 + 8 * g) = v4;
+        }
+    }
+    return;
+  }
   const float inv = 1.0f / l_tot;
   if (score_lane && hi == 0) zstat[head] = make_float2(m_run, inv);
   if (qrow < M) {
@@ -385,16 +406,61 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
   }
 }
 
+// Merges the key splits of decode_attn_kernel: per (query, head) the splits' (max m_s, sum l_s,
+// unnormalised output o_s) combine as o = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s with
+// m = max_s m_s, splits added in order.  One thread per output dimension.
+__global__ void __launch_bounds__(128)
+decode_attn_merge_kernel(const float* __restrict__ po, const float2* __restrict__ pml, int n_splits,
+                         int M, int n_heads, int hd, uint16_t* __restrict__ o,
+                         float2* __restrict__ zstat) {
+  const int row = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
+  if (dim >= hd) return;
+  const int d = n_heads * hd;
+  float m = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, pml[((size_t)s * M + row) * n_heads + head].x);
+  float l = 0.f, acc = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float2 ml = pml[((size_t)s * M + row) * n_heads + head];
+    const float w = ml.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml.x - m);
+    l += w * ml.y;
+    acc += w * po[((size_t)s * M + row) * d + head * hd + dim];
+  }
+  const float inv = 1.0f / l;
+  o[(size_t)row * d + head * hd + dim] = to_bf16(acc * inv);
+  if (zstat != nullptr && row == M - 1 && dim == 0) zstat[head] = make_float2(m, inv);
+}
+
+size_t decode_attention_workspace_bytes(int d_model, int n_heads) {
+  // 16 splits of up to 128 queries: fp32 outputs and (max, sum) pairs
+  return (size_t)16 * 128 * ((size_t)d_model * 4 + (size_t)n_heads * 8);
+}
+
 hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, const void* k,
                                    const void* vt, int vt_ld, const unsigned long long* sel_bits,
                                    int n_keys, void* o, int n_heads, int head_dim, hipStream_t st,
-                                   float* z, void* zstat, int z_ld) {
+                                   float* z, void* zstat, int z_ld, void* split_ws,
+                                   size_t split_ws_bytes) {
   if (M <= 0 || n_keys <= 0) return hipErrorInvalidValue;
   if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
   if (vt_ld < (n_keys + 63) / 64 * 64) return hipErrorInvalidValue;
   if (z != nullptr && (zstat == nullptr || z_ld < (n_keys + 63) / 64 * 64)) return hipErrorInvalidValue;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
-  dim3 grid(n_heads, (M + 127) / 128), block(256);
+  // Few queries (a decoding step's one new token and a handful of revived ones) make few
+  // workgroups: split the keys so that about 512 are in flight, each with at least two key tiles.
+  const int qblocks = (M + 127) / 128, d_model = n_heads * head_dim;
+  int n_splits = 1;
+  if (split_ws != nullptr && qblocks == 1) {
+    const int tiles = (n_keys + 63) / 64;
+    n_splits = 512 / n_heads;
+    if (n_splits > tiles / 2) n_splits = tiles / 2;
+    if (n_splits > 16) n_splits = 16;
+    const size_t per_split = (size_t)M * ((size_t)d_model * 4 + (size_t)n_heads * 8);
+    while (n_splits > 1 && (size_t)n_splits * per_split > split_ws_bytes) --n_splits;
+    if (n_splits < 1) n_splits = 1;
+  }
+  float* po = (float*)split_ws;
+  float2* pml = (float2*)((char*)split_ws + (size_t)n_splits * M * d_model * 4);
+  dim3 grid(n_heads, qblocks, n_splits), block(256);
 #define LZ_DATT(HD)                                                                                \
   do {                                                                                             \
     constexpr int LDS_BYTES = 2 * 2 * 64 * HD * 2;                                                 \
@@ -408,11 +474,16 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
     }                                                                                              \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, qpos, M,              \
                        (const uint16_t*)k, (const uint16_t*)vt, vt_ld, sel_bits, n_keys,           \
-                       (uint16_t*)o, n_heads, scale_log2e, z, (float2*)zstat, z_ld);               \
+                       (uint16_t*)o, n_heads, scale_log2e, z, (float2*)zstat, z_ld, n_splits, po,  \
+                       pml);                                                                       \
   } while (0)
   if (head_dim == 128) LZ_DATT(128);
   else LZ_DATT(64);
 #undef LZ_DATT
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_splits == 1) return e;
+  hipLaunchKernelGGL(decode_attn_merge_kernel, dim3(M, n_heads), dim3(128), 0, st, po, pml, n_splits, M,
+                     n_heads, head_dim, (uint16_t*)o, z != nullptr ? (float2*)zstat : nullptr);
   return hipGetLastError();
 }
 

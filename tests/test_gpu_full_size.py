@@ -193,3 +193,114 @@ def test_batch8(model7b):
     _check_layer(w, out, l, wl.schedule, lo=lo, hi=hi, tag="batch8 seq %d" % b)
     for bb in (0, 7):
         _check_logits(w, out, bb)
+
+
+# ---------------------------------------------------------------------------- decoding steps
+
+def _greedy(logits):
+    return torch.argmax(logits).to(torch.int32).reshape(1)
+
+
+def test_7b_dense_decoding_step_equals_prefill_of_the_extended_prompt(model7b):
+    """Sec. 3.1: with a complete KV cache a decoding step gives what prefilling the longer prompt
+    gives.  Two different kernel paths (single-row skinny GEMMs and split-key attention against
+    256-row tiles and the flash kernel) are each held to 2e-2 of the logit range against the
+    checker, so against each other they may differ by twice that."""
+    w, model = model7b
+    n = 700
+    ids = synth.make_prompt(n + 2, SHAPE.vocab, 4242)
+    dev_ids = torch.from_numpy(ids.astype(np.int32)).to(DEV)
+    out = model.prefill(dev_ids[:n].contiguous(), [])
+    gen = B.Generation(model, [], out, n + 4)
+    for t in range(2):
+        so = gen.step(dev_ids[n + t: n + t + 1].contiguous())
+        torch.cuda.synchronize()
+        assert so.status == 0 and so.n_ran == [1] * SHAPE.n_layers
+        step_logits = so.logits.double().cpu().numpy()
+        view = gen.view()
+        k_new = [view["k"][l][n + t].clone() for l in (0, 15, 31)]
+        full = model.prefill(dev_ids[: n + t + 1].contiguous(), [])
+        torch.cuda.synchronize()
+        ref = full.logits[0].double().cpu().numpy()
+        rng_ = ref.max() - ref.min()
+        err = np.abs(step_logits - ref).max() / rng_
+        print("dense step %d vs prefill: logit error %.4f of the range" % (t, err))
+        assert err <= 4e-2
+        # the new token's K rows: layer 0 depends on one projection only; deeper rows carry the
+        # rounding noise both paths accumulated over the layers below (bf16 residual stream)
+        for k_step, l in zip(k_new, (0, 15, 31)):
+            a, b = _f64(k_step), _f64(full.k(l)[n + t].reshape(-1))
+            rel = np.abs(a - b).max() / np.abs(b).max()
+            print("   K row of the new token at layer %2d: %.4f of the largest entry" % (l, rel))
+            assert rel <= (3e-2 if l == 0 else 8e-2)
+    gen.close()
+
+
+def test_7b_pruned_decoding_steps(model7b):
+    """The headline workload's prefill followed by decoding steps with revival, in the launch
+    configuration `bench.py --decode` times.  Checked: what holds at any size (counts, nesting,
+    nothing recomputed, Eq. 1 sums to one and vanishes outside the selection), the selection of
+    every pruning layer recomputed exactly from the GPU's own fp32 scores of the layer below (the
+    integer half of the step), and layer 0's scores recomputed by the checker from the cache."""
+    w, model = model7b
+    wl = synth.WORKLOADS["7b_3376"]
+    inp, out = _run(model, wl, flags=0)
+    sched = list(wl.schedule)
+    prune_layers = [l for l, p in sched if p < 1000]
+    L, n = SHAPE.n_layers, int(inp["token_ids"].shape[0])
+    gen = B.Generation(model, sched, out, n + 8)
+    tok = _greedy(out.logits[0])
+    torch.cuda.synchronize()
+    had = [gen.view()["has_kv"][l].clone() for l in range(L)]
+    for t in range(3):
+        n_tot = n + t + 1
+        tok_host = int(tok.item())
+        so = gen.step(tok)
+        torch.cuda.synchronize()
+        assert so.status == 0
+        counts = O.keep_counts(n_tot, L, sched)
+        view = gen.view()
+        prev_sel = np.arange(n_tot)
+        for l in range(L):
+            m = so.selected(l)
+            sel = np.arange(n_tot) if m is None else np.nonzero(m.cpu().numpy())[0]
+            assert len(sel) == counts[l] == so.n_selected[l] and sel[-1] == n_tot - 1
+            assert np.all(np.isin(sel, prev_sel))
+            ran = so.ran_pos(l).cpu().numpy()
+            had_l = had[l].cpu().numpy().astype(bool)
+            assert np.array_equal(ran, sel[~had_l[sel]])                 # exactly the selected tokens without K,V
+            now = view["has_kv"][l].cpu().numpy().astype(bool)
+            assert np.array_equal(now, had_l | np.isin(np.arange(len(now)), ran))
+            s = so.scores(l).double().cpu().numpy()
+            assert abs(s.sum() - 1.0) < 2e-4 and s.min() >= 0.0
+            outside = np.ones(n_tot, dtype=bool)
+            outside[sel] = False
+            assert not s[outside].any()
+            if l + 1 in prune_layers:
+                # the next layer's selection, from these very scores: new token + best of the rest
+                cand = sel[:-1]
+                s32 = so.scores(l).cpu().numpy()[cand]
+                order = np.argsort(-s32, kind="stable")[: counts[l + 1] - 1]
+                want = np.sort(np.concatenate([cand[order], [n_tot - 1]]))
+                m1 = so.selected(l + 1).cpu().numpy()
+                assert np.array_equal(np.nonzero(m1)[0], want), "selection at layer %d" % (l + 1)
+            prev_sel = sel
+        # layer 0, recomputed: the new token's q and k from its embedding row, Eq. 1 over the cache
+        lw_bits = synth.layer_to_host_bits(w, 0)
+        lw = O.LayerWeights({k: [v] for k, v in lw_bits.items()}, 0, np.float64)
+        emb = _f64(w["embed"][tok_host])
+        x = O.rmsnorm(emb[None, :], lw.attn_norm, SHAPE.rms_eps)
+        pos = np.asarray([n_tot - 1])
+        q = O.round_to_bf16(O.rope((x @ lw.wq.T).reshape(1, SHAPE.n_heads, SHAPE.head_dim), pos, SHAPE.rope_theta))
+        k = O.round_to_bf16(O.rope((x @ lw.wk.T).reshape(1, SHAPE.n_heads, SHAPE.head_dim), pos, SHAPE.rope_theta))
+        k_cache = _f64(view["k"][0][:n_tot]).reshape(n_tot, SHAPE.n_heads, SHAPE.head_dim)
+        assert np.abs(k_cache[-1] - k[0]).max() <= 3e-2 * np.abs(k[0]).max()
+        s_ref = O.last_row_scores(q[0], k_cache)
+        s_gpu = so.scores(0).double().cpu().numpy()
+        err = np.abs(s_gpu / s_ref - 1).max()
+        print("step %d: rows per stage %s, layer-0 score error %.4f" % (t, sorted(set(so.n_ran), reverse=True), err))
+        assert err < 2e-2
+        had = [view["has_kv"][l].clone() for l in range(L)]
+        tok = _greedy(so.logits)
+    assert float(torch.stack([h[:n].float().mean() for h in had]).mean()) <= 1.0
+    gen.close()
