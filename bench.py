@@ -367,8 +367,10 @@ def main() -> int:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "shape": "llama-2-7b (32 layers, d 4096, 32x128 heads, ffn 11008, vocab 32000)"
-                   if shape is synth.LLAMA7B else "tiny", "prompt_tokens": n_tokens, "batch": len(cu) - 1,
+        "config": {"workload": wl.name,
+                   "shape": "%d layers, d %d, %dx%d heads, ffn %d, vocab %d" % (
+                       shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab),
+                   "prompt_tokens": n_tokens, "batch": len(cu) - 1,
                    "keep_schedule_permille_of_survivors": sched,
                    "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True)},
         "ttft_ms": round(ms, 4), "ttft_ms_median": round(ttft_median, 4), "ttft_ms_min": round(ttft_min, 4),

@@ -42,7 +42,7 @@ def _run(model, wl, flags=B.LAZYLLM_KEEP_HIDDEN):
 
 
 def _check_structure(wl, inp, out):
-    L = SHAPE.n_layers
+    L = wl.shape.n_layers
     cu0 = inp["cu_seqlens"]
     assert out.status == 0
     for b in range(len(cu0) - 1):
@@ -69,7 +69,7 @@ def _check_structure(wl, inp, out):
     assert sum(out.n_tokens) <= int(cu0[-1]) * L
 
 
-def _check_layer(w, out, l, schedule, lo=None, hi=None, tag=""):
+def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE):
     """Recompute layer l from the GPU's own input and compare what the layer produced."""
     n = out.n_tokens[l]
     lo = 0 if lo is None else lo
@@ -78,8 +78,8 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag=""):
     lw = O.LayerWeights({k: [v] for k, v in lw_bits.items()}, 0, np.float64)
     h_in = _f64(out.hidden_in(l)[lo:hi])
     pos = out.kept_pos(l)[lo:hi].cpu().numpy().astype(np.int64)
-    h_ref, k_ref, v_ref, s_ref = O.decoder_layer(h_in, pos, lw, SHAPE.n_heads, SHAPE.head_dim, SHAPE.rms_eps,
-                                                 SHAPE.rope_theta, store=O.round_to_bf16)
+    h_ref, k_ref, v_ref, s_ref = O.decoder_layer(h_in, pos, lw, shape.n_heads, shape.head_dim, shape.rms_eps,
+                                                 shape.rope_theta, store=O.round_to_bf16)
     k = _f64(out.k(l)[lo:hi]); v = _f64(out.v(l)[lo:hi])
     ek = np.abs(k - k_ref).max() / np.abs(k_ref).max()
     ev = np.abs(v - v_ref).max() / np.abs(v_ref).max()
@@ -88,7 +88,7 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag=""):
     sched = dict(schedule)
     rep = {"layer": l, "k": float(ek), "v": float(ev), "s": float(es)}
     single = (lo == 0 and hi == n)
-    if l + 1 < SHAPE.n_layers:
+    if l + 1 < shape.n_layers:
         if (l + 1) in sched and sched[l + 1] < 1000:
             # the selection that enters layer l+1, by the margin rule
             m = hi - lo
@@ -123,12 +123,12 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag=""):
     return rep
 
 
-def _check_logits(w, out, b=0):
-    L = SHAPE.n_layers
+def _check_logits(w, out, b=0, shape=SHAPE):
+    L = shape.n_layers
     last_row = int(out.cu_kept(L - 1)[b + 1]) - 1
     h_last = _f64(out.hidden_out[last_row])
     g = _f64(w["final_norm"]); wl = _f64(w["lm_head"])
-    ref = wl @ O.rmsnorm(h_last, g, SHAPE.rms_eps)
+    ref = wl @ O.rmsnorm(h_last, g, shape.rms_eps)
     got = out.logits[b].cpu().numpy().astype(np.float64)
     err = np.abs(got - ref).max() / (ref.max() - ref.min())
     print("logits err/range", err, flush=True)
@@ -193,6 +193,21 @@ def test_batch8(model7b):
     _check_layer(w, out, l, wl.schedule, lo=lo, hi=hi, tag="batch8 seq %d" % b)
     for bb in (0, 7):
         _check_logits(w, out, bb)
+
+
+def test_second_model_shape_xgen7b():
+    """The paper's second model (Sec. 5: XGen 7B): same decoder, larger vocabulary, other epsilon."""
+    wl = synth.WORKLOADS["xgen7b_3376"]
+    shape = wl.shape
+    w = synth.make_weights(shape, wl.weight_seed, DEV)
+    model = B.Model(shape.as_dict(), w, DEV)
+    inp, out = _run(model, wl)
+    assert sorted(set(out.n_tokens), reverse=True) == [3376, 2364, 1182, 355]
+    _check_structure(wl, inp, out)
+    for l in (7, 8, 31):
+        _check_layer(w, out, l, wl.schedule, tag="xgen7b", shape=shape)
+    _check_logits(w, out, shape=shape)
+    model.close()
 
 
 # ---------------------------------------------------------------------------- decoding steps
