@@ -1303,8 +1303,11 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // 104 -> 90 us, down projection 227 -> 211 us; gate/up at M = 355: 88 -> 77 us).
     const long tiles192 = (long)((M + 191) / 192) * (N / 256);
     // a handful of token rows (decoding): stream the weights, see gemm_skinny_kernel.  Only for
-    // callers that keep the ticket counters of the workspace zeroed (ra.skinny).
-    if (ra.skinny && M <= 32 && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
+    // callers that keep the ticket counters of the workspace zeroed (ra.skinny).  The partial
+    // tiles it exchanges grow with M: measured against the tile kernels it wins up to about 8
+    // rows (QKV 28 vs 43 us at M = 2, 33 vs 43 at 8, 40 vs 43 at 16; down 28 / 35 / 43 vs 38), and
+    // up to 32 rows for the rotary epilogue, whose tile form has only 48 workgroups at d = 4096.
+    if (ra.skinny && (M <= 8 || (epilogue == EPI_QKV_ROPE && M <= 32)) && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
         N % 128 == 0 && lda % 8 == 0 && ldw % 8 == 0)
       cfg = 8;
     if (cfg != 0) {}
