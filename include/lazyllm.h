@@ -7,7 +7,9 @@
  * attending to it (Eq. 1), pruning layers keep the top-k percentile of the
  * surviving tokens (Sec. 3.2, "Progressive Token Pruning"), hidden states and
  * position ids are compacted, and the hidden states of dropped tokens are
- * parked in an Aux Cache (Sec. 3.2, "Aux Cache").
+ * parked in an Aux Cache (Sec. 3.2, "Aux Cache").  Decoding steps after such a
+ * prefill (lazyllm_decode_step) select afresh in every step and revive pruned
+ * tokens from the Aux Cache.
  *
  * Conventions
  *   - "device" pointers are HIP device memory owned by the caller unless said
@@ -16,7 +18,8 @@
  *     [out_features, in_features] (y = x W^T).
  *   - every call that enqueues work takes a hipStream_t as void*; work is
  *     asynchronous on that stream and the results are valid once the caller
- *     has synchronised it.  Nothing here synchronises except model_create.
+ *     has synchronised it.  Nothing here synchronises except model_create
+ *     and lazyllm_decode_step (once per pruning layer, see there).
  *   - return value 0 is success, negative values are lazyllm_status codes.
  *     No call throws or aborts.  Argument validation happens before the first
  *     HIP call, so the error paths can be exercised without a GPU.
