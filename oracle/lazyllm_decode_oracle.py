@@ -72,8 +72,9 @@ class Generation:
         self.n_prompt, self.n_tokens, self.cap = int(n_prompt), int(n_prompt), int(capacity)
         if capacity < n_prompt:
             raise ValueError("capacity below the prompt length")
-        self.k = [np.full((capacity, self.H, self.hd), np.nan, dtype=dtype) for _ in range(self.L)]
-        self.v = [np.full((capacity, self.H, self.hd), np.nan, dtype=dtype) for _ in range(self.L)]
+        self.Hkv = int(np.asarray(weights["wk"][0]).shape[0]) // self.hd     # K,V heads (grouped-query models)
+        self.k = [np.full((capacity, self.Hkv, self.hd), np.nan, dtype=dtype) for _ in range(self.L)]
+        self.v = [np.full((capacity, self.Hkv, self.hd), np.nan, dtype=dtype) for _ in range(self.L)]
         self.has_kv = [np.zeros(capacity, dtype=bool) for _ in range(self.L)]
         self.aux_h = [np.full((capacity, self.d), np.nan, dtype=dtype) for _ in range(self.L)]
         self.has_aux = [np.zeros(capacity, dtype=bool) for _ in range(self.L)]
@@ -114,6 +115,7 @@ class Generation:
                     or want[-1] != new_pos):
                 raise ValueError("forced selection is not valid at layer %d" % l)
         store, dtype, H, hd, d = self.store, self.dtype, self.H, self.hd, self.d
+        Hkv, group = self.Hkv, self.H // self.Hkv
         selected = np.arange(n_tot, dtype=np.int64)                       # candidates of layer 0: everything
         run_pos = np.asarray([new_pos], dtype=np.int64)                   # tokens carrying a hidden state
         run_h = P._as_float(np.asarray(self.weights["embed"])[[int(token_id)]], dtype)
@@ -156,8 +158,8 @@ class Generation:
             m = run_pos.shape[0]
             x = P.rmsnorm(run_h, lw.attn_norm, self.eps)
             q = store(P.rope((x @ lw.wq.T).reshape(m, H, hd), run_pos, self.theta))
-            k = store(P.rope((x @ lw.wk.T).reshape(m, H, hd), run_pos, self.theta))
-            v = store((x @ lw.wv.T).reshape(m, H, hd))
+            k = store(P.rope((x @ lw.wk.T).reshape(m, Hkv, hd), run_pos, self.theta))
+            v = store((x @ lw.wv.T).reshape(m, Hkv, hd))
             self.k[l][run_pos], self.v[l][run_pos] = k, v
             self.has_kv[l][run_pos] = True
             self.times_computed[l, run_pos] += 1
@@ -167,9 +169,9 @@ class Generation:
             o = np.empty((m, H, hd), dtype=dtype)
             s = np.zeros(selected.shape[0], dtype=dtype)
             for head in range(H):
-                z = (q[:, head, :] @ kc[:, head, :].T) / math.sqrt(hd)
+                z = (q[:, head, :] @ kc[:, head // group, :].T) / math.sqrt(hd)
                 prob = P.softmax_rows(np.where(visible, z, -np.inf))
-                o[:, head, :] = prob @ vc[:, head, :]
+                o[:, head, :] = prob @ vc[:, head // group, :]
                 s += prob[m - 1]                                           # Eq. 1: the new token's row
             s_prev = s / H
             o = store(o)

@@ -29,6 +29,9 @@ is silent (each also listed in the design notes):
     the original position of every token dropped there.
   * model fine print (only "Llama 2, 32 layers, width 4096" is stated):
     pre-norm RMSNorm, multi-head attention, SwiGLU MLP, untied LM head, no bias.
+    Grouped-query attention (fewer K,V heads than query heads, each shared by a
+    group) is accepted as a model variant: Eq. 1 stays the mean over all query
+    heads' maps.
 
 Parity pins for each function live in tests/test_oracle_*.py (library
 transformer, closed forms, brute force, invariants).  Absolute logits of the
@@ -117,28 +120,31 @@ def attention_map(q: np.ndarray, k: np.ndarray) -> np.ndarray:
 def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Multi-head causal attention and Eq. 1 scores.
 
-    q, k, v: [m, H, hd].  Returns (o[m, H, hd], s[m]) where
-    s_i = (1/H) sum_h A_h[last query, key i]   (Eq. 1).
-    The full m x m map of each head is materialised, as in the definition.
+    q: [m, H, hd]; k, v: [m, Hkv, hd] with Hkv dividing H (grouped-query attention: query head h
+    reads K,V head h // (H / Hkv); Hkv = H is plain multi-head attention).  Returns
+    (o[m, H, hd], s[m]) where s_i = (1/H) sum_h A_h[last query, key i]   (Eq. 1, the mean over
+    all H attention maps).  The full m x m map of each head is materialised, as in the definition.
     """
     m, H, hd = q.shape
-    o = np.empty_like(v)
+    group = H // k.shape[1]
+    o = np.empty_like(q)
     s = np.zeros(m, dtype=q.dtype)
     for head in range(H):
-        P = attention_map(q[:, head, :], k[:, head, :])
-        o[:, head, :] = P @ v[:, head, :]
+        P = attention_map(q[:, head, :], k[:, head // group, :])
+        o[:, head, :] = P @ v[:, head // group, :]
         s += P[m - 1, :]
     return o, s / H
 
 
 def last_row_scores(q_last: np.ndarray, k: np.ndarray) -> np.ndarray:
-    """Eq. 1 from the last query alone: q_last[H, hd], k[m, H, hd] -> s[m].
+    """Eq. 1 from the last query alone: q_last[H, hd], k[m, Hkv, hd] -> s[m].
 
     The last row of a causal map has no masked entry, so it is the plain
     softmax of q_last . k_i / sqrt(hd) over all m tokens, then the head mean.
     """
-    m, H, hd = k.shape
-    z = np.einsum("hd,mhd->hm", q_last, k) / math.sqrt(hd)
+    m, Hkv, hd = k.shape
+    kk = np.repeat(k, q_last.shape[0] // Hkv, axis=1)
+    z = np.einsum("hd,mhd->hm", q_last, kk) / math.sqrt(hd)
     return np.mean(softmax_rows(z), axis=0)
 
 
@@ -205,15 +211,16 @@ def decoder_layer(h: np.ndarray, pos: np.ndarray, lw: LayerWeights, n_heads: int
 
     `store` is applied wherever a tensor is written back to memory (identity,
     or round_to_bf16 to model bf16 activations).  Returns (h_out, k, v, s) with
-    k, v [m, H, hd] as they enter the KV cache and s the Eq. 1 scores.
+    k, v [m, Hkv, hd] as they enter the KV cache (Hkv = rows of wk / hd) and s the Eq. 1 scores.
     """
     m, d = h.shape
+    n_kv_heads = lw.wk.shape[0] // head_dim          # grouped-query attention when below n_heads
     # The normalised activations x and y are not rounding points: the data flow being modelled
     # folds RMSNorm into the projections and never writes them to memory.
     x = rmsnorm(h, lw.attn_norm, eps)
     q = (x @ lw.wq.T).reshape(m, n_heads, head_dim)
-    k = (x @ lw.wk.T).reshape(m, n_heads, head_dim)
-    v = store((x @ lw.wv.T).reshape(m, n_heads, head_dim))
+    k = (x @ lw.wk.T).reshape(m, n_kv_heads, head_dim)
+    v = store((x @ lw.wv.T).reshape(m, n_kv_heads, head_dim))
     q = store(rope(q, pos, theta))
     k = store(rope(k, pos, theta))
     o, s = causal_attention(q, k, v)

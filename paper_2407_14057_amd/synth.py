@@ -33,11 +33,16 @@ class ModelShape:
     vocab: int
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
+    n_kv_heads: int = 0            # K,V heads; 0 = as many as query heads (no grouped-query attention)
+
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads if self.n_kv_heads else self.n_heads
 
     def as_dict(self) -> Dict[str, float]:
         return dict(n_layers=self.n_layers, d_model=self.d_model, n_heads=self.n_heads,
                     head_dim=self.head_dim, d_ffn=self.d_ffn, vocab=self.vocab,
-                    rms_eps=self.rms_eps, rope_theta=self.rope_theta)
+                    rms_eps=self.rms_eps, rope_theta=self.rope_theta, n_kv_heads=self.kv_heads)
 
 
 TINY = ModelShape(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
@@ -83,10 +88,11 @@ _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up",
 def weight_shapes(s: ModelShape) -> Dict[str, Tuple[int, ...]]:
     """Shape of each tensor, nn.Linear convention [out_features, in_features]."""
     d, f = s.d_model, s.d_ffn
+    kvd = s.kv_heads * s.head_dim
     return {
         "embed": (s.vocab, d), "final_norm": (d,), "lm_head": (s.vocab, d),
         "attn_norm": (d,), "ffn_norm": (d,),
-        "wq": (d, d), "wk": (d, d), "wv": (d, d), "wo": (d, d),
+        "wq": (d, d), "wk": (kvd, d), "wv": (kvd, d), "wo": (d, d),
         "w_gate": (f, d), "w_up": (f, d), "w_down": (d, f),
     }
 

@@ -250,3 +250,64 @@ def test_tiny512_regression_fixture():
     for key in ("scores_layer1_first8", "scores_layer3_last4", "logits_first8"):
         assert np.allclose(got[key], want[key], rtol=1e-9, atol=1e-12), key
     assert abs(got["logits_sum"] - want["logits_sum"]) < 1e-7
+
+
+def test_grouped_query_attention_matches_library_transformer():
+    """Model variant with fewer K,V heads than query heads: hidden states, K/V and Eq. 1 (the mean
+    over ALL query heads' maps) against HF's Llama with num_key_value_heads below the head count."""
+    shape = dataclasses.replace(SMALL, n_kv_heads=2)
+    wb = _weights(shape, seed=17)
+    assert wb["wk"][0].shape == (2 * shape.head_dim, shape.d_model)
+    ids = synth.make_prompt(80, shape.vocab, 6)
+    res = O.prefill(shape.as_dict(), wb, ids, [], keep_hidden=True)
+    from transformers import LlamaConfig, LlamaForCausalLM
+    cfg = LlamaConfig(vocab_size=shape.vocab, hidden_size=shape.d_model, intermediate_size=shape.d_ffn,
+                      num_hidden_layers=shape.n_layers, num_attention_heads=shape.n_heads,
+                      num_key_value_heads=2, rms_norm_eps=shape.rms_eps, rope_theta=shape.rope_theta,
+                      max_position_embeddings=4096, attn_implementation="eager", tie_word_embeddings=False,
+                      attention_bias=False, mlp_bias=False)
+    model = LlamaForCausalLM(cfg).eval().double()
+    f = lambda bits: torch.from_numpy(O.bf16_bits_to_float(bits, np.float64))
+    sd = {"model.embed_tokens.weight": f(wb["embed"]), "model.norm.weight": f(wb["final_norm"]),
+          "lm_head.weight": f(wb["lm_head"])}
+    names = {"attn_norm": "input_layernorm", "ffn_norm": "post_attention_layernorm",
+             "wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj",
+             "wo": "self_attn.o_proj", "w_gate": "mlp.gate_proj", "w_up": "mlp.up_proj",
+             "w_down": "mlp.down_proj"}
+    for l in range(shape.n_layers):
+        for mine, theirs in names.items():
+            sd[f"model.layers.{l}.{theirs}.weight"] = f(wb[mine][l])
+    missing, unexpected = model.load_state_dict(sd, strict=False)
+    assert not [m for m in missing if "rotary" not in m] and not unexpected
+    with torch.no_grad():
+        out = model(torch.from_numpy(ids.astype(np.int64))[None], output_attentions=True,
+                    output_hidden_states=True, use_cache=True)
+    tol = 2e-6
+    assert np.allclose(res.logits, out.logits[0, -1].numpy(), atol=tol)
+    for l in range(shape.n_layers):
+        assert np.allclose(res.hidden_in[l], out.hidden_states[l][0].numpy(), atol=tol)
+        A = out.attentions[l][0].numpy()                       # [H, query, key]
+        assert A.shape[0] == shape.n_heads
+        assert np.allclose(res.scores[l], A[:, -1, :].mean(axis=0), atol=tol)
+        assert res.k[l].shape == (80, 2, shape.head_dim)
+
+
+def test_grouped_query_pruned_prefill_and_decoding_keep_their_structure():
+    from oracle import lazyllm_decode_oracle as D
+    shape = dataclasses.replace(SMALL, n_kv_heads=1)
+    wb = _weights(shape, seed=19)
+    ids = synth.make_prompt(60, shape.vocab, 8)
+    sched = [(1, 700), (3, 500)]
+    res = O.prefill(shape.as_dict(), wb, ids, sched)
+    assert [len(p) for p in res.kept_pos] == O.keep_counts(60, shape.n_layers, sched)
+    # with one K,V head shared by all query heads the dense step still equals the longer prefill
+    dense = O.prefill(shape.as_dict(), wb, ids, [])
+    gen = D.Generation(shape.as_dict(), wb, [], dense, 60, 62)
+    out = gen.step(5)
+    full = O.prefill(shape.as_dict(), wb, np.concatenate([ids, [5]]), [])
+    assert np.allclose(out.logits, full.logits, atol=1e-10)
+    gen2 = D.Generation(shape.as_dict(), wb, sched, res, 60, 63)
+    for tok in (1, 2, 3):
+        o2 = gen2.step(tok)
+        assert all(abs(s.sum() - 1) < 1e-12 for s in o2.scores)
+    assert gen2.times_computed.max() == 1
