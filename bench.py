@@ -368,8 +368,9 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name,
-                   "shape": "%d layers, d %d, %dx%d heads, ffn %d, vocab %d" % (
-                       shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab),
+                   "shape": "%d layers, d %d, %dx%d heads (%d K,V heads), ffn %d, vocab %d" % (
+                       shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.kv_heads, shape.d_ffn,
+                       shape.vocab),
                    "prompt_tokens": n_tokens, "batch": len(cu) - 1,
                    "keep_schedule_permille_of_survivors": sched,
                    "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True)},

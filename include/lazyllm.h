@@ -50,10 +50,16 @@ typedef enum lazyllm_status {
  * followed by an MLP; Llama 2 conventions: pre-norm RMSNorm, rotary position
  * embedding with half-split pairing, SwiGLU MLP, untied LM head, no biases).
  * Supported: head_dim 64 or 128, d_model == n_heads * head_dim,
- * d_model % 64 == 0, 1 <= n_layers <= LAZYLLM_MAX_LAYERS. */
+ * d_model % 128 == 0, 1 <= n_layers <= LAZYLLM_MAX_LAYERS.
+ * n_kv_heads: grouped-query attention as a model variant -- that many K,V
+ * heads, each read by n_heads / n_kv_heads consecutive query heads; 0 means
+ * n_heads (plain multi-head attention, the paper's models).  It must divide
+ * n_heads and n_kv_heads * head_dim must be a multiple of 128.  Eq. 1 is the
+ * mean over all n_heads attention maps either way. */
 typedef struct lazyllm_config {
   int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_theta;
+  int32_t n_kv_heads;
 } lazyllm_config;
 
 /* Device pointers to bf16 weights.  The per-layer members are HOST arrays of
@@ -62,8 +68,8 @@ typedef struct lazyllm_weights {
   const void* embed;              /* [vocab, d_model] */
   const void* const* attn_norm;   /* [d_model] each */
   const void* const* wq;          /* [d_model, d_model] */
-  const void* const* wk;
-  const void* const* wv;
+  const void* const* wk;          /* [n_kv_heads * head_dim, d_model] */
+  const void* const* wv;          /* [n_kv_heads * head_dim, d_model] */
   const void* const* wo;
   const void* const* ffn_norm;    /* [d_model] */
   const void* const* w_gate;      /* [d_ffn, d_model] */
@@ -111,8 +117,8 @@ typedef struct lazyllm_result {
   float* logits;                        /* fp32 [batch, vocab], last token of each prompt */
   int32_t* kept_pos[LAZYLLM_MAX_LAYERS];/* int32 [n_tokens[l]] original position in its prompt */
   int32_t* cu_kept[LAZYLLM_MAX_LAYERS]; /* int32 [batch+1] row offsets per sequence */
-  void* k[LAZYLLM_MAX_LAYERS];          /* bf16 [n_tokens[l], n_heads, head_dim], rotary applied */
-  void* v[LAZYLLM_MAX_LAYERS];          /* bf16 [n_tokens[l], n_heads, head_dim] */
+  void* k[LAZYLLM_MAX_LAYERS];          /* bf16 [n_tokens[l], n_kv_heads, head_dim], rotary applied */
+  void* v[LAZYLLM_MAX_LAYERS];          /* bf16 [n_tokens[l], n_kv_heads, head_dim] */
   float* scores[LAZYLLM_MAX_LAYERS];    /* fp32 [n_tokens[l]]  Eq. 1, or NULL */
   /* Aux Cache: only for layers that prune (NULL / 0 elsewhere).  Row i is a
    * token dropped on entry to layer l: its layer-l input hidden state and its
@@ -203,9 +209,10 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
  *
  * The generation state lives in ONE caller-owned device buffer and is indexed by original
  * position (capacity = prompt length + the most tokens that will be generated):
- *   per layer   K  bf16 [capacity, d_model]            row p = token at position p
- *               Vt bf16 [d_model, vt_ld]               column p (V transposed, vt_ld = capacity
- *                                                      rounded up to 64)
+ *   per layer   K  bf16 [capacity, kv_dim]             row p = token at position p
+ *               Vt bf16 [kv_dim, vt_ld]                column p (V transposed, vt_ld = capacity
+ *                                                      rounded up to 64; kv_dim = n_kv_heads *
+ *                                                      head_dim, = d_model without shared heads)
  *   per pruning layer and the layers up to the next one (they share one set of tokens)
  *               has_kv  uint8 [capacity]               1 where K,V exist
  *   per pruning layer

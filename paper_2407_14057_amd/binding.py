@@ -26,7 +26,7 @@ EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
 class lazyllm_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("n_kv_heads", C.c_int32)]
 
 
 class lazyllm_weights(C.Structure):
@@ -200,7 +200,12 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
 def make_config(shape: Dict[str, float]) -> lazyllm_config:
     return lazyllm_config(int(shape["n_layers"]), int(shape["d_model"]), int(shape["n_heads"]),
                           int(shape["head_dim"]), int(shape["d_ffn"]), int(shape["vocab"]),
-                          float(shape["rms_eps"]), float(shape["rope_theta"]))
+                          float(shape["rms_eps"]), float(shape["rope_theta"]),
+                          int(shape.get("n_kv_heads", 0) or 0))
+
+
+def _kv_heads(cfg: lazyllm_config) -> int:
+    return cfg.n_kv_heads if cfg.n_kv_heads > 0 else cfg.n_heads
 
 
 def make_schedule(schedule: Sequence[Tuple[int, int]]):
@@ -442,12 +447,14 @@ class PrefillOutput:
         return self._view(self.res.cu_kept[l], self.batch + 1, torch.int32)
 
     def k(self, l):
-        return self._view(self.res.k[l], self.n_tokens[l] * self.cfg.d_model, torch.bfloat16).view(
-            self.n_tokens[l], self.cfg.n_heads, self.cfg.head_dim)
+        hkv, hd = _kv_heads(self.cfg), self.cfg.head_dim
+        return self._view(self.res.k[l], self.n_tokens[l] * hkv * hd, torch.bfloat16).view(
+            self.n_tokens[l], hkv, hd)
 
     def v(self, l):
-        return self._view(self.res.v[l], self.n_tokens[l] * self.cfg.d_model, torch.bfloat16).view(
-            self.n_tokens[l], self.cfg.n_heads, self.cfg.head_dim)
+        hkv, hd = _kv_heads(self.cfg), self.cfg.head_dim
+        return self._view(self.res.v[l], self.n_tokens[l] * hkv * hd, torch.bfloat16).view(
+            self.n_tokens[l], hkv, hd)
 
     def scores(self, l):
         return self._view(self.res.scores[l], self.n_tokens[l], torch.float32)
@@ -604,11 +611,12 @@ class Generation:
         """{'k': [..], 'vt': [..], 'has_kv': [..], 'aux_h': [..], 'has_aux': [..]} torch views by layer."""
         v = lazyllm_generation_get_view(self.handle)
         cap, d, ld = v.capacity, self.cfg.d_model, v.vt_ld
+        kvd = _kv_heads(self.cfg) * self.cfg.head_dim
         out = {"n_tokens": v.n_tokens, "capacity": cap, "vt_ld": ld, "k": [], "vt": [], "has_kv": [],
                "aux_h": [], "has_aux": []}
         for l in range(v.n_layers):
-            out["k"].append(_buf_view(self.state, v.k[l], cap * d, torch.bfloat16).view(cap, d))
-            out["vt"].append(_buf_view(self.state, v.vt[l], d * ld, torch.bfloat16).view(d, ld))
+            out["k"].append(_buf_view(self.state, v.k[l], cap * kvd, torch.bfloat16).view(cap, kvd))
+            out["vt"].append(_buf_view(self.state, v.vt[l], kvd * ld, torch.bfloat16).view(kvd, ld))
             out["has_kv"].append(_buf_view(self.state, v.has_kv[l], cap, torch.uint8))
             a = _buf_view(self.state, v.aux_h[l], cap * d, torch.bfloat16)
             out["aux_h"].append(None if a is None else a.view(cap, d))

@@ -75,12 +75,19 @@ bool config_ok(const lazyllm_config* c) {
   if (c->n_heads < 1 || c->n_heads > 256) return false;
   if ((int64_t)c->n_heads * c->head_dim != c->d_model) return false;
   if (c->d_model % 128 != 0 || c->d_model > 16384) return false;
+  // grouped-query attention: n_kv_heads K,V heads, each shared by n_heads / n_kv_heads query
+  // heads (0 = n_heads); the K,V width must be a multiple of 128 like d_model
+  if (c->n_kv_heads < 0 || c->n_kv_heads > c->n_heads) return false;
+  if (c->n_kv_heads > 0 && (c->n_heads % c->n_kv_heads != 0 || (c->n_kv_heads * c->head_dim) % 128 != 0))
+    return false;
   if (c->d_ffn < 1 || c->vocab < 1) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return false;
   return true;
 }
 
 inline int ffn_padded(int f) { return (f + 127) / 128 * 128; }
+inline int kv_heads(const lazyllm_config* c) { return c->n_kv_heads > 0 ? c->n_kv_heads : c->n_heads; }
+inline int kv_dim(const lazyllm_config* c) { return kv_heads(c) * c->head_dim; }
 
 bool schedule_ok(int n_layers, const lazyllm_keep* sched, int n_sched) {
   if (n_sched < 0 || n_sched > LAZYLLM_MAX_LAYERS) return false;
@@ -157,7 +164,7 @@ void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_s
   w->ssq1 = take((size_t)T * 8);
   w->q = take((size_t)T * d * 2);
   w->o = take((size_t)T * d * 2);
-  w->vt = take(d * vt_ld * 2);
+  w->vt = take((size_t)kv_dim(c) * vt_ld * 2);
   w->vt_col = take((size_t)T * 4);
   w->act = take((size_t)T * fp * 2);
   w->score = take(score_scratch_bytes((int)T, batch, c->n_heads));
@@ -198,8 +205,8 @@ void layout_output(const lazyllm_config* c, const Stages* st, int batch, uint32_
   }
   for (int l = 0; l < c->n_layers; ++l) {
     const size_t n = (size_t)st->total[st->stage_of_layer[l]];
-    o->k[l] = take(n * d * 2);
-    o->v[l] = take(n * d * 2);
+    o->k[l] = take(n * (size_t)kv_dim(c) * 2);
+    o->v[l] = take(n * (size_t)kv_dim(c) * 2);
     o->scores[l] = take(n * 4);
   }
   if (flags & LAZYLLM_KEEP_HIDDEN) {
@@ -222,7 +229,7 @@ struct lazyllm_model {
 
 extern "C" {
 
-int lazyllm_abi_version(void) { return 1; }
+int lazyllm_abi_version(void) { return 2; }
 
 const char* lazyllm_strerror(int status) {
   switch (status) {
@@ -295,8 +302,8 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
   if (m == nullptr) return LAZYLLM_ENOMEM;
   m->cfg = *cfg;
   m->f_pad = ffn_padded(cfg->d_ffn);
-  const size_t d = cfg->d_model, f = cfg->d_ffn, fp = m->f_pad, V = cfg->vocab;
-  const size_t per_layer = align_up(d * 2) * 2 + align_up(3 * d * d * 2) + align_up(d * d * 2) +
+  const size_t d = cfg->d_model, f = cfg->d_ffn, fp = m->f_pad, V = cfg->vocab, kvd = kv_dim(cfg);
+  const size_t per_layer = align_up(d * 2) * 2 + align_up((d + 2 * kvd) * d * 2) + align_up(d * d * 2) +
                            align_up(2 * fp * d * 2) + align_up(d * fp * 2);
   const size_t bytes = align_up(V * d * 2) * 2 + align_up(d * 2) + per_layer * L;
   hipError_t e = hipMalloc((void**)&m->blob, bytes);
@@ -327,13 +334,13 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
     p = take(d * 2);
     chk(hipMemcpyAsync(p, w->ffn_norm[l], d * 2, hipMemcpyDeviceToDevice, st));
     m->ffn_norm.push_back(p);
-    p = take(3 * d * d * 2);                       // fused [q; k; v] rows
+    p = take((d + 2 * kvd) * d * 2);               // fused [q; k; v] rows
     chk(hipMemcpyAsync(p, w->wq[l], d * d * 2, hipMemcpyDeviceToDevice, st));
-    chk(hipMemcpyAsync(p + d * d * 2, w->wk[l], d * d * 2, hipMemcpyDeviceToDevice, st));
-    chk(hipMemcpyAsync(p + 2 * d * d * 2, w->wv[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    chk(hipMemcpyAsync(p + d * d * 2, w->wk[l], kvd * d * 2, hipMemcpyDeviceToDevice, st));
+    chk(hipMemcpyAsync(p + (d + kvd) * d * 2, w->wv[l], kvd * d * 2, hipMemcpyDeviceToDevice, st));
     // RMSNorm gains ride in the weights: x*g . w = x . (g*w); the 1/rms factor is applied by the
     // GEMM epilogue (exact for gains of 1, one more bf16 rounding of the weight otherwise)
-    chk(launch_scale_cols(p, w->attn_norm[l], 3 * d, (int)d, st));
+    chk(launch_scale_cols(p, w->attn_norm[l], d + 2 * kvd, (int)d, st));
     m->wqkv.push_back(p);
     p = take(d * d * 2);
     chk(hipMemcpyAsync(p, w->wo[l], d * d * 2, hipMemcpyDeviceToDevice, st));
@@ -401,6 +408,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   char* W = (char*)workspace;
   char* O = (char*)out_buf;
   const int L = c->n_layers, d = c->d_model, H = c->n_heads, hd = c->head_dim, B = batch;
+  const int kvd = kv_dim(c), kv_group = H / kv_heads(c);
   const int BW = B + 1;
   memset(res, 0, sizeof(*res));
   res->batch = B;
@@ -491,7 +499,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     EpiArgs ra{};
     ra.pos = res->kept_pos[l]; ra.table = rope;
     ra.q = (uint16_t*)(W + ws.q); ra.k = (uint16_t*)res->k[l]; ra.v = (uint16_t*)res->v[l];
-    ra.d_model = d; ra.head_dim = hd;
+    ra.d_model = d; ra.head_dim = hd; ra.kv_dim = kvd;
     // ... and V also transposed into the workspace copy the attention kernel reads
     ra.vt = (uint16_t*)(W + ws.vt); ra.vt_ld = (int)stg.vt_ld[s];
     ra.vt_col = B > 1 ? (const int32_t*)(W + ws.vt_col) : nullptr;
@@ -499,9 +507,9 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     if (stg.first_layer[s] == l)
       LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 0.0,
              launch_vt_stage_setup(W + ws.vt, B > 1 ? (int32_t*)(W + ws.vt_col) : nullptr, cu,
-                                   cu_vt + s * BW, 0, B, (int)stg.vt_ld[s], d, st));
-    LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * 3.0 * dd * dd,
-           launch_gemm(h, m->wqkv[l], nullptr, nullptr, n, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st,
+                                   cu_vt + s * BW, 0, B, (int)stg.vt_ld[s], kvd, st));
+    LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * (dd + 2.0 * kvd) * dd,
+           launch_gemm(h, m->wqkv[l], nullptr, nullptr, n, d + 2 * kvd, d, d, d, 0, EPI_QKV_ROPE, st,
                        &ra));
     // Eq. 1 needs the last query's logits against every key, which the attention kernel has
     // in registers anyway: it leaves them in the score scratch (the gate/up launch below turns
@@ -512,7 +520,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                             stg.max_rows[s], (int)stg.vt_ld[s], H, hd, st,
                             scored ? score_z(W + ws.score) : nullptr,
                             scored ? score_zstat(W + ws.score, (int)stg.vt_ld[s], H) : nullptr,
-                            (int)stg.vt_ld[s]));
+                            (int)stg.vt_ld[s], kv_group));
     EpiArgs eo{};
     eo.ssq_out = ssq_ffn;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
@@ -596,8 +604,8 @@ void layout_generation(const lazyllm_config* c, const Stages* st, int cap, GenLa
     g->aux_h[s] = s > 0 ? take((size_t)cap * d * 2) : 0;
   }
   for (int l = 0; l < c->n_layers; ++l) {
-    g->k[l] = take((size_t)cap * d * 2);
-    g->vt[l] = take(d * (size_t)g->vt_ld * 2);
+    g->k[l] = take((size_t)cap * kv_dim(c) * 2);
+    g->vt[l] = take((size_t)kv_dim(c) * g->vt_ld * 2);
   }
   g->total = off;
 }
@@ -722,8 +730,8 @@ int lazyllm_generation_create(const lazyllm_model* m, const lazyllm_keep* sched,
     const int s = stg.stage_of_layer[l];
     const int n = prefill->n_tokens[l];
     chk(launch_scatter_rows(prefill->k[l], prefill->kept_pos[l], n, S + gl.k[l],
-                            stg.first_layer[s] == l ? (uint8_t*)(S + gl.has_kv[s]) : nullptr, d, st));
-    chk(launch_scatter_vt(prefill->v[l], prefill->kept_pos[l], n, d, S + gl.vt[l], gl.vt_ld, st));
+                            stg.first_layer[s] == l ? (uint8_t*)(S + gl.has_kv[s]) : nullptr, kv_dim(c), st));
+    chk(launch_scatter_vt(prefill->v[l], prefill->kept_pos[l], n, kv_dim(c), S + gl.vt[l], gl.vt_ld, st));
     if (s > 0 && stg.first_layer[s] == l)
       chk(launch_scatter_rows(prefill->aux_h[l], prefill->aux_pos[l], prefill->n_aux[l],
                               S + gl.aux_h[s], (uint8_t*)(S + gl.has_aux[s]), d, st));
@@ -778,6 +786,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
   if (ws_bytes < ws.total) return LAZYLLM_ENOSPC;
 
   const int L = c->n_layers, d = c->d_model, H = c->n_heads, hd = c->head_dim, fp = m->f_pad;
+  const int kvd = kv_dim(c), kv_group = H / kv_heads(c);
   const int cap = g->capacity, new_pos = g->n_tokens, n_tot = g->n_tokens + 1;
   const GenLayout& gl = g->gl;
   char* S = g->state;
@@ -851,18 +860,18 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     ra.pos = rpos; ra.table = rope;
     ra.q = (uint16_t*)(W + ws.q); ra.k = (uint16_t*)(S + gl.k[l]); ra.v = nullptr;
     ra.k_row = rpos;                                   // K,V land at the rows of their positions
-    ra.d_model = d; ra.head_dim = hd;
+    ra.d_model = d; ra.head_dim = hd; ra.kv_dim = kvd;
     ra.vt = (uint16_t*)(S + gl.vt[l]); ra.vt_ld = gl.vt_ld; ra.vt_col = rpos;
     ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
     ra.skinny = 1;
-    LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, M, 2.0 * M * 3.0 * dd * dd,
-           launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, 3 * d, d, d, d, 0, EPI_QKV_ROPE, st, &ra,
+    LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, M, 2.0 * M * (dd + 2.0 * kvd) * dd,
+           launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, d + 2 * kvd, d, d, d, 0, EPI_QKV_ROPE, st, &ra,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
     LZ_RUN(LAZYLLM_STEP_ATTENTION, l, M, 4.0 * (double)M * (double)sel_count[s] * dd,
            launch_decode_attention(W + ws.q, rpos, M, S + gl.k[l], S + gl.vt[l], gl.vt_ld,
                                    s > 0 ? bits_of(s) : nullptr, n_tot, W + ws.o, H, hd, st,
                                    score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld,
-                                   W + ws.att_ws, decode_attention_workspace_bytes(d, H)));
+                                   W + ws.att_ws, decode_attention_workspace_bytes(d, H), kv_group));
     EpiArgs eo{};
     eo.ssq_out = ssq_ffn; eo.skinny = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, M, 2.0 * M * dd * dd,

@@ -30,7 +30,7 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
                   const uint16_t* __restrict__ vt, uint16_t* __restrict__ o,
                   const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
                   int vt_ld, int n_heads, float scale_log2e, float* __restrict__ z,
-                  float2* __restrict__ zstat, int z_ld) {
+                  float2* __restrict__ zstat, int z_ld, int kv_group) {
   constexpr int CHK = HD / 8;                 // 16-byte chunks per K row
   constexpr int KSTEPS = HD / 16;             // k-steps of the first product
   constexpr int HS = HD / 32;                 // 32-row blocks of O^T
@@ -57,6 +57,8 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   const int qb = qblocks - 1 - blockIdx.y;    // longest blocks first
   const int q0 = qb * ATT_BM;
   const int d = n_heads * HD;
+  // grouped-query attention: kv_group query heads read one K,V head; rows of K are kvd wide
+  const int kvd = d / kv_group, kvh = head / kv_group;
   const int hi = lane >> 5, l31 = lane & 31;
 
   // ---- Q fragments (B operand of the first product), straight from global memory
@@ -71,8 +73,8 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
 
   // ---- copy plan
   const int ntiles = min((n + ATT_BN - 1) / ATT_BN, (q0 + ATT_BM) / ATT_BN);
-  const uint16_t* kbase = k + (size_t)row0 * d + head * HD;
-  const uint16_t* vbase = vt + (size_t)head * HD * vt_ld + (cu_vt ? cu_vt[b] : 0);
+  const uint16_t* kbase = k + (size_t)row0 * kvd + kvh * HD;
+  const uint16_t* vbase = vt + (size_t)kvh * HD * vt_ld + (cu_vt ? cu_vt[b] : 0);
   auto issue = [&](int stage, int k0) {
     char* sk = lds + stage * STAGE;
     char* sv = sk + K_TILE;
@@ -83,7 +85,7 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
       const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
       int key = k0 + r;
       key = key < n ? key : n - 1;
-      g2l16(kbase + (size_t)key * d + c * 8, sk + slab * 1024);
+      g2l16(kbase + (size_t)key * kvd + c * 8, sk + slab * 1024);
     }
 #pragma unroll
     for (int qi = 0; qi < V_INSTR; ++qi) {
@@ -316,8 +318,9 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
                             int n_heads, int head_dim, hipStream_t st, float* z, void* zstat,
-                            int z_ld) {
+                            int z_ld, int kv_group) {
   if (max_rows <= 0) return hipSuccess;
+  if (kv_group < 1 || n_heads % kv_group != 0) return hipErrorInvalidValue;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
   // 8-wave workgroups (one per CU, four stages) when they alone fill the chip: they halve the
   // L2 -> LDS traffic per query.  Otherwise 4-wave ones, which spread a short sequence over
@@ -337,7 +340,7 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
     dim3 grid(n_heads, (max_rows + 32 * NW - 1) / (32 * NW), batch), block(64 * NW);             \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
-                       scale_log2e, z, (float2*)zstat, z_ld);                                    \
+                       scale_log2e, z, (float2*)zstat, z_ld, kv_group);                          \
   } while (0)
   if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
   if (head_dim == 128 && nw == 8) LZ_ATT(128, 8, 4);

@@ -120,6 +120,7 @@ struct EpiArgs {
   uint16_t* k;
   uint16_t* v;
   int d_model, head_dim;
+  int kv_dim;                        // width of the k and v parts (K,V heads x head_dim); 0 = d_model
   // optional transposed copy of V for the attention kernel: vt[H*hd][vt_ld], token `row` in column
   // vt_col[row] (row itself when vt_col is null); vt == nullptr: not written
   uint16_t* vt;
@@ -188,7 +189,7 @@ hipError_t launch_vt_stage_setup(void* vt, int32_t* vt_col, const int32_t* cu, c
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
                             int n_heads, int head_dim, hipStream_t st, float* z = nullptr,
-                            void* zstat = nullptr, int z_ld = 0);
+                            void* zstat = nullptr, int z_ld = 0, int kv_group = 1);
 // Eq. 1 from the logits the attention kernel left in `scratch` (z, zstat of launch_attention
 // = score_z(scratch), score_zstat(scratch, z_ld, H); z_ld = vt_ld, sequence b at cu_vt[b]).
 float* score_z(void* scratch);
@@ -236,7 +237,8 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
                                    const void* vt, int vt_ld, const unsigned long long* sel_bits,
                                    int n_keys, void* o, int n_heads, int head_dim, hipStream_t st,
                                    float* z = nullptr, void* zstat = nullptr, int z_ld = 0,
-                                   void* split_ws = nullptr, size_t split_ws_bytes = 0);
+                                   void* split_ws = nullptr, size_t split_ws_bytes = 0,
+                                   int kv_group = 1);
 size_t decode_attention_workspace_bytes(int d_model, int n_heads);
 
 struct PlanArgs {

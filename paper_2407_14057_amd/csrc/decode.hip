@@ -212,7 +212,7 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
                    const unsigned long long* __restrict__ sel_bits, int n_keys,
                    uint16_t* __restrict__ o, int n_heads, float scale_log2e, float* __restrict__ z,
                    float2* __restrict__ zstat, int z_ld, int n_splits, float* __restrict__ po,
-                   float2* __restrict__ pml) {
+                   float2* __restrict__ pml, int kv_group) {
   constexpr int NW = 4, BN = 64;
   constexpr int CHK = HD / 8, KSTEPS = HD / 16, HS = HD / 32;
   constexpr int K_TILE = BN * HD * 2, STAGE = 2 * K_TILE;
@@ -225,6 +225,7 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
   const int head = blockIdx.x;
   const int q0 = blockIdx.y * (32 * NW);
   const int d = n_heads * HD;
+  const int kvd = d / kv_group, kvh = head / kv_group;      // grouped-query attention: shared K,V heads
   const int hi = lane >> 5, l31 = lane & 31;
   const int qrow = q0 + wave * 32 + l31;
   const int qrow_c = qrow < M ? qrow : M - 1;
@@ -248,8 +249,8 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
     for (int s = 0; s < KSTEPS; ++s) qf[s] = *(const bf16x8_t*)(qp + s * 16);
   }
 
-  const uint16_t* kbase = k + head * HD;
-  const uint16_t* vbase = vt + (size_t)head * HD * vt_ld;
+  const uint16_t* kbase = k + kvh * HD;
+  const uint16_t* vbase = vt + (size_t)kvh * HD * vt_ld;
   auto issue = [&](int stage, int k0) {
     char* sk = lds + stage * STAGE;
     char* sv = sk + K_TILE;
@@ -260,7 +261,7 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
       const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
       int key = k0 + r;
       key = key < n_keys ? key : n_keys - 1;
-      g2l16(kbase + (size_t)key * d + c * 8, sk + slab * 1024);
+      g2l16(kbase + (size_t)key * kvd + c * 8, sk + slab * 1024);
     }
 #pragma unroll
     for (int qi = 0; qi < V_INSTR; ++qi) {
@@ -439,8 +440,9 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
                                    const void* vt, int vt_ld, const unsigned long long* sel_bits,
                                    int n_keys, void* o, int n_heads, int head_dim, hipStream_t st,
                                    float* z, void* zstat, int z_ld, void* split_ws,
-                                   size_t split_ws_bytes) {
+                                   size_t split_ws_bytes, int kv_group) {
   if (M <= 0 || n_keys <= 0) return hipErrorInvalidValue;
+  if (kv_group < 1 || n_heads % kv_group != 0) return hipErrorInvalidValue;
   if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
   if (vt_ld < (n_keys + 63) / 64 * 64) return hipErrorInvalidValue;
   if (z != nullptr && (zstat == nullptr || z_ld < (n_keys + 63) / 64 * 64)) return hipErrorInvalidValue;
@@ -475,7 +477,7 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, qpos, M,              \
                        (const uint16_t*)k, (const uint16_t*)vt, vt_ld, sel_bits, n_keys,           \
                        (uint16_t*)o, n_heads, scale_log2e, z, (float2*)zstat, z_ld, n_splits, po,  \
-                       pml);                                                                       \
+                       pml, kv_group);                                                             \
   } while (0)
   if (head_dim == 128) LZ_DATT(128);
   else LZ_DATT(64);

@@ -66,13 +66,17 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
     if (EPI != EPI_QKV_ROPE64 && EPI != EPI_QKV_ROPE128 && !valid) continue;
     if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
       constexpr int hd = (EPI == EPI_QKV_ROPE64) ? 64 : 128, half = hd >> 1;
-      const int d = ra.d_model;
+      // columns [0, d) are q, then kvd of k and kvd of v (kvd = d unless K,V heads are shared by
+      // groups of query heads); rows of q are d wide, rows of k and v kvd
+      const int d = ra.d_model, kvd = ra.kv_dim > 0 ? ra.kv_dim : d;
       const int col0 = n0 + wn * TN * 32;              // first column of this wave
-      const int region = col0 / d;                      // 0 q, 1 k, 2 v (uniform per wave)
+      const int region = col0 < d ? 0 : col0 < d + kvd ? 1 : 2;   // q, k, v (uniform per wave)
+      const int rcol0 = col0 - (region == 0 ? 0 : region == 1 ? d : d + kvd);
+      const int rld = region == 0 ? d : kvd;
       if (region != 2 && !valid) continue;              // (the V branch keeps every lane: lane pairs exchange data)
       const int orow = (region == 1 && ra.k_row != nullptr && valid) ? ra.k_row[row] : row;
-      uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)orow * d +
-                      (col0 - region * d) + feat_l;
+      uint16_t* dst = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (size_t)orow * rld +
+                      rcol0 + feat_l;
       if (region == 2) {
         // V goes to the KV cache row-major and, for the attention kernel's second product,
         // transposed: a register holds one feature of 32 consecutive tokens across lanes, so
@@ -81,7 +85,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
         int vcol = 0;
         if (ra.vt != nullptr && valid) {
           vcol = ra.vt_col != nullptr ? ra.vt_col[row] : row;
-          vtp = ra.vt + (size_t)(col0 - region * d + feat_l) * ra.vt_ld + vcol;
+          vtp = ra.vt + (size_t)(rcol0 + feat_l) * ra.vt_ld + vcol;
         }
         // Neighbouring lanes hold neighbouring tokens: lane pairs swap one value each so that an
         // even lane writes tokens (t, t+1) of one feature and the odd lane (t-1, t) of the next
@@ -665,10 +669,12 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   int old;
   const int32_t* orow = nullptr;                    // output row of tile row r, if not m0 + r
   if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
-    const int region = n0 / ra.d_model;             // the tile lies inside q, k or v
+    const int dq = ra.d_model, kvd = ra.kv_dim > 0 ? ra.kv_dim : dq;
+    const int region = n0 < dq ? 0 : n0 < dq + kvd ? 1 : 2;   // the tile lies inside q, k or v
     if (region == 2 && ra.v == nullptr) return;     // (the transposed copy went out with the epilogue)
-    obase = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) + (n0 - region * ra.d_model);
-    old = ra.d_model;
+    obase = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) +
+            (n0 - (region == 0 ? 0 : region == 1 ? dq : dq + kvd));
+    old = region == 0 ? dq : kvd;
     if (region == 1) orow = ra.k_row;
   } else {
     obase = C + (EPI == EPI_SWIGLU ? n0 / 2 : n0);
@@ -697,7 +703,7 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   // the tile goes out through LDS when whole 16-byte chunks of every row are addressable
   // (not for the SiLU*mul epilogue: its tile is half as wide, its GEMM runs several rounds whose
   // stores already spread out in time, and staging measured 1.6 % slower there)
-  ea.stage_out = (epi == EPI_QKV_ROPE) ? (ra.d_model % BN == 0 && ra.d_model % 8 == 0)
+  ea.stage_out = (epi == EPI_QKV_ROPE) ? (ra.d_model % BN == 0 && (ra.kv_dim > 0 ? ra.kv_dim : ra.d_model) % BN == 0)
                  : (epi != EPI_SWIGLU && ldc % 8 == 0 && ((uintptr_t)C & 15) == 0);
   const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
   dim3 grid(tiles_m * tiles_n + side), block(512);
@@ -1279,8 +1285,9 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
   EpiArgs ra{};
   if (rope != nullptr) ra = *rope;
   if (epilogue == EPI_QKV_ROPE) {
+    const int kvd = rope != nullptr ? (rope->kv_dim > 0 ? rope->kv_dim : rope->d_model) : 0;
     if (rope == nullptr || (rope->head_dim != 64 && rope->head_dim != 128) ||
-        N != 3 * rope->d_model || rope->d_model % 128 != 0)
+        N != rope->d_model + 2 * kvd || rope->d_model % 128 != 0 || kvd % 128 != 0)
       return hipErrorInvalidValue;
   }
   if (group_m == 0) group_m = 4;

@@ -48,6 +48,9 @@ class ModelShape:
 TINY = ModelShape(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
 LLAMA7B = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=11008, vocab=32000)
 # the paper's second model: the same decoder stack with a 51200-entry vocabulary and eps 1e-6
+# a grouped-query variant at 8B scale (Llama-3-8B-like: 8 K,V heads for 32 query heads, wider MLP and vocabulary)
+GQA8B = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=14336, vocab=128256,
+                   rope_theta=500000.0, n_kv_heads=8)
 XGEN7B = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=11008, vocab=51200, rms_eps=1e-6)
 
 
@@ -78,6 +81,7 @@ WORKLOADS: Dict[str, Workload] = {
     "7b_3376_needles": Workload("7b_3376_needles", LLAMA7B, 1002, 2004, (3376,),
                                 ((4, 500), (12, 500), (20, 500)), needle_seed=3004, n_needles=64),
     "xgen7b_3376": Workload("xgen7b_3376", XGEN7B, 1003, 2006, (3376,), ((8, 700), (16, 500), (24, 300))),
+    "gqa8b_3376": Workload("gqa8b_3376", GQA8B, 1004, 2007, (3376,), ((8, 700), (16, 500), (24, 300))),
     "7b_batch8": Workload("7b_batch8", LLAMA7B, 1002, 2005, _batch_lengths(4005, 8, 1024, 8192),
                           ((8, 700), (16, 500), (24, 300))),
 }

@@ -68,7 +68,7 @@ def _check_caches(shape, view, g16, n_tot, prune_layers):
         idx = np.nonzero(has)[0]
         k = _f(view["k"][l])[idx]
         v = _f(view["vt"][l]).T[idx]
-        rk, rv = g16.k[l][idx].reshape(len(idx), d), g16.v[l][idx].reshape(len(idx), d)
+        rk, rv = g16.k[l][idx].reshape(len(idx), -1), g16.v[l][idx].reshape(len(idx), -1)
         worst = max(worst, np.abs(k - rk).max() / max(np.abs(rk).max(), 1e-9),
                     np.abs(v - rv).max() / max(np.abs(rv).max(), 1e-9))
         # rows without K,V were never written
@@ -180,6 +180,17 @@ def test_head_dim_128(hd128):
     shape, wb, model = hd128
     ids = synth.make_prompt(150, shape.vocab, 73)
     run_case(shape, wb, model, ids, [(1, 800), (3, 300)], [9, 8, 7, 6], label="hd128")
+
+
+@pytest.mark.parametrize("base,kv", [(synth.TINY, 2), (HD128, 1)])
+def test_shared_kv_heads(base, kv):
+    """Grouped-query variant: K,V heads shared by groups of query heads (caches half as wide)."""
+    shape = dataclasses.replace(base, n_kv_heads=kv)
+    wb, model = _model(shape, 1041 + kv, jitter=0.2)
+    ids = synth.make_prompt(210, shape.vocab, 77)
+    rep = run_case(shape, wb, model, ids, [(1, 700), (3, 400)], [3, 1000, 17, 4], label="gqa %d" % kv)
+    assert sum(sum(r) for r in rep["revived"]) > 0
+    model.close()
 
 
 def test_dense_schedule_never_revives(tiny):

@@ -31,6 +31,10 @@ def _f64(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
+def _greedy(logits):
+    return torch.argmax(logits).to(torch.int32).reshape(1)
+
+
 def _run(model, wl, flags=B.LAZYLLM_KEEP_HIDDEN):
     inp = synth.make_workload_inputs(wl)
     ids = torch.from_numpy(inp["token_ids"]).to(DEV)
@@ -210,11 +214,41 @@ def test_second_model_shape_xgen7b():
     model.close()
 
 
+def test_grouped_query_shape_8b():
+    """Model variant with 8 K,V heads for 32 query heads (and a 14336-wide MLP, 128256-entry vocabulary)."""
+    wl = synth.WORKLOADS["gqa8b_3376"]
+    shape = wl.shape
+    w = synth.make_weights(shape, wl.weight_seed, DEV)
+    model = B.Model(shape.as_dict(), w, DEV)
+    inp, out = _run(model, wl)
+    assert sorted(set(out.n_tokens), reverse=True) == [3376, 2364, 1182, 355]
+    assert out.k(31).shape == (355, 8, 128)
+    _check_structure(wl, inp, out)
+    for l in (0, 15, 31):
+        _check_layer(w, out, l, wl.schedule, tag="gqa8b", shape=shape)
+    _check_logits(w, out, shape=shape)
+    # one decoding step on top: structure only (selection recomputed exactly from the scores)
+    sched = list(wl.schedule)
+    gen = B.Generation(model, sched, out, 3376 + 2)
+    so = gen.step(_greedy(out.logits[0]))
+    torch.cuda.synchronize()
+    assert so.status == 0
+    counts = O.keep_counts(3377, shape.n_layers, sched)
+    for l in range(shape.n_layers):
+        assert so.n_selected[l] == counts[l]
+        s = so.scores(l).double().cpu().numpy()
+        assert abs(s.sum() - 1.0) < 2e-4
+    for p, _ in sched:
+        cand = np.arange(3377)[:-1] if so.selected(p - 1) is None else np.nonzero(so.selected(p - 1).cpu().numpy())[0][:-1]
+        s32 = so.scores(p - 1).cpu().numpy()[cand]
+        order = np.argsort(-s32, kind="stable")[: counts[p] - 1]
+        want = np.sort(np.concatenate([cand[order], [3376]]))
+        assert np.array_equal(np.nonzero(so.selected(p).cpu().numpy())[0], want)
+    gen.close()
+    model.close()
+
+
 # ---------------------------------------------------------------------------- decoding steps
-
-def _greedy(logits):
-    return torch.argmax(logits).to(torch.int32).reshape(1)
-
 
 def test_7b_dense_decoding_step_equals_prefill_of_the_extended_prompt(model7b):
     """Sec. 3.1: with a complete KV cache a decoding step gives what prefilling the longer prompt

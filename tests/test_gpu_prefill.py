@@ -149,6 +149,22 @@ def test_tiny_shapes_and_schedules(tiny_gains, n, sched):
     check_against_checker(shape, wb, ids, sched, out, verbose="n=%d %s" % (n, sched))
 
 
+@pytest.mark.parametrize("heads,hd,kv", [(4, 64, 2), (2, 128, 1), (8, 64, 2)])
+@pytest.mark.parametrize("n,sched", [(300, [(1, 800), (3, 300)]), (65, [])])
+def test_shared_kv_heads(heads, hd, kv, n, sched):
+    """Grouped-query variant: K,V heads shared by groups of query heads; Eq. 1 over all query heads."""
+    import dataclasses
+    shape = dataclasses.replace(synth.TINY, n_heads=heads, head_dim=hd, d_model=heads * hd, n_kv_heads=kv)
+    w = synth.make_weights(shape, 1100 + heads + kv, "cpu", gain_jitter=0.2)
+    model = B.Model(shape.as_dict(), _to_dev(w), DEV)
+    ids = synth.make_prompt(n, shape.vocab, 900 + n)
+    out = _run(model, ids, sched)
+    assert out.status == 0 and out.k(0).shape == (n, kv, hd)
+    check_against_checker(shape, synth.weights_to_host_bits(w), ids, sched, out,
+                          verbose="gqa H=%d hd=%d kv=%d n=%d" % (heads, hd, kv, n))
+    model.close()
+
+
 def test_keep_everything_equals_dense_bit_for_bit(tiny):
     shape, wb, model = tiny
     ids = synth.make_prompt(400, shape.vocab, 41)

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(B._SIGNATURES), "binding and header disagree"
-    assert lib.lazyllm_abi_version() == 1
+    assert lib.lazyllm_abi_version() == 2
     assert lib.lazyllm_strerror(-1) == b"invalid argument"
     assert lib.lazyllm_strerror(-2) == b"workspace or output buffer too small"
 
@@ -82,6 +82,15 @@ def test_sizes_are_positive_and_monotone():
     assert B.lazyllm_workspace_bytes(cfg, 0, 1, 1) == 0
     assert B.lazyllm_workspace_bytes(cfg, 10, 1, 11) == 0
     assert B.lazyllm_output_bytes(cfg, [0], []) == 0
+    # shared K,V heads: the count must divide the heads and keep the K,V width a multiple of 128
+    gqa = dict(synth.TINY.as_dict())
+    gqa["n_kv_heads"] = 2
+    cfg2 = B.make_config(gqa)
+    assert B.lazyllm_workspace_bytes(cfg2, 512, 1, 512) > 0
+    assert 0 < B.lazyllm_output_bytes(cfg2, [512], []) < o_dense          # K,V are half as wide
+    for bad_kv in (3, 1, 5, -1):                   # 3 does not divide 4; 1 x 64 is not a multiple of 128
+        gqa["n_kv_heads"] = bad_kv
+        assert B.lazyllm_workspace_bytes(B.make_config(gqa), 512, 1, 512) == 0, bad_kv
 
 
 def test_null_arguments_return_einval_without_touching_the_gpu():
