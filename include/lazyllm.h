@@ -311,7 +311,12 @@ int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* 
  * Requires N % 128 == 0, K % 64 == 0, 16-byte aligned rows.
  * workspace: optional device scratch of lazyllm_op_gemm_workspace_bytes() (256-byte
  * aligned) that lets epilogues 0 and 1 use the stream-K schedule for shapes whose tile
- * count does not divide over the CUs; NULL = never. */
+ * count does not divide over the CUs; NULL = never.
+ * Bits 8..15 of `epilogue` force a tile configuration (measurement hook; 0 = the
+ * library chooses): 2 = 128x128, 4 = 128x256, 5 = 256x256 ping-pong, 7 = 192x256
+ * ping-pong, 6 = 128x128 stream-K (needs the workspace), 8 = the weight-streaming
+ * kernel of the decoding steps (M <= 32, needs the workspace).  EINVAL where a
+ * configuration does not fit the shape. */
 size_t lazyllm_op_gemm_workspace_bytes(void);
 int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,
                     int32_t K, int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue,
