@@ -174,9 +174,28 @@ def decode_bench(args, wl, shape, model, ids, sched, n_tokens, torch, B) -> int:
             rows.append({"step": t + 1, "ms": round(ms, 3), "token_layers_run": int(sum(so.n_ran)),
                          "most_rows_in_a_layer": max(so.n_ran)})
             assert so.status == 0
+        prof = None
+        if name == "dense":
+            # one more unpruned step with per-launch events: where a step's time goes, and the rate at
+            # which its largest launch (the gate/up projection: 2 * d_ffn * d_model bf16 weights) streams
+            B.lazyllm_profile_begin()
+            so = gen.step(tok)
+            recs = B.lazyllm_profile_end(1 << 16)
+            by = {}
+            for r in recs:
+                a = by.setdefault(r["step"], [0.0, 0])
+                a[0] += r["ms"]; a[1] += 1
+            gu_ms, gu_n = by["gemm_gate_up"]
+            gu_bytes = 2.0 * 2.0 * shape.d_ffn * shape.d_model
+            achieved = gu_bytes / (gu_ms / gu_n * 1e-3) / 1e9
+            prof = {"ms_by_step": {k: round(v[0], 4) for k, v in sorted(by.items(), key=lambda kv: -kv[1][0])},
+                    "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<EPI_SWIGLU> (gate/up projection, one token row)",
+                                 "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                 "frac": round(achieved / PEAK_HBM_GBS, 4), "avg_launch_ms": round(gu_ms / gu_n, 5),
+                                 "algorithmic_bytes_per_launch": gu_bytes, "traffic": None}}
         view = gen.view()
         computed = float(sum(float(view["has_kv"][l][:n_tokens].float().mean()) for l in range(L)) / L)
-        runs[name] = {"prefill_ms": round(prefill_ms, 3), "steps": rows,
+        runs[name] = {"prefill_ms": round(prefill_ms, 3), "steps": rows, "profiled_step": prof,
                       "decode_ms_total": round(sum(r["ms"] for r in rows), 3),
                       "generation_ms": round(prefill_ms + sum(r["ms"] for r in rows), 3),
                       "prompt_token_layers_computed": round(computed, 4)}
