@@ -260,12 +260,20 @@ def main() -> int:
     n_cpu_layers = min(4, shape.n_layers)          # the CPU checker's bounded sample: these layers
     cpu_layer_bits = [synth.layer_to_host_bits(weights, l) for l in range(n_cpu_layers)]
     embed_bits = weights["embed"].cpu().view(torch.int16).numpy().view(np.uint16)
+    # checksum of the inputs as the library gets them (bf16 bit patterns summed per tensor as integers,
+    # tensors weighted by their order), so that two reports can be told to be about the same bytes
+    wsum, idx = 0, 0
+    for name in sorted(weights):
+        for t in (weights[name] if isinstance(weights[name], list) else [weights[name]]):
+            idx += 1
+            wsum = (wsum + idx * int(t.view(torch.int16).to(torch.int64).sum().item())) % (1 << 61)
     model = B.Model(shape.as_dict(), weights, dev)
     del weights
     torch.cuda.empty_cache()
 
     inp = synth.make_workload_inputs(wl)
     ids = torch.from_numpy(inp["token_ids"]).to(dev)
+    ids_sum = int(np.dot(inp["token_ids"].astype(np.int64), np.arange(1, inp["token_ids"].shape[0] + 1)) % (1 << 61))
     scale = None if inp["embed_scale"] is None else torch.from_numpy(inp["embed_scale"]).to(dev)
     cu = [int(x) for x in inp["cu_seqlens"]]
     sched = list(wl.schedule)
@@ -386,6 +394,8 @@ def main() -> int:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
+        "inputs": {"weight_seed": wl.weight_seed, "prompt_seed": wl.prompt_seed,
+                   "weights_checksum": wsum, "token_ids_checksum": ids_sum},
         "config": {"workload": wl.name,
                    "shape": "%d layers, d %d, %dx%d heads (%d K,V heads), ffn %d, vocab %d" % (
                        shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.kv_heads, shape.d_ffn,
