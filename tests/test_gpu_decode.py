@@ -250,3 +250,39 @@ def test_steps_are_bit_identical_across_runs(tiny_wide):
         logits.append(got)
         gen.close()
     assert all(torch.equal(a, b) for a, b in zip(*logits))
+
+
+def test_long_sequence_selection_beyond_lds(tiny):
+    """More tokens than the selection kernel keeps in LDS (15360): the step's selection must still
+    be exactly the top-k of the GPU's own fp32 scores among the tokens selected a layer below, and
+    the rows that ran exactly the selected tokens without K,V."""
+    shape, wb, model = tiny
+    n = 15500
+    ids = synth.make_prompt(n, shape.vocab, 78)
+    sched = [(2, 500), (3, 300)]
+    out = model.prefill(torch.from_numpy(ids.astype(np.int32)).to(DEV), sched)
+    gen = B.Generation(model, sched, out, n + 3)
+    torch.cuda.synchronize()
+    L = shape.n_layers
+    for t, tok in enumerate((5, 6)):
+        n_tot = n + t + 1
+        had = [gen.view()["has_kv"][l].clone().cpu().numpy().astype(bool) for l in range(L)]
+        so = gen.step(torch.tensor([tok], dtype=torch.int32, device=DEV))
+        torch.cuda.synchronize()
+        assert so.status == 0
+        counts = O.keep_counts(n_tot, L, sched)
+        prev = np.arange(n_tot)
+        for l in range(L):
+            m = so.selected(l)
+            sel = np.arange(n_tot) if m is None else np.nonzero(m.cpu().numpy())[0]
+            assert len(sel) == counts[l]
+            if l in (2, 3):
+                cand = prev[:-1]
+                s32 = so.scores(l - 1).cpu().numpy()[cand]
+                order = np.argsort(-s32, kind="stable")[: counts[l] - 1]
+                assert np.array_equal(sel, np.sort(np.concatenate([cand[order], [n_tot - 1]])))
+            assert np.array_equal(so.ran_pos(l).cpu().numpy(), sel[~had[l][sel]])
+            s = so.scores(l).double().cpu().numpy()
+            assert abs(s.sum() - 1.0) < 2e-4
+            prev = sel
+    gen.close()
