@@ -819,6 +819,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
   int cur = 0, M = 1;
 
   LZ_HIP(launch_gemm_counters_clear(W + ws.gemm_ws, st));
+  LZ_HIP(launch_decode_attention_counters_clear(W + ws.att_ws, decode_attention_workspace_bytes(d, H), st));
   LZ_RUN(LAZYLLM_STEP_EMBED, -1, 1, 2.0 * rowb,
          launch_gen_embed(m->embed, token_id, c->vocab, d, new_pos, hbuf[0], ssq_attn, run_pos_of(0),
                           live_row, (uint8_t*)(S + gl.has_kv[0]), res->status, st));

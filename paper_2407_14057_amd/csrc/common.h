@@ -240,6 +240,8 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
                                    void* split_ws = nullptr, size_t split_ws_bytes = 0,
                                    int kv_group = 1);
 size_t decode_attention_workspace_bytes(int d_model, int n_heads);
+// the ticket counters at the end of that workspace must be zero before the first attention launch
+hipError_t launch_decode_attention_counters_clear(void* split_ws, size_t split_ws_bytes, hipStream_t st);
 
 struct PlanArgs {
   int32_t n_stages;                     // pruning stages after stage 0

@@ -407,6 +407,233 @@ decode_attn_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ q
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Attention of a step in which only the new token runs the layer (no revived rows): one query
+// per head against the selected keys.  There is no contraction to speak of, the kernel is a
+// stream of the K,V cache, so it uses no MFMA and no LDS staging.  A wave takes 64 keys at a
+// time (one word of the selection mask): 16-byte loads, HD/8 lanes per key row of K and 8 lanes
+// per dimension row of V^T, all of a chunk's loads in flight before the first use; rows of K
+// whose key takes no part are not read.  The G query heads that share a K,V head are served by
+// the same loads.  Scores move from "lanes of a key" to "lane = key" through a wave-private LDS
+// row, the probabilities move back the same way.  The 4 waves of a workgroup interleave the
+// chunks of the workgroup's key range and are merged through LDS; key ranges (blockIdx.y, at
+// most 16) are merged by the workgroup that finishes last.  `counters` (one per K,V head) must
+// be zero on entry and are zero again on exit.
+// ------------------------------------------------------------------------------------------
+template <int HD, int G>
+__global__ void __launch_bounds__(256)
+decode_attn1_kernel(const uint16_t* __restrict__ q, const int32_t* __restrict__ qpos,
+                    const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt, int vt_ld,
+                    const unsigned long long* __restrict__ sel_bits, int n_keys,
+                    uint16_t* __restrict__ o, int n_heads, float scale_log2e, float* __restrict__ z,
+                    float2* __restrict__ zstat, int z_ld, int n_splits, float* __restrict__ po,
+                    float2* __restrict__ pml, unsigned* __restrict__ counters) {
+  constexpr int CHK = HD / 8;        // lanes per key row of K (16 bytes each)
+  constexpr int KPI = 64 / CHK;      // keys per K load instruction
+  constexpr int NKI = CHK;           // K load instructions per 64 keys
+  constexpr int NVI = HD / 8;        // V^T load instructions per 64 keys (8 dimension rows each)
+  __shared__ float sc[4][G][64];
+  __shared__ float mo[4][G][HD + 2];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kvh = blockIdx.x, sp = blockIdx.y;
+  const int d = n_heads * HD, kvd = d / G;
+  const int my_pos = qpos[0];
+  const int n_vis = min(n_keys, my_pos + 1);                 // keys 0 .. n_vis-1 can be seen at all
+  const int chunks = (n_vis + 63) / 64;
+  const int per_split = (chunks + n_splits - 1) / n_splits;
+  const int c_lo = sp * per_split, c_hi = min(c_lo + per_split, chunks);
+  const int kl = lane % CHK, kg = lane / CHK;
+
+  float qf[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    unpack8(*(const uint4*)(q + (size_t)(kvh * G + g) * HD + kl * 8), qf[g]);
+  float acc[G][NVI], m_run[G], l_run[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m_run[g] = -INFINITY;
+    l_run[g] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NVI; ++i) acc[g][i] = 0.f;
+  }
+  const uint16_t* kbase = k + (size_t)kvh * HD + kl * 8;
+  const uint16_t* vbase = vt + ((size_t)kvh * HD + (lane >> 3)) * vt_ld + (lane & 7) * 8;
+
+  for (int c = c_lo + wave; c < c_hi; c += 4) {
+    const int k0 = c * 64;
+    unsigned long long word = sel_bits != nullptr ? sel_bits[c] : ~0ull;
+    if (k0 + 64 > n_vis) word &= (1ull << (n_vis - k0)) - 1ull;
+    uint4 kr[NKI], vr[NVI];
+#pragma unroll
+    for (int i = 0; i < NKI; ++i) {
+      const int j = i * KPI + kg;
+      kr[i] = make_uint4(0u, 0u, 0u, 0u);
+      if ((word >> j) & 1ull) kr[i] = *(const uint4*)(kbase + (size_t)(k0 + j) * kvd);
+    }
+#pragma unroll
+    for (int i = 0; i < NVI; ++i) vr[i] = *(const uint4*)(vbase + (size_t)i * 8 * vt_ld + k0);
+    // scores: each lane's 8 dimensions, then a sum over the CHK lanes of a key
+#pragma unroll
+    for (int i = 0; i < NKI; ++i) {
+      float kf[8];
+      unpack8(kr[i], kf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf(kf[e], qf[g][e], s);
+#pragma unroll
+        for (int off = 1; off < CHK; off <<= 1) s += __shfl_xor(s, off, 64);
+        if (kl == 0) sc[wave][g][i * KPI + kg] = s;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const bool vis = ((word >> lane) & 1ull) != 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float s = vis ? sc[wave][g][lane] * scale_log2e : -INFINITY;
+      if (z != nullptr) z[(size_t)(kvh * G + g) * z_ld + k0 + lane] = s;
+      const float m_new = fmaxf(m_run[g], wave_max(s));
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_use);
+      const float p = __builtin_amdgcn_exp2f(s - m_use);
+      m_run[g] = m_new;
+      l_run[g] = l_run[g] * alpha + p;
+#pragma unroll
+      for (int i = 0; i < NVI; ++i) acc[g][i] *= alpha;
+      sc[wave][g][lane] = p;
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float4 p0 = *(const float4*)&sc[wave][g][(lane & 7) * 8];
+      const float4 p1 = *(const float4*)&sc[wave][g][(lane & 7) * 8 + 4];
+      const float pp[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+      for (int i = 0; i < NVI; ++i) {
+        float vf[8];
+        unpack8(vr[i], vf);
+        float a = acc[g][i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a = fmaf(vf[e], pp[e], a);
+        acc[g][i] = a;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();                         // the next chunk overwrites sc
+  }
+
+  // per wave: finish the sums over lanes and leave (output, max, sum) in LDS
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const float l = wave_sum(l_run[g]);
+#pragma unroll
+    for (int i = 0; i < NVI; ++i) {
+      float a = acc[g][i];
+      a += __shfl_xor(a, 1, 64);
+      a += __shfl_xor(a, 2, 64);
+      a += __shfl_xor(a, 4, 64);
+      if ((lane & 7) == 0) mo[wave][g][i * 8 + (lane >> 3)] = a;
+    }
+    if (lane == 0) {
+      mo[wave][g][HD] = m_run[g];
+      mo[wave][g][HD + 1] = l;
+    }
+  }
+  __syncthreads();
+  // the workgroup's 4 waves, merged: thread -> (head g, dimension)
+  constexpr int NPASS = (G * HD + 255) / 256;
+  float ov[NPASS], lv[NPASS], mv[NPASS];
+#pragma unroll
+  for (int ps = 0; ps < NPASS; ++ps) {
+    const int idx = ps * 256 + threadIdx.x;
+    const int g = idx < G * HD ? idx / HD : 0, dim = idx % HD;
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) m = fmaxf(m, mo[w][g][HD]);
+    float a = 0.f, l = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = mo[w][g][HD];
+      const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - m);
+      a += f * mo[w][g][dim];
+      l += f * mo[w][g][HD + 1];
+    }
+    ov[ps] = a; lv[ps] = l; mv[ps] = m;
+  }
+  if (n_splits > 1) {
+    // Key ranges over workgroups: every workgroup leaves (output, max, sum) in the workspace and
+    // draws a ticket from its K,V head's counter; the one that draws the last ticket merges all
+    // ranges in range order and resets the counter.  Partial results are written with
+    // agent-scope atomic stores and read with agent-scope atomic loads (both bypass the
+    // non-coherent caches), so that no release fence -- a write-back of the whole L2 -- is needed;
+    // the stores have completed (vmcnt) before the ticket is drawn.
+    __shared__ unsigned last_flag;
+    float* pmlf = (float*)pml;
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) {
+      const int idx = ps * 256 + threadIdx.x;
+      if (idx < G * HD) {
+        const int head = kvh * G + idx / HD, dim = idx % HD;
+        __hip_atomic_store(po + (size_t)sp * d + head * HD + dim, ov[ps], __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        if (dim == 0) {
+          __hip_atomic_store(pmlf + 2 * ((size_t)sp * n_heads + head), mv[ps], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(pmlf + 2 * ((size_t)sp * n_heads + head) + 1, lv[ps], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+      last_flag = __hip_atomic_fetch_add(counters + kvh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                          (unsigned)(n_splits - 1) ? 1u : 0u;
+    __syncthreads();
+    if (last_flag == 0) return;
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) {
+      const int idx = ps * 256 + threadIdx.x;
+      const int head = kvh * G + (idx < G * HD ? idx / HD : 0), dim = idx % HD;
+      float ms[16], ls[16], os[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const bool on = u < n_splits;
+        ms[u] = on ? __hip_atomic_load(pmlf + 2 * ((size_t)u * n_heads + head), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
+        ls[u] = on ? __hip_atomic_load(pmlf + 2 * ((size_t)u * n_heads + head) + 1, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+        os[u] = on ? __hip_atomic_load(po + (size_t)u * d + head * HD + dim, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+      }
+      float m = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) m = fmaxf(m, ms[u]);
+      float a = 0.f, l = 0.f;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const float f = ms[u] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms[u] - m);
+        a += f * os[u];
+        l += f * ls[u];
+      }
+      ov[ps] = a; lv[ps] = l; mv[ps] = m;
+    }
+    if (threadIdx.x == 0) counters[kvh] = 0;                 // ready for the next launch
+  }
+#pragma unroll
+  for (int ps = 0; ps < NPASS; ++ps) {
+    const int idx = ps * 256 + threadIdx.x;
+    if (idx < G * HD) {
+      const int head = kvh * G + idx / HD, dim = idx % HD;
+      const float inv = 1.0f / lv[ps];
+      o[head * HD + dim] = to_bf16(ov[ps] * inv);
+      if (dim == 0 && zstat != nullptr) zstat[head] = make_float2(mv[ps], inv);
+    }
+  }
+}
+
 // Merges the key splits of decode_attn_kernel: per (query, head) the splits' (max m_s, sum l_s,
 // unnormalised output o_s) combine as o = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s with
 // m = max_s m_s, splits added in order.  One thread per output dimension.
@@ -431,9 +658,17 @@ decode_attn_merge_kernel(const float* __restrict__ po, const float2* __restrict_
   if (zstat != nullptr && row == M - 1 && dim == 0) zstat[head] = make_float2(m, inv);
 }
 
+constexpr size_t DATT_COUNTER_BYTES = 4096;       // one ticket counter per K,V head
+
 size_t decode_attention_workspace_bytes(int d_model, int n_heads) {
-  // 16 splits of up to 128 queries: fp32 outputs and (max, sum) pairs
-  return (size_t)16 * 128 * ((size_t)d_model * 4 + (size_t)n_heads * 8);
+  // 16 splits of up to 128 queries: fp32 outputs and (max, sum) pairs; then the one-query
+  // kernel's ticket counters
+  return (size_t)16 * 128 * ((size_t)d_model * 4 + (size_t)n_heads * 8) + DATT_COUNTER_BYTES;
+}
+
+hipError_t launch_decode_attention_counters_clear(void* split_ws, size_t split_ws_bytes, hipStream_t st) {
+  if (split_ws == nullptr || split_ws_bytes < DATT_COUNTER_BYTES) return hipErrorInvalidValue;
+  return launch_fill_zero((char*)split_ws + split_ws_bytes - DATT_COUNTER_BYTES, DATT_COUNTER_BYTES, st);
 }
 
 hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, const void* k,
@@ -460,8 +695,42 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
     while (n_splits > 1 && (size_t)n_splits * per_split > split_ws_bytes) --n_splits;
     if (n_splits < 1) n_splits = 1;
   }
+  // only the new token runs the layer: the streaming kernel, about four 64-key chunks per workgroup
+  unsigned* counters = nullptr;
+  if (split_ws != nullptr) {
+    if (split_ws_bytes < DATT_COUNTER_BYTES || (size_t)(n_heads / kv_group) * 4 > DATT_COUNTER_BYTES)
+      return hipErrorInvalidValue;
+    split_ws_bytes -= DATT_COUNTER_BYTES;
+    counters = (unsigned*)((char*)split_ws + split_ws_bytes);
+  }
+  const bool one_query = M == 1 && split_ws != nullptr && (kv_group == 1 || kv_group == 2 || kv_group == 4);
+  if (one_query) {
+    const int chunks = (n_keys + 63) / 64;
+    n_splits = (chunks + 3) / 4;
+    if (n_splits > 16) n_splits = 16;
+    const size_t per_split = (size_t)d_model * 4 + (size_t)n_heads * 8;
+    while (n_splits > 1 && (size_t)n_splits * per_split > split_ws_bytes) --n_splits;
+  }
   float* po = (float*)split_ws;
   float2* pml = (float2*)((char*)split_ws + (size_t)n_splits * M * d_model * 4);
+  if (one_query) {
+    dim3 grid1(n_heads / kv_group, n_splits);
+#define LZ_DATT1(HD, G)                                                                            \
+  hipLaunchKernelGGL((decode_attn1_kernel<HD, G>), grid1, dim3(256), 0, st, (const uint16_t*)q, qpos, \
+                     (const uint16_t*)k, (const uint16_t*)vt, vt_ld, sel_bits, n_keys, (uint16_t*)o, \
+                     n_heads, scale_log2e, z, (float2*)zstat, z_ld, n_splits, po, pml, counters)
+    if (head_dim == 128) {
+      if (kv_group == 1) LZ_DATT1(128, 1);
+      else if (kv_group == 2) LZ_DATT1(128, 2);
+      else LZ_DATT1(128, 4);
+    } else {
+      if (kv_group == 1) LZ_DATT1(64, 1);
+      else if (kv_group == 2) LZ_DATT1(64, 2);
+      else LZ_DATT1(64, 4);
+    }
+#undef LZ_DATT1
+    return hipGetLastError();
+  }
   dim3 grid(n_heads, qblocks, n_splits), block(256);
 #define LZ_DATT(HD)                                                                                \
   do {                                                                                             \
