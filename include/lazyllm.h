@@ -338,6 +338,31 @@ int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R
                             uint64_t* ssq_clear, void* workspace, size_t ws_bytes,
                             void* hip_stream);
 
+/* ---- 8-bit floating point variant of the projections' GEMM --------------------------------
+ * An extension for the gfx950 8-bit matrix instructions; the paper itself computes in 16-bit
+ * floating point (Sec. 5, implementation details).  Operands are OFP8 E4M3 codes (OCP 8-bit
+ * Floating Point Specification: bias 7, no infinities, S.1111.111 = NaN, largest value 448) with
+ * one fp32 scale per row, both K-contiguous.
+ *
+ * lazyllm_op_quantize_fp8: x [rows, K] bf16 (device, row stride ldx elements, 16-byte aligned)
+ *   -> codes [rows, K] uint8 (device, row stride ldq bytes, 8-byte aligned) and scale [rows] fp32
+ *   (device): scale = max|row| / 448 in fp32 (1 for an all-zero row), code = E4M3(x / scale) with
+ *   the division in fp32, round to nearest, ties to even, saturating.  K % 8 == 0, K <= 16384,
+ *   ldx % 8 == 0, ldq % 8 == 0; inputs must be finite.  One pass over x.
+ *
+ * lazyllm_op_gemm_fp8: C[m, n] = a_scale[m] * w_scale[n] * sum_k a[m, k] * w[n, k], accumulated in
+ *   fp32, then the epilogue (0 store, 1 + R, 2 SiLU(gate)*up over interleaved columns, as in
+ *   lazyllm_op_gemm), written as bf16.  a_codes [M, K] and w_codes [N, K] are E4M3 codes (device,
+ *   16-byte aligned, row strides lda, ldw bytes, multiples of 16); w_scale 16-byte aligned.
+ *   N % 256 == 0, K % 128 == 0, M * lda and N * ldw below 2^32.  C, R as in lazyllm_op_gemm.
+ * Both return LAZYLLM_EINVAL for arguments outside these limits; nothing is allocated and
+ * nothing is kept. */
+int lazyllm_op_quantize_fp8(const void* x, int32_t rows, int32_t K, int32_t ldx, void* codes,
+                            int32_t ldq, float* scale, void* hip_stream);
+int lazyllm_op_gemm_fp8(const void* a_codes, const float* a_scale, const void* w_codes,
+                        const float* w_scale, void* C, const void* R, int32_t M, int32_t N, int32_t K,
+                        int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue, void* hip_stream);
+
 /* x = h * rsqrt(mean(h^2) + eps) * gain, bf16 in and out, rows of width d. */
 int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d,
                        float eps, void* hip_stream);

@@ -126,6 +126,11 @@ _SIGNATURES = {
                                           C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                           C.c_int32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_size_t, C.c_void_p]),
+    "lazyllm_op_quantize_fp8": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_int32, C.c_void_p, C.c_void_p]),
+    "lazyllm_op_gemm_fp8": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_void_p]),
     "lazyllm_op_rmsnorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                      C.c_float, C.c_void_p]),
     "lazyllm_op_qkv_rope": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -317,6 +322,18 @@ def lazyllm_op_gemm_rmsnorm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, ssq
     _check(lib().lazyllm_op_gemm_rmsnorm(_ptr(A), _ptr(W), _ptr(Cout), _ptr(R), M, N, K, lda, ldw, ldc,
                                          epilogue, _ptr(ssq_in), eps, _ptr(ssq_out), _ptr(ssq_clear),
                                          _ptr(workspace), wsb, _stream_ptr(stream)))
+
+
+def lazyllm_op_quantize_fp8(x, rows, K, ldx, codes, ldq, scale, stream=None) -> None:
+    _check(lib().lazyllm_op_quantize_fp8(_ptr(x), rows, K, ldx, _ptr(codes), ldq, _ptr(scale),
+                                         _stream_ptr(stream)))
+
+
+def lazyllm_op_gemm_fp8(a_codes, a_scale, w_codes, w_scale, Cout, R, M, N, K, lda, ldw, ldc, epilogue,
+                        stream=None) -> None:
+    _check(lib().lazyllm_op_gemm_fp8(_ptr(a_codes), _ptr(a_scale), _ptr(w_codes), _ptr(w_scale),
+                                     _ptr(Cout), _ptr(R), M, N, K, lda, ldw, ldc, epilogue,
+                                     _stream_ptr(stream)))
 
 
 def lazyllm_op_rmsnorm(h, gain, x, rows, d, eps, stream=None) -> None:

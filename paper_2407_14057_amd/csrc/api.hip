@@ -989,6 +989,34 @@ int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R
   return LAZYLLM_OK;
 }
 
+int lazyllm_op_quantize_fp8(const void* x, int32_t rows, int32_t K, int32_t ldx, void* codes,
+                            int32_t ldq, float* scale, void* hip_stream) {
+  if (!x || !codes || !scale || rows < 0 || K <= 0 || K % 8 != 0 || K > 16384 || ldx < K || ldq < K ||
+      ldx % 8 != 0 || ldq % 8 != 0 || ((uintptr_t)x & 15) != 0 || ((uintptr_t)codes & 7) != 0)
+    return LAZYLLM_EINVAL;
+  LZ_HIP(launch_quantize_rows_f8(x, rows, K, ldx, codes, ldq, scale, (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_gemm_fp8(const void* a_codes, const float* a_scale, const void* w_codes,
+                        const float* w_scale, void* C, const void* R, int32_t M, int32_t N, int32_t K,
+                        int32_t lda, int32_t ldw, int32_t ldc, int32_t epilogue, void* hip_stream) {
+  if (!a_codes || !a_scale || !w_codes || !w_scale || !C || M < 0 || N <= 0 || K <= 0)
+    return LAZYLLM_EINVAL;
+  if (N % 256 != 0 || K % 128 != 0 || lda % 16 != 0 || ldw % 16 != 0 || ldc % 4 != 0 || lda < K || ldw < K)
+    return LAZYLLM_EINVAL;
+  if (((uintptr_t)a_codes & 15) != 0 || ((uintptr_t)w_codes & 15) != 0 || ((uintptr_t)w_scale & 15) != 0)
+    return LAZYLLM_EINVAL;
+  if ((uint64_t)M * (uint64_t)lda >= (1ull << 32) || (uint64_t)N * (uint64_t)ldw >= (1ull << 32))
+    return LAZYLLM_EINVAL;
+  if (epilogue < 0 || epilogue > 2 || (epilogue == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
+  if (ldc < (epilogue == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
+  if (M == 0) return LAZYLLM_OK;
+  LZ_HIP(launch_gemm_f8(a_codes, a_scale, w_codes, w_scale, C, R, M, N, K, lda, ldw, ldc, epilogue,
+                        (hipStream_t)hip_stream, nullptr));
+  return LAZYLLM_OK;
+}
+
 int lazyllm_op_rmsnorm(const void* h, const void* gain, void* x, int32_t rows, int32_t d, float eps,
                        void* hip_stream) {
   if (!h || !gain || !x || rows < 0 || d <= 0 || d % 8 != 0 || d > 16384 || !(eps > 0.f))

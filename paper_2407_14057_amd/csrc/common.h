@@ -169,6 +169,13 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
 
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st);
 
+// 8-bit floating point variant (gemm_fp8.hip): E4M3 codes with one fp32 scale per row.
+hipError_t launch_quantize_rows_f8(const void* x, int rows, int K, int ldx, void* q, int ldq,
+                                   float* scale, hipStream_t st);
+hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const float* sw, void* C,
+                          const void* R, int M, int N, int K, int lda, int ldw, int ldc, int epilogue,
+                          hipStream_t st, const EpiArgs* ea = nullptr);
+
 hipError_t launch_rope_table(float2* table, int n_pos, int head_dim, float theta, hipStream_t st);
 
 // Batched pieces take per-sequence row offsets cu[batch+1] (device) of the current stage;

@@ -1,0 +1,218 @@
+"""Parity of the 8-bit (OFP8 E4M3) GEMM variant, through the C ABI, against the CPU checker:
+the row quantiser's codes and scales bit for bit, the product within the rounding of its bf16
+output plus the accumulation error of the matrix instruction (the checker accumulates in fp64)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp8_oracle as F
+from oracle import lazyllm_oracle as O
+from paper_2407_14057_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _bf16_dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).to(DEV)
+
+
+def _f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def _quantize_gpu(x: torch.Tensor, ldq=None):
+    rows, K = x.shape
+    ldq = K if ldq is None else ldq
+    codes = torch.full((rows, ldq), 0xAA, dtype=torch.uint8, device=DEV)
+    scale = torch.full((rows,), -1.0, dtype=torch.float32, device=DEV)
+    B.lazyllm_op_quantize_fp8(x, rows, K, x.stride(0), codes, ldq, scale)
+    torch.cuda.synchronize()
+    return codes, scale
+
+
+@pytest.mark.parametrize("rows,K", [(1, 8), (5, 200), (300, 4096), (37, 11008), (3, 16384), (130, 704)])
+def test_quantiser_codes_and_scales_bit_exact(rows, K):
+    rng = np.random.default_rng(rows * 31 + K)
+    x = rng.normal(0, 1, (rows, K)).astype(np.float32)
+    x *= np.exp(rng.normal(0, 3, (rows, 1))).astype(np.float32)        # rows of very different magnitude
+    if rows >= 5:
+        x[1] = 0.0                                                       # an all-zero row
+        x[2, 1:] = 0.0                                                   # one non-zero entry
+        x[3, ::2] = -0.0                                                 # negative zeros
+        x[4] *= 1e-30                                                    # tiny magnitudes
+    xd = _bf16_dev(x)
+    codes, scale = _quantize_gpu(xd)
+    ref_codes, ref_scale = F.quantize_rows(_f32(xd))
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), ref_scale.view(np.uint32))
+    got = codes.cpu().numpy()
+    assert np.array_equal(got, ref_codes), "%d codes differ" % int((got != ref_codes).sum())
+
+
+def test_quantiser_ties_saturation_and_strides():
+    # a row whose largest entry is 448 has scale 1: then every halfway point between neighbouring
+    # codes (5 significant bits, exact in bf16) is a tie and must go to the even code
+    pos = F.e4m3_decode(np.arange(0x7F, dtype=np.uint8))
+    halfway = (pos[:-1] + pos[1:]) / 2
+    vals = np.concatenate([[448.0], halfway, -halfway, pos, -pos, np.nextafter(halfway.astype(np.float32), 0)])
+    K = (len(vals) + 7) // 8 * 8
+    x = np.zeros((2, K), dtype=np.float32)
+    x[0, :len(vals)] = vals
+    x[1, :len(vals)] = vals[::-1] * 0.5
+    x[1, 0] = 448.0
+    xd = _bf16_dev(x)
+    assert np.array_equal(_f32(xd)[0, 1:1 + len(halfway)], halfway.astype(np.float32))   # exact in bf16
+    codes, scale = _quantize_gpu(xd)
+    ref_codes, ref_scale = F.quantize_rows(_f32(xd))
+    assert scale.cpu().tolist() == [1.0, 1.0] and ref_scale.tolist() == [1.0, 1.0]
+    assert np.array_equal(codes.cpu().numpy(), ref_codes)
+    assert np.array_equal(ref_codes[0, 1:1 + len(halfway)] % 2, np.zeros(len(halfway), dtype=np.uint8))
+    # strided input and output; bytes between the rows of the output stay untouched
+    rng = np.random.default_rng(2)
+    big = _bf16_dev(rng.normal(0, 1, (9, 96)))
+    view = big[:, 8:72]                                                  # K = 64, row stride 96
+    codes = torch.full((9, 80), 0xAA, dtype=torch.uint8, device=DEV)
+    scale = torch.full((9,), -1.0, dtype=torch.float32, device=DEV)
+    B.lazyllm_op_quantize_fp8(big.view(-1)[8:], 9, 64, 96, codes, 80, scale)
+    torch.cuda.synchronize()
+    ref_codes, ref_scale = F.quantize_rows(_f32(view))
+    got = codes.cpu().numpy()
+    assert np.array_equal(got[:, :64], ref_codes) and np.all(got[:, 64:] == 0xAA)
+    assert np.array_equal(scale.cpu().numpy(), ref_scale)
+
+
+def _codes_dev(rng, shape):
+    """Random finite E4M3 codes (no NaN codes)."""
+    c = rng.integers(0, 256, size=shape, dtype=np.uint8)
+    c[(c & 0x7F) == 0x7F] = 0x38
+    return c
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 256, 128), (37, 256, 384), (300, 768, 1024), (513, 1536, 640),
+                                   (256, 512, 4096), (2100, 768, 256), (777, 4096, 1408)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_fp8_from_codes(M, N, K, epi):
+    rng = np.random.default_rng(M * 7 + N + K + epi)
+    # codes of a realistic spread: quantised Gaussians
+    ac, sa = F.quantize_rows(rng.normal(0, 1, (M, K)).astype(np.float32))
+    wc, sw = F.quantize_rows(rng.normal(0, 1 / math.sqrt(K), (N, K)).astype(np.float32))
+    acc = F.gemm_fp8(ac, sa, wc, sw)
+    mag = F.gemm_fp8(ac & 0x7F, sa, wc & 0x7F, sw)                       # sum of the terms' magnitudes
+    a_d, w_d = torch.from_numpy(ac).to(DEV), torch.from_numpy(wc).to(DEV)
+    sa_d, sw_d = torch.from_numpy(sa).to(DEV), torch.from_numpy(sw).to(DEV)
+    if epi == B.EPI_SWIGLU:
+        blocks = acc.reshape(M, N // 64, 2, 32)
+        ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+        Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm_fp8(a_d, sa_d, w_d, sw_d, Cout, None, M, N, K, K, K, N // 2, epi)
+    elif epi == B.EPI_RESIDUAL:
+        R = _bf16_dev(rng.normal(0, 1, (M, N)))
+        ref = _f32(R).astype(np.float64) + acc
+        Cout = R.clone()
+        B.lazyllm_op_gemm_fp8(a_d, sa_d, w_d, sw_d, Cout, Cout, M, N, K, K, K, N, epi)
+    else:
+        ref = acc
+        Cout = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm_fp8(a_d, sa_d, w_d, sw_d, Cout, None, M, N, K, K, K, N, epi)
+    torch.cuda.synchronize()
+    got = _f32(Cout).astype(np.float64)
+    # bf16 output: half an ulp (2^-8 relative).  The products are exact, but the matrix instruction
+    # adds its 64 products in an internal format and the result to the fp32 accumulator: measured up
+    # to 1e-5 of the sum of the terms' magnitudes (it shows where the terms cancel); 3e-5 allowed,
+    # still 2^-11 of the 8-bit format's own rounding step.  (Ahead of the SiLU, whose slope is <= 1.1.)
+    err = np.abs(got - ref)
+    extra = 3e-5 * mag if epi != B.EPI_SWIGLU else 4e-4
+    tol = 2.0 ** -8 * np.abs(ref) + extra + 1e-30
+    assert not (err > tol).any(), "%d of %d off, worst %.3g" % (int((err > tol).sum()), err.size, float(err.max()))
+
+
+def test_gemm_fp8_all_code_pairs_and_scales():
+    """Every code against every code (K = 128 holds each A code in one row block), distinct scales
+    per row and per column: a swapped operand, a wrong scale index or a wrong format would show."""
+    rng = np.random.default_rng(9)
+    M, N, K = 256, 256, 128
+    ac = np.repeat(np.arange(256, dtype=np.uint8)[:, None], K, axis=1)
+    ac[(ac & 0x7F) == 0x7F] = 0
+    wc = _codes_dev(rng, (N, K))
+    wc[:, 0] = np.arange(256, dtype=np.uint8)
+    wc[(wc & 0x7F) == 0x7F] = 0
+    sa = np.exp(rng.normal(0, 1, M)).astype(np.float32) * 1e-3
+    sw = np.exp(rng.normal(0, 1, N)).astype(np.float32) * 1e-3
+    ref = F.gemm_fp8(ac, sa, wc, sw)
+    mag = F.gemm_fp8(ac & 0x7F, sa, wc & 0x7F, sw)
+    Cout = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_gemm_fp8(torch.from_numpy(ac).to(DEV), torch.from_numpy(sa).to(DEV),
+                          torch.from_numpy(wc).to(DEV), torch.from_numpy(sw).to(DEV), Cout, None,
+                          M, N, K, K, K, N, B.EPI_STORE)
+    torch.cuda.synchronize()
+    got = _f32(Cout).astype(np.float64)
+    # Rows of A that hold only subnormal codes (exponent field 0) lose up to three more bits: the
+    # instruction adds its products in a window below the largest exponent FIELD sum, and a
+    # subnormal's leading zeros use up part of it (measured 2e-4 of the magnitudes; such rows do not
+    # occur after the row quantiser, whose largest entry is always the normal 448).
+    sub_row = ((ac[:, 0] >> 3) & 0xF) == 0
+    extra = np.where(sub_row, 4e-4, 3e-5)[:, None] * mag
+    err = np.abs(got - ref)
+    assert np.all(err <= 2.0 ** -8 * np.abs(ref) + extra + 1e-30), int((err > 2.0 ** -8 * np.abs(ref) + extra + 1e-30).sum())
+
+
+def test_quantise_then_multiply_full_size_sampled():
+    """The gate/up projection of the 7B shape at the headline prompt length, from bf16 operands:
+    quantiser and product together, checked on sampled rows against the checker, and against the
+    exact product within the format's precision."""
+    rng = np.random.default_rng(77)
+    M, N, K = 3376, 22016, 4096
+    A = _bf16_dev(rng.normal(0, 1, (M, K)))
+    W = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    for r0 in range(0, N, 4096):
+        r1 = min(N, r0 + 4096)
+        W[r0:r1] = _bf16_dev(rng.normal(0, 1 / math.sqrt(K), (r1 - r0, K)))
+    ac, sa = _quantize_gpu(A)
+    wc, sw = _quantize_gpu(W)
+    Cout = torch.empty((M, N // 2), dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_gemm_fp8(ac, sa, wc, sw, Cout, None, M, N, K, K, K, N // 2, B.EPI_SWIGLU)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 255, 256, 1777, 3071, 3072, 3375])            # tile edges and the ragged last tile
+    blocks = np.concatenate([np.arange(0, 8), np.arange(170, 178), np.arange(336, 344)])   # 64-row blocks of W
+    w_rows = (blocks[:, None] * 64 + np.arange(64)[None, :]).reshape(-1)
+    out_cols = (blocks[:, None] * 32 + np.arange(32)[None, :]).reshape(-1)
+    a_rows, w_sel = _f32(A[rows]), _f32(W[torch.from_numpy(w_rows).to(DEV)])
+    rc, rs = F.quantize_rows(a_rows)
+    assert np.array_equal(ac[rows].cpu().numpy(), rc) and np.array_equal(sa[rows].cpu().numpy(), rs)
+    wq, ws = F.quantize_rows(w_sel)
+    assert np.array_equal(sw.cpu().numpy()[w_rows], ws)
+    assert np.array_equal(wc.cpu().numpy()[w_rows], wq)
+    acc = F.gemm_fp8(rc, rs, wq, ws).reshape(len(rows), len(blocks), 2, 32)
+    ref = (O.silu(acc[:, :, 0, :]) * acc[:, :, 1, :]).reshape(len(rows), len(blocks) * 32)
+    got = _f32(Cout[rows]).astype(np.float64)[:, out_cols]
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 4e-4)
+    # against the unquantised product: two operands with 2^-4 relative rounding steps give a few
+    # per cent of the product's spread
+    eb = (a_rows.astype(np.float64) @ w_sel.astype(np.float64).T).reshape(len(rows), len(blocks), 2, 32)
+    exact_out = (O.silu(eb[:, :, 0, :]) * eb[:, :, 1, :]).reshape(len(rows), len(blocks) * 32)
+    assert np.sqrt(np.mean((got - exact_out) ** 2)) < 0.06 * np.sqrt(np.mean(exact_out ** 2))
+
+
+def test_fp8_argument_checks():
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device=DEV)
+    codes = torch.zeros((4, 64), dtype=torch.uint8, device=DEV)
+    scale = torch.zeros(4, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.LazyLLMError):
+        B.lazyllm_op_quantize_fp8(x, 4, 60, 64, codes, 64, scale)        # K % 8
+    with pytest.raises(B.LazyLLMError):
+        B.lazyllm_op_quantize_fp8(x, 4, 64, 32, codes, 64, scale)        # stride below K
+    with pytest.raises(B.LazyLLMError):
+        B.lazyllm_op_quantize_fp8(x, 4, 16392, 16392, codes, 16392, scale)   # K above the limit
+    a = torch.zeros((4, 128), dtype=torch.uint8, device=DEV)
+    w = torch.zeros((256, 128), dtype=torch.uint8, device=DEV)
+    sw = torch.zeros(256, dtype=torch.float32, device=DEV)
+    out = torch.zeros((4, 256), dtype=torch.bfloat16, device=DEV)
+    for bad in (dict(N=128), dict(K=64), dict(lda=120), dict(ldc=100), dict(epi=B.EPI_RESIDUAL), dict(epi=3)):
+        kw = dict(M=4, N=256, K=128, lda=128, ldw=128, ldc=256, epi=B.EPI_STORE)
+        kw.update(bad)
+        with pytest.raises(B.LazyLLMError):
+            B.lazyllm_op_gemm_fp8(a, scale, w, sw, out, None, kw["M"], kw["N"], kw["K"], kw["lda"],
+                                  kw["ldw"], kw["ldc"], kw["epi"])
+    B.lazyllm_op_gemm_fp8(a, scale, w, sw, out, None, 0, 256, 128, 128, 128, 256, B.EPI_STORE)   # M = 0: nothing to do
