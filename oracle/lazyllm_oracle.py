@@ -205,26 +205,59 @@ class LayerWeights:
             setattr(self, name, _as_float(weights[name][l], dtype))
 
 
+def projection_8bit(a: np.ndarray, w: np.ndarray, gain: Optional[np.ndarray] = None,
+                    eps: float = 0.0) -> np.ndarray:
+    """A projection as the 8-bit GEMM variant defines it (an extension; the paper's models
+    compute in 16-bit floating point): rows of `a` and rows of the stored weight are quantised
+    to OFP8 E4M3 with one scale per row (fp8_oracle.quantize_rows) and multiplied
+    (fp8_oracle.gemm_fp8).  With `gain`, the projection is that of RMSNorm(a): the gain is folded
+    into the stored 16-bit weight, w' = bf16(w * gain), the UNnormalised rows of `a` are what
+    is quantised, and 1/rms(a) scales the product's rows."""
+    from . import fp8_oracle as F8
+    wf = w if gain is None else round_to_bf16(w * gain[None, :])
+    ac, sa = F8.quantize_rows(a)
+    wc, sw = F8.quantize_rows(wf)
+    y = F8.gemm_fp8(ac, sa, wc, sw)
+    if gain is not None:
+        y = y / np.sqrt(np.mean(a * a, axis=-1, keepdims=True) + eps)
+    return y
+
+
 def decoder_layer(h: np.ndarray, pos: np.ndarray, lw: LayerWeights, n_heads: int, head_dim: int,
-                  eps: float, theta: float, store=lambda t: t):
+                  eps: float, theta: float, store=lambda t: t, gemm8: bool = False):
     """One pre-norm Llama layer on m tokens with original positions pos.
 
     `store` is applied wherever a tensor is written back to memory (identity,
     or round_to_bf16 to model bf16 activations).  Returns (h_out, k, v, s) with
     k, v [m, Hkv, hd] as they enter the KV cache (Hkv = rows of wk / hd) and s the Eq. 1 scores.
+    gemm8: the four projections run as projection_8bit (everything else is unchanged).
     """
     m, d = h.shape
     n_kv_heads = lw.wk.shape[0] // head_dim          # grouped-query attention when below n_heads
+    kvd = n_kv_heads * head_dim
     # The normalised activations x and y are not rounding points: the data flow being modelled
     # folds RMSNorm into the projections and never writes them to memory.
-    x = rmsnorm(h, lw.attn_norm, eps)
-    q = (x @ lw.wq.T).reshape(m, n_heads, head_dim)
-    k = (x @ lw.wk.T).reshape(m, n_kv_heads, head_dim)
-    v = store((x @ lw.wv.T).reshape(m, n_kv_heads, head_dim))
+    if gemm8:
+        qkv = projection_8bit(h, np.concatenate([lw.wq, lw.wk, lw.wv], axis=0), lw.attn_norm, eps)
+        q = qkv[:, :d].reshape(m, n_heads, head_dim)
+        k = qkv[:, d:d + kvd].reshape(m, n_kv_heads, head_dim)
+        v = store(qkv[:, d + kvd:].reshape(m, n_kv_heads, head_dim))
+    else:
+        x = rmsnorm(h, lw.attn_norm, eps)
+        q = (x @ lw.wq.T).reshape(m, n_heads, head_dim)
+        k = (x @ lw.wk.T).reshape(m, n_kv_heads, head_dim)
+        v = store((x @ lw.wv.T).reshape(m, n_kv_heads, head_dim))
     q = store(rope(q, pos, theta))
     k = store(rope(k, pos, theta))
     o, s = causal_attention(q, k, v)
     o = store(o)
+    if gemm8:
+        h = store(h + projection_8bit(o.reshape(m, d), lw.wo))
+        f = lw.w_gate.shape[0]
+        gu = projection_8bit(h, np.concatenate([lw.w_gate, lw.w_up], axis=0), lw.ffn_norm, eps)
+        a = store(silu(gu[:, :f]) * gu[:, f:])
+        h = store(h + projection_8bit(a, lw.w_down))
+        return h, k, v, s
     h = store(h + o.reshape(m, d) @ lw.wo.T)
     y = rmsnorm(h, lw.ffn_norm, eps)
     a = store(swiglu(y, lw.w_gate, lw.w_up))
@@ -249,7 +282,7 @@ def prefill(shape: Dict[str, float], weights: Dict[str, object], token_ids: np.n
             schedule: Sequence[Tuple[int, int]], *, dtype=np.float64, bf16_storage: bool = False,
             forced_keep: Optional[Dict[int, np.ndarray]] = None,
             embed_scale: Optional[np.ndarray] = None, n_layers: Optional[int] = None,
-            keep_hidden: bool = False) -> PrefillResult:
+            keep_hidden: bool = False, gemm8: bool = False) -> PrefillResult:
     """Prefill one prompt with progressive token pruning.
 
     shape: dict with n_layers, d_model, n_heads, head_dim, d_ffn, vocab, rms_eps,
@@ -257,6 +290,7 @@ def prefill(shape: Dict[str, float], weights: Dict[str, object], token_ids: np.n
     forced_keep: {layer: original positions to keep there} overrides the
     oracle's own choice at that layer (for comparing downstream of a near-tie).
     n_layers: run only the first n_layers layers (bounded timing samples).
+    gemm8: the layers' projections in the 8-bit variant (see projection_8bit).
     """
     L = int(shape["n_layers"]) if n_layers is None else int(n_layers)
     H, hd = int(shape["n_heads"]), int(shape["head_dim"])
@@ -296,7 +330,7 @@ def prefill(shape: Dict[str, float], weights: Dict[str, object], token_ids: np.n
         if keep_hidden:
             res.hidden_in.append(h.copy())
         lw = LayerWeights(weights, l, dtype)
-        h, k, v, s_prev = decoder_layer(h, pos, lw, H, hd, eps, theta, store)
+        h, k, v, s_prev = decoder_layer(h, pos, lw, H, hd, eps, theta, store, gemm8)
         res.kept_pos.append(pos.copy())
         res.k.append(k)
         res.v.append(v)

@@ -104,3 +104,60 @@ def test_product_against_rational_arithmetic():
     assert np.max(np.abs(got - exact) / scale) < 0.08
     # transposed operands give the transposed product (rows of W are output features)
     assert np.allclose(F.gemm_fp8(wc, sw, ac, sa), got.T, rtol=1e-12, atol=0)
+
+
+# ---------------------------------------------------------------- the projections of a layer
+
+from oracle import lazyllm_oracle as O
+from paper_2407_14057_amd import synth
+
+
+def test_projection_is_exact_when_nothing_needs_rounding():
+    """Operands whose rows quantise without loss (entries are E4M3 values times a power of two,
+    largest magnitude 448 * 2^j) must give the plain product, with and without the folded
+    RMSNorm: a dropped or misplaced scale, a gain folded on the wrong axis or a missing 1/rms
+    would show."""
+    rng = np.random.default_rng(21)
+    vals = F.e4m3_decode(np.arange(0x7F, dtype=np.uint8))
+    M, N, K = 7, 9, 40
+    a = rng.choice(vals, (M, K)) * rng.choice([-1.0, 1.0], (M, K))
+    a[:, 0] = 448.0
+    a *= 2.0 ** rng.integers(-6, 3, (M, 1))
+    w = rng.choice(vals, (N, K)) * rng.choice([-1.0, 1.0], (N, K))
+    w[:, 3] = -448.0
+    w *= 2.0 ** rng.integers(-12, -4, (N, 1))
+    assert np.allclose(O.projection_8bit(a, w), a @ w.T, rtol=1e-12, atol=0)
+    # with a gain: entries of w * gain must stay E4M3 values relative to the row's peak, so the
+    # weights are taken from the values >= 0.5, the gains from {1/4, 1/2, 1, 2, 4}, and the peak
+    # (448 under the largest gain) is planted in column 3
+    big = vals[vals >= 0.5]
+    w = rng.choice(big, (N, K)) * rng.choice([-1.0, 1.0], (N, K))
+    gain = 2.0 ** rng.integers(-2, 3, K).astype(np.float64)
+    gain[3] = 4.0
+    w[:, 3] = -448.0
+    w *= 2.0 ** rng.integers(-12, -4, (N, 1))
+    eps = 1e-5
+    got = O.projection_8bit(a, w, gain, eps)
+    want = O.rmsnorm(a, gain, eps) @ w.T
+    assert np.allclose(got, want, rtol=1e-12, atol=0)
+    assert not np.allclose(got, O.rmsnorm(a, np.ones(K), eps) @ w.T, rtol=1e-3, atol=0)
+
+
+def test_layer_with_8bit_projections_is_close_to_the_exact_layer_but_not_equal():
+    shape = synth.TINY
+    w = synth.weights_to_host_bits(synth.make_weights(shape, 5, "cpu", gain_jitter=0.25))
+    lw = O.LayerWeights(w, 1, np.float64)
+    rng = np.random.default_rng(4)
+    m = 48
+    h = O.round_to_bf16(rng.normal(0, 1, (m, shape.d_model)))
+    pos = np.arange(m)
+    ref = O.decoder_layer(h, pos, lw, shape.n_heads, shape.head_dim, shape.rms_eps, shape.rope_theta)
+    got = O.decoder_layer(h, pos, lw, shape.n_heads, shape.head_dim, shape.rms_eps, shape.rope_theta, gemm8=True)
+    for name, r, g, tol in (("h", ref[0], got[0], 0.05), ("k", ref[1], got[1], 0.08), ("v", ref[2], got[2], 0.08)):
+        rel = np.sqrt(np.mean((g - r) ** 2) / np.mean(r ** 2))
+        assert 1e-4 < rel < tol, (name, rel)                         # quantised, but to the format's precision
+    assert abs(got[3].sum() - 1.0) < 1e-9                            # Eq. 1 is still a mean of distributions
+    # fusing the rows of several weight matrices into one product changes nothing (scales are per row)
+    sep = np.concatenate([O.projection_8bit(h, lw.wq, lw.attn_norm, 1e-5), O.projection_8bit(h, lw.wk, lw.attn_norm, 1e-5)], axis=1)
+    fused = O.projection_8bit(h, np.concatenate([lw.wq, lw.wk], axis=0), lw.attn_norm, 1e-5)
+    assert np.array_equal(sep, fused)
