@@ -55,11 +55,21 @@ typedef enum lazyllm_status {
  * heads, each read by n_heads / n_kv_heads consecutive query heads; 0 means
  * n_heads (plain multi-head attention, the paper's models).  It must divide
  * n_heads and n_kv_heads * head_dim must be a multiple of 128.  Eq. 1 is the
- * mean over all n_heads attention maps either way. */
+ * mean over all n_heads attention maps either way.
+ * gemm_dtype: arithmetic of the four projections of every layer in the
+ * prefill.  0 = 16-bit floating point, the paper's (Sec. 5, implementation
+ * details).  1 = the 8-bit variant (see lazyllm_op_gemm_fp8): the stored
+ * weights (RMSNorm gains folded in) are quantised once at model creation,
+ * the activations row by row in front of each projection, OFP8 E4M3 codes
+ * with one fp32 scale per row; attention, normalisation, scoring, selection
+ * and the LM head are unchanged.  It needs d_model % 256 == 0,
+ * (d_model + 2 * n_kv_heads * head_dim) % 256 == 0 and d_ffn <= 16384, and
+ * such a model has no decoding steps (lazyllm_generation_create refuses it). */
 typedef struct lazyllm_config {
   int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_theta;
   int32_t n_kv_heads;
+  int32_t gemm_dtype;
 } lazyllm_config;
 
 /* Device pointers to bf16 weights.  The per-layer members are HOST arrays of

@@ -67,8 +67,12 @@ def quantize_rows(x: np.ndarray):
     amax = np.max(np.abs(x32), axis=1) if x32.shape[1] > 0 else np.zeros(x32.shape[0], np.float32)
     scale = (amax / np.float32(E4M3_MAX)).astype(np.float32)
     scale = np.where(amax == 0, np.float32(1.0), scale).astype(np.float32)
-    y = (x32 / scale[:, None]).astype(np.float32)          # binary32 division
-    return e4m3_encode(y), scale
+    codes = np.empty(x32.shape, dtype=np.uint8)
+    step = max(1, (1 << 22) // max(1, x32.shape[1]))       # row blocks: bounds the temporaries, nothing else
+    for r0 in range(0, x32.shape[0], step):
+        y = (x32[r0:r0 + step] / scale[r0:r0 + step, None]).astype(np.float32)      # binary32 division
+        codes[r0:r0 + step] = e4m3_encode(y)
+    return codes, scale
 
 
 def gemm_fp8(a_codes: np.ndarray, sa: np.ndarray, w_codes: np.ndarray, sw: np.ndarray) -> np.ndarray:

@@ -26,7 +26,8 @@ EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
 class lazyllm_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("n_kv_heads", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("n_kv_heads", C.c_int32),
+                ("gemm_dtype", C.c_int32)]
 
 
 class lazyllm_weights(C.Structure):
@@ -206,7 +207,7 @@ def make_config(shape: Dict[str, float]) -> lazyllm_config:
     return lazyllm_config(int(shape["n_layers"]), int(shape["d_model"]), int(shape["n_heads"]),
                           int(shape["head_dim"]), int(shape["d_ffn"]), int(shape["vocab"]),
                           float(shape["rms_eps"]), float(shape["rope_theta"]),
-                          int(shape.get("n_kv_heads", 0) or 0))
+                          int(shape.get("n_kv_heads", 0) or 0), int(shape.get("gemm_dtype", 0) or 0))
 
 
 def _kv_heads(cfg: lazyllm_config) -> int:

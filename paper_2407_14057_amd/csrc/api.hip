@@ -82,6 +82,13 @@ bool config_ok(const lazyllm_config* c) {
     return false;
   if (c->d_ffn < 1 || c->vocab < 1) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return false;
+  if (c->gemm_dtype != 0 && c->gemm_dtype != 1) return false;
+  if (c->gemm_dtype == 1) {
+    // the 8-bit tile kernel works on 256 x 256 tiles and 128-element K steps; the row quantiser
+    // holds a row of up to 16384 elements
+    const int kvd = (c->n_kv_heads > 0 ? c->n_kv_heads : c->n_heads) * c->head_dim;
+    if (c->d_model % 256 != 0 || (c->d_model + 2 * kvd) % 256 != 0 || c->d_ffn > 16384) return false;
+  }
   return true;
 }
 
@@ -149,7 +156,7 @@ void build_stages(int n_layers, const lazyllm_keep* sched, int n_sched, const in
 
 // ---- workspace layout -------------------------------------------------------------------
 struct Workspace {
-  size_t h0, h1, ssq0, ssq1, q, o, vt, vt_col, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, total;
+  size_t h0, h1, ssq0, ssq1, q, o, vt, vt_col, act, score, rope, keep_idx, prune_idx, xf, gemm_ws, a8, sa8, total;
 };
 
 void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_seqlen,
@@ -173,6 +180,9 @@ void layout_workspace(const lazyllm_config* c, long long T, int batch, int max_s
   w->prune_idx = take((size_t)T * 4);
   w->xf = take((size_t)batch * d * 4);
   w->gemm_ws = take(gemm_workspace_bytes());
+  // 8-bit variant: the codes and row scales of the activations in front of a projection
+  w->a8 = take(c->gemm_dtype == 1 ? (size_t)T * (d > fp ? d : fp) : 0);
+  w->sa8 = take(c->gemm_dtype == 1 ? (size_t)T * 4 : 0);
   w->total = off;
 }
 
@@ -225,11 +235,14 @@ struct lazyllm_model {
   char* blob;                                   // one device allocation holding everything below
   const void *embed, *final_norm, *lm_head;
   std::vector<const void*> attn_norm, ffn_norm, wqkv, wo, wgu, wdown;
+  // 8-bit variant (cfg.gemm_dtype == 1): E4M3 codes of the same four matrices and one scale per row
+  std::vector<const void*> wqkv8, wo8, wgu8, wdown8;
+  std::vector<const float*> sqkv, so, sgu, sdown;
 };
 
 extern "C" {
 
-int lazyllm_abi_version(void) { return 2; }
+int lazyllm_abi_version(void) { return 3; }
 
 const char* lazyllm_strerror(int status) {
   switch (status) {
@@ -305,7 +318,11 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
   const size_t d = cfg->d_model, f = cfg->d_ffn, fp = m->f_pad, V = cfg->vocab, kvd = kv_dim(cfg);
   const size_t per_layer = align_up(d * 2) * 2 + align_up((d + 2 * kvd) * d * 2) + align_up(d * d * 2) +
                            align_up(2 * fp * d * 2) + align_up(d * fp * 2);
-  const size_t bytes = align_up(V * d * 2) * 2 + align_up(d * 2) + per_layer * L;
+  const bool f8 = cfg->gemm_dtype == 1;
+  const size_t per_layer8 = !f8 ? 0 : align_up((d + 2 * kvd) * d) + align_up(d * d) + align_up(2 * fp * d) +
+                                          align_up(d * fp) + align_up((d + 2 * kvd) * 4) + 2 * align_up(d * 4) +
+                                          align_up(2 * fp * 4);
+  const size_t bytes = align_up(V * d * 2) * 2 + align_up(d * 2) + (per_layer + per_layer8) * L;
   hipError_t e = hipMalloc((void**)&m->blob, bytes);
   if (e != hipSuccess) {
     delete m;
@@ -352,6 +369,21 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
     p = take(d * fp * 2);                          // down, K zero-padded to f_pad
     chk(launch_copy_rows(w->w_down[l], p, (int)d, (int)f, (int)f, (int)fp, st));
     m->wdown.push_back(p);
+    if (f8) {
+      // the stored matrices (gains folded in, fused, padded) quantised row by row
+      auto quant = [&](const void* src, size_t rows, size_t K, std::vector<const void*>& codes,
+                       std::vector<const float*>& scales) {
+        char* c8 = take(rows * K);
+        float* sc = (float*)take(rows * 4);
+        chk(launch_quantize_rows_f8(src, (int)rows, (int)K, (int)K, c8, (int)K, sc, st));
+        codes.push_back(c8);
+        scales.push_back(sc);
+      };
+      quant(m->wqkv[l], d + 2 * kvd, d, m->wqkv8, m->sqkv);
+      quant(m->wo[l], d, d, m->wo8, m->so);
+      quant(m->wgu[l], 2 * fp, d, m->wgu8, m->sgu);
+      quant(m->wdown[l], d, fp, m->wdown8, m->sdown);
+    }
   }
   if (rc == LAZYLLM_OK) chk(hipStreamSynchronize(st));
   if (rc != LAZYLLM_OK) {
@@ -483,6 +515,20 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       cur ^= 1;
     }
     char* h = hbuf[cur];
+    // One projection: the 16-bit GEMM, or in the 8-bit variant the row quantiser on the operand
+    // followed by the 8-bit GEMM with the same epilogue (both in the step's timing).
+    auto project = [&](const void* A, int K, const void* w16, const void* w8, const float* sw8,
+                       void* Cout, const void* R, int N, int ldc, int epi, const EpiArgs* ea,
+                       bool stream_k) -> hipError_t {
+      if (c->gemm_dtype == 0)
+        return launch_gemm(A, w16, Cout, R, n, N, K, K, K, ldc, epi, st, ea,
+                           stream_k ? W + ws.gemm_ws : nullptr, stream_k ? gemm_workspace_bytes() : 0);
+      hipError_t qe = launch_quantize_rows_f8(A, n, K, K, W + ws.a8, K, (float*)(W + ws.sa8), st);
+      if (qe != hipSuccess) return qe;
+      return launch_gemm_f8(W + ws.a8, (const float*)(W + ws.sa8), w8, sw8, Cout, R, n, N, K, K, K, ldc,
+                            epi, st, ea);
+    };
+    const bool f8 = c->gemm_dtype == 1;
     if (flags & LAZYLLM_KEEP_HIDDEN) {
       res->hidden_in[l] = O + ob.hidden_in[l];
       LZ_HIP(hipMemcpyAsync(res->hidden_in[l], h, (size_t)n * d * 2, hipMemcpyDeviceToDevice, st));
@@ -509,8 +555,8 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
              launch_vt_stage_setup(W + ws.vt, B > 1 ? (int32_t*)(W + ws.vt_col) : nullptr, cu,
                                    cu_vt + s * BW, 0, B, (int)stg.vt_ld[s], kvd, st));
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, n, 2.0 * n * (dd + 2.0 * kvd) * dd,
-           launch_gemm(h, m->wqkv[l], nullptr, nullptr, n, d + 2 * kvd, d, d, d, 0, EPI_QKV_ROPE, st,
-                       &ra));
+           project(h, d, m->wqkv[l], f8 ? m->wqkv8[l] : nullptr, f8 ? m->sqkv[l] : nullptr, nullptr,
+                   nullptr, d + 2 * kvd, 0, EPI_QKV_ROPE, &ra, false));
     // Eq. 1 needs the last query's logits against every key, which the attention kernel has
     // in registers anyway: it leaves them in the score scratch (the gate/up launch below turns
     // them into the head-averaged probabilities).
@@ -524,8 +570,8 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     EpiArgs eo{};
     eo.ssq_out = ssq_ffn;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
-           launch_gemm(W + ws.o, m->wo[l], h, h, n, d, d, d, d, d, EPI_RESIDUAL, st, &eo,
-                       W + ws.gemm_ws, gemm_workspace_bytes()));
+           project(W + ws.o, d, m->wo[l], f8 ? m->wo8[l] : nullptr, f8 ? m->so[l] : nullptr, h, h, d, d,
+                   EPI_RESIDUAL, &eo, true));
     EpiArgs eg{};
     eg.ssq_in = ssq_ffn; eg.ssq_mul = ssq_mul; eg.eps = c->rms_eps; eg.ssq_clear = ssq_attn;
     if (scored) {
@@ -539,13 +585,13 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       eg.sf_max_rows = stg.max_rows[s]; eg.sf_batch = B;
     }
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, n, 2.0 * n * 2.0 * (double)c->d_ffn * dd,
-           launch_gemm(h, m->wgu[l], W + ws.act, nullptr, n, 2 * fp, d, d, d, fp, EPI_SWIGLU, st,
-                       &eg));
+           project(h, d, m->wgu[l], f8 ? m->wgu8[l] : nullptr, f8 ? m->sgu[l] : nullptr, W + ws.act,
+                   nullptr, 2 * fp, fp, EPI_SWIGLU, &eg, false));
     EpiArgs ed{};
     ed.ssq_out = ssq_attn;
     LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, n, 2.0 * n * (double)c->d_ffn * dd,
-           launch_gemm(W + ws.act, m->wdown[l], h, h, n, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
-                       W + ws.gemm_ws, gemm_workspace_bytes()));
+           project(W + ws.act, fp, m->wdown[l], f8 ? m->wdown8[l] : nullptr, f8 ? m->sdown[l] : nullptr,
+                   h, h, d, d, EPI_RESIDUAL, &ed, true));
   }
   const int s_last = stg.stage_of_layer[L - 1];
   if (flags & LAZYLLM_KEEP_HIDDEN) {
@@ -686,6 +732,7 @@ int lazyllm_generation_create(const lazyllm_model* m, const lazyllm_keep* sched,
   if (m == nullptr || prefill == nullptr || state == nullptr || out == nullptr) return LAZYLLM_EINVAL;
   if (((uintptr_t)state & 255) != 0) return LAZYLLM_EINVAL;
   const lazyllm_config* c = &m->cfg;
+  if (c->gemm_dtype != 0) return LAZYLLM_EINVAL;     // the decoding steps exist in 16-bit arithmetic only
   if (!schedule_ok(c->n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
   if (prefill->batch != 1 || prefill->n_layers != c->n_layers) return LAZYLLM_EINVAL;
   const int n_prompt = prefill->n_tokens[0];

@@ -75,7 +75,8 @@ hipError_t launch_quantize_rows_f8(const void* x, int rows, int K, int ldx, void
 }
 
 // ------------------------------------------------------------------------------------------
-// Tile kernel: 256 x 256 tile on 8 waves (4 x 2 waves of 64 x 128), 128 K elements (= 128 bytes
+// Tile kernel: 256 x 256 tile on 8 waves (4 x 2 waves of 64 x 128; TM = 1: 128 x 256 tile, waves
+// of 32 x 128, for launches that would not fill the chip otherwise), 128 K elements (= 128 bytes
 // per operand row, the same LDS geometry as the 16-bit kernels) per step, two LDS stages filled
 // by global -> LDS copies.  Same ping-pong schedule as the 16-bit kernel: the two waves of a SIMD
 // run half a step apart, one in a phase of 8 back-to-back MFMAs (64 cycles each) with the copies
@@ -86,17 +87,18 @@ hipError_t launch_quantize_rows_f8(const void* x, int rows, int K, int ldx, void
 // ------------------------------------------------------------------------------------------
 constexpr int F8_BK = 128;                          // K elements (bytes) per step
 
-template <int EPI>
+template <int EPI, int TM>
 __global__ void __launch_bounds__(512)
 gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
                const float* __restrict__ sa, const float* __restrict__ sw,
                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K,
                int lda, int ldw, int ldc, int tiles_m, int tiles_n, int group_m, EpiArgs ra) {
-  constexpr int NWAVES = 8, WM = 4, WN = 2, TM = 2, TN = 4;
+  constexpr int NWAVES = 8, WM = 4, WN = 2, TN = 4;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;    // copies per wave and K step
   constexpr int NCOPY = A_INSTR + W_INSTR;
-  static_assert(NCOPY <= TM * TN, "one copy behind each MFMA of a phase");
+  constexpr int CPM = (NCOPY + TM * TN - 1) / (TM * TN);                 // copies behind one MFMA
+  static_assert((TM == 1 || TM == 2) && NCOPY % CPM == 0 && NCOPY / CPM <= TM * TN, "128- or 256-row tiles");
   constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x >= tiles_m * tiles_n) {     // side job (see EpiArgs): Eq. 1 scores
@@ -193,13 +195,14 @@ gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
     _Pragma("unroll") for (int i = 0; i < TM; ++i)                                             \
       _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
         LZ_F8_MFMA(i, j);                                                                      \
-        if (i * TN + j < NCOPY) issue_one((stage), (k0), i * TN + j);                          \
+        _Pragma("unroll") for (int cc = 0; cc < CPM; ++cc)                                     \
+          if ((i * TN + j) * CPM + cc < NCOPY) issue_one((stage), (k0), (i * TN + j) * CPM + cc); \
       }                                                                                        \
-    _Pragma("unroll") for (int n = 0; n < NCOPY; ++n) {                                        \
+    _Pragma("unroll") for (int n = 0; n < NCOPY / CPM; ++n) {                                  \
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                       \
-      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);                                       \
+      __builtin_amdgcn_sched_group_barrier(0x010, CPM, 0);                                     \
     }                                                                                          \
-    if (TM * TN > NCOPY) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NCOPY, 0);      \
+    if (TM * TN > NCOPY / CPM) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NCOPY / CPM, 0); \
     __builtin_amdgcn_s_setprio(0);                                                             \
   } while (0)
 #define LZ_FRAG(base, h)                                                                       \
@@ -344,8 +347,7 @@ gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
 hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const float* sw, void* C,
                           const void* R, int M, int N, int K, int lda, int ldw, int ldc, int epilogue,
                           hipStream_t st, const EpiArgs* ea_in) {
-  constexpr int BM = 256, BN = 256;
-  constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  constexpr int BN = 256;
   if (M <= 0) return hipSuccess;
   if (N % BN != 0 || K % F8_BK != 0 || lda % 16 != 0 || ldw % 16 != 0 || lda < K || ldw < K ||
       ((uintptr_t)A & 15) != 0 || ((uintptr_t)W & 15) != 0 || ((uintptr_t)sw & 15) != 0)
@@ -358,27 +360,42 @@ hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const f
     if (ea_in == nullptr || (ea.head_dim != 64 && ea.head_dim != 128) || N != ea.d_model + 2 * kvd)
       return hipErrorInvalidValue;
   }
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  // One workgroup per CU is resident, so a launch takes ceil(tiles / 256) rounds of one tile's K
+  // loop: 128-row tiles (half the work each) when that is fewer half-rounds than 256-row tiles
+  // need whole ones.  Every output element sees the same sequence of additions either way.
+  const int tiles_n = N / BN;
+  const long t256 = (long)((M + 255) / 256) * tiles_n, t128 = (long)((M + 127) / 128) * tiles_n;
+  const bool tall = (t128 + 255) / 256 >= 2 * ((t256 + 255) / 256);
+  const int BM = tall ? 256 : 128;
+  const int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  const int tiles_m = (M + BM - 1) / BM;
   ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
   ea.stage_out = (epilogue == EPI_QKV_ROPE)
                      ? (ea.d_model % BN == 0 && (ea.kv_dim > 0 ? ea.kv_dim : ea.d_model) % BN == 0)
                      : (epilogue != EPI_SWIGLU && ldc % 8 == 0 && ((uintptr_t)C & 15) == 0);
   const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
-  const int group_m = tiles_m < 8 ? tiles_m : 8;
+  const int band = tall ? 8 : 16;
+  const int group_m = tiles_m < band ? tiles_m : band;
   dim3 grid(tiles_m * tiles_n + side), block(512);
-#define LZ_GEMM(E)                                                                               \
+#define LZ_GEMM2(E, TMV)                                                                         \
   do {                                                                                           \
-    auto kern = gemm_f8_kernel<E>;                                                               \
+    auto kern = gemm_f8_kernel<E, TMV>;                                                          \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,             \
+                                         2 * (128 * TMV + BN) * ROW_BYTES);                      \
       if (e != hipSuccess) return e;                                                             \
       attr_set = true;                                                                           \
     }                                                                                            \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint8_t*)A, (const uint8_t*)W,   \
                        sa, sw, (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc,         \
                        tiles_m, tiles_n, group_m, ea);                                           \
+  } while (0)
+#define LZ_GEMM(E)                                                                               \
+  do {                                                                                           \
+    if (tall) LZ_GEMM2(E, 2);                                                                    \
+    else LZ_GEMM2(E, 1);                                                                         \
   } while (0)
   if (epilogue == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epilogue == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
@@ -389,6 +406,7 @@ hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const f
   }
   else return hipErrorInvalidValue;
 #undef LZ_GEMM
+#undef LZ_GEMM2
   return hipGetLastError();
 }
 

@@ -34,6 +34,7 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     n_kv_heads: int = 0            # K,V heads; 0 = as many as query heads (no grouped-query attention)
+    gemm_dtype: int = 0            # projections of the prefill: 0 = 16-bit floats, 1 = the 8-bit (OFP8 E4M3) variant
 
     @property
     def kv_heads(self) -> int:
@@ -42,7 +43,8 @@ class ModelShape:
     def as_dict(self) -> Dict[str, float]:
         return dict(n_layers=self.n_layers, d_model=self.d_model, n_heads=self.n_heads,
                     head_dim=self.head_dim, d_ffn=self.d_ffn, vocab=self.vocab,
-                    rms_eps=self.rms_eps, rope_theta=self.rope_theta, n_kv_heads=self.kv_heads)
+                    rms_eps=self.rms_eps, rope_theta=self.rope_theta, n_kv_heads=self.kv_heads,
+                    gemm_dtype=self.gemm_dtype)
 
 
 TINY = ModelShape(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024)
@@ -52,6 +54,9 @@ LLAMA7B = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=
 GQA8B = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=14336, vocab=128256,
                    rope_theta=500000.0, n_kv_heads=8)
 XGEN7B = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=11008, vocab=51200, rms_eps=1e-6)
+# the same models with the projections in the 8-bit variant
+TINY_FP8 = ModelShape(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024, gemm_dtype=1)
+LLAMA7B_FP8 = ModelShape(n_layers=32, d_model=4096, n_heads=32, head_dim=128, d_ffn=11008, vocab=32000, gemm_dtype=1)
 
 
 @dataclass(frozen=True)
@@ -84,6 +89,9 @@ WORKLOADS: Dict[str, Workload] = {
     "gqa8b_3376": Workload("gqa8b_3376", GQA8B, 1004, 2007, (3376,), ((8, 700), (16, 500), (24, 300))),
     "7b_batch8": Workload("7b_batch8", LLAMA7B, 1002, 2005, _batch_lengths(4005, 8, 1024, 8192),
                           ((8, 700), (16, 500), (24, 300))),
+    # the small and the headline case with the projections in the 8-bit variant (same weights, same prompts)
+    "tiny512_fp8": Workload("tiny512_fp8", TINY_FP8, 1001, 2001, (512,), ((2, 700), (3, 500))),
+    "7b_3376_fp8": Workload("7b_3376_fp8", LLAMA7B_FP8, 1002, 2002, (3376,), ((8, 700), (16, 500), (24, 300))),
 }
 
 _PER_LAYER = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")

@@ -216,3 +216,74 @@ def test_fp8_argument_checks():
             B.lazyllm_op_gemm_fp8(a, scale, w, sw, out, None, kw["M"], kw["N"], kw["K"], kw["lda"],
                                   kw["ldw"], kw["ldc"], kw["epi"])
     B.lazyllm_op_gemm_fp8(a, scale, w, sw, out, None, 0, 256, 128, 128, 128, 256, B.EPI_STORE)   # M = 0: nothing to do
+
+
+# ------------------------------------------------------------ the prefill with 8-bit projections
+
+from paper_2407_14057_amd import synth
+from test_gpu_prefill import check_against_checker, _run, _to_dev
+
+# The checker quantises the same way, so the two differ only where bf16 storage noise moves an
+# activation across a rounding boundary of the 8-bit format: a few per cent of the entries, each
+# then off by one 8-bit step (2^-4 relative) -- about four times the 16-bit path's noise.
+# Measured on the small model: K, V 0.075 of their largest entry, scores 1.4e-2, logits 0.04 of their range.
+TOL8 = {"kv": 1e-1, "s64": 4e-2, "s16": 4e-2, "logits": 6e-2, "aux": 0.1, "band": 3e-2}
+
+
+@pytest.fixture(scope="module")
+def tiny8():
+    w = synth.make_weights(synth.TINY_FP8, 1001, "cpu", gain_jitter=0.3)
+    model = B.Model(synth.TINY_FP8.as_dict(), _to_dev(w), DEV)
+    yield synth.TINY_FP8, synth.weights_to_host_bits(w), model
+    model.close()
+
+
+def test_tiny512_fp8_matches_checker(tiny8):
+    shape, wb, model = tiny8
+    wl = synth.WORKLOADS["tiny512_fp8"]
+    inp = synth.make_workload_inputs(wl)
+    out = _run(model, inp["token_ids"], wl.schedule)
+    assert out.status == 0 and out.n_tokens == [512, 512, 359, 180]
+    rep = check_against_checker(shape, wb, inp["token_ids"], list(wl.schedule), out, verbose="tiny512_fp8",
+                                gemm8=True, tol=TOL8)
+    # and it is the 8-bit arithmetic that ran: the 16-bit checker is further away than the 8-bit one
+    ref = O.prefill(shape.as_dict(), wb, inp["token_ids"], [], keep_hidden=False)
+    dense = _run(model, inp["token_ids"], [])
+    l16 = np.abs(dense.logits[0].cpu().numpy() - ref.logits).max() / (ref.logits.max() - ref.logits.min())
+    ref8 = O.prefill(shape.as_dict(), wb, inp["token_ids"], [], gemm8=True)
+    l8 = np.abs(dense.logits[0].cpu().numpy() - ref8.logits).max() / (ref8.logits.max() - ref8.logits.min())
+    print("dense logits vs 16-bit checker %.4f, vs 8-bit checker %.4f" % (l16, l8))
+    assert l8 < l16
+
+
+@pytest.mark.parametrize("n,sched", [(1, []), (65, [(1, 900), (2, 500), (3, 100)]), (300, [(3, 1)]),
+                                     (777, [(1, 300)])])
+def test_tiny_fp8_shapes_and_schedules(tiny8, n, sched):
+    shape, wb, model = tiny8
+    ids = synth.make_prompt(n, shape.vocab, 300 + n)
+    out = _run(model, ids, sched)
+    assert out.status == 0
+    check_against_checker(shape, wb, ids, sched, out, verbose="fp8 n=%d %s" % (n, sched), gemm8=True, tol=TOL8)
+
+
+def test_fp8_runs_are_bit_identical_and_batches_are_independent(tiny8):
+    shape, wb, model = tiny8
+    lens = [130, 512, 77]
+    ids = np.concatenate([synth.make_prompt(n, shape.vocab, 900 + n) for n in lens])
+    cu = [0, 130, 642, 719]
+    sched = [(1, 800), (3, 400)]
+    a = _run(model, ids, sched, cu=cu)
+    snap = a.logits.clone()
+    b = _run(model, ids, sched, cu=cu)
+    assert torch.equal(snap, b.logits)
+    for i, n in enumerate(lens):
+        single = _run(model, ids[cu[i]:cu[i + 1]], sched)
+        assert torch.equal(single.logits[0], snap[i])
+
+
+def test_fp8_model_has_no_decoding_steps(tiny8):
+    shape, wb, model = tiny8
+    ids = synth.make_prompt(64, shape.vocab, 1)
+    out = _run(model, ids, [])
+    with pytest.raises(B.LazyLLMError):
+        B.Generation(model, [], out, 80)

@@ -73,7 +73,13 @@ def _check_structure(wl, inp, out):
     assert sum(out.n_tokens) <= int(cu0[-1]) * L
 
 
-def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE):
+TOL = {"kv": 2e-2, "s": 2e-2, "h": 3e-2, "band": 1e-3}
+# 8-bit projections: the checker quantises the same way, the two differ where bf16 storage noise
+# moves an activation across a rounding boundary of the 8-bit format (one 2^-4 step each)
+TOL8 = {"kv": 1e-1, "s": 5e-2, "h": 1e-1, "band": 3e-2}
+
+
+def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE, gemm8=False, tol=TOL):
     """Recompute layer l from the GPU's own input and compare what the layer produced."""
     n = out.n_tokens[l]
     lo = 0 if lo is None else lo
@@ -83,7 +89,7 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE):
     h_in = _f64(out.hidden_in(l)[lo:hi])
     pos = out.kept_pos(l)[lo:hi].cpu().numpy().astype(np.int64)
     h_ref, k_ref, v_ref, s_ref = O.decoder_layer(h_in, pos, lw, shape.n_heads, shape.head_dim, shape.rms_eps,
-                                                 shape.rope_theta, store=O.round_to_bf16)
+                                                 shape.rope_theta, store=O.round_to_bf16, gemm8=gemm8)
     k = _f64(out.k(l)[lo:hi]); v = _f64(out.v(l)[lo:hi])
     ek = np.abs(k - k_ref).max() / np.abs(k_ref).max()
     ev = np.abs(v - v_ref).max() / np.abs(v_ref).max()
@@ -97,7 +103,7 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE):
             # the selection that enters layer l+1, by the margin rule
             m = hi - lo
             kk = O.keep_count(m, sched[l + 1])
-            _, decided = O.decision_margin(s_ref, kk, rel=1e-3)
+            _, decided = O.decision_margin(s_ref, kk, rel=tol["band"])
             own, _ = O.select_tokens(s_ref, kk)
             want = np.zeros(m, dtype=bool); want[own] = True
             if single:
@@ -113,7 +119,7 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE):
                 h_next = _f64(out.hidden_in(l + 1))
                 eh = np.abs(h_next - h_ref[got]).max() / np.abs(h_ref).max()
                 aux = _f64(out.aux_h(l + 1))
-                assert np.abs(aux - h_ref[~got]).max() / np.abs(h_ref).max() < 3e-2
+                assert np.abs(aux - h_ref[~got]).max() / np.abs(h_ref).max() < tol["h"]
                 rep["h"] = float(eh)
         elif single:
             h_next = _f64(out.hidden_in(l + 1))
@@ -121,9 +127,9 @@ def _check_layer(w, out, l, schedule, lo=None, hi=None, tag="", shape=SHAPE):
     elif single:
         rep["h"] = float(np.abs(_f64(out.hidden_out) - h_ref).max() / np.abs(h_ref).max())
     print(tag, rep, flush=True)
-    assert ek < 2e-2 and ev < 2e-2, rep
-    assert es < 2e-2, rep
-    assert rep.get("h", 0.0) < 3e-2, rep
+    assert ek < tol["kv"] and ev < tol["kv"], rep
+    assert es < tol["s"], rep
+    assert rep.get("h", 0.0) < tol["h"], rep
     return rep
 
 
@@ -153,6 +159,26 @@ def test_headline_3376(model7b):
     _, out2 = _run(model, wl, flags=0)
     assert torch.equal(snap[0], out2.logits) and torch.equal(snap[1], out2.kept_pos(31))
     assert torch.equal(snap[2], out2.k(31))
+
+
+def test_headline_3376_with_8bit_projections(model7b):
+    """The headline workload on the same weights with the projections in the 8-bit variant."""
+    w, _ = model7b
+    wl = synth.WORKLOADS["7b_3376_fp8"]
+    model = B.Model(wl.shape.as_dict(), w, DEV)
+    try:
+        inp, out = _run(model, wl)
+        assert sorted(set(out.n_tokens), reverse=True) == [3376, 2364, 1182, 355]
+        _check_structure(wl, inp, out)
+        for l in (0, 15, 31):
+            _check_layer(w, out, l, wl.schedule, tag="7b_3376_fp8", shape=wl.shape, gemm8=True, tol=TOL8)
+        _check_logits(w, out, shape=wl.shape)          # final norm and LM head are the 16-bit ones
+        snap = (out.logits.clone(), out.kept_pos(31).clone(), out.k(31).clone())
+        _, out2 = _run(model, wl, flags=0)
+        assert torch.equal(snap[0], out2.logits) and torch.equal(snap[1], out2.kept_pos(31))
+        assert torch.equal(snap[2], out2.k(31))
+    finally:
+        model.close()
 
 
 def test_needles_3376(model7b):

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(B._SIGNATURES), "binding and header disagree"
-    assert lib.lazyllm_abi_version() == 2
+    assert lib.lazyllm_abi_version() == 3
     assert lib.lazyllm_strerror(-1) == b"invalid argument"
     assert lib.lazyllm_strerror(-2) == b"workspace or output buffer too small"
 
@@ -91,6 +91,17 @@ def test_sizes_are_positive_and_monotone():
     for bad_kv in (3, 1, 5, -1):                   # 3 does not divide 4; 1 x 64 is not a multiple of 128
         gqa["n_kv_heads"] = bad_kv
         assert B.lazyllm_workspace_bytes(B.make_config(gqa), 512, 1, 512) == 0, bad_kv
+    # 8-bit projections: a larger workspace (codes and scales of the activations); shapes whose
+    # widths are not multiples of 256 and unknown arithmetic codes are refused
+    f8 = dict(synth.TINY.as_dict())
+    f8["gemm_dtype"] = 1
+    assert B.lazyllm_workspace_bytes(B.make_config(f8), 512, 1, 512) > w1
+    assert B.lazyllm_workspace_bytes(B.make_config(synth.TINY_FP8.as_dict()), 512, 1, 512) > w1
+    f8["d_model"], f8["n_heads"] = 384, 6
+    assert B.lazyllm_workspace_bytes(B.make_config(f8), 512, 1, 512) == 0
+    f8 = dict(synth.TINY.as_dict())
+    f8["gemm_dtype"] = 2
+    assert B.lazyllm_workspace_bytes(B.make_config(f8), 512, 1, 512) == 0
 
 
 def test_null_arguments_return_einval_without_touching_the_gpu():
