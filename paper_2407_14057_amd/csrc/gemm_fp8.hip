@@ -231,41 +231,53 @@ gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
     __builtin_amdgcn_sched_barrier(0);                                                         \
   } while (0)
 
+  // NSTAGE LDS stages: the copies of K step t + NSTAGE - 1 are issued while step t computes, so
+  // NSTAGE - 1 steps are in flight.  The 128-row tile has room for three stages (48 KB each); it
+  // is chosen for launches of few workgroups, where one step in flight per CU (a round trip to
+  // HBM per 48 KB) would be the bound.  Waiting for "all but the newest PEND copies" is enough
+  // to know that the next step has landed: the counter retires copies in issue order.
+  constexpr int NSTAGE = TM == 1 ? 3 : 2;
+  constexpr int PEND = (NSTAGE - 2) * NCOPY;
   const int KT = K / F8_BK;
-  issue(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int s0 = 0; s0 < NSTAGE - 1; ++s0) issue(s0, (s0 < KT ? s0 : KT - 1) * F8_BK);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PEND) : "memory");
   __syncthreads();
   if (group == 1) LZ_PHASE_END();                 // the second group starts one phase later
   const bool idle_wave = m0 + wm * TM * 32 >= M;
+  int st_cur = 0, st_fill = NSTAGE - 1;
   for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = lds + (kt & 1) * STAGE_BYTES;
-    // the last step copies itself again into the stage nobody reads any more (no branch in the
-    // MFMA stream; the copy is drained by the waits below like any other)
-    const int k_next = (kt + 1 < KT ? kt + 1 : kt) * F8_BK;
+    const char* cur = lds + st_cur * STAGE_BYTES;
+    // past the last step the copies fetch the last step again, into a stage nobody reads any
+    // more (no branch in the MFMA stream; they are drained by the waits like any other)
+    const int k_next = (kt + NSTAGE - 1 < KT ? kt + NSTAGE - 1 : KT - 1) * F8_BK;
     if (idle_wave) {                               // all rows past M: copies and barriers only
       LZ_PHASE_END();
 #pragma unroll
-      for (int q = 0; q < NCOPY; ++q) issue_one((kt + 1) & 1, k_next, q);
+      for (int q = 0; q < NCOPY; ++q) issue_one(st_fill, k_next, q);
       LZ_PHASE_END();
-      if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (group == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PEND) : "memory");
       LZ_PHASE_END();
-      if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (group == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PEND) : "memory");
       LZ_PHASE_END();
-      continue;
+    } else {
+      LZ_MEM_PHASE(cur, 0);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      LZ_PHASE_END();
+      LZ_COMPUTE_COPY_PHASE(st_fill, k_next);
+      LZ_PHASE_END();
+      LZ_MEM_PHASE(cur, 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (group == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PEND) : "memory");
+      LZ_PHASE_END();
+      LZ_COMPUTE_PHASE();
+      if (group == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PEND) : "memory");
+      LZ_PHASE_END();
     }
-    LZ_MEM_PHASE(cur, 0);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    LZ_PHASE_END();
-    LZ_COMPUTE_COPY_PHASE((kt + 1) & 1, k_next);
-    LZ_PHASE_END();
-    LZ_MEM_PHASE(cur, 1);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    LZ_PHASE_END();
-    LZ_COMPUTE_PHASE();
-    if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    LZ_PHASE_END();
+    st_cur = st_cur + 1 == NSTAGE ? 0 : st_cur + 1;
+    st_fill = st_fill + 1 == NSTAGE ? 0 : st_fill + 1;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // (the refetches of the last step)
   if (group == 0) LZ_PHASE_END();
 #undef LZ_MEM_PHASE
 #undef LZ_FRAG
@@ -360,14 +372,16 @@ hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const f
     if (ea_in == nullptr || (ea.head_dim != 64 && ea.head_dim != 128) || N != ea.d_model + 2 * kvd)
       return hipErrorInvalidValue;
   }
-  // One workgroup per CU is resident, so a launch takes ceil(tiles / 256) rounds of one tile's K
-  // loop: 128-row tiles (half the work each) when that is fewer half-rounds than 256-row tiles
-  // need whole ones.  Every output element sees the same sequence of additions either way.
+  // One workgroup per CU is resident.  A launch whose 128-row tiles still fit one round of the
+  // 256 CUs takes those (half the K-loop work per workgroup, twice the workgroups); anything
+  // larger takes 256-row tiles, which reuse each W slab for twice the rows (measured: gate/up at
+  // 2364 rows 214 us against 262 us with 128-row tiles, although the latter need fewer
+  // half-rounds).  Every output element sees the same sequence of additions either way.
   const int tiles_n = N / BN;
-  const long t256 = (long)((M + 255) / 256) * tiles_n, t128 = (long)((M + 127) / 128) * tiles_n;
-  const bool tall = (t128 + 255) / 256 >= 2 * ((t256 + 255) / 256);
+  const long t128 = (long)((M + 127) / 128) * tiles_n;
+  const bool tall = t128 > 256;
   const int BM = tall ? 256 : 128;
-  const int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  const int LDS_BYTES = (tall ? 2 : 3) * (BM + BN) * ROW_BYTES;
   const int tiles_m = (M + BM - 1) / BM;
   ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
   ea.stage_out = (epilogue == EPI_QKV_ROPE)
@@ -384,7 +398,7 @@ hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const f
     if (!attr_set) {                                                                             \
       hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
                                          hipFuncAttributeMaxDynamicSharedMemorySize,             \
-                                         2 * (128 * TMV + BN) * ROW_BYTES);                      \
+                                         (TMV == 1 ? 3 : 2) * (128 * TMV + BN) * ROW_BYTES);                      \
       if (e != hipSuccess) return e;                                                             \
       attr_set = true;                                                                           \
     }                                                                                            \
