@@ -7,7 +7,7 @@
 //
 // Two kernels: the row quantiser (16-bit floats -> codes + scale) and the tile kernel.
 #include "common.h"
-#include "gemm_epilogue.h"
+#include "gemm_shared.h"
 
 namespace lz {
 
@@ -115,23 +115,7 @@ gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
   const int group = wave >> 2;                    // waves w and w+4 share a SIMD
 
   int tile_m, tile_n;
-  {
-    // consecutive workgroup ids go to different XCDs: give each XCD a contiguous run of tiles,
-    // walked in bands of group_m tile rows so that its L2 sees each W column block once per band
-    const int T = tiles_m * tiles_n;
-    const int pid = blockIdx.x;
-    const int xcd = pid & 7, local = pid >> 3;
-    const int per = (T + 7) >> 3;
-    const int tall = (T & 7) == 0 ? 8 : (T & 7);
-    const int np = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    const int width = group_m * tiles_n;
-    const int grp = np / width;
-    const int first_m = grp * group_m;
-    const int gsz = min(tiles_m - first_m, group_m);
-    const int in_group = np - grp * width;
-    tile_m = first_m + in_group % gsz;
-    tile_n = in_group / gsz;
-  }
+  workgroup_tile((int)blockIdx.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int crow = lane >> 3;
@@ -312,48 +296,7 @@ gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
     gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra);
     return;
   }
-  // ---- staged output: tile -> LDS in the MFMA layout's order, LDS -> global in whole rows
-  constexpr int BNO = BN, NCH = BNO / 8;
-  __syncthreads();                                  // every wave is done reading the stages
-  if (EPI == EPI_RESIDUAL) {
-    constexpr int RPI = 64 / NCH, R_INSTR = BM / RPI / NWAVES;
-#pragma unroll
-    for (int q = 0; q < R_INSTR; ++q) {
-      const int instr = wave * R_INSTR + q;
-      const int rr = instr * RPI + lane / NCH;
-      const int chunk = (lane % NCH) ^ (rr & (NCH - 1));
-      int gr = m0 + rr;
-      gr = gr < M ? gr : M - 1;
-      g2l16(R + (size_t)gr * ldc + n0 + chunk * 8, lds + instr * 1024);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-  }
-  gemm_epilogue<TM, TN, EPI, true, NCH>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, nullptr, lds);
-  __syncthreads();
-  uint16_t* obase;
-  int old;
-  const int32_t* orow = nullptr;                    // output row of tile row r, if not m0 + r
-  if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
-    const int dq = ra.d_model, kvd = ra.kv_dim > 0 ? ra.kv_dim : dq;
-    const int region = n0 < dq ? 0 : n0 < dq + kvd ? 1 : 2;   // the tile lies inside q, k or v
-    if (region == 2 && ra.v == nullptr) return;
-    obase = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) +
-            (n0 - (region == 0 ? 0 : region == 1 ? dq : dq + kvd));
-    old = region == 0 ? dq : kvd;
-    if (region == 1) orow = ra.k_row;
-  } else {
-    obase = C + n0;
-    old = ldc;
-  }
-  for (int idx = threadIdx.x; idx < BM * NCH; idx += NWAVES * 64) {
-    const int r = idx / NCH, ch = idx % NCH;
-    if (m0 + r < M) {
-      const size_t dr = orow != nullptr ? (size_t)orow[m0 + r] : (size_t)(m0 + r);
-      *(uint4*)(obase + dr * old + ch * 8) =
-          *(const uint4*)(lds + r * (NCH * 16) + ((ch ^ (r & (NCH - 1))) << 4));
-    }
-  }
+  staged_tile_out<TM, TN, EPI, BM, BN, NWAVES>(acc, C, R, M, ldc, m0, n0, wm, wn, wave, lane, ra, nullptr, lds);
 }
 
 hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const float* sw, void* C,

@@ -1,5 +1,6 @@
-// Epilogues of the GEMM kernels (shared by the 16-bit and the 8-bit tile kernels): what happens to
-// a wave's TM x TN accumulator blocks after the K loop.
+// Pieces shared by the 16-bit and the 8-bit tile kernels: the workgroup -> tile map, what happens to
+// a wave's TM x TN accumulator blocks after the K loop (the epilogues), and the tile's way out
+// through LDS.
 #pragma once
 #include "common.h"
 
@@ -215,6 +216,81 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
         ss += __shfl_xor(ss, 32, 64);
         if (lane < 32) atomicAdd(ra.ssq_out + row, ssq_to_fixed(ss));
       }
+    }
+  }
+}
+
+// ---- workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with
+// its own L2), so ids are first regrouped per XCD, then walked in bands of group_m tile rows so
+// that concurrently running tiles share A and W slabs in L2.
+__device__ __forceinline__ void workgroup_tile(int pid, int tiles_m, int tiles_n, int group_m,
+                                               int& tile_m, int& tile_n) {
+  const int T = tiles_m * tiles_n;
+  const int xcd = pid & 7, local = pid >> 3;
+  const int per = (T + 7) >> 3;
+  const int tall = (T & 7) == 0 ? 8 : (T & 7);
+  const int np = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+  const int width = group_m * tiles_n;
+  const int group = np / width;
+  const int first_m = group * group_m;
+  const int gsz = min(tiles_m - first_m, group_m);
+  const int in_group = np - group * width;
+  tile_m = first_m + in_group % gsz;
+  tile_n = in_group / gsz;
+}
+
+// ---- staged output of a BM x BN tile held by NWAVES waves of TM x TN blocks (see stage_off):
+// tile -> LDS in the MFMA layout's order, LDS -> global in whole rows.  `lds` is the kernel's
+// dynamic LDS, free once every wave has left the K loop (the caller's copies have landed).
+template <int TM, int TN, int EPI, int BM, int BN, int NWAVES>
+__device__ __forceinline__ void staged_tile_out(floatx16_t (&acc)[TM][TN], uint16_t* __restrict__ C,
+                                                const uint16_t* __restrict__ R, int M, int ldc, int m0,
+                                                int n0, int wm, int wn, int wave, int lane,
+                                                const EpiArgs& ra, const float* rs, char* lds) {
+  // BNO = output columns of the tile, NCH = its 16-byte chunks per row
+  constexpr int BNO = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int NCH = BNO / 8;
+  static_assert((NCH & (NCH - 1)) == 0, "chunks per row must be a power of two");
+  __syncthreads();                                  // every wave is done reading the stages
+  if (EPI == EPI_RESIDUAL) {
+    // the residual tile comes in the same way (whole rows, straight into LDS); a wave
+    // instruction covers 64 / NCH rows
+    constexpr int RPI = 64 / NCH, R_INSTR = BM / RPI / NWAVES;
+#pragma unroll
+    for (int q = 0; q < R_INSTR; ++q) {
+      const int instr = wave * R_INSTR + q;
+      const int rr = instr * RPI + lane / NCH;
+      const int chunk = (lane % NCH) ^ (rr & (NCH - 1));
+      int gr = m0 + rr;
+      gr = gr < M ? gr : M - 1;
+      g2l16(R + (size_t)gr * ldc + n0 + chunk * 8, lds + instr * 1024);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  gemm_epilogue<TM, TN, EPI, true, NCH>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs, lds);
+  __syncthreads();
+  uint16_t* obase;
+  int old;
+  const int32_t* orow = nullptr;                    // output row of tile row r, if not m0 + r
+  if (EPI == EPI_QKV_ROPE64 || EPI == EPI_QKV_ROPE128) {
+    const int dq = ra.d_model, kvd = ra.kv_dim > 0 ? ra.kv_dim : dq;
+    const int region = n0 < dq ? 0 : n0 < dq + kvd ? 1 : 2;   // the tile lies inside q, k or v
+    if (region == 2 && ra.v == nullptr) return;     // (the transposed copy went out with the epilogue)
+    obase = (region == 0 ? ra.q : region == 1 ? ra.k : ra.v) +
+            (n0 - (region == 0 ? 0 : region == 1 ? dq : dq + kvd));
+    old = region == 0 ? dq : kvd;
+    if (region == 1) orow = ra.k_row;
+  } else {
+    obase = C + (EPI == EPI_SWIGLU ? n0 / 2 : n0);
+    old = ldc;
+  }
+  for (int idx = threadIdx.x; idx < BM * NCH; idx += NWAVES * 64) {
+    const int r = idx / NCH, ch = idx % NCH;
+    if (m0 + r < M) {
+      const size_t dr = orow != nullptr ? (size_t)orow[m0 + r] : (size_t)(m0 + r);
+      *(uint4*)(obase + dr * old + ch * 8) =
+          *(const uint4*)(lds + r * (NCH * 16) + ((ch ^ (r & (NCH - 1))) << 4));
     }
   }
 }
