@@ -682,13 +682,21 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
   if (vt_ld < (n_keys + 63) / 64 * 64) return hipErrorInvalidValue;
   if (z != nullptr && (zstat == nullptr || z_ld < (n_keys + 63) / 64 * 64)) return hipErrorInvalidValue;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)head_dim);
-  // Few queries (a decoding step's one new token and a handful of revived ones) make few
-  // workgroups: split the keys so that about 512 are in flight, each with at least two key tiles.
+  unsigned* counters = nullptr;                      // (the one-query kernel's tickets: end of the workspace)
+  if (split_ws != nullptr) {
+    if (split_ws_bytes < DATT_COUNTER_BYTES || (size_t)(n_heads / kv_group) * 4 > DATT_COUNTER_BYTES)
+      return hipErrorInvalidValue;
+    split_ws_bytes -= DATT_COUNTER_BYTES;
+    counters = (unsigned*)((char*)split_ws + split_ws_bytes);
+  }
+  // A step's queries (the new token and the revived ones) make few workgroups: split the keys so
+  // that about 512 are in flight, each with at least two key tiles, as far as the workspace for
+  // the splits' partial results reaches.
   const int qblocks = (M + 127) / 128, d_model = n_heads * head_dim;
   int n_splits = 1;
-  if (split_ws != nullptr && qblocks == 1) {
+  if (split_ws != nullptr) {
     const int tiles = (n_keys + 63) / 64;
-    n_splits = 512 / n_heads;
+    n_splits = 512 / (n_heads * qblocks);
     if (n_splits > tiles / 2) n_splits = tiles / 2;
     if (n_splits > 16) n_splits = 16;
     const size_t per_split = (size_t)M * ((size_t)d_model * 4 + (size_t)n_heads * 8);
@@ -696,13 +704,6 @@ hipError_t launch_decode_attention(const void* q, const int32_t* qpos, int M, co
     if (n_splits < 1) n_splits = 1;
   }
   // only the new token runs the layer: the streaming kernel, about four 64-key chunks per workgroup
-  unsigned* counters = nullptr;
-  if (split_ws != nullptr) {
-    if (split_ws_bytes < DATT_COUNTER_BYTES || (size_t)(n_heads / kv_group) * 4 > DATT_COUNTER_BYTES)
-      return hipErrorInvalidValue;
-    split_ws_bytes -= DATT_COUNTER_BYTES;
-    counters = (unsigned*)((char*)split_ws + split_ws_bytes);
-  }
   const bool one_query = M == 1 && split_ws != nullptr && (kv_group == 1 || kv_group == 2 || kv_group == 4);
   if (one_query) {
     const int chunks = (n_keys + 63) / 64;
