@@ -1034,13 +1034,18 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     else if (N % 256 == 0 && big_tiles >= 150 && big_tiles <= 205 && tiles192 <= 256 &&
              epilogue != EPI_QKV_ROPE) cfg = 7;
     else if (N % 256 == 0 && big_tiles >= 150) cfg = 5;
-    else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = (N % 256 == 0) ? 4 : 0;
+    // rotary epilogue with 128-wide heads: a wave must hold whole heads (128 columns), so the
+    // 128x128 tile is cut into 4 waves of 32x128 (QKV at 229 rows: 46 us against 67 us for the
+    // 128x256 tile of 64x128 waves, which makes half as many workgroups; level from 1000 rows on)
+    else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = 3;
     else cfg = 2;
     if (cfg == 0) return hipErrorInvalidValue;
   }
   switch (cfg) {
     case 2:                                             // 128x128, 4 waves of 64x64
             return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 3:                                             // 128x128, 4 waves of 32x128 (whole heads per wave)
+            return launch_cfg<4, 1, 1, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 5:                                             // 256x256, 8 waves of 64x128, ping-pong

@@ -100,6 +100,34 @@ def test_gemm_skinny(M, N, K, epi):
     assert torch.equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (229, 768, 256), (700, 1536, 704)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_tile_of_32_row_waves(M, N, K, epi):
+    """The 128x128 tile cut into four waves of 32x128 (forced; the form the rotary epilogue with
+    128-wide heads uses below the large-tile threshold) gives the bits of the 64x64-wave tile."""
+    rng = np.random.default_rng(M * 3 + N + K + epi)
+    A = _rand_bf16(rng, (M, K)); W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    R = _rand_bf16(rng, (M, N))
+    outs = []
+    for cfg in (2, 3):
+        if epi == B.EPI_SWIGLU:
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, epi | (cfg << 8))
+        else:
+            Cout = R.clone()
+            B.lazyllm_op_gemm(A, W, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N, epi | (cfg << 8))
+        torch.cuda.synchronize()
+        outs.append(Cout)
+    assert torch.equal(outs[0], outs[1])
+    acc = _f64(A) @ _f64(W).T
+    if epi == B.EPI_SWIGLU:
+        blocks = acc.reshape(M, N // 64, 2, 32)
+        ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+    else:
+        ref = acc + (_f64(R) if epi == B.EPI_RESIDUAL else 0.0)
+    _assert_bf16_close(_f64(outs[1]), ref, 1.0, "gemm 32x128 waves")
+
+
 def test_gemm_skinny_refuses_more_than_32_rows():
     A = torch.zeros(33, 64, dtype=torch.bfloat16, device=DEV)
     W = torch.zeros(128, 64, dtype=torch.bfloat16, device=DEV)
