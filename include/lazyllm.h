@@ -63,8 +63,10 @@ typedef enum lazyllm_status {
  * the activations row by row in front of each projection, OFP8 E4M3 codes
  * with one fp32 scale per row; attention, normalisation, scoring, selection
  * and the LM head are unchanged.  It needs d_model % 256 == 0,
- * (d_model + 2 * n_kv_heads * head_dim) % 256 == 0 and d_ffn <= 16384, and
- * such a model has no decoding steps (lazyllm_generation_create refuses it). */
+ * (d_model + 2 * n_kv_heads * head_dim) % 256 == 0 and d_ffn <= 16384.  The
+ * decoding steps always compute in 16-bit floating point (one token row is
+ * bound by streaming the weights, not by the matrix cores); on such a model
+ * they continue from the K,V and Aux Cache the 8-bit prefill left. */
 typedef struct lazyllm_config {
   int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
   float rms_eps, rope_theta;

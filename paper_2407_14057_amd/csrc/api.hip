@@ -732,7 +732,6 @@ int lazyllm_generation_create(const lazyllm_model* m, const lazyllm_keep* sched,
   if (m == nullptr || prefill == nullptr || state == nullptr || out == nullptr) return LAZYLLM_EINVAL;
   if (((uintptr_t)state & 255) != 0) return LAZYLLM_EINVAL;
   const lazyllm_config* c = &m->cfg;
-  if (c->gemm_dtype != 0) return LAZYLLM_EINVAL;     // the decoding steps exist in 16-bit arithmetic only
   if (!schedule_ok(c->n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
   if (prefill->batch != 1 || prefill->n_layers != c->n_layers) return LAZYLLM_EINVAL;
   const int n_prompt = prefill->n_tokens[0];

@@ -58,7 +58,7 @@ def _f(t):
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def _check_caches(shape, view, g16, n_tot, prune_layers):
+def _check_caches(shape, view, g16, n_tot, prune_layers, kv_tol=3e-2, aux_tol=0.05):
     L, d = shape.n_layers, shape.d_model
     worst = 0.0
     for l in range(L):
@@ -80,14 +80,17 @@ def _check_caches(shape, view, g16, n_tot, prune_layers):
             ia = np.nonzero(ha)[0]
             if len(ia):
                 a, ra = _f(view["aux_h"][l])[ia], g16.aux_h[l][ia]
-                assert np.abs(a - ra).max() <= 0.05 * max(1.0, np.abs(ra).max())
+                assert np.abs(a - ra).max() <= aux_tol * max(1.0, np.abs(ra).max())
         else:
             assert view["aux_h"][l] is None
-    assert worst < 3e-2, worst
+    assert worst < kv_tol, worst
     return worst
 
 
-def run_case(shape, wb, model, ids, schedule, new_tokens, extra=3, label="", band=1e-3, s_tol=(2e-2, 5e-2)):
+def run_case(shape, wb, model, ids, schedule, new_tokens, extra=3, label="", band=1e-3, s_tol=(2e-2, 5e-2),
+             gemm8=False, logit_tol=2e-2, kv_tol=3e-2, aux_tol=0.05):
+    """gemm8: the model's prefill ran its projections in the 8-bit variant and so does the checker's;
+    the decoding steps are 16-bit on both sides."""
     sd, L = shape.as_dict(), shape.n_layers
     ids = np.asarray(ids)
     out = model.prefill(torch.from_numpy(ids.astype(np.int32)).to(DEV), schedule)
@@ -95,8 +98,8 @@ def run_case(shape, wb, model, ids, schedule, new_tokens, extra=3, label="", ban
     assert out.status == 0
     prune_layers = [l for l, p in schedule if p < 1000]
     forced = {p: out.kept_pos(p).cpu().numpy().astype(np.int64) for p in prune_layers}
-    ref16 = O.prefill(sd, wb, ids, schedule, bf16_storage=True, forced_keep=forced)
-    ref64 = O.prefill(sd, wb, ids, schedule, forced_keep=forced)
+    ref16 = O.prefill(sd, wb, ids, schedule, bf16_storage=True, forced_keep=forced, gemm8=gemm8)
+    ref64 = O.prefill(sd, wb, ids, schedule, forced_keep=forced, gemm8=gemm8)
     cap = len(ids) + len(new_tokens) + extra
     gen = B.Generation(model, schedule, out, cap)
     g16 = D.Generation(sd, wb, schedule, ref16, len(ids), cap, bf16_storage=True)
@@ -108,7 +111,7 @@ def run_case(shape, wb, model, ids, schedule, new_tokens, extra=3, label="", ban
         pos = out.kept_pos(l).long()
         assert torch.equal(view["k"][l][pos], out.k(l).reshape(len(pos), -1))
         assert torch.equal(view["vt"][l].t()[pos], out.v(l).reshape(len(pos), -1))
-    _check_caches(shape, view, g16, len(ids), prune_layers)
+    _check_caches(shape, view, g16, len(ids), prune_layers, kv_tol, aux_tol)
 
     report = {"revived": [], "undecided": 0, "logit_err": 0.0, "s16": 0.0, "s64": 0.0}
     for t, tok in enumerate(new_tokens):
@@ -150,10 +153,10 @@ def run_case(shape, wb, model, ids, schedule, new_tokens, extra=3, label="", ban
         logits = so.logits.cpu().numpy().astype(np.float64)
         rng_ = r64.logits.max() - r64.logits.min()
         report["logit_err"] = max(report["logit_err"], float(np.abs(logits - r64.logits).max() / rng_))
-        _check_caches(shape, gen.view(), g16, n_tot, prune_layers)
+        _check_caches(shape, gen.view(), g16, n_tot, prune_layers, kv_tol, aux_tol)
     print(label, report)
     assert report["s16"] < s_tol[0] and report["s64"] < s_tol[1], report
-    assert report["logit_err"] <= 2e-2, report
+    assert report["logit_err"] <= logit_tol, report
     gen.close()
     return report
 

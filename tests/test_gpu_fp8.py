@@ -281,9 +281,14 @@ def test_fp8_runs_are_bit_identical_and_batches_are_independent(tiny8):
         assert torch.equal(single.logits[0], snap[i])
 
 
-def test_fp8_model_has_no_decoding_steps(tiny8):
+def test_decoding_steps_after_an_8bit_prefill(tiny8):
+    """Decoding steps compute in 16-bit arithmetic on every model; after a prefill with 8-bit
+    projections they continue from the K,V and Aux Cache that prefill left.  Same comparison as
+    for the 16-bit model, the checker's prefill in the 8-bit mode, tolerances of the 8-bit prefill
+    where its results are compared (caches), wider bands where they feed the steps."""
+    from test_gpu_decode import run_case
     shape, wb, model = tiny8
-    ids = synth.make_prompt(64, shape.vocab, 1)
-    out = _run(model, ids, [])
-    with pytest.raises(B.LazyLLMError):
-        B.Generation(model, [], out, 80)
+    ids = synth.make_prompt(300, shape.vocab, 77)
+    rep = run_case(shape, wb, model, ids, [(1, 800), (3, 400)], [5, 17, 900, 3], label="decode after fp8 prefill",
+                   band=3e-2, s_tol=(3e-2, 3e-2), gemm8=True, logit_tol=3e-2, kv_tol=1e-1, aux_tol=0.1)
+    assert sum(sum(r) for r in rep["revived"]) > 0            # revivals happened
