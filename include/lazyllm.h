@@ -350,6 +350,16 @@ int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R
                             uint64_t* ssq_clear, void* workspace, size_t ws_bytes,
                             void* hip_stream);
 
+/* Weight layout of the decoding steps' weight-streaming kernel (for callers that cannot change
+ * the model: measurement and tests).  W [N, K] bf16 (device, row stride ldw elements) is rewritten
+ * into `packed` (N * K * 2 bytes, device, 16-byte aligned): for every group of 128 output
+ * features and every 32-element K step the 8 KB that the kernel copies into one LDS slot, stored
+ * contiguously, steps of a group one after the other -- each wave then reads one sequential
+ * stream.  N % 128 == 0, K % 64 == 0.  lazyllm_op_gemm reads such a weight when bit 30 of
+ * `epilogue` is set together with the forced configuration 8 (ldw is then ignored). */
+int lazyllm_op_pack_weight_stream(const void* W, int32_t N, int32_t K, int32_t ldw, void* packed,
+                                  void* hip_stream);
+
 /* ---- 8-bit floating point variant of the projections' GEMM --------------------------------
  * An extension for the gfx950 8-bit matrix instructions; the paper itself computes in 16-bit
  * floating point (Sec. 5, implementation details).  Operands are OFP8 E4M3 codes (OCP 8-bit

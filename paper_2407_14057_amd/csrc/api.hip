@@ -236,6 +236,8 @@ struct lazyllm_model {
   const void *embed, *final_norm, *lm_head;
   std::vector<const void*> attn_norm, ffn_norm, wqkv, wo, wgu, wdown;
   // 8-bit variant (cfg.gemm_dtype == 1): E4M3 codes of the same four matrices and one scale per row
+  // the same four matrices in the layout of the decoding steps' weight-streaming kernel
+  std::vector<const void*> wqkv_s, wo_s, wgu_s, wdown_s;
   std::vector<const void*> wqkv8, wo8, wgu8, wdown8;
   std::vector<const float*> sqkv, so, sgu, sdown;
 };
@@ -316,8 +318,8 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
   m->cfg = *cfg;
   m->f_pad = ffn_padded(cfg->d_ffn);
   const size_t d = cfg->d_model, f = cfg->d_ffn, fp = m->f_pad, V = cfg->vocab, kvd = kv_dim(cfg);
-  const size_t per_layer = align_up(d * 2) * 2 + align_up((d + 2 * kvd) * d * 2) + align_up(d * d * 2) +
-                           align_up(2 * fp * d * 2) + align_up(d * fp * 2);
+  const size_t per_layer = align_up(d * 2) * 2 + 2 * (align_up((d + 2 * kvd) * d * 2) + align_up(d * d * 2) +
+                                                      align_up(2 * fp * d * 2) + align_up(d * fp * 2));
   const bool f8 = cfg->gemm_dtype == 1;
   const size_t per_layer8 = !f8 ? 0 : align_up((d + 2 * kvd) * d) + align_up(d * d) + align_up(2 * fp * d) +
                                           align_up(d * fp) + align_up((d + 2 * kvd) * 4) + 2 * align_up(d * 4) +
@@ -369,6 +371,18 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
     p = take(d * fp * 2);                          // down, K zero-padded to f_pad
     chk(launch_copy_rows(w->w_down[l], p, (int)d, (int)f, (int)f, (int)fp, st));
     m->wdown.push_back(p);
+    {
+      // ... and once more as sequential streams for the decoding steps (see launch_pack_stream)
+      auto stream_copy = [&](const void* src, size_t rows, size_t K, std::vector<const void*>& dst) {
+        char* ps = take(rows * K * 2);
+        chk(launch_pack_stream(src, (int)rows, (int)K, (int)K, ps, st));
+        dst.push_back(ps);
+      };
+      stream_copy(m->wqkv[l], d + 2 * kvd, d, m->wqkv_s);
+      stream_copy(m->wo[l], d, d, m->wo_s);
+      stream_copy(m->wgu[l], 2 * fp, d, m->wgu_s);
+      stream_copy(m->wdown[l], d, fp, m->wdown_s);
+    }
     if (f8) {
       // the stored matrices (gains folded in, fused, padded) quantised row by row
       auto quant = [&](const void* src, size_t rows, size_t K, std::vector<const void*>& codes,
@@ -910,7 +924,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     ra.d_model = d; ra.head_dim = hd; ra.kv_dim = kvd;
     ra.vt = (uint16_t*)(S + gl.vt[l]); ra.vt_ld = gl.vt_ld; ra.vt_col = rpos;
     ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
-    ra.skinny = 1;
+    ra.skinny = 1; ra.w_stream = m->wqkv_s[l];
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, M, 2.0 * M * (dd + 2.0 * kvd) * dd,
            launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, d + 2 * kvd, d, d, d, 0, EPI_QKV_ROPE, st, &ra,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -920,7 +934,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
                                    score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld,
                                    W + ws.att_ws, decode_attention_workspace_bytes(d, H), kv_group));
     EpiArgs eo{};
-    eo.ssq_out = ssq_ffn; eo.skinny = 1;
+    eo.ssq_out = ssq_ffn; eo.skinny = 1; eo.w_stream = m->wo_s[l];
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, M, 2.0 * M * dd * dd,
            launch_gemm(W + ws.o, m->wo[l], h, h, M, d, d, d, d, d, EPI_RESIDUAL, st, &eo,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -932,12 +946,12 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     eg.sf_cu = nullptr; eg.sf_cu_z = nullptr;
     eg.sf_n_single = n_tot; eg.sf_heads = H; eg.sf_z_ld = z_ld;
     eg.sf_max_rows = n_tot; eg.sf_batch = 1;
-    eg.skinny = 1;
+    eg.skinny = 1; eg.w_stream = m->wgu_s[l];
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, M, 2.0 * M * 2.0 * (double)c->d_ffn * dd,
            launch_gemm(h, m->wgu[l], W + ws.act, nullptr, M, 2 * fp, d, d, d, fp, EPI_SWIGLU, st, &eg,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
     EpiArgs ed{};
-    ed.ssq_out = ssq_attn; ed.skinny = 1;
+    ed.ssq_out = ssq_attn; ed.skinny = 1; ed.w_stream = m->wdown_s[l];
     LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, M, 2.0 * M * (double)c->d_ffn * dd,
            launch_gemm(W + ws.act, m->wdown[l], h, h, M, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -1032,6 +1046,15 @@ int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R
   const bool sk_ok = !ssq_in && !ssq_clear;
   LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, &ea,
                      sk_ok ? workspace : nullptr, sk_ok ? ws_bytes : 0));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_pack_weight_stream(const void* W, int32_t N, int32_t K, int32_t ldw, void* packed,
+                                  void* hip_stream) {
+  if (!W || !packed || N <= 0 || K <= 0 || N % 128 != 0 || K % 64 != 0 || ldw % 8 != 0 || ldw < K ||
+      ((uintptr_t)W & 15) != 0 || ((uintptr_t)packed & 15) != 0)
+    return LAZYLLM_EINVAL;
+  LZ_HIP(launch_pack_stream(W, N, K, ldw, packed, (hipStream_t)hip_stream));
   return LAZYLLM_OK;
 }
 

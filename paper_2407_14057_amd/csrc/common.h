@@ -155,6 +155,12 @@ struct EpiArgs {
   // the caller keeps the ticket counters at the end of the GEMM workspace zeroed
   // (launch_gemm_counters_clear once before the first use): M <= 32 may take the skinny kernel
   int skinny;
+  // the W argument is in the weight-streaming kernel's own layout (launch_pack_stream); only that
+  // kernel can read it, so the launch fails where another kernel would be chosen
+  int w_packed;
+  // the same weight in that layout, if the caller has one: used (instead of W) whenever the
+  // weight-streaming kernel is chosen
+  const void* w_stream;
 };
 constexpr float SSQ_FIX = 4294967296.0f;      // 2^32
 __device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {
@@ -168,6 +174,7 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
                        const EpiArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
 
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st);
+hipError_t launch_pack_stream(const void* W, int N, int K, int ldw, void* Wp, hipStream_t st);
 
 // 8-bit floating point variant (gemm_fp8.hip): E4M3 codes with one fp32 scale per row.
 hipError_t launch_quantize_rows_f8(const void* x, int rows, int K, int ldx, void* q, int ldq,

@@ -778,18 +778,25 @@ gemm_skinny_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ 
 
   // copy plan: instruction t fills rows 16t..16t+15 of the slot, lane p row p/4, stored chunk
   // p%4 = logical chunk (p%4) ^ swz32(row)
+  // With ra.w_packed the weight is stored as the sequence of these slot images (see
+  // pack_stream_kernel): a step's 8 KB are contiguous in memory and a wave's steps follow each
+  // other, so every wave reads one sequential stream instead of 64-byte pieces of 128 rows.
   char* ring = lds + wave * 2 * SKN_SLOT;
+  const bool packed = ra.w_packed != 0;
   uint32_t w_off[SKN_DMA];
 #pragma unroll
   for (int t = 0; t < SKN_DMA; ++t) {
     const int tr = t * 16 + (lane >> 2);
-    w_off[t] = (uint32_t)(((size_t)(n0 + tr) * ldw + (((lane & 3) ^ swz32(tr)) * 8)) * 2);
+    w_off[t] = packed ? (uint32_t)(t * 1024 + lane * 16)
+                      : (uint32_t)(((size_t)(n0 + tr) * ldw + (((lane & 3) ^ swz32(tr)) * 8)) * 2);
   }
-  const char* gw = (const char*)W + (size_t)s_begin * SKN_BK * 2;
+  const size_t w_step = packed ? (size_t)SKN_WSLOT : (size_t)SKN_BK * 2;
+  const char* gw = (const char*)W + (packed ? ((size_t)cg * ksteps + s_begin) * SKN_WSLOT
+                                            : (size_t)s_begin * SKN_BK * 2);
   auto issue = [&](int slot, int step) {           // step counted from s_begin
 #pragma unroll
     for (int t = 0; t < SKN_DMA; ++t)
-      g2l16(gw + (size_t)step * SKN_BK * 2 + w_off[t], ring + slot * SKN_SLOT + t * 1024);
+      g2l16(gw + (size_t)step * w_step + w_off[t], ring + slot * SKN_SLOT + t * 1024);
   };
   // the A slice: one or two more instructions, 16 token rows each
   uint32_t a_off[AR / 16];
@@ -927,6 +934,32 @@ gemm_skinny_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ 
 
 constexpr size_t SKN_COUNTER_BYTES = 4096;         // one counter per 128 output features
 
+// W [N][K] -> the skinny kernel's stream layout: for every group of 128 output features and every
+// 32-element K step the 8 KB image of that step's LDS slot (row r of the group at 64-byte row r,
+// its 16-byte chunk c at position c ^ swz32(r)), groups outermost, steps contiguous.
+__global__ void __launch_bounds__(256)
+pack_stream_kernel(const uint4* __restrict__ W, int ldw8, int ksteps, size_t n_chunks, uint4* __restrict__ Wp) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= n_chunks) return;
+  const int p = (int)(e & 63), t = (int)((e >> 6) & 7);
+  const size_t gs = e >> 9;                          // group * ksteps + step
+  const int step = (int)(gs % ksteps);
+  const size_t group = gs / ksteps;
+  const int tr = t * 16 + (p >> 2);
+  const int lc = (p & 3) ^ swz32(tr);
+  Wp[e] = W[(group * 128 + tr) * (size_t)ldw8 + step * 4 + lc];
+}
+
+hipError_t launch_pack_stream(const void* W, int N, int K, int ldw, void* Wp, hipStream_t st) {
+  if (N <= 0 || K <= 0 || N % 128 != 0 || K % SKN_BK != 0 || ldw % 8 != 0 || ldw < K ||
+      ((uintptr_t)W & 15) != 0 || ((uintptr_t)Wp & 15) != 0)
+    return hipErrorInvalidValue;
+  const size_t n_chunks = (size_t)N * K / 8;
+  hipLaunchKernelGGL(pack_stream_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st,
+                     (const uint4*)W, ldw / 8, K / SKN_BK, n_chunks, (uint4*)Wp);
+  return hipGetLastError();
+}
+
 static hipError_t launch_skinny(const void* A, const void* W, void* C, const void* R, int M, int N,
                                 int K, int lda, int ldw, int ldc, int epi, const EpiArgs& ra,
                                 void* ws, hipStream_t st) {
@@ -994,9 +1027,11 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
   // Bits 8..15 of `epilogue` force a tile configuration and bits 16..21 a band height (tuning
   // hook for measurements); 0 = choose here.
   int cfg = (epilogue >> 8) & 0xff, group_m = (epilogue >> 16) & 0x3f;
+  const bool packed_flag = (epilogue & (1 << 30)) != 0;
   epilogue &= 0xff;
   EpiArgs ra{};
   if (rope != nullptr) ra = *rope;
+  if (packed_flag) ra.w_packed = 1;
   if (epilogue == EPI_QKV_ROPE) {
     const int kvd = rope != nullptr ? (rope->kv_dim > 0 ? rope->kv_dim : rope->d_model) : 0;
     if (rope == nullptr || (rope->head_dim != 64 && rope->head_dim != 128) ||
@@ -1041,6 +1076,7 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     else cfg = 2;
     if (cfg == 0) return hipErrorInvalidValue;
   }
+  if (ra.w_packed && cfg != 8) return hipErrorInvalidValue;
   switch (cfg) {
     case 2:                                             // 128x128, 4 waves of 64x64
             return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
@@ -1057,6 +1093,10 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out, st);
     case 8:                                             // M <= 32: weight streaming
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
+            if (ra.w_stream != nullptr && !ra.w_packed) {
+              ra.w_packed = 1;
+              W = ra.w_stream;
+            }
             return launch_skinny(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, ra, sk_ws, st);
     default: return hipErrorInvalidValue;
   }

@@ -128,6 +128,41 @@ def test_gemm_tile_of_32_row_waves(M, N, K, epi):
     _assert_bf16_close(_f64(outs[1]), ref, 1.0, "gemm 32x128 waves")
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (3, 384, 704), (8, 4096, 4096), (20, 256, 1408)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_skinny_streamed_weight_layout(M, N, K, epi):
+    """The weight rewritten as sequential streams (lazyllm_op_pack_weight_stream) must give the
+    bits of the row-major weight: the kernel sees the same LDS slots either way."""
+    rng = np.random.default_rng(M * 13 + N + K + epi)
+    A = _rand_bf16(rng, (M, K))
+    Wbig = _rand_bf16(rng, (N, K + 8), 1.0 / math.sqrt(K))      # a row stride above K
+    W = Wbig[:, :K]
+    Wp = torch.full((N, K), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_pack_weight_stream(Wbig, N, K, K + 8, Wp)
+    # the packed form is a permutation of the 16-byte chunks
+    torch.cuda.synchronize()
+    a = np.sort(W.contiguous().view(torch.int16).cpu().numpy().reshape(-1, 8).view(np.int64).ravel())
+    b = np.sort(Wp.view(torch.int16).cpu().numpy().reshape(-1, 8).view(np.int64).ravel())
+    assert np.array_equal(a.reshape(-1), b.reshape(-1))
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    R = _rand_bf16(rng, (M, N))
+    outs = []
+    for w, ldw, flag in ((Wbig, K + 8, 0), (Wp, K, 1 << 30)):
+        e = epi | (8 << 8) | flag
+        if epi == B.EPI_SWIGLU:
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, w, Cout, None, M, N, K, K, ldw, N // 2, e, workspace=ws)
+        else:
+            Cout = R.clone()
+            B.lazyllm_op_gemm(A, w, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, ldw, N, e, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(Cout)
+    assert torch.equal(outs[0], outs[1])
+    # a packed weight cannot be read by any other kernel
+    with pytest.raises(B.LazyLLMError):
+        B.lazyllm_op_gemm(A, Wp, outs[0], None, M, N, K, K, K, outs[0].shape[1], B.EPI_STORE | (2 << 8) | (1 << 30), workspace=ws)
+
+
 def test_gemm_skinny_refuses_more_than_32_rows():
     A = torch.zeros(33, 64, dtype=torch.bfloat16, device=DEV)
     W = torch.zeros(128, 64, dtype=torch.bfloat16, device=DEV)
