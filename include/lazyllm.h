@@ -350,6 +350,16 @@ int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R
                             uint64_t* ssq_clear, void* workspace, size_t ws_bytes,
                             void* hip_stream);
 
+/* Weight layout of the tile kernels inside the model (for measurement and tests).  W [N, K] bf16
+ * (device, row stride ldw elements) is rewritten K-step-major into `packed` (N * K * 2 bytes,
+ * device, 16-byte aligned): [K / 64][N][64], i.e. the 128 bytes of one 64-element K step of all
+ * rows one after the other, so that the W slab a tile needs for one step is one contiguous run
+ * instead of one cache line from each of 256 rows.  K % 64 == 0.  lazyllm_op_gemm reads such a
+ * weight when bit 29 of `epilogue` is set (ldw is then ignored; every tile configuration, not
+ * configuration 8). */
+int lazyllm_op_pack_weight_ksteps(const void* W, int32_t N, int32_t K, int32_t ldw, void* packed,
+                                  void* hip_stream);
+
 /* Weight layout of the decoding steps' weight-streaming kernel (for callers that cannot change
  * the model: measurement and tests).  W [N, K] bf16 (device, row stride ldw elements) is rewritten
  * into `packed` (N * K * 2 bytes, device, 16-byte aligned): for every group of 128 output

@@ -129,6 +129,8 @@ _SIGNATURES = {
                                           C.c_void_p, C.c_size_t, C.c_void_p]),
     "lazyllm_op_pack_weight_stream": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                                 C.c_void_p]),
+    "lazyllm_op_pack_weight_ksteps": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                                C.c_void_p]),
     "lazyllm_op_quantize_fp8": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_int32, C.c_void_p, C.c_void_p]),
     "lazyllm_op_gemm_fp8": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -329,6 +331,10 @@ def lazyllm_op_gemm_rmsnorm(A, W, Cout, R, M, N, K, lda, ldw, ldc, epilogue, ssq
 
 def lazyllm_op_pack_weight_stream(W, N, K, ldw, packed, stream=None) -> None:
     _check(lib().lazyllm_op_pack_weight_stream(_ptr(W), N, K, ldw, _ptr(packed), _stream_ptr(stream)))
+
+
+def lazyllm_op_pack_weight_ksteps(W, N, K, ldw, packed, stream=None) -> None:
+    _check(lib().lazyllm_op_pack_weight_ksteps(_ptr(W), N, K, ldw, _ptr(packed), _stream_ptr(stream)))
 
 
 def lazyllm_op_quantize_fp8(x, rows, K, ldx, codes, ldq, scale, stream=None) -> None:

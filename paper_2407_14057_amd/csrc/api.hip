@@ -346,6 +346,24 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
   p = take(d * 2);
   chk(hipMemcpyAsync(p, w->final_norm, d * 2, hipMemcpyDeviceToDevice, st));
   m->final_norm = p;
+  // The four matrices of a layer are first put together row-major in a staging buffer (fused,
+  // gains folded in, padded) and then stored in the forms the kernels read: K-step-major for the
+  // tile kernels, sequential streams for the decoding steps' weight-streaming kernel, and, for the
+  // 8-bit variant, E4M3 codes with row scales.  The staging buffer is reused layer after layer
+  // (everything runs in order on one stream) and freed at the end.
+  const size_t n_qkv = (d + 2 * kvd) * d * 2, n_o = d * d * 2, n_gu = 2 * fp * d * 2, n_down = d * fp * 2;
+  char* staging = nullptr;
+  e = hipMalloc((void**)&staging, align_up(n_qkv) + align_up(n_o) + align_up(n_gu) + align_up(n_down));
+  if (e != hipSuccess) {
+    (void)hipFree(m->blob);
+    delete m;
+    g_last_hip_error = (int)e;
+    return e == hipErrorOutOfMemory ? LAZYLLM_ENOMEM : LAZYLLM_EHIP;
+  }
+  char* t_qkv = staging;
+  char* t_o = t_qkv + align_up(n_qkv);
+  char* t_gu = t_o + align_up(n_o);
+  char* t_down = t_gu + align_up(n_gu);
   for (int l = 0; l < L && rc == LAZYLLM_OK; ++l) {
     p = take(d * 2);
     chk(hipMemcpyAsync(p, w->attn_norm[l], d * 2, hipMemcpyDeviceToDevice, st));
@@ -353,53 +371,44 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
     p = take(d * 2);
     chk(hipMemcpyAsync(p, w->ffn_norm[l], d * 2, hipMemcpyDeviceToDevice, st));
     m->ffn_norm.push_back(p);
-    p = take((d + 2 * kvd) * d * 2);               // fused [q; k; v] rows
-    chk(hipMemcpyAsync(p, w->wq[l], d * d * 2, hipMemcpyDeviceToDevice, st));
-    chk(hipMemcpyAsync(p + d * d * 2, w->wk[l], kvd * d * 2, hipMemcpyDeviceToDevice, st));
-    chk(hipMemcpyAsync(p + (d + kvd) * d * 2, w->wv[l], kvd * d * 2, hipMemcpyDeviceToDevice, st));
+    // fused [q; k; v] rows
+    chk(hipMemcpyAsync(t_qkv, w->wq[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    chk(hipMemcpyAsync(t_qkv + d * d * 2, w->wk[l], kvd * d * 2, hipMemcpyDeviceToDevice, st));
+    chk(hipMemcpyAsync(t_qkv + (d + kvd) * d * 2, w->wv[l], kvd * d * 2, hipMemcpyDeviceToDevice, st));
     // RMSNorm gains ride in the weights: x*g . w = x . (g*w); the 1/rms factor is applied by the
     // GEMM epilogue (exact for gains of 1, one more bf16 rounding of the weight otherwise)
-    chk(launch_scale_cols(p, w->attn_norm[l], d + 2 * kvd, (int)d, st));
-    m->wqkv.push_back(p);
-    p = take(d * d * 2);
-    chk(hipMemcpyAsync(p, w->wo[l], d * d * 2, hipMemcpyDeviceToDevice, st));
-    m->wo.push_back(p);
-    p = take(2 * fp * d * 2);                      // gate/up interleaved in 32-row blocks
-    chk(launch_interleave_gate_up(w->w_gate[l], w->w_up[l], p, (int)f, (int)fp, (int)d, st));
-    chk(launch_scale_cols(p, w->ffn_norm[l], 2 * fp, (int)d, st));
-    m->wgu.push_back(p);
-    p = take(d * fp * 2);                          // down, K zero-padded to f_pad
-    chk(launch_copy_rows(w->w_down[l], p, (int)d, (int)f, (int)f, (int)fp, st));
-    m->wdown.push_back(p);
-    {
-      // ... and once more as sequential streams for the decoding steps (see launch_pack_stream)
-      auto stream_copy = [&](const void* src, size_t rows, size_t K, std::vector<const void*>& dst) {
-        char* ps = take(rows * K * 2);
-        chk(launch_pack_stream(src, (int)rows, (int)K, (int)K, ps, st));
-        dst.push_back(ps);
-      };
-      stream_copy(m->wqkv[l], d + 2 * kvd, d, m->wqkv_s);
-      stream_copy(m->wo[l], d, d, m->wo_s);
-      stream_copy(m->wgu[l], 2 * fp, d, m->wgu_s);
-      stream_copy(m->wdown[l], d, fp, m->wdown_s);
-    }
-    if (f8) {
-      // the stored matrices (gains folded in, fused, padded) quantised row by row
-      auto quant = [&](const void* src, size_t rows, size_t K, std::vector<const void*>& codes,
-                       std::vector<const float*>& scales) {
+    chk(launch_scale_cols(t_qkv, w->attn_norm[l], d + 2 * kvd, (int)d, st));
+    chk(hipMemcpyAsync(t_o, w->wo[l], d * d * 2, hipMemcpyDeviceToDevice, st));
+    // gate/up interleaved in 32-row blocks
+    chk(launch_interleave_gate_up(w->w_gate[l], w->w_up[l], t_gu, (int)f, (int)fp, (int)d, st));
+    chk(launch_scale_cols(t_gu, w->ffn_norm[l], 2 * fp, (int)d, st));
+    // down, K zero-padded to f_pad
+    chk(launch_copy_rows(w->w_down[l], t_down, (int)d, (int)f, (int)f, (int)fp, st));
+    auto store = [&](const char* src, size_t rows, size_t K, std::vector<const void*>& tiles,
+                     std::vector<const void*>& streams, std::vector<const void*>& codes,
+                     std::vector<const float*>& scales) {
+      char* pb = take(rows * K * 2);
+      chk(launch_pack_kblock(src, (int)rows, (int)K, (int)K, pb, st));
+      tiles.push_back(pb);
+      char* ps = take(rows * K * 2);
+      chk(launch_pack_stream(src, (int)rows, (int)K, (int)K, ps, st));
+      streams.push_back(ps);
+      if (f8) {
         char* c8 = take(rows * K);
         float* sc = (float*)take(rows * 4);
         chk(launch_quantize_rows_f8(src, (int)rows, (int)K, (int)K, c8, (int)K, sc, st));
         codes.push_back(c8);
         scales.push_back(sc);
-      };
-      quant(m->wqkv[l], d + 2 * kvd, d, m->wqkv8, m->sqkv);
-      quant(m->wo[l], d, d, m->wo8, m->so);
-      quant(m->wgu[l], 2 * fp, d, m->wgu8, m->sgu);
-      quant(m->wdown[l], d, fp, m->wdown8, m->sdown);
-    }
+      }
+    };
+    store(t_qkv, d + 2 * kvd, d, m->wqkv, m->wqkv_s, m->wqkv8, m->sqkv);
+    store(t_o, d, d, m->wo, m->wo_s, m->wo8, m->so);
+    store(t_gu, 2 * fp, d, m->wgu, m->wgu_s, m->wgu8, m->sgu);
+    store(t_down, d, fp, m->wdown, m->wdown_s, m->wdown8, m->sdown);
   }
   if (rc == LAZYLLM_OK) chk(hipStreamSynchronize(st));
+  else (void)hipStreamSynchronize(st);
+  (void)hipFree(staging);
   if (rc != LAZYLLM_OK) {
     (void)hipFree(m->blob);
     delete m;
@@ -534,9 +543,12 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     auto project = [&](const void* A, int K, const void* w16, const void* w8, const float* sw8,
                        void* Cout, const void* R, int N, int ldc, int epi, const EpiArgs* ea,
                        bool stream_k) -> hipError_t {
-      if (c->gemm_dtype == 0)
-        return launch_gemm(A, w16, Cout, R, n, N, K, K, K, ldc, epi, st, ea,
+      if (c->gemm_dtype == 0) {
+        EpiArgs eb = *ea;
+        eb.w_blocked = 1;                            // the model's 16-bit weights are K-step-major
+        return launch_gemm(A, w16, Cout, R, n, N, K, K, K, ldc, epi, st, &eb,
                            stream_k ? W + ws.gemm_ws : nullptr, stream_k ? gemm_workspace_bytes() : 0);
+      }
       hipError_t qe = launch_quantize_rows_f8(A, n, K, K, W + ws.a8, K, (float*)(W + ws.sa8), st);
       if (qe != hipSuccess) return qe;
       return launch_gemm_f8(W + ws.a8, (const float*)(W + ws.sa8), w8, sw8, Cout, R, n, N, K, K, K, ldc,
@@ -924,7 +936,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     ra.d_model = d; ra.head_dim = hd; ra.kv_dim = kvd;
     ra.vt = (uint16_t*)(S + gl.vt[l]); ra.vt_ld = gl.vt_ld; ra.vt_col = rpos;
     ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
-    ra.skinny = 1; ra.w_stream = m->wqkv_s[l];
+    ra.skinny = 1; ra.w_stream = m->wqkv_s[l]; ra.w_blocked = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_QKV, l, M, 2.0 * M * (dd + 2.0 * kvd) * dd,
            launch_gemm(h, m->wqkv[l], nullptr, nullptr, M, d + 2 * kvd, d, d, d, 0, EPI_QKV_ROPE, st, &ra,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -934,7 +946,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
                                    score_z(W + ws.score), score_zstat(W + ws.score, z_ld, H), z_ld,
                                    W + ws.att_ws, decode_attention_workspace_bytes(d, H), kv_group));
     EpiArgs eo{};
-    eo.ssq_out = ssq_ffn; eo.skinny = 1; eo.w_stream = m->wo_s[l];
+    eo.ssq_out = ssq_ffn; eo.skinny = 1; eo.w_stream = m->wo_s[l]; eo.w_blocked = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_O, l, M, 2.0 * M * dd * dd,
            launch_gemm(W + ws.o, m->wo[l], h, h, M, d, d, d, d, d, EPI_RESIDUAL, st, &eo,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -946,12 +958,12 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
     eg.sf_cu = nullptr; eg.sf_cu_z = nullptr;
     eg.sf_n_single = n_tot; eg.sf_heads = H; eg.sf_z_ld = z_ld;
     eg.sf_max_rows = n_tot; eg.sf_batch = 1;
-    eg.skinny = 1; eg.w_stream = m->wgu_s[l];
+    eg.skinny = 1; eg.w_stream = m->wgu_s[l]; eg.w_blocked = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_GATE_UP, l, M, 2.0 * M * 2.0 * (double)c->d_ffn * dd,
            launch_gemm(h, m->wgu[l], W + ws.act, nullptr, M, 2 * fp, d, d, d, fp, EPI_SWIGLU, st, &eg,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
     EpiArgs ed{};
-    ed.ssq_out = ssq_attn; ed.skinny = 1; ed.w_stream = m->wdown_s[l];
+    ed.ssq_out = ssq_attn; ed.skinny = 1; ed.w_stream = m->wdown_s[l]; ed.w_blocked = 1;
     LZ_RUN(LAZYLLM_STEP_GEMM_DOWN, l, M, 2.0 * M * (double)c->d_ffn * dd,
            launch_gemm(W + ws.act, m->wdown[l], h, h, M, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
@@ -1055,6 +1067,15 @@ int lazyllm_op_pack_weight_stream(const void* W, int32_t N, int32_t K, int32_t l
       ((uintptr_t)W & 15) != 0 || ((uintptr_t)packed & 15) != 0)
     return LAZYLLM_EINVAL;
   LZ_HIP(launch_pack_stream(W, N, K, ldw, packed, (hipStream_t)hip_stream));
+  return LAZYLLM_OK;
+}
+
+int lazyllm_op_pack_weight_ksteps(const void* W, int32_t N, int32_t K, int32_t ldw, void* packed,
+                                  void* hip_stream) {
+  if (!W || !packed || N <= 0 || K <= 0 || K % 64 != 0 || ldw % 8 != 0 || ldw < K ||
+      ((uintptr_t)W & 15) != 0 || ((uintptr_t)packed & 15) != 0)
+    return LAZYLLM_EINVAL;
+  LZ_HIP(launch_pack_kblock(W, N, K, ldw, packed, (hipStream_t)hip_stream));
   return LAZYLLM_OK;
 }
 

@@ -161,6 +161,11 @@ struct EpiArgs {
   // the same weight in that layout, if the caller has one: used (instead of W) whenever the
   // weight-streaming kernel is chosen
   const void* w_stream;
+  // W is stored K-step-major: [K / 64][N][64], each 64-element step of all rows contiguous (a
+  // tile's W slab of one step is one contiguous run).  Filled in by the launcher: bytes from one
+  // K step of a row to the next (128 for the row-major form).
+  int w_blocked;
+  unsigned long long w_step_bytes;
 };
 constexpr float SSQ_FIX = 4294967296.0f;      // 2^32
 __device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {
@@ -175,6 +180,7 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
 
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st);
 hipError_t launch_pack_stream(const void* W, int N, int K, int ldw, void* Wp, hipStream_t st);
+hipError_t launch_pack_kblock(const void* W, int N, int K, int ldw, void* Wb, hipStream_t st);
 
 // 8-bit floating point variant (gemm_fp8.hip): E4M3 codes with one fp32 scale per row.
 hipError_t launch_quantize_rows_f8(const void* x, int rows, int K, int ldx, void* q, int ldq,

@@ -64,11 +64,12 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
   }
 
+  const size_t wstep = (size_t)ra.w_step_bytes;     // 128, or N * 128 for the K-step-major weight
   auto issue = [&](int stage, int k0) {
     char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
     char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
     const char* ga = (const char*)A + (size_t)k0 * 2;
-    const char* gw = (const char*)W + (size_t)k0 * 2;
+    const char* gw = (const char*)W + (size_t)(k0 / BK) * wstep;
 #pragma unroll
     for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
 #pragma unroll
@@ -168,6 +169,8 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   const int threads = WM * WN * 64;
   EpiArgs ea = ra;
+  ea.w_step_bytes = ra.w_blocked ? (unsigned long long)N * ROW_BYTES : (unsigned long long)ROW_BYTES;
+  if (ra.w_blocked) ldw = BK;                       // rows of one K step are 128 bytes apart
   ea.sf_blocks_per_seq = (ea.sf_max_rows + threads - 1) / threads;
   const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
   dim3 grid(tiles_m * tiles_n + side), block(threads);
@@ -266,11 +269,12 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     r = r < N ? r : N - 1;
     w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
   }
+  const size_t wstep = (size_t)ra.w_step_bytes;     // 128, or N * 128 for the K-step-major weight
   auto issue = [&](int stage, int k0) {
     char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
     char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
     const char* ga = (const char*)A + (size_t)k0 * 2;
-    const char* gw = (const char*)W + (size_t)k0 * 2;
+    const char* gw = (const char*)W + (size_t)(k0 / BK) * wstep;
 #pragma unroll
     for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
 #pragma unroll
@@ -282,7 +286,7 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
       g2l16((const char*)A + (size_t)k0 * 2 + a_off[q],
             lds + stage * STAGE_BYTES + (wave * A_INSTR + q) * 1024);
     else
-      g2l16((const char*)W + (size_t)k0 * 2 + w_off[q - A_INSTR],
+      g2l16((const char*)W + (size_t)(k0 / BK) * wstep + w_off[q - A_INSTR],
             lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR + q - A_INSTR) * 1024);
   };
 
@@ -412,6 +416,8 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   if (N % BN != 0) return hipErrorInvalidValue;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   EpiArgs ea = ra;
+  ea.w_step_bytes = ra.w_blocked ? (unsigned long long)N * ROW_BYTES : (unsigned long long)ROW_BYTES;
+  if (ra.w_blocked) ldw = BK;                       // rows of one K step are 128 bytes apart
   ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
   // the tile goes out through LDS when whole 16-byte chunks of every row are addressable
   // (not for the SiLU*mul epilogue: its tile is half as wide, its GEMM runs several rounds whose
@@ -465,7 +471,7 @@ __global__ void __launch_bounds__(256)
 gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, float* __restrict__ partial,
                int M, int N, int K, int lda, int ldw, int ldc, int tiles_m, int tiles_n, int G,
-               unsigned long long* __restrict__ ssq_out) {
+               unsigned long long* __restrict__ ssq_out, size_t wstep) {
   constexpr int WM = 2, WN = 2, TM = 2, TN = 2, NWAVES = 4;
   constexpr int BM = SK_BM, BN = SK_BN;
   constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;
@@ -523,7 +529,7 @@ gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
       char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
       char* sw = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
       const char* ga = (const char*)A + (size_t)kt * BK * 2;
-      const char* gw = (const char*)W + (size_t)kt * BK * 2;
+      const char* gw = (const char*)W + (size_t)kt * wstep;
 #pragma unroll
       for (int q = 0; q < A_INSTR; ++q) g2l16(ga + a_off[q], sa + q * 1024);
 #pragma unroll
@@ -685,8 +691,10 @@ size_t gemm_workspace_bytes() { return (size_t)SK_GRID * 2 * SK_TILE_ELEMS * siz
 
 static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R, float* partial,
                             int M, int N, int K, int lda, int ldw, int ldc, int epi,
-                            unsigned long long* ssq_out, hipStream_t st) {
+                            unsigned long long* ssq_out, bool w_blocked, hipStream_t st) {
   constexpr int LDS_BYTES = 2 * (SK_BM + SK_BN) * ROW_BYTES;
+  const size_t wstep = w_blocked ? (size_t)N * ROW_BYTES : (size_t)ROW_BYTES;   // bytes from one K step of a row to the next
+  if (w_blocked) ldw = BK;
   const int tiles_m = (M + SK_BM - 1) / SK_BM, tiles_n = N / SK_BN, KT = K / BK;
   const long long U = (long long)tiles_m * tiles_n * KT;
   const int G = SK_GRID;
@@ -702,7 +710,7 @@ static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R
     }                                                                                            \
     hipLaunchKernelGGL(kern, dim3(G), dim3(256), LDS_BYTES, st, (const uint16_t*)A,              \
                        (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, partial, M, N, K,   \
-                       lda, ldw, ldc, tiles_m, tiles_n, G, ssq_out);                             \
+                       lda, ldw, ldc, tiles_m, tiles_n, G, ssq_out, wstep);                      \
     hipError_t e = hipGetLastError();                                                            \
     if (e != hipSuccess) return e;                                                               \
     hipLaunchKernelGGL(gemm_sk_fixup_kernel<E>, dim3(tiles_m * tiles_n, 16), dim3(256), 0, st,   \
@@ -950,6 +958,27 @@ pack_stream_kernel(const uint4* __restrict__ W, int ldw8, int ksteps, size_t n_c
   Wp[e] = W[(group * 128 + tr) * (size_t)ldw8 + step * 4 + lc];
 }
 
+// W [N][K] -> K-step-major [K / 64][N][64]: one thread per 16-byte chunk.
+__global__ void __launch_bounds__(256)
+pack_kblock_kernel(const uint4* __restrict__ W, int ldw8, int N, size_t n_chunks, uint4* __restrict__ Wb) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= n_chunks) return;
+  const int c = (int)(e & 7);
+  const size_t rn = e >> 3;                          // kt * N + n
+  const size_t kt = rn / N, n = rn % N;
+  Wb[e] = W[n * (size_t)ldw8 + kt * 8 + c];
+}
+
+hipError_t launch_pack_kblock(const void* W, int N, int K, int ldw, void* Wb, hipStream_t st) {
+  if (N <= 0 || K <= 0 || K % BK != 0 || ldw % 8 != 0 || ldw < K || ((uintptr_t)W & 15) != 0 ||
+      ((uintptr_t)Wb & 15) != 0)
+    return hipErrorInvalidValue;
+  const size_t n_chunks = (size_t)N * K / 8;
+  hipLaunchKernelGGL(pack_kblock_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st,
+                     (const uint4*)W, ldw / 8, N, n_chunks, (uint4*)Wb);
+  return hipGetLastError();
+}
+
 hipError_t launch_pack_stream(const void* W, int N, int K, int ldw, void* Wp, hipStream_t st) {
   if (N <= 0 || K <= 0 || N % 128 != 0 || K % SKN_BK != 0 || ldw % 8 != 0 || ldw < K ||
       ((uintptr_t)W & 15) != 0 || ((uintptr_t)Wp & 15) != 0)
@@ -1027,11 +1056,12 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
   // Bits 8..15 of `epilogue` force a tile configuration and bits 16..21 a band height (tuning
   // hook for measurements); 0 = choose here.
   int cfg = (epilogue >> 8) & 0xff, group_m = (epilogue >> 16) & 0x3f;
-  const bool packed_flag = (epilogue & (1 << 30)) != 0;
+  const bool packed_flag = (epilogue & (1 << 30)) != 0, blocked_flag = (epilogue & (1 << 29)) != 0;
   epilogue &= 0xff;
   EpiArgs ra{};
   if (rope != nullptr) ra = *rope;
   if (packed_flag) ra.w_packed = 1;
+  if (blocked_flag) ra.w_blocked = 1;
   if (epilogue == EPI_QKV_ROPE) {
     const int kvd = rope != nullptr ? (rope->kv_dim > 0 ? rope->kv_dim : rope->d_model) : 0;
     if (rope == nullptr || (rope->head_dim != 64 && rope->head_dim != 128) ||
@@ -1077,6 +1107,7 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     if (cfg == 0) return hipErrorInvalidValue;
   }
   if (ra.w_packed && cfg != 8) return hipErrorInvalidValue;
+  if (ra.w_blocked && cfg == 8 && ra.w_stream == nullptr) return hipErrorInvalidValue;
   switch (cfg) {
     case 2:                                             // 128x128, 4 waves of 64x64
             return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
@@ -1090,7 +1121,8 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_pp<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 6:                                             // 128x128 stream-K + fix-up
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
-            return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out, st);
+            return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out,
+                             ra.w_blocked != 0, st);
     case 8:                                             // M <= 32: weight streaming
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
             if (ra.w_stream != nullptr && !ra.w_packed) {

@@ -163,6 +163,38 @@ def test_gemm_skinny_streamed_weight_layout(M, N, K, epi):
         B.lazyllm_op_gemm(A, Wp, outs[0], None, M, N, K, K, K, outs[0].shape[1], B.EPI_STORE | (2 << 8) | (1 << 30), workspace=ws)
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(2, 300, 768, 256), (3, 229, 1536, 704), (4, 130, 512, 192), (5, 513, 1536, 704),
+                                       (7, 700, 768, 1408), (6, 355, 4096, 1408), (0, 2100, 6144, 512), (0, 37, 256, 128)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_k_step_major_weight_layout(cfg, M, N, K, epi):
+    """The weight stored K-step-major (lazyllm_op_pack_weight_ksteps, the form the model keeps) must
+    give the bits of the row-major weight in every tile configuration: only addresses change."""
+    if cfg == 6 and epi == B.EPI_SWIGLU:
+        pytest.skip("the stream-K schedule has no SiLU*mul epilogue")
+    rng = np.random.default_rng(cfg * 101 + M + N + K + epi)
+    A = _rand_bf16(rng, (M, K))
+    Wbig = _rand_bf16(rng, (N, K + 16), 1.0 / math.sqrt(K))
+    Wb = torch.full((N, K), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_pack_weight_ksteps(Wbig, N, K, K + 16, Wb)
+    torch.cuda.synchronize()
+    want = Wbig[:, :K].reshape(N, K // 64, 64).permute(1, 0, 2).contiguous()
+    assert torch.equal(Wb.view(K // 64, N, 64), want)
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    R = _rand_bf16(rng, (M, N))
+    outs = []
+    for w, ldw, flag in ((Wbig, K + 16, 0), (Wb, K, 1 << 29)):
+        e = epi | (cfg << 8) | flag
+        if epi == B.EPI_SWIGLU:
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, w, Cout, None, M, N, K, K, ldw, N // 2, e, workspace=ws)
+        else:
+            Cout = R.clone()
+            B.lazyllm_op_gemm(A, w, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, ldw, N, e, workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(Cout)
+    assert torch.equal(outs[0], outs[1])
+
+
 def test_gemm_skinny_refuses_more_than_32_rows():
     A = torch.zeros(33, 64, dtype=torch.bfloat16, device=DEV)
     W = torch.zeros(128, 64, dtype=torch.bfloat16, device=DEV)
