@@ -387,6 +387,9 @@ int lazyllm_op_pack_weight_stream(const void* W, int32_t N, int32_t K, int32_t l
  *   lazyllm_op_gemm), written as bf16.  a_codes [M, K] and w_codes [N, K] are E4M3 codes (device,
  *   16-byte aligned, row strides lda, ldw bytes, multiples of 16); w_scale 16-byte aligned.
  *   N % 256 == 0, K % 128 == 0, M * lda and N * ldw below 2^32.  C, R as in lazyllm_op_gemm.
+ *   Bit 29 of `epilogue`: w_codes is K-step-major, [K / 128][N][128] (the form the model keeps;
+ *   lazyllm_op_pack_weight_ksteps on the codes taken as N rows of K / 2 16-bit units); ldw is
+ *   then ignored.
  * Both return LAZYLLM_EINVAL for arguments outside these limits; nothing is allocated and
  * nothing is kept. */
 int lazyllm_op_quantize_fp8(const void* x, int32_t rows, int32_t K, int32_t ldx, void* codes,

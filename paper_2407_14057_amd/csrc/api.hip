@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "../../include/lazyllm.h"
@@ -353,7 +354,9 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
   // (everything runs in order on one stream) and freed at the end.
   const size_t n_qkv = (d + 2 * kvd) * d * 2, n_o = d * d * 2, n_gu = 2 * fp * d * 2, n_down = d * fp * 2;
   char* staging = nullptr;
-  e = hipMalloc((void**)&staging, align_up(n_qkv) + align_up(n_o) + align_up(n_gu) + align_up(n_down));
+  const size_t n_codes = f8 ? std::max(std::max(n_qkv, n_o), std::max(n_gu, n_down)) / 2 : 0;
+  e = hipMalloc((void**)&staging, align_up(n_qkv) + align_up(n_o) + align_up(n_gu) + align_up(n_down) +
+                                      align_up(n_codes));
   if (e != hipSuccess) {
     (void)hipFree(m->blob);
     delete m;
@@ -364,6 +367,7 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
   char* t_o = t_qkv + align_up(n_qkv);
   char* t_gu = t_o + align_up(n_o);
   char* t_down = t_gu + align_up(n_gu);
+  char* t_codes = t_down + align_up(n_down);
   for (int l = 0; l < L && rc == LAZYLLM_OK; ++l) {
     p = take(d * 2);
     chk(hipMemcpyAsync(p, w->attn_norm[l], d * 2, hipMemcpyDeviceToDevice, st));
@@ -394,9 +398,12 @@ int lazyllm_model_create(const lazyllm_config* cfg, const lazyllm_weights* w, vo
       chk(launch_pack_stream(src, (int)rows, (int)K, (int)K, ps, st));
       streams.push_back(ps);
       if (f8) {
+        // codes row by row into the staging buffer, then K-step-major like the 16-bit form
+        // (a row of K codes = K / 2 16-bit units: the same rearrangement in 128-byte pieces)
         char* c8 = take(rows * K);
         float* sc = (float*)take(rows * 4);
-        chk(launch_quantize_rows_f8(src, (int)rows, (int)K, (int)K, c8, (int)K, sc, st));
+        chk(launch_quantize_rows_f8(src, (int)rows, (int)K, (int)K, t_codes, (int)K, sc, st));
+        chk(launch_pack_kblock(t_codes, (int)rows, (int)(K / 2), (int)(K / 2), c8, st));
         codes.push_back(c8);
         scales.push_back(sc);
       }
@@ -551,8 +558,10 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       }
       hipError_t qe = launch_quantize_rows_f8(A, n, K, K, W + ws.a8, K, (float*)(W + ws.sa8), st);
       if (qe != hipSuccess) return qe;
+      EpiArgs e8 = *ea;
+      e8.w_blocked = 1;                              // the model's codes are K-step-major too
       return launch_gemm_f8(W + ws.a8, (const float*)(W + ws.sa8), w8, sw8, Cout, R, n, N, K, K, K, ldc,
-                            epi, st, ea);
+                            epi, st, &e8);
     };
     const bool f8 = c->gemm_dtype == 1;
     if (flags & LAZYLLM_KEEP_HIDDEN) {
@@ -1099,11 +1108,15 @@ int lazyllm_op_gemm_fp8(const void* a_codes, const float* a_scale, const void* w
     return LAZYLLM_EINVAL;
   if ((uint64_t)M * (uint64_t)lda >= (1ull << 32) || (uint64_t)N * (uint64_t)ldw >= (1ull << 32))
     return LAZYLLM_EINVAL;
+  const bool blocked = (epilogue & (1 << 29)) != 0;   // w_codes K-step-major: [K / 128][N][128]
+  if (epilogue >= 0) epilogue &= ~(1 << 29);
   if (epilogue < 0 || epilogue > 2 || (epilogue == EPI_RESIDUAL && !R)) return LAZYLLM_EINVAL;
   if (ldc < (epilogue == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
   if (M == 0) return LAZYLLM_OK;
+  EpiArgs ea{};
+  ea.w_blocked = blocked ? 1 : 0;
   LZ_HIP(launch_gemm_f8(a_codes, a_scale, w_codes, w_scale, C, R, M, N, K, lda, ldw, ldc, epilogue,
-                        (hipStream_t)hip_stream, nullptr));
+                        (hipStream_t)hip_stream, &ea));
   return LAZYLLM_OK;
 }
 

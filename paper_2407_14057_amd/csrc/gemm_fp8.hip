@@ -136,19 +136,21 @@ gemm_f8_kernel(const uint8_t* __restrict__ A, const uint8_t* __restrict__ W,
     r = r < N ? r : N - 1;
     w_off[q] = (uint32_t)((size_t)r * ldw + cchunk * 16);
   }
+  const size_t wstep = (size_t)ra.w_step_bytes;     // 128, or N * 128 for the K-step-major weight
   auto issue = [&](int stage, int k0) {
     char* sal = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
     char* swl = lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR) * 1024;
+    const char* gw = (const char*)W + (size_t)(k0 / F8_BK) * wstep;
 #pragma unroll
     for (int q = 0; q < A_INSTR; ++q) g2l16((const char*)A + k0 + a_off[q], sal + q * 1024);
 #pragma unroll
-    for (int q = 0; q < W_INSTR; ++q) g2l16((const char*)W + k0 + w_off[q], swl + q * 1024);
+    for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], swl + q * 1024);
   };
   auto issue_one = [&](int stage, int k0, int q) {
     if (q < A_INSTR)
       g2l16((const char*)A + k0 + a_off[q], lds + stage * STAGE_BYTES + (wave * A_INSTR + q) * 1024);
     else
-      g2l16((const char*)W + k0 + w_off[q - A_INSTR],
+      g2l16((const char*)W + (size_t)(k0 / F8_BK) * wstep + w_off[q - A_INSTR],
             lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR + q - A_INSTR) * 1024);
   };
 
@@ -326,6 +328,9 @@ hipError_t launch_gemm_f8(const void* A, const float* sa, const void* W, const f
   const int BM = tall ? 256 : 128;
   const int LDS_BYTES = (tall ? 2 : 3) * (BM + BN) * ROW_BYTES;
   const int tiles_m = (M + BM - 1) / BM;
+  // K-step-major codes ([K / 128][N][128], see launch_pack_kblock): rows of a step 128 bytes apart
+  ea.w_step_bytes = ea.w_blocked ? (unsigned long long)N * ROW_BYTES : (unsigned long long)ROW_BYTES;
+  if (ea.w_blocked) ldw = F8_BK;
   ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
   ea.stage_out = (epilogue == EPI_QKV_ROPE)
                      ? (ea.d_model % BN == 0 && (ea.kv_dim > 0 ? ea.kv_dim : ea.d_model) % BN == 0)

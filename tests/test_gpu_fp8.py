@@ -128,6 +128,33 @@ def test_gemm_fp8_from_codes(M, N, K, epi):
     assert not (err > tol).any(), "%d of %d off, worst %.3g" % (int((err > tol).sum()), err.size, float(err.max()))
 
 
+@pytest.mark.parametrize("M,N,K", [(37, 256, 384), (300, 768, 1024), (2100, 768, 256)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_fp8_k_step_major_codes(M, N, K, epi):
+    """Weight codes stored K-step-major (the model's form) give the bits of the row-major codes."""
+    rng = np.random.default_rng(M + N + K + epi)
+    a_d = torch.from_numpy(_codes_dev(rng, (M, K))).to(DEV)
+    w_d = torch.from_numpy(_codes_dev(rng, (N, K))).to(DEV)
+    sa_d = torch.from_numpy(np.exp(rng.normal(0, 1, M)).astype(np.float32) * 1e-2).to(DEV)
+    sw_d = torch.from_numpy(np.exp(rng.normal(0, 1, N)).astype(np.float32) * 1e-2).to(DEV)
+    wb = torch.empty_like(w_d)
+    B.lazyllm_op_pack_weight_ksteps(w_d, N, K // 2, K // 2, wb)
+    torch.cuda.synchronize()
+    assert torch.equal(wb.view(K // 128, N, 128), w_d.view(N, K // 128, 128).permute(1, 0, 2).contiguous())
+    R = _bf16_dev(rng.normal(0, 1, (M, N)))
+    outs = []
+    for w, flag in ((w_d, 0), (wb, 1 << 29)):
+        if epi == B.EPI_SWIGLU:
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm_fp8(a_d, sa_d, w, sw_d, Cout, None, M, N, K, K, K, N // 2, epi | flag)
+        else:
+            Cout = R.clone()
+            B.lazyllm_op_gemm_fp8(a_d, sa_d, w, sw_d, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N, epi | flag)
+        torch.cuda.synchronize()
+        outs.append(Cout)
+    assert torch.equal(outs[0], outs[1])
+
+
 def test_gemm_fp8_all_code_pairs_and_scales():
     """Every code against every code (K = 128 holds each A code in one row block), distinct scales
     per row and per column: a swapped operand, a wrong scale index or a wrong format would show."""
