@@ -20,7 +20,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch the dominant kernel (gate/up GEMM, SwiGLU epilogue) moves through the L2s'
 # fabric side, averaged over the 32 launches of a 7b_3376 step: rocprofv3 FETCH_SIZE x 2 KiB +
 # WRITE_SIZE x 1 KiB, factors calibrated on a 1 GiB copy (profiles/gemm_attention_7b_3376_pmc.md).
-TRAFFIC_GATE_UP_7B_3376 = 741.89e6
+TRAFFIC_GATE_UP_7B_3376 = 747.85e6
 STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<4,2,2,4,EPI_SWIGLU> (RMSNorm scale + gate/up projection + SiLU*mul)",
                "gemm_qkv": "gemm_pp_kernel<4,2,2,4,EPI_QKV_ROPE128> (RMSNorm scale + QKV projection + RoPE + V^T)",
                "gemm_down": "gemm_pp_kernel<4,2,2,4,EPI_RESIDUAL> (down projection + residual + row sums of squares)",
