@@ -6,6 +6,11 @@
 // in registers for the whole K loop).  K advances 64 elements per step; the A and W slabs of
 // a step are copied global -> LDS by global_load_lds (no register staging) into one of two
 // LDS stages while the other stage feeds the MFMAs.
+//
+// W may be row-major [N][K] (row stride ldw) or K-step-major [K/64][N][64] (EpiArgs::w_blocked, the
+// order the model keeps its weights in): the kernels only differ in two byte strides, row to row
+// (ldw * 2 or 128) and K step to K step (128 or N * 128).  K-step-major, the slab of one step is
+// one contiguous run, which the memory system serves better than one line from each of 256 rows.
 #include "common.h"
 #include "gemm_shared.h"
 
