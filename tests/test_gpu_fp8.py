@@ -319,3 +319,26 @@ def test_decoding_steps_after_an_8bit_prefill(tiny8):
     rep = run_case(shape, wb, model, ids, [(1, 800), (3, 400)], [5, 17, 900, 3], label="decode after fp8 prefill",
                    band=3e-2, s_tol=(3e-2, 3e-2), gemm8=True, logit_tol=3e-2, kv_tol=1e-1, aux_tol=0.1)
     assert sum(sum(r) for r in rep["revived"]) > 0            # revivals happened
+
+
+@pytest.mark.parametrize("heads,hd,kv", [(4, 64, 2), (2, 128, 1)])
+def test_fp8_with_shared_kv_heads_batches_and_flags(heads, hd, kv):
+    """The 8-bit projections together with the other variants of the path: grouped-query attention
+    (a narrower k/v part of the fused QKV matrix), a ragged batch, hidden-state copies."""
+    import dataclasses
+    shape = dataclasses.replace(synth.TINY_FP8, n_heads=heads, head_dim=hd, d_model=heads * hd, n_kv_heads=kv)
+    w = synth.make_weights(shape, 1200 + heads + kv, "cpu", gain_jitter=0.2)
+    model = B.Model(shape.as_dict(), _to_dev(w), DEV)
+    wb = synth.weights_to_host_bits(w)
+    sched = [(1, 800), (3, 300)]
+    lens = [300, 65]
+    ids = np.concatenate([synth.make_prompt(n, shape.vocab, 950 + n) for n in lens])
+    cu = [0, 300, 365]
+    out = _run(model, ids, sched, cu=cu, flags=B.LAZYLLM_KEEP_HIDDEN)
+    assert out.status == 0 and out.k(0).shape == (365, kv, hd)
+    for b in range(2):
+        check_against_checker(shape, wb, ids[cu[b]:cu[b + 1]], sched, out, seq=b,
+                              verbose="fp8 gqa H=%d hd=%d kv=%d seq %d" % (heads, hd, kv, b), gemm8=True, tol=TOL8)
+    plain = _run(model, ids, sched, cu=cu)
+    assert torch.equal(plain.logits, out.logits)
+    model.close()
