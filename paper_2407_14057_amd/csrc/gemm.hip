@@ -1094,10 +1094,12 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     const long tiles192 = (long)((M + 191) / 192) * (N / 256);
     // a handful of token rows (decoding): stream the weights, see gemm_skinny_kernel.  Only for
     // callers that keep the ticket counters of the workspace zeroed (ra.skinny).  The partial
-    // tiles it exchanges grow with M: measured against the tile kernels it wins up to about 8
-    // rows (QKV 28 vs 43 us at M = 2, 33 vs 43 at 8, 40 vs 43 at 16; down 28 / 35 / 43 vs 38), and
-    // up to 32 rows for the rotary epilogue, whose tile form has only 48 workgroups at d = 4096.
-    if (ra.skinny && (M <= 8 || (epilogue == EPI_QKV_ROPE && M <= 32)) && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
+    // tiles it exchanges grow with M and with the K split.  Measured against the tile kernels with
+    // the weights in each kernel's own order, cold: QKV 28 / 31 / 36 / 46 us at 4 / 8 / 16 / 24 rows
+    // against 41; O 15 / 16 / 20 / 23 against 25; gate/up 48 / 51 / 57 / 65 against 59; down (K = 2.7 N,
+    // the deepest split) 28 / 32 / 40 / 56 against 35.
+    const int skinny_rows = K > 2 * N ? 8 : 16;
+    if (ra.skinny && M <= skinny_rows && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
         N % 128 == 0 && lda % 8 == 0 && ldw % 8 == 0)
       cfg = 8;
     if (cfg != 0) {}
