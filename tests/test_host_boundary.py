@@ -121,3 +121,16 @@ def test_null_arguments_return_einval_without_touching_the_gpu():
     assert lib.lazyllm_op_score(1, 1, 1, 1, 0, 4, 64, None) == B.LAZYLLM_EINVAL
     assert lib.lazyllm_op_score_scratch_bytes(0, 4) == 0
     assert lib.lazyllm_model_create(None, None, None, None) == B.LAZYLLM_EINVAL
+    # the 8-bit variant's steps and the weight re-ordering steps
+    assert lib.lazyllm_op_quantize_fp8(None, 4, 64, 64, None, 64, None, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_quantize_fp8(16, 4, 60, 64, 16, 64, 16, None) == B.LAZYLLM_EINVAL            # K % 8
+    assert lib.lazyllm_op_quantize_fp8(16, 4, 16392, 16392, 16, 16392, 16, None) == B.LAZYLLM_EINVAL   # K > 16384
+    assert lib.lazyllm_op_gemm_fp8(None, None, None, None, None, None, 4, 256, 128, 128, 128, 256, 0, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_gemm_fp8(16, 16, 16, 16, 16, None, 4, 128, 128, 128, 128, 128, 0, None) == B.LAZYLLM_EINVAL   # N % 256
+    assert lib.lazyllm_op_gemm_fp8(16, 16, 16, 16, 16, None, 4, 256, 64, 64, 64, 256, 0, None) == B.LAZYLLM_EINVAL      # K % 128
+    assert lib.lazyllm_op_gemm_fp8(16, 16, 16, 16, 16, None, 4, 256, 128, 128, 128, 256, 1, None) == B.LAZYLLM_EINVAL   # residual w/o R
+    assert lib.lazyllm_op_gemm_fp8(24, 16, 16, 16, 16, None, 4, 256, 128, 128, 128, 256, 0, None) == B.LAZYLLM_EINVAL   # alignment
+    assert lib.lazyllm_op_pack_weight_ksteps(None, 128, 64, 64, None, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_pack_weight_ksteps(16, 128, 100, 104, 16, None) == B.LAZYLLM_EINVAL         # K % 64
+    assert lib.lazyllm_op_pack_weight_stream(16, 100, 64, 64, 16, None) == B.LAZYLLM_EINVAL           # N % 128
+    assert lib.lazyllm_op_pack_weight_stream(16, 128, 64, 32, 16, None) == B.LAZYLLM_EINVAL           # stride below K
