@@ -1073,7 +1073,15 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
         N != rope->d_model + 2 * kvd || rope->d_model % 128 != 0 || kvd % 128 != 0)
       return hipErrorInvalidValue;
   }
-  if (group_m == 0) group_m = 4;
+  if (group_m == 0) {
+    // Band height of the tile walk (tile rows that share a run of W column blocks in an XCD's L2).
+    // Measured with cold K-step-major weights at 3376 / 2364 / 1182 rows: the QKV shape (48 column
+    // blocks) is best walked column by column over all tile rows (299 / 202 / 106 us against 303 /
+    // 212 / 109 with bands of 4), the gate/up shape (86 column blocks) in bands of 2 (521 / 392 us
+    // against 526 / 400), of 1 below 8 tile rows (203 against 213); 4 elsewhere (within 1 %).
+    const int tm256 = (M + 255) / 256;
+    group_m = epilogue == EPI_QKV_ROPE ? (tm256 < 63 ? tm256 : 63) : epilogue == EPI_SWIGLU ? (tm256 >= 8 ? 2 : 1) : 4;
+  }
   if (cfg == 0) {
     // 256x256 tiles on 8 waves in ping-pong phases have the best reuse and keep the matrix pipe
     // fed; when they would leave much of the 256 CUs idle, smaller tiles on 4 waves win.  The
