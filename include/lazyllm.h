@@ -57,8 +57,9 @@ typedef enum lazyllm_status {
  * n_heads and n_kv_heads * head_dim must be a multiple of 128.  Eq. 1 is the
  * mean over all n_heads attention maps either way.
  * gemm_dtype: arithmetic of the four projections of every layer in the
- * prefill.  0 = 16-bit floating point, the paper's (Sec. 5, implementation
- * details).  1 = the 8-bit variant (see lazyllm_op_gemm_fp8): the stored
+ * prefill.  0 = 16-bit floating point (bf16 storage, fp32 accumulation; the
+ * paper's Sec. 4 names its hardware and framework but no precision, the
+ * benchmark this library is measured on is quoted at bf16).  1 = the 8-bit variant (see lazyllm_op_gemm_fp8): the stored
  * weights (RMSNorm gains folded in) are quantised once at model creation,
  * the activations row by row in front of each projection, OFP8 E4M3 codes
  * with one fp32 scale per row; attention, normalisation, scoring, selection
@@ -91,7 +92,7 @@ typedef struct lazyllm_weights {
   const void* lm_head;            /* [vocab, d_model] */
 } lazyllm_weights;
 
-/* One pruning layer (Sec. 4.2's three knobs: how many pruning layers, where,
+/* One pruning layer (Sec. 5.2's three knobs: how many pruning layers, where,
  * how much).  The scores of layer `layer`-1 decide which tokens enter
  * `layer`; keep_permille/1000 is the fraction kept of the tokens that ran
  * `layer`-1, counted as max(1, ceil(m * keep_permille / 1000)) in integer
@@ -289,7 +290,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
  * Between profile_begin and profile_end every kernel launch of lazyllm_prefill* is
  * bracketed by hipEvents on the call's stream.  profile_end waits for the recorded work,
  * then writes up to `capacity` records (launch order) and the total count.  `work` is the
- * launch's algorithmic work: FLOPs for the GEMM and attention steps (Sec. 4.3: linear layers
+ * launch's algorithmic work: FLOPs for the GEMM and attention steps (Sec. 5.3: linear layers
  * grow linearly, attention quadratically with the tokens computed), bytes for the
  * bandwidth-bound steps.  Not thread-safe; one stream at a time.
  * Steps without a launch of their own never appear: RMSNorm is folded into the QKV and gate/up
@@ -371,10 +372,10 @@ int lazyllm_op_pack_weight_stream(const void* W, int32_t N, int32_t K, int32_t l
                                   void* hip_stream);
 
 /* ---- 8-bit floating point variant of the projections' GEMM --------------------------------
- * An extension for the gfx950 8-bit matrix instructions; the paper itself computes in 16-bit
- * floating point (Sec. 5, implementation details).  Operands are OFP8 E4M3 codes (OCP 8-bit
- * Floating Point Specification: bias 7, no infinities, S.1111.111 = NaN, largest value 448) with
- * one fp32 scale per row, both K-contiguous.
+ * An extension for the gfx950 8-bit matrix instructions; it is not the paper's arithmetic (its
+ * Sec. 4 names hardware and framework only) and never the arithmetic of the headline figure.
+ * Operands are OFP8 E4M3 codes (OCP 8-bit Floating Point Specification: bias 7, no infinities,
+ * S.1111.111 = NaN, largest value 448) with one fp32 scale per row, both K-contiguous.
  *
  * lazyllm_op_quantize_fp8: x [rows, K] bf16 (device, row stride ldx elements, 16-byte aligned)
  *   -> codes [rows, K] uint8 (device, row stride ldq bytes, 8-byte aligned) and scale [rows] fp32

@@ -311,3 +311,81 @@ def test_grouped_query_pruned_prefill_and_decoding_keep_their_structure():
         o2 = gen2.step(tok)
         assert all(abs(s.sum() - 1) < 1e-12 for s in o2.scores)
     assert gen2.times_computed.max() == 1
+
+
+# ---------------------------------------------------------------- bf16-storage rounding points
+
+def _recording_store(log):
+    def store(t):
+        log.append(np.array(t, copy=True))
+        return t
+    return store
+
+
+def test_storage_mode_rounds_exactly_the_tensors_the_data_flow_writes():
+    """The bf16-storage mode models stores to bf16 tensors: per layer v, q (after the rotary
+    embedding), k (after it), the attention output o, h after the attention block, the SwiGLU
+    output a, h after the MLP block -- in that order, each once -- and NOT the normalised
+    activations x, y (RMSNorm is folded into the projections that consume it, so they are never
+    written).  A rounding point added, dropped, moved or reordered fails here."""
+    shape = SMALL
+    wb = _weights(shape)
+    H, hd, d, f = shape.n_heads, shape.head_dim, shape.d_model, shape.d_ffn
+    m = 37
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((m, d))
+    pos = np.sort(rng.choice(500, m, replace=False)).astype(np.int64)
+    lw = O.LayerWeights(wb, 1, np.float64)
+    log = []
+    h_out, k, v, s = O.decoder_layer(h, pos, lw, H, hd, shape.rms_eps, shape.rope_theta, store=_recording_store(log))
+    assert [t.shape for t in log] == [(m, H, hd), (m, H, hd), (m, H, hd), (m, H, hd), (m, d), (m, f), (m, d)]
+    # what each store receives, from the layer equations written out with library routines
+    rms = lambda t, g: torch.nn.functional.rms_norm(torch.from_numpy(t), (d,), torch.from_numpy(g), shape.rms_eps).numpy()
+    x = rms(h, lw.attn_norm)
+    assert np.allclose(log[0], (x @ lw.wv.T).reshape(m, H, hd), atol=1e-12)                     # v, unrotated
+    assert np.allclose(log[1], O.rope((x @ lw.wq.T).reshape(m, H, hd), pos, shape.rope_theta), atol=1e-12)
+    assert np.allclose(log[2], O.rope((x @ lw.wk.T).reshape(m, H, hd), pos, shape.rope_theta), atol=1e-12)
+    sdpa = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(log[1]).permute(1, 0, 2)[None], torch.from_numpy(log[2]).permute(1, 0, 2)[None],
+        torch.from_numpy(log[0]).permute(1, 0, 2)[None], is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.allclose(log[3], sdpa, atol=1e-12)                                               # o
+    h1 = h + log[3].reshape(m, d) @ lw.wo.T
+    assert np.allclose(log[4], h1, atol=1e-12)                                                 # h after attention
+    y = rms(h1, lw.ffn_norm)
+    a = torch.nn.functional.silu(torch.from_numpy(y @ lw.w_gate.T)).numpy() * (y @ lw.w_up.T)
+    assert np.allclose(log[5], a, atol=1e-12)                                                  # SwiGLU output
+    assert np.allclose(log[6], h1 + a @ lw.w_down.T, atol=1e-12)                               # h after the MLP
+    assert np.array_equal(log[6], h_out) and np.array_equal(log[2], k) and np.array_equal(log[0], v)
+    # neither normalised activation is ever handed to store
+    for t in log:
+        assert t.shape != (m, d) or (not np.allclose(t, x) and not np.allclose(t, y))
+
+
+def test_storage_mode_identity_is_the_plain_path_and_rounding_is_real():
+    shape = SMALL
+    wb = _weights(shape)
+    ids = synth.make_prompt(64, shape.vocab, 8)
+    sched = [(1, 700), (3, 500)]
+    plain = O.prefill(shape.as_dict(), wb, ids, sched)
+    ident = O.prefill(shape.as_dict(), wb, ids, sched, bf16_storage=False)
+    assert np.array_equal(plain.logits, ident.logits)
+    # decoder_layer with an explicit identity store: bit for bit the default
+    lw = O.LayerWeights(wb, 0, np.float64)
+    h = np.random.default_rng(5).standard_normal((20, shape.d_model))
+    pos = np.arange(20, dtype=np.int64)
+    a = O.decoder_layer(h, pos, lw, shape.n_heads, shape.head_dim, shape.rms_eps, shape.rope_theta)
+    b = O.decoder_layer(h, pos, lw, shape.n_heads, shape.head_dim, shape.rms_eps, shape.rope_theta, store=lambda t: t)
+    assert all(np.array_equal(u, w_) for u, w_ in zip(a, b))
+    # with bf16 storage every returned tensor is a bf16 value, and the result differs from fp64
+    r = O.prefill(shape.as_dict(), wb, ids, sched, bf16_storage=True, keep_hidden=True)
+    for l in range(shape.n_layers):
+        for t in (r.k[l], r.v[l]) + ((r.hidden_in[l],) if l > 0 else ()):
+            assert np.array_equal(t, O.round_to_bf16(t))
+    assert np.array_equal(r.hidden_out, O.round_to_bf16(r.hidden_out))
+    assert not np.array_equal(r.logits, plain.logits)
+    # the embedding rows are bf16 already: without a per-token scale nothing is rounded before layer 0,
+    # with one the scaled row is (it is what the embedding step writes)
+    scale = np.full(64, 3.0, dtype=np.float32); scale[5] = 1.0 / 3.0
+    rs = O.prefill(shape.as_dict(), wb, ids, [], bf16_storage=True, embed_scale=scale, keep_hidden=True, n_layers=1)
+    e = O.bf16_bits_to_float(wb["embed"][ids]) * scale[:, None].astype(np.float64)
+    assert np.array_equal(rs.hidden_in[0], O.round_to_bf16(e)) and not np.array_equal(rs.hidden_in[0], e)
