@@ -17,10 +17,22 @@ if ROOT not in sys.path:
 PEAK_FP8_TFLOPS = 5000.0         # MI355X dense fp8 matrix peak
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-# Bytes per launch the dominant kernel (gate/up GEMM, SwiGLU epilogue) moves through the L2s'
-# fabric side, averaged over the 32 launches of a 7b_3376 step: rocprofv3 FETCH_SIZE x 2 KiB +
-# WRITE_SIZE x 1 KiB, factors calibrated on a 1 GiB copy (profiles/gemm_attention_7b_3376_pmc.md).
-TRAFFIC_GATE_UP_7B_3376 = 747.85e6
+PMC_PROFILE = os.path.join(ROOT, "profiles", "gemm_attention_7b_3376_pmc.md")
+
+
+def gate_up_traffic_bytes():
+    """Bytes per launch the dominant kernel (gate/up GEMM, SwiGLU epilogue) moves through the L2s'
+    fabric side, averaged over the 32 launches of a 7b_3376 step: rocprofv3 FETCH_SIZE x 2 KiB +
+    WRITE_SIZE x 1 KiB, factors calibrated on a 1 GiB copy.  Read from the committed counter summary
+    (the line "Gate/up projection, all four stages: <x> MB per launch"); None if it is not there."""
+    import re
+    try:
+        m = re.search(r"Gate/up projection, all four stages: ([0-9.]+) MB per launch", open(PMC_PROFILE).read())
+    except OSError:
+        return None
+    return float(m.group(1)) * 1e6 if m else None
+
+
 STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<4,2,2,4,EPI_SWIGLU> (RMSNorm scale + gate/up projection + SiLU*mul)",
                "gemm_qkv": "gemm_pp_kernel<4,2,2,4,EPI_QKV_ROPE128> (RMSNorm scale + QKV projection + RoPE + V^T)",
                "gemm_down": "gemm_pp_kernel<4,2,2,4,EPI_RESIDUAL> (down projection + residual + row sums of squares)",
@@ -223,6 +235,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="7b_3376")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-layers", type=int, default=0, metavar="N",
+                    help="time the CPU checker on the first N layers only and scale by token-layers "
+                         "(default 0: the whole pruned prefill, all layers, timed as it is)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short timings of the other workloads (tiny512, 7b_8192, needles, batch of 8)")
     ap.add_argument("--no-dense", action="store_true", help="skip the unpruned comparison run")
     ap.add_argument("--breakdown", action="store_true", help="print the per-step time table to stderr")
     ap.add_argument("--kernels", action="store_true",
@@ -259,9 +276,18 @@ def main() -> int:
     weights = synth.make_weights(shape, wl.weight_seed, wdev)
     if wdev == "cpu":
         weights = {k: ([t.to(dev) for t in v] if isinstance(v, list) else v.to(dev)) for k, v in weights.items()}
-    n_cpu_layers = min(1 if f8 else 4, shape.n_layers)      # the CPU checker's bounded sample: these layers
-    cpu_layer_bits = [synth.layer_to_host_bits(weights, l) for l in range(n_cpu_layers)]
-    embed_bits = weights["embed"].cpu().view(torch.int16).numpy().view(np.uint16)
+    # the CPU checker gets the same bytes (bf16 bit patterns on the host); the 8-bit variant's checker
+    # is slow (per-row quantisation in numpy), so its sample is the first layer unless told otherwise
+    cpu_layers = args.cpu_baseline_layers if args.cpu_baseline_layers > 0 else (1 if f8 else 0)
+    cpu_layers = min(cpu_layers, shape.n_layers)
+    want_cpu = not args.no_cpu_baseline and len(wl.seqlens) == 1
+    host_bits = None
+    if want_cpu:
+        if cpu_layers:
+            host_bits = {k: ([synth.layer_to_host_bits(weights, l)[k] for l in range(cpu_layers)] if isinstance(v, list)
+                             else v.cpu().view(torch.int16).numpy().view(np.uint16)) for k, v in weights.items()}
+        else:
+            host_bits = synth.weights_to_host_bits(weights)
     # checksum of the inputs as the library gets them (bf16 bit patterns summed per tensor as integers,
     # tensors weighted by their order), so that two reports can be told to be about the same bytes
     wsum, idx = 0, 0
@@ -327,7 +353,7 @@ def main() -> int:
     dom = max(gemm_steps, key=lambda s: by_step.get(s, [0, 0, 0])[0])
     dms, dwork, dn = by_step[dom]
     achieved = dwork / (dms * 1e-3) / 1e12                       # TFLOP/s over this step's launches
-    traffic = TRAFFIC_GATE_UP_7B_3376 if (dom == "gemm_gate_up" and wl.name == "7b_3376") else None
+    traffic = gate_up_traffic_bytes() if (dom == "gemm_gate_up" and wl.name == "7b_3376") else None
     peak = PEAK_FP8_TFLOPS if f8 else PEAK_BF16_TFLOPS
     kernel = ("quantize_rows_f8_kernel + gemm_f8_kernel (%s)" % dom) if f8 else STEP_KERNEL[dom]
     roofline = {"bound": "mfma", "kernel": kernel, "achieved": round(achieved, 1),
@@ -363,23 +389,93 @@ def main() -> int:
 
     total_flops = sum(by_step[s][1] for s in gemm_steps + ("attention",) if s in by_step) / args.steps
 
-    # ---- CPU checker on a bounded sample: decoder layer 0 on the full prompt (rank 0, N=1)
+    # ---- a TTFT sample that counts the host's enqueue time: the stream is idle when the call starts
+    synced = []
+    for _ in range(min(args.steps, 10)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step(sched)
+        torch.cuda.synchronize()
+        synced.append((time.perf_counter() - t0) * 1e3)
+    synced.sort()
+
+    # ---- what Eq. 1 costs inside the prefill: the same profiled pass with scores only where a
+    # pruning layer consumes them (the attention kernel then skips the logit side output and the
+    # gate/up launch its finishing workgroups on the other layers)
+    score_cost = None
+    if len(cu) == 2:
+        B.lazyllm_profile_begin()
+        for _ in range(args.steps):
+            model.prefill(ids, sched, cu_seqlens=cu, embed_scale=scale, flags=B.LAZYLLM_SCORE_ONLY_USED)
+        recs_u = B.lazyllm_profile_end(1 << 20)
+        tot_u = {}
+        for r in recs_u:
+            tot_u[r["step"]] = tot_u.get(r["step"], 0.0) + r["ms"]
+        score_cost = {k: round((by_step[k][0] - tot_u.get(k, 0.0)) / args.steps, 4) for k in ("attention", "gemm_gate_up")}
+        score_cost["note"] = ("ms per prefill that scoring all 32 layers adds to these two steps, against scoring "
+                              "only the %d layers whose successor prunes" % len([1 for _, p in sched if p < 1000]))
+
+    # ---- the other workloads, a few steps each (same model where the shape is the same)
+    others = None
+    if wl.name == "7b_3376" and not args.no_other_workloads:
+        others = {}
+        for name in ("tiny512", "7b_8192", "7b_3376_needles", "7b_batch8"):
+            w2 = synth.WORKLOADS[name]
+            m2 = model
+            if w2.shape != shape:
+                wt = synth.make_weights(w2.shape, w2.weight_seed, "cpu")
+                wt = {k: ([t.to(dev) for t in v] if isinstance(v, list) else v.to(dev)) for k, v in wt.items()}
+                m2 = B.Model(w2.shape.as_dict(), wt, dev)
+            i2 = synth.make_workload_inputs(w2)
+            ids2 = torch.from_numpy(i2["token_ids"]).to(dev)
+            sc2 = None if i2["embed_scale"] is None else torch.from_numpy(i2["embed_scale"]).to(dev)
+            cu2 = [int(x) for x in i2["cu_seqlens"]]
+
+            def timed2(schedule, steps, warmup):
+                for _ in range(warmup):
+                    m2.prefill(ids2, schedule, cu_seqlens=cu2, embed_scale=sc2)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    o2 = m2.prefill(ids2, schedule, cu_seqlens=cu2, embed_scale=sc2)
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e3 / steps, o2
+            k2 = 5 if ids2.numel() < 20000 else 3
+            ms2, o2 = timed2(list(w2.schedule), k2, 2)
+            assert o2.status == 0
+            d2, _ = timed2([], 3, 1)
+            others[name] = {"prompt_tokens": int(ids2.numel()), "batch": len(cu2) - 1, "steps": k2,
+                            "ttft_ms": round(ms2, 4), "tokens_per_s": round(ids2.numel() / (ms2 * 1e-3), 1),
+                            "dense_ttft_ms": round(d2, 4), "pruned_vs_dense_speedup": round(d2 / ms2, 3),
+                            "tokens_per_layer_stage": sorted(set(o2.n_tokens), reverse=True)}
+            if m2 is not model:
+                m2.close()
+            del ids2, o2
+            torch.cuda.empty_cache()
+
+    # ---- the CPU checker, as it stands, timed on this machine's host cores (rank 0, N=1): the whole
+    # pruned prefill of the same prompt with the same weights -- embedding, all layers with its own
+    # scoring, selection and compaction, final norm, LM head -- in its fp32 variant
     cpu = None
-    if not args.no_cpu_baseline and len(cu) == 2:
+    if want_cpu:
         from oracle import lazyllm_oracle as O
         sd = shape.as_dict()
-        h0 = O.bf16_bits_to_float(embed_bits[inp["token_ids"]])
-        if inp["embed_scale"] is not None:
-            h0 = h0 * inp["embed_scale"][:, None].astype(np.float64)
-        lws = [O.LayerWeights({k: [v] for k, v in bits.items()}, 0, np.float64) for bits in cpu_layer_bits]
         t0 = time.perf_counter()
-        hh = h0
-        for lw in lws:
-            hh, _, _, _ = O.decoder_layer(hh, np.arange(n_tokens), lw, shape.n_heads, shape.head_dim,
-                                          shape.rms_eps, shape.rope_theta, gemm8=f8)
-        t_layer = (time.perf_counter() - t0) / len(lws)
-        token_layers = sum(B.lazyllm_keep_counts(n_tokens, shape.n_layers, sched))
-        est_total = t_layer * token_layers / n_tokens
+        ref = O.prefill(sd, host_bits, inp["token_ids"], sched, dtype=np.float32, embed_scale=inp["embed_scale"],
+                        n_layers=(cpu_layers or None), gemm8=f8)
+        t_cpu = time.perf_counter() - t0
+        counts = B.lazyllm_keep_counts(n_tokens, shape.n_layers, sched)
+        if cpu_layers:
+            est_total = t_cpu * sum(counts) / sum(counts[:cpu_layers])
+            sample = ("the first %d of %d layers of the pruned prefill (fp32 variant) took %.1f s; scaled by "
+                      "token-layers (%d of %d) to the whole call" % (cpu_layers, shape.n_layers, t_cpu, sum(counts),
+                                                                      sum(counts[:cpu_layers])))
+        else:
+            est_total = t_cpu
+            sample = ("whole pruned prefill of the same %d-token prompt, all %d layers, the checker's own selections, "
+                      "fp32 variant (numpy): %.1f s" % (n_tokens, shape.n_layers, t_cpu))
+            same = int(np.argmax(ref.logits)) == int(torch.argmax(out.logits[0]).item())
+            sample += "; first token %s the GPU's" % ("equals" if same else "differs from")
         try:
             cores = len(os.sched_getaffinity(0))
         except AttributeError:
@@ -388,9 +484,7 @@ def main() -> int:
         if env_threads:
             cores = min(cores, int(env_threads))
         cpu = {"value": round(n_tokens / est_total, 2), "unit": "tokens/s", "cores": cores, "kind": "oracle",
-               "sample": "decoder layers 0-%d of the same model on the full %d-token prompt in fp64 took %.1f s "
-                         "(%.1f s per layer); scaled by token-layers (%d of %d per layer) to the whole pruned prefill"
-                         % (len(lws) - 1, n_tokens, t_layer * len(lws), t_layer, token_layers, n_tokens)}
+               "dtype": "f32", "seconds": round(t_cpu, 2), "sample": sample}
 
     line = {
         "metric": "pruned-prefill TTFT (ms) + prompt tokens/s, 7B shape, 3376-token prompt"
@@ -410,12 +504,14 @@ def main() -> int:
                    "keep_schedule_permille_of_survivors": sched,
                    "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True)},
         "ttft_ms": round(ms, 4), "ttft_ms_median": round(ttft_median, 4), "ttft_ms_min": round(ttft_min, 4),
+        "ttft_ms_host_synced_median": round(synced[len(synced) // 2], 4),
         "ttft_runs": len(each), "dense_ttft_ms": None if dense_ms is None else round(dense_ms, 4),
         "pruned_vs_dense_speedup": None if dense_ms is None else round(dense_ms / ms, 3),
         "whole_call_tflops": round(total_flops / (ms * 1e-3) / 1e12, 1),
         "whole_call_mfma_frac": None if f8 else round(total_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "profiled_ms_per_step": round(total_prof_ms, 4),
-        "roofline": roofline, "cpu_baseline": cpu, "breakdown": breakdown,
+        "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
+        "scoring_cost_ms": score_cost, "breakdown": breakdown,
     }
     print(json.dumps(line))
     model.close()

@@ -10,3 +10,15 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the C-ABI library)")
+
+
+def progress(msg: str) -> None:
+    """A line in gpurun_out/test_progress.log (pytest captures stdout): long checker computations
+    inside one test leave a trace of where they are."""
+    try:
+        d = os.path.join(ROOT, "gpurun_out")
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(msg.rstrip("\n") + "\n")
+    except OSError:
+        pass

@@ -416,6 +416,38 @@ def test_attention_sharp_rows():
     assert np.abs(_f64(o) - o_ref.reshape(rows, d)).max() < 3e-2
 
 
+@pytest.mark.parametrize("rows", [1793, 2364, 3376])
+def test_attention_headline_form(rows):
+    """The kernel form the 7B workloads launch: 32 heads of 128, more than 1792 rows (8 waves per
+    workgroup, 4 stages), element by element against the checker's full attention maps."""
+    got, ref = _attention_case(rows, 32, 128, rows + 11)
+    err = np.abs(got - ref)
+    assert err.max() < 2e-2, "worst %.3g" % err.max()
+    assert np.sqrt((err ** 2).mean()) < 3e-3
+    # rows past the first 256-query block see several key steps: no row is left at its fill value
+    assert np.abs(got).max() < 8.0
+
+
+def test_attention_headline_form_sharp_rows():
+    """Large, uneven logits at the headline shape: late keys that exceed the running maximum by
+    far more than the lazy-rescale threshold, so the accumulator rescale path runs in the 8-wave
+    form too."""
+    rows, H, hd = 2048, 32, 128
+    rng = np.random.default_rng(78)
+    d = H * hd
+    q = _rand_bf16(rng, (rows, d), 3.0); k = _rand_bf16(rng, (rows, d), 3.0); v = _rand_bf16(rng, (rows, d))
+    # every 97th key is much larger: whoever sees it first must raise its reference point
+    k[::97] *= 3.0
+    pad = (rows + 63) // 64 * 64
+    vt = torch.zeros(d, pad, dtype=torch.bfloat16, device=DEV); vt[:, :rows] = v.t()
+    o = torch.empty(rows, d, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_attention(q, k, vt.contiguous(), pad, o, rows, H, hd)
+    torch.cuda.synchronize()
+    sh = (rows, H, hd)
+    o_ref, _ = O.causal_attention(_f64(q).reshape(sh), _f64(k).reshape(sh), _f64(v).reshape(sh))
+    assert np.abs(_f64(o) - o_ref.reshape(rows, d)).max() < 3e-2
+
+
 @pytest.mark.parametrize("rows", [1, 2, 31, 32, 33, 64, 65, 127, 128, 129, 255, 257, 515, 1000, 2364])
 @pytest.mark.parametrize("H,hd", [(4, 64), (2, 128), (32, 128)])
 def test_attention_score(rows, H, hd):
