@@ -440,6 +440,21 @@ size_t lazyllm_op_score_scratch_bytes(int32_t rows, int32_t n_heads);
 int lazyllm_op_score(const void* q_last, const void* k, float* s, void* scratch, int32_t rows,
                      int32_t n_heads, int32_t head_dim, void* hip_stream);
 
+/* lazyllm_op_score for callers that cannot allocate device memory or pass a scratch buffer:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as lazyllm_op_score, but the scratch (per-head logits and
+ * softmax statistics) lives in a device array that is part of the library image,
+ * LAZYLLM_SCORE_STATIC_SCRATCH_BYTES per GPU, held until the process ends.  The call allocates
+ * nothing, frees nothing and does not synchronise; the device of `hip_stream` must be current.
+ * LAZYLLM_ENOSPC when lazyllm_op_score_scratch_bytes(rows, n_heads) exceeds the array (e.g.
+ * 32 heads: up to about 39 000 rows; 64 heads: about 19 000); nothing is truncated.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or threads) race and must be ordered by the caller.  Nothing in the array needs to
+ * start at zero, so a call is not affected by what an earlier, larger call left there. */
+#define LAZYLLM_SCORE_STATIC_SCRATCH_BYTES (6u * 1024u * 1024u)
+int lazyllm_op_score_static(const void* q_last, const void* k, float* s, int32_t rows,
+                            int32_t n_heads, int32_t head_dim, void* hip_stream);
+
 /* Top-k percentile rule (Sec. 3.2): of m tokens with scores s keep the last
  * one and the k-1 best others (higher fp32 score first, then lower index).
  * keep_idx: int32 [k] ascending; prune_idx: int32 [m-k] ascending. */

@@ -151,6 +151,8 @@ _SIGNATURES = {
     "lazyllm_op_score_scratch_bytes": (C.c_size_t, [C.c_int32, C.c_int32]),
     "lazyllm_op_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_void_p]),
+    "lazyllm_op_score_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_void_p]),
     "lazyllm_op_select": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                     C.c_void_p]),
     "lazyllm_op_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -384,6 +386,11 @@ def lazyllm_op_score_scratch_bytes(rows: int, n_heads: int) -> int:
 def lazyllm_op_score(q_last, k, s, scratch, rows, n_heads, head_dim, stream=None) -> None:
     _check(lib().lazyllm_op_score(_ptr(q_last), _ptr(k), _ptr(s), _ptr(scratch), rows, n_heads,
                                   head_dim, _stream_ptr(stream)))
+
+
+def lazyllm_op_score_static(q_last, k, s, rows, n_heads, head_dim, stream=None) -> None:
+    _check(lib().lazyllm_op_score_static(_ptr(q_last), _ptr(k), _ptr(s), rows, n_heads, head_dim,
+                                         _stream_ptr(stream)))
 
 
 def lazyllm_op_select(s, m, k, keep_idx, prune_idx, stream=None) -> None:

@@ -230,6 +230,10 @@ void layout_output(const lazyllm_config* c, const Stages* st, int batch, uint32_
 
 }  // namespace
 
+namespace lz {
+void set_last_hip_error(int e) { g_last_hip_error = e; }
+}  // namespace lz
+
 struct lazyllm_model {
   lazyllm_config cfg;
   int f_pad;

@@ -172,6 +172,9 @@ __device__ __forceinline__ unsigned long long ssq_to_fixed(float ss) {
   return (unsigned long long)(fminf(ss, 1.0e9f) * SSQ_FIX);
 }
 
+// records a failing HIP call for lazyllm_last_hip_error() (this thread)
+void set_last_hip_error(int e);
+
 // sk_ws: optional scratch of gemm_workspace_bytes() for the stream-K variant (fp32 partial tiles).
 size_t gemm_workspace_bytes();
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,

@@ -22,7 +22,7 @@ def _declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = B.lib()
     names = _declared_symbols()
-    assert len(names) >= 21
+    assert len(names) >= 22
     assert lib.lazyllm_op_gemm_workspace_bytes() > 0
     for n in names:
         assert hasattr(lib, n), n
@@ -134,3 +134,17 @@ def test_null_arguments_return_einval_without_touching_the_gpu():
     assert lib.lazyllm_op_pack_weight_ksteps(16, 128, 100, 104, 16, None) == B.LAZYLLM_EINVAL         # K % 64
     assert lib.lazyllm_op_pack_weight_stream(16, 100, 64, 64, 16, None) == B.LAZYLLM_EINVAL           # N % 128
     assert lib.lazyllm_op_pack_weight_stream(16, 128, 64, 32, 16, None) == B.LAZYLLM_EINVAL           # stride below K
+
+
+def test_static_scratch_scoring_validates_before_any_hip_call():
+    """The allocation-free Eq. 1 entry point rejects bad arguments and sizes beyond its static
+    scratch on the host (no GPU here: reaching a HIP call would fail differently)."""
+    lib = B.lib()
+    one = 4096
+    assert lib.lazyllm_op_score_static(None, one, one, 10, 4, 64, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_score_static(one, one, one, 0, 4, 64, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_score_static(one, one, one, 10, 4, 96, None) == B.LAZYLLM_EINVAL
+    assert lib.lazyllm_op_score_static(one, one, one, 40000, 64, 128, None) == B.LAZYLLM_ENOSPC
+    # the limit is the scratch size the buffer form would ask for
+    assert B.lazyllm_op_score_scratch_bytes(39000, 32) <= 6 * 1024 * 1024 < B.lazyllm_op_score_scratch_bytes(40000, 32)
+    assert lib.lazyllm_op_score_static(one, one, one, 40000, 32, 128, None) == B.LAZYLLM_ENOSPC
