@@ -509,6 +509,8 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   plan.n_stages = stg.n_stages - 1;
   for (int s = 1; s < stg.n_stages; ++s) plan.permille[s - 1] = stg.permille[s];
   const double dd = (double)d, rowb = dd * 2.0;      // bytes of one bf16 row
+  // tickets and flags of the GEMM forms that exchange partial tiles between workgroups
+  LZ_HIP(launch_gemm_counters_clear(W + ws.gemm_ws, st));
   LZ_RUN(LAZYLLM_STEP_PLAN, -1, T, 0.0,
          launch_plan(cu_dev, seqlens[0], B, T, plan, cu_stage, cu_aux, cu_vt, res->status, st));
   float2* rope = (float2*)(W + ws.rope);
@@ -557,8 +559,10 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       if (c->gemm_dtype == 0) {
         EpiArgs eb = *ea;
         eb.w_blocked = 1;                            // the model's 16-bit weights are K-step-major
-        return launch_gemm(A, w16, Cout, R, n, N, K, K, K, ldc, epi, st, &eb,
-                           stream_k ? W + ws.gemm_ws : nullptr, stream_k ? gemm_workspace_bytes() : 0);
+        eb.psk_ready = 1;                            // (flags cleared at the start of this call)
+        (void)stream_k;
+        return launch_gemm(A, w16, Cout, R, n, N, K, K, K, ldc, epi, st, &eb, W + ws.gemm_ws,
+                           gemm_workspace_bytes());
       }
       hipError_t qe = launch_quantize_rows_f8(A, n, K, K, W + ws.a8, K, (float*)(W + ws.sa8), st);
       if (qe != hipSuccess) return qe;
@@ -1035,12 +1039,18 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
   if (ldc < (epi == EPI_SWIGLU ? N / 2 : N)) return LAZYLLM_EINVAL;
   if (M == 0) return LAZYLLM_OK;
   if (workspace != nullptr && ((uintptr_t)workspace & 255) != 0) return LAZYLLM_EINVAL;
-  if (((epilogue >> 8) & 0xff) == 8) {
-    // the skinny kernel's tickets live at the end of the workspace and must start at zero
-    if (M > 32 || workspace == nullptr || ws_bytes < gemm_workspace_bytes()) return LAZYLLM_EINVAL;
+  const int forced = (epilogue >> 8) & 0xff;
+  if (forced == 8 && M > 32) return LAZYLLM_EINVAL;
+  if ((forced == 8 || forced == 9 || forced == 10) && (workspace == nullptr || ws_bytes < gemm_workspace_bytes()))
+    return LAZYLLM_EINVAL;
+  EpiArgs ea{};
+  if (workspace != nullptr && ws_bytes >= gemm_workspace_bytes()) {
+    // the tickets of the weight-streaming kernel and the flags of the persistent stream-K kernel
+    // live at the end of the workspace and must start at zero
     LZ_HIP(launch_gemm_counters_clear(workspace, (hipStream_t)hip_stream));
+    ea.psk_ready = 1;
   }
-  LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, nullptr,
+  LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, &ea,
                      workspace, ws_bytes));
   return LAZYLLM_OK;
 }

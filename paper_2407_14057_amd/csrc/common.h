@@ -155,6 +155,11 @@ struct EpiArgs {
   // the caller keeps the ticket counters at the end of the GEMM workspace zeroed
   // (launch_gemm_counters_clear once before the first use): M <= 32 may take the skinny kernel
   int skinny;
+  // the caller keeps the flags of the persistent stream-K kernel (also at the end of the GEMM
+  // workspace) zeroed likewise: launches whose tile count leaves the last round of the chip partly
+  // idle may take that kernel
+  int psk_ready;
+  int psk_xmode;                     // filled in by the launcher: how partial tiles are exchanged
   // the W argument is in the weight-streaming kernel's own layout (launch_pack_stream); only that
   // kernel can read it, so the launch fails where another kernel would be chosen
   int w_packed;

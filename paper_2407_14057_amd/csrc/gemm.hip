@@ -11,10 +11,20 @@
 // order the model keeps its weights in): the kernels only differ in two byte strides, row to row
 // (ldw * 2 or 128) and K step to K step (128 or N * 128).  K-step-major, the slab of one step is
 // one contiguous run, which the memory system serves better than one line from each of 256 rows.
+#include <stdlib.h>
+
 #include "common.h"
 #include "gemm_shared.h"
 
 namespace lz {
+
+// Workspace of the forms that exchange partial sums between workgroups.  Layout: fp32 partial tiles
+// (64 MB) | 4 KB of tickets of the skinny kernel (see gemm_skinny_kernel) | 4 KB of flags of the
+// persistent stream-K kernel (see gemm_psk_kernel).  Tickets and flags must be zero before the
+// first launch that uses them; every launch leaves them zero again.
+constexpr int SK_GRID = 512;
+constexpr size_t SK_PART_BYTES = (size_t)SK_GRID * 2 * 128 * 128 * sizeof(float);
+constexpr size_t SK_TICKET_BYTES = 4096, PSK_FLAG_BYTES = 4096;
 
 template <int WM, int WN, int TM, int TN, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64)
@@ -459,6 +469,420 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
 }
 
 // ------------------------------------------------------------------------------------------
+// Persistent stream-K form of the ping-pong kernel.  A data-parallel launch runs ceil(T / 256)
+// rounds of tiles on 256 CUs however few tiles the last round holds (1204 tiles: 5 rounds for
+// 4.7 rounds of work; 160 tiles: one round on 62 % of the chip).  Here G workgroups, one per CU
+// and all resident at once, each take an equal share of the work:
+//   * the first floor(T / G) * G tiles run data-parallel, workgroup g taking tiles g, g + G, ...
+//     (same tile walk as the data-parallel kernel, so the L2 sharing is unchanged);
+//   * the K steps of the remaining Rm < G tiles, U = Rm * KT units, are cut into G equal
+//     contiguous ranges.  A range is shorter than a tile, so it covers the END of one tile
+//     (the workgroup that holds a tile's last K steps OWNS the tile) and/or the START or a
+//     middle piece of the next (a piece it does not own).
+// Order inside a workgroup: its data-parallel tiles first (all workgroups of an XCD then walk K in
+// step and share operand slabs through the L2, which a head start of a few K steps would undo),
+// then the piece it does not own -- a tile's first K steps, so these start together at K = 0;
+// the fp32 partial sums go to the workspace, lane-major, 16 bytes per lane and store, followed by
+// a release fence and a flag -- and its own piece LAST: these end together at K = KT, and the
+// other pieces of the tile were finished before the owner is (every workgroup gives its piece
+// away before it starts its own).  The owner adds them in ascending K order (a fixed order:
+// results do not depend on timing) and runs the normal epilogue.  Waits are bounded: if a flag
+// never comes (it cannot, unless fewer than G workgroups fit on the device, which the launcher
+// checks), the owner gives up, counts the failure in the workspace and finishes.
+// Flags are zero on entry; the owner resets the flags it consumed.
+// ------------------------------------------------------------------------------------------
+constexpr unsigned PSK_SPIN_LIMIT = 1u << 22;      // about a second of polling
+
+template <int WM, int WN, int TM, int TN, int EPI>
+__global__ void __launch_bounds__(512)
+gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
+                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K,
+                int lda, int ldw, int ldc, int tiles_m, int tiles_n, int group_m, int G,
+                float* __restrict__ part, unsigned* __restrict__ flags, EpiArgs ra) {
+  constexpr int NWAVES = 8;
+  static_assert(WM * WN == NWAVES, "eight waves: two per SIMD");
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;
+  constexpr int NCOPY = A_INSTR + W_INSTR;
+  static_assert(BM % 64 == 0 && BN % 64 == 0 && NCOPY <= 2 * TM * TN, "tile/wave mismatch");
+  constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+  constexpr int TILE_FLOATS = BM * BN;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  __shared__ unsigned wait_failed;
+  if ((int)blockIdx.x >= G) {                     // side job (see EpiArgs): Eq. 1 scores
+    const int sb = (int)blockIdx.x - G;
+    score_finish_block<true>(ra.sf_z, ra.sf_stat, ra.sf_s, ra.sf_cu, ra.sf_n_single, ra.sf_heads,
+                             ra.sf_z_ld, ra.sf_cu_z, true, sb / ra.sf_blocks_per_seq,
+                             (sb % ra.sf_blocks_per_seq) * (int)blockDim.x, (float2*)lds);
+    return;
+  }
+
+  // `lane` is passed through an empty asm at the start of every section below: the compiler then
+  // cannot keep per-lane values of one section (epilogue addresses, say) alive across the K loop
+  // of another, which cost the loops their registers (spills that wait behind the tile copies)
+  int lane = threadIdx.x & 63;
+#define LZ_FRESH_LANE() asm volatile("" : "+v"(lane))
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int group = wave >> 2;                    // waves w and w+4 share a SIMD
+  const int g = (int)blockIdx.x;
+
+  // ---- this workgroup's share.  The remainder tiles are split XCD by XCD: workgroup ids are dealt
+  // round-robin over the 8 XCDs and the tile walk gives XCD x the tiles whose id is x mod 8, so
+  // the G / 8 workgroups of an XCD cut up the K steps of THAT XCD's remainder tiles: neighbours in
+  // the walk keep sharing operand slabs through their L2, as in the data-parallel rounds.
+  const int T = tiles_m * tiles_n, KT = K / BK;
+  const int full = T / G, Rm = T - full * G;
+  const int xcd = g & 7, gi = g >> 3, GX = G >> 3;
+  const int Rx = Rm > xcd ? (Rm - xcd + 7) >> 3 : 0;           // remainder tiles of this XCD
+  const long long U = (long long)Rx * KT;
+  auto ubegin = [&](int i) { return (long long)i * U / GX; };   // first unit of the XCD's i-th workgroup
+  auto sk_pid = [&](int t) { return full * G + xcd + 8 * t; };  // tile id of the XCD's t-th remainder tile
+  const long long u0 = ubegin(gi), u1 = ubegin(gi + 1);
+  int own_tile = -1, own_ka = 0, oth_tile = -1, oth_ka = 0, oth_kb = 0;
+  if (u1 > u0) {
+    const int ta = (int)(u0 / KT), tb = (int)((u1 - 1) / KT);
+    if (ta == tb) {
+      if (u1 == (long long)(ta + 1) * KT) { own_tile = ta; own_ka = (int)(u0 - (long long)ta * KT); }
+      else { oth_tile = ta; oth_ka = (int)(u0 - (long long)ta * KT); oth_kb = (int)(u1 - (long long)ta * KT); }
+    } else {                                      // the end of tile ta and the start of tile ta + 1
+      own_tile = ta; own_ka = (int)(u0 - (long long)ta * KT);
+      oth_tile = tb; oth_ka = 0; oth_kb = (int)(u1 - (long long)tb * KT);
+    }
+  }
+
+  const uint32_t wstep32 = (uint32_t)ra.w_step_bytes;
+
+  // ---- K steps ka .. kb-1 of tile `pid` into acc (the ping-pong schedule of gemm_pp_kernel, stage
+  // (kt - ka) & 1; every wave passes the same number of barriers).  On return every wave has read
+  // its last fragments; the caller must pass a workgroup barrier before LDS is written again.
+  auto run_range = [&](int pid, int ka, int kb, floatx16_t (&acc)[TM][TN], float (&rs)[TM], int& m0,
+                       int& n0) {
+    LZ_FRESH_LANE();
+    int tile_m, tile_n;
+    workgroup_tile(pid, tiles_m, tiles_n, group_m, tile_m, tile_n);
+    m0 = tile_m * BM; n0 = tile_n * BN;
+    const int crow = lane >> 3;
+    uint32_t koff[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      koff[ks] = (uint32_t)(((ks * 2 + (lane >> 5)) ^ swz64(lane & 31)) * 16);
+    const uint32_t a_row = (uint32_t)((wm * TM * 32 + (lane & 31)) * ROW_BYTES);
+    const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
+    uint32_t a_off[A_INSTR], w_off[W_INSTR];
+#pragma unroll
+    for (int q = 0; q < A_INSTR; ++q) {
+      const int tr = (wave * A_INSTR + q) * 8 + crow;
+      const int cchunk = (lane & 7) ^ swz64(tr);
+      int r = m0 + tr;
+      r = r < M ? r : M - 1;
+      a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
+    }
+#pragma unroll
+    for (int q = 0; q < W_INSTR; ++q) {
+      const int tr = (wave * W_INSTR + q) * 8 + crow;
+      const int cchunk = (lane & 7) ^ swz64(tr);
+      int r = n0 + tr;
+      r = r < N ? r : N - 1;
+      w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
+    }
+    // (uniform base + 32-bit per-lane offset: sixteen 64-bit per-lane pointers would not fit the
+    // register budget next to the accumulators; the launcher checks that the operands span < 4 GB)
+    auto issue_one = [&](int stage, int kt, int q) {
+      if (q < A_INSTR)
+        g2l16((const char*)A + (uint32_t)(a_off[q] + (uint32_t)kt * (uint32_t)(BK * 2)),
+              lds + stage * STAGE_BYTES + (wave * A_INSTR + q) * 1024);
+      else
+        g2l16((const char*)W + (uint32_t)(w_off[q - A_INSTR] + (uint32_t)kt * wstep32),
+              lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR + q - A_INSTR) * 1024);
+    };
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    bf16x8_t af[2][TM], wf[2][TN];
+
+#define LZ_COMPUTE_COPY_PHASE(stage, ktn)                                                      \
+  do {                                                                                         \
+    __builtin_amdgcn_s_setprio(1);                                                             \
+    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                           \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                       \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[k2][j], af[k2][i], acc[i][j], \
+                                                              0, 0, 0);                        \
+          if ((k2 * TM + i) * TN + j < NCOPY) issue_one((stage), (ktn), (k2 * TM + i) * TN + j); \
+        }                                                                                      \
+    _Pragma("unroll") for (int n = 0; n < NCOPY; ++n) {                                        \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                       \
+      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);                                       \
+    }                                                                                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * TM * TN - NCOPY, 0);                       \
+    __builtin_amdgcn_s_setprio(0);                                                             \
+  } while (0)
+#define LZ_MEM_PHASE(st, h)                                                                    \
+  do {                                                                                         \
+    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2) {                                         \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+        af[k2][i] = *(const bf16x8_t*)((st) + a_row + i * 32 * ROW_BYTES + koff[2 * (h) + k2]); \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+        wf[k2][j] = *(const bf16x8_t*)((st) + w_row + j * 32 * ROW_BYTES + koff[2 * (h) + k2]); \
+    }                                                                                          \
+  } while (0)
+#define LZ_COMPUTE_PHASE()                                                                     \
+  do {                                                                                         \
+    __builtin_amdgcn_s_setprio(1);                                                             \
+    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                           \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                         \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[k2][j], af[k2][i], acc[i][j], \
+                                                              0, 0, 0);                        \
+    __builtin_amdgcn_s_setprio(0);                                                             \
+  } while (0)
+#define LZ_PHASE_END()                                                                         \
+  do {                                                                                         \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+    asm volatile("s_barrier" ::: "memory");                                                    \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  } while (0)
+
+#pragma unroll
+    for (int q = 0; q < NCOPY; ++q) issue_one(0, ka, q);
+    load_row_scales<TM>(rs, ra, M, m0, wm, lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (group == 1) LZ_PHASE_END();
+    const bool idle_wave = m0 + wm * TM * 32 >= M;
+    if (idle_wave) {
+      // all of this wave's rows are past M (last tile row): it copies its share of the stages and
+      // keeps the barriers, but runs no MFMA (a loop of its own, so that the accumulators of the
+      // working waves' loop have one definition)
+      for (int kt = ka; kt < kb; ++kt) {
+        const int par = (kt - ka) & 1;
+        const int k_next = kt + 1 < kb ? kt + 1 : kt;
+        LZ_PHASE_END();
+#pragma unroll
+        for (int q = 0; q < NCOPY; ++q) issue_one(par ^ 1, k_next, q);
+        LZ_PHASE_END();
+        if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        LZ_PHASE_END();
+        if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        LZ_PHASE_END();
+      }
+    } else
+    for (int kt = ka; kt < kb; ++kt) {
+      const int par = (kt - ka) & 1;
+      const char* cur = lds + par * STAGE_BYTES;
+      const int k_next = kt + 1 < kb ? kt + 1 : kt;
+      LZ_MEM_PHASE(cur, 0);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      LZ_PHASE_END();
+      LZ_COMPUTE_COPY_PHASE(par ^ 1, k_next);
+      LZ_PHASE_END();
+      LZ_MEM_PHASE(cur, 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      LZ_PHASE_END();
+      LZ_COMPUTE_PHASE();
+      if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      LZ_PHASE_END();
+    }
+    if (group == 0) LZ_PHASE_END();
+#undef LZ_MEM_PHASE
+#undef LZ_COMPUTE_PHASE
+#undef LZ_COMPUTE_COPY_PHASE
+#undef LZ_PHASE_END
+  };
+
+  auto finish_tile = [&](floatx16_t (&acc)[TM][TN], const float (&rs)[TM], int m0, int n0) {
+    LZ_FRESH_LANE();
+    if (EPI == EPI_SWIGLU || !ra.stage_out) {
+      gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
+    } else {
+      static_assert(BM * ((EPI == EPI_SWIGLU) ? BN / 2 : BN) * 2 <= 2 * STAGE_BYTES, "staged tile must fit the stages");
+      staged_tile_out<TM, TN, EPI, BM, BN, NWAVES>(acc, C, R, M, ldc, m0, n0, wm, wn, wave, lane, ra, rs, lds);
+    }
+    __syncthreads();                                // the next item refills stage 0
+  };
+
+  // ---- 1. whole tiles
+  for (int r = 0; r < full; ++r) {
+    floatx16_t acc[TM][TN];
+    float rs[TM];
+    int m0, n0;
+    run_range(r * G + g, 0, KT, acc, rs, m0, n0);
+    finish_tile(acc, rs, m0, n0);
+  }
+
+  // ---- 2. the piece of somebody else's tile: partial sums to slot g, then the flag
+  if (oth_tile >= 0) {
+    floatx16_t acc[TM][TN];
+    float rs[TM];
+    int m0, n0;
+    run_range(sk_pid(oth_tile), oth_ka, oth_kb, acc, rs, m0, n0);
+    LZ_FRESH_LANE();
+    float4* dst = (float4*)(part + (size_t)g * TILE_FLOATS);
+    {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4)
+            dst[((wave * (TM * TN) + i * TN + j) * 4 + q4) * 64 + lane] =
+                make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2],
+                            acc[i][j][4 * q4 + 3]);
+        }
+      // every wave's stores have reached the L2 (vmcnt), then ONE wave writes the L2 back: a
+      // release fence per wave would be eight write-backs of the same cache
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (wave == 0 && ra.psk_xmode != 2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    }
+    if (threadIdx.x == 0)
+      __hip_atomic_store(flags + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // ---- 3. the end of the tile this workgroup owns, plus the pieces the others left
+  if (own_tile >= 0) {
+    floatx16_t acc[TM][TN];
+    float rs[TM];
+    int m0, n0;
+    run_range(sk_pid(own_tile), own_ka, KT, acc, rs, m0, n0);
+    if (own_ka > 0) {
+      // the tile's other pieces belong to this XCD's workgroups i_first .. gi-1 (ids xcd + 8 i)
+      int i_first = gi;
+      while (i_first > 0 && ubegin(i_first) > (long long)own_tile * KT) --i_first;
+      if (threadIdx.x == 0) {
+        unsigned failed = 0;
+        for (int ip = i_first; ip < gi; ++ip) {
+          if (ubegin(ip + 1) <= ubegin(ip)) continue;         // an empty range wrote nothing
+          const int gp = xcd + 8 * ip;
+          unsigned spins = 0;
+          while (__hip_atomic_load(flags + gp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+            __builtin_amdgcn_s_sleep(8);
+            if (++spins >= PSK_SPIN_LIMIT) { failed = 1; break; }
+          }
+        }
+        wait_failed = failed;
+        if (failed) atomicAdd(flags + 1023, 1u);              // (the last word counts give-ups)
+      }
+      if (ra.psk_xmode < 2 && wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      __syncthreads();
+      LZ_FRESH_LANE();
+      if (wait_failed == 0) {
+        for (int ip = i_first; ip < gi; ++ip) {               // ascending K order
+          if (ubegin(ip + 1) <= ubegin(ip)) continue;
+          const float4* src = (const float4*)(part + (size_t)(xcd + 8 * ip) * TILE_FLOATS);
+          // four blocks (64 registers, free now that the operand fragments are dead) per round trip
+          constexpr int NB = TM * TN, BATCH = 4;
+          static_assert(NB % 2 == 0, "blocks are fetched in batches");
+#pragma unroll
+          for (int b0 = 0; b0 < NB; b0 += BATCH) {
+            floatx4_t v[BATCH][4];
+            {
+#pragma unroll
+              for (int u = 0; u < BATCH; ++u)
+                if (b0 + u < NB) {
+#pragma unroll
+                  for (int q4 = 0; q4 < 4; ++q4) {
+                    const float4 t = src[((wave * NB + b0 + u) * 4 + q4) * 64 + lane];
+                    v[u][q4] = floatx4_t{t.x, t.y, t.z, t.w};
+                  }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u)
+              if (b0 + u < NB) {
+                const int i = (b0 + u) / TN, j = (b0 + u) % TN;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                  acc[i][j][4 * q4] += v[u][q4][0]; acc[i][j][4 * q4 + 1] += v[u][q4][1];
+                  acc[i][j][4 * q4 + 2] += v[u][q4][2]; acc[i][j][4 * q4 + 3] += v[u][q4][3];
+                }
+              }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
+      __syncthreads();
+      if (threadIdx.x == 0)
+        for (int ip = i_first; ip < gi; ++ip)
+          __hip_atomic_store(flags + xcd + 8 * ip, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    finish_tile(acc, rs, m0, n0);
+  }
+#undef LZ_FRESH_LANE
+}
+
+// Workgroups of the persistent kernel that are resident at once (one per CU when the device is
+// otherwise idle); 0 if the runtime cannot tell.
+template <typename KernT>
+static int psk_resident_workgroups(KernT kern, int lds_bytes) {
+  int dev = 0, per_cu = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, 512, (size_t)lds_bytes) != hipSuccess)
+    return 0;
+  return per_cu >= 1 ? cus : 0;
+}
+
+template <int WM, int WN, int TM, int TN>
+static hipError_t launch_psk(const void* A, const void* W, void* C, const void* R, int M, int N,
+                             int K, int lda, int ldw, int ldc, int epi, int group_m,
+                             const EpiArgs& ra, void* ws, hipStream_t st) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  if (N % BN != 0 || ws == nullptr) return hipErrorInvalidValue;
+  // the kernel addresses both operands with 32-bit byte offsets
+  if ((unsigned long long)M * lda * 2 >= (1ull << 32) ||
+      (unsigned long long)N * (ra.w_blocked ? K : ldw) * 2 >= (1ull << 32))
+    return hipErrorInvalidValue;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  EpiArgs ea = ra;
+  ea.w_step_bytes = ra.w_blocked ? (unsigned long long)N * ROW_BYTES : (unsigned long long)ROW_BYTES;
+  if (ra.w_blocked) ldw = BK;
+  ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
+  ea.stage_out = (epi == EPI_QKV_ROPE) ? (ra.d_model % BN == 0 && (ra.kv_dim > 0 ? ra.kv_dim : ra.d_model) % BN == 0)
+                 : (epi != EPI_SWIGLU && ldc % 8 == 0 && ((uintptr_t)C & 15) == 0);
+  const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
+  float* part = (float*)ws;
+  unsigned* flags = (unsigned*)((char*)ws + SK_PART_BYTES + SK_TICKET_BYTES);
+  static const int xmode = [] { const char* e = getenv("LAZYLLM_PSK_XMODE"); return e ? atoi(e) : 0; }();
+  ea.psk_xmode = xmode;
+#define LZ_GEMM(E)                                                                               \
+  do {                                                                                           \
+    auto kern = gemm_psk_kernel<WM, WN, TM, TN, E>;                                              \
+    static int resident = -1;                                                                    \
+    if (resident < 0) {                                                                          \
+      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                             \
+      resident = psk_resident_workgroups(kern, LDS_BYTES);                                       \
+    }                                                                                            \
+    int G = resident < 256 ? resident : 256;                                                     \
+    G &= ~7;                                         /* whole rounds over the 8 XCDs */          \
+    if (G < 8 || (size_t)G * BM * BN * sizeof(float) > SK_PART_BYTES || G > 1016)                \
+      return hipErrorInvalidConfiguration;                                                       \
+    hipLaunchKernelGGL(kern, dim3(G + side), dim3(512), LDS_BYTES, st, (const uint16_t*)A,       \
+                       (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw,  \
+                       ldc, tiles_m, tiles_n, group_m, G, part, flags, ea);                      \
+  } while (0)
+  if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
+  else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
+  else if (epi == EPI_SWIGLU) LZ_GEMM(EPI_SWIGLU);
+  else if (epi == EPI_QKV_ROPE) {
+    if (ra.head_dim == 64) LZ_GEMM(EPI_QKV_ROPE64);
+    else if constexpr (TN >= 4) LZ_GEMM(EPI_QKV_ROPE128);
+    else return hipErrorInvalidValue;
+  }
+  else return hipErrorInvalidValue;
+#undef LZ_GEMM
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Stream-K on 128x128 tiles (4 waves of 64x64): for shapes whose tile count does not divide
 // over the 256 CUs.  The (tile, K step) pairs are numbered tile-major and cut into G equal
 // contiguous ranges, one per persistent workgroup (two fit on a CU).  A workgroup finishes
@@ -690,9 +1114,8 @@ gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C
   }
 }
 
-constexpr int SK_GRID = 512;
-// (the last 4 KB hold the skinny kernel's tickets, see gemm_skinny_kernel)
-size_t gemm_workspace_bytes() { return (size_t)SK_GRID * 2 * SK_TILE_ELEMS * sizeof(float) + 4096; }
+static_assert(SK_PART_BYTES == (size_t)SK_GRID * 2 * SK_TILE_ELEMS * sizeof(float), "partial tiles of the 128x128 stream-K form");
+size_t gemm_workspace_bytes() { return SK_PART_BYTES + SK_TICKET_BYTES + PSK_FLAG_BYTES; }
 
 static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R, float* partial,
                             int M, int N, int K, int lda, int ldw, int ldc, int epi,
@@ -1008,7 +1431,7 @@ static hipError_t launch_skinny(const void* A, const void* W, void* C, const voi
   if (ks < 1) ks = 1;
   const int max_ks = (ksteps + 15) / 16;
   if (ks > max_ks) ks = max_ks;
-  const size_t part_bytes = gemm_workspace_bytes() - SKN_COUNTER_BYTES;
+  const size_t part_bytes = SK_PART_BYTES;
   while (ks > 1 && (size_t)n_groups * ks * SKN_TILE * sizeof(float) > part_bytes) --ks;
   const int steps = (ksteps + 4 * ks - 1) / (4 * ks);
   EpiArgs ea = ra;
@@ -1050,7 +1473,8 @@ static hipError_t launch_skinny(const void* A, const void* W, void* C, const voi
 }
 
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st) {
-  return launch_fill_zero((char*)sk_ws + gemm_workspace_bytes() - SKN_COUNTER_BYTES, SKN_COUNTER_BYTES, st);
+  static_assert(SKN_COUNTER_BYTES == SK_TICKET_BYTES, "ticket area");
+  return launch_fill_zero((char*)sk_ws + SK_PART_BYTES, SK_TICKET_BYTES + PSK_FLAG_BYTES, st);
 }
 
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
@@ -1113,6 +1537,19 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     if (ra.skinny && M <= skinny_rows && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
         N % 128 == 0 && lda % 8 == 0 && ldw % 8 == 0)
       cfg = 8;
+    // Persistent stream-K over the 256x256 tiles when the last data-parallel round would leave
+    // much of the chip idle.  The exchange of partial tiles costs about 25 us per launch (write,
+    // L2 write-back, read) and the cut tiles share less in the L2, so it pays only from about half
+    // an empty round on (a third with the long K of the down projection).  Measured, cold weights:
+    // down projection at 4916 / 2364 / 1967 rows 466 -> 401, 228 -> 209, 194 -> 163 us, QKV at 1967
+    // rows 206 -> 182 us, O at 4916 rows 183 -> 174 us; gate/up at 3376 rows (4.7 rounds) 517 -> 534:
+    // not taken.
+    if (cfg == 0 && ra.psk_ready && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
+        N % 256 == 0 && big_tiles >= 128 && epilogue != EPI_SWIGLU) {     // (gate/up at 2364 rows, 3.36 rounds: 389 -> 388 us, not worth it)
+      const long rounds = (big_tiles + 255) / 256;
+      const double slack = (double)rounds - (double)big_tiles / 256.0;
+      if (slack >= (K >= 8192 ? 0.3 : 0.45)) cfg = 9;
+    }
     if (cfg != 0) {}
     else if (N % 256 == 0 && big_tiles >= 150 && big_tiles <= 205 && tiles192 <= 256 &&
              epilogue != EPI_QKV_ROPE) cfg = 7;
@@ -1137,6 +1574,12 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_pp<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 7:                                             // 192x256, 8 waves of 96x64, ping-pong
             return launch_pp<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 9:                                             // 256x256 ping-pong, persistent stream-K
+            if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes() || !ra.psk_ready) return hipErrorInvalidValue;
+            return launch_psk<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, sk_ws, st);
+    case 10:                                            // 192x256 ping-pong, persistent stream-K
+            if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes() || !ra.psk_ready) return hipErrorInvalidValue;
+            return launch_psk<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, sk_ws, st);
     case 6:                                             // 128x128 stream-K + fix-up
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
             return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out,

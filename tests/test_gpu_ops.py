@@ -226,6 +226,43 @@ def test_gemm_stream_k(M, N, K, epi):
     assert torch.equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("cfg", [9, 10])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (300, 768, 256), (2364, 4096, 1024), (1182, 4096, 4096),
+                                   (3376, 2048, 512), (700, 22016, 256), (5000, 256, 128), (8192, 8192, 128)])
+@pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
+def test_gemm_persistent_stream_k(cfg, M, N, K, epi):
+    """The persistent stream-K schedule of the ping-pong tiles (forced): shapes with fewer tiles than
+    CUs (every tile cut into several K pieces), with whole data-parallel rounds plus a cut remainder,
+    with exactly whole rounds, and a single K step.  Same result as the plain product up to the order
+    of the fp32 partial sums, the same bits on every run, flags left at zero, no wait given up."""
+    rng = np.random.default_rng(M + N + K + epi + cfg)
+    A = _rand_bf16(rng, (M, K)); W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    acc = _f64(A) @ _f64(W).T
+    if epi == B.EPI_SWIGLU:
+        blocks = acc.reshape(M, N // 64, 2, 32)
+        ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+        R = None
+    else:
+        R = _rand_bf16(rng, (M, N))
+        ref = acc + (_f64(R) if epi == B.EPI_RESIDUAL else 0.0)
+    outs = []
+    for _ in range(2):
+        if epi == B.EPI_SWIGLU:
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, epi | (cfg << 8), workspace=ws)
+        else:
+            Cout = R.clone()
+            B.lazyllm_op_gemm(A, W, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N,
+                              epi | (cfg << 8), workspace=ws)
+        torch.cuda.synchronize()
+        outs.append(Cout)
+        tail = ws[-4096:].view(torch.int32)
+        assert int(tail.abs().sum().item()) == 0          # flags consumed and reset, no wait given up
+    _assert_bf16_close(_f64(outs[0]), ref, 1.0, "gemm persistent stream-K")
+    assert torch.equal(outs[0], outs[1])
+
+
 def _ssq_fixed(rows_f64):
     """Row sums of squares in the library's 2^-32 fixed point (from fp64, for inputs)."""
     return torch.from_numpy(np.floor((rows_f64 ** 2).sum(axis=1) * 2.0 ** 32).astype(np.uint64).view(np.int64)).to(DEV)
