@@ -468,7 +468,8 @@ int lazyllm_op_gather(const void* h, const int32_t* pos, const int32_t* keep_idx
                       const int32_t* prune_idx, int32_t n_prune, void* h_out, int32_t* pos_out,
                       void* aux_h, int32_t* aux_pos, int32_t d, void* hip_stream);
 
-/* logits[V] = rmsnorm(h_last, gain) . W_lm^T, fp32 out; xf: device fp32[d] scratch. */
+/* logits[V] = rmsnorm(h_last, gain) . W_lm^T, fp32 out; xf: device fp32[d] scratch (written only
+ * by the two-launch form that rows wider than 32768 elements take). */
 int lazyllm_op_lm_head(const void* h_last, const void* gain, const void* w_lm, float* xf,
                        float* logits, int32_t d, int32_t vocab, float eps, void* hip_stream);
 

@@ -642,11 +642,17 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     LZ_HIP(hipMemcpyAsync(res->hidden_out, hbuf[cur], (size_t)stg.total[s_last] * d * 2,
                           hipMemcpyDeviceToDevice, st));
   }
-  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, (double)c->vocab * rowb,
-         launch_final_norm(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm,
-                           (float*)(W + ws.xf), d, c->rms_eps, st));
-  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, 0.0,
-         launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, B, d, c->vocab, st));
+  if (lm_head_fused_fits(B, d)) {
+    LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, (double)c->vocab * rowb,
+           launch_lm_head_fused(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm, m->lm_head,
+                                res->logits, d, c->vocab, c->rms_eps, st));
+  } else {
+    LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, (double)c->vocab * rowb,
+           launch_final_norm(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm,
+                             (float*)(W + ws.xf), d, c->rms_eps, st));
+    LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, 0.0,
+           launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, B, d, c->vocab, st));
+  }
   return LAZYLLM_OK;
 }
 
@@ -985,11 +991,17 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
            launch_gemm(W + ws.act, m->wdown[l], h, h, M, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
   }
-  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, (double)c->vocab * rowb,
-         launch_final_norm(hbuf[cur], nullptr, M, 1, m->final_norm, (float*)(W + ws.xf), d,
-                           c->rms_eps, st));
-  LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, 0.0,
-         launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, 1, d, c->vocab, st));
+  if (lm_head_fused_fits(1, d)) {
+    LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, (double)c->vocab * rowb,
+           launch_lm_head_fused(hbuf[cur], nullptr, M, 1, m->final_norm, m->lm_head, res->logits, d, c->vocab,
+                                c->rms_eps, st));
+  } else {
+    LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, (double)c->vocab * rowb,
+           launch_final_norm(hbuf[cur], nullptr, M, 1, m->final_norm, (float*)(W + ws.xf), d,
+                             c->rms_eps, st));
+    LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, 0.0,
+           launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, 1, d, c->vocab, st));
+  }
   g->n_tokens = n_tot;
   return LAZYLLM_OK;
 }
@@ -1237,6 +1249,11 @@ int lazyllm_op_lm_head(const void* h_last, const void* gain, const void* w_lm, f
       !(eps > 0.f))
     return LAZYLLM_EINVAL;
   hipStream_t st = (hipStream_t)hip_stream;
+  if (lm_head_fused_fits(1, d)) {
+    // (one launch: every workgroup normalises the row itself; xf is then not used)
+    LZ_HIP(launch_lm_head_fused(h_last, nullptr, 1, 1, gain, w_lm, logits, d, vocab, eps, st));
+    return LAZYLLM_OK;
+  }
   LZ_HIP(launch_final_norm(h_last, nullptr, 1, 1, gain, xf, d, eps, st));
   LZ_HIP(launch_lm_head(xf, w_lm, logits, 1, d, vocab, st));
   return LAZYLLM_OK;

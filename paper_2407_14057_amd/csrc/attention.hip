@@ -13,6 +13,8 @@
 // mapped to keys through a fixed permutation (bits 2 and 3 swapped) chosen so that the 8
 // accumulator values a lane holds for one 16-key step are exactly the 8 consecutive keys the
 // B operand of the second product expects from that lane.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace lz {
@@ -315,6 +317,343 @@ flash_attn_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Ping-pong form for long sequences (8 waves = 256 queries of one head per workgroup, NS stages).
+// The flash_attn_kernel above keeps all eight waves in step (one barrier per 64-key step, after
+// the softmax), so the two waves of a SIMD do their matrix work at the same time and their
+// vector work at the same time, and the matrix pipe idles through every softmax.  Measured on
+// this part, matrix and vector instructions of two waves on one SIMD DO run side by side (32
+// MFMAs against 32 fma + exp2 + add groups: 0.60 us together, 0.56 us for the MFMAs alone), so
+// here the two waves of a SIMD (w and w + 4) run half a step apart, as in the GEMM's ping-pong
+// schedule: a wave alternates a MATRIX half step  M(i) = [O^T += Vt(i-1) P^T(i-1)] [S^T(i) = K(i) Q^T]
+// (32 MFMAs back to back, the LDS reads of the next operands in their shadow) and a VECTOR half
+// step  V(i) = softmax of step i's 64 keys (mask, running maximum, exp2, bf16 P), and while one
+// wave of the pair is in M the other is in V.  A bare s_barrier closes every phase:
+//   phase:       0      1      2      3      4    ...
+//   waves 0-3:  M(0)   V(0)   M(1)   V(1)   M(2)  ...
+//   waves 4-7:   -     M(0)   V(0)   M(1)   V(1)  ...
+// Tile t (K rows and Vt columns of keys 64t .. 64t+63) is copied into stage t mod NS by all
+// waves at the start of phase 2(t - NS + 1) + 2, when nobody reads tile t - NS any more (its last
+// use is M(t - NS + 1) of waves 4-7 in phase 2(t - NS + 1) + 1); every wave waits for its share of
+// tile i + 1 before the barrier that ends phase 2i + 1, so M(i + 1) finds it complete.
+// ------------------------------------------------------------------------------------------
+template <int HD, int NS>
+__global__ void __launch_bounds__(512)
+flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                     const uint16_t* __restrict__ vt, uint16_t* __restrict__ o,
+                     const int32_t* __restrict__ cu, const int32_t* __restrict__ cu_vt, int n_single,
+                     int vt_ld, int n_heads, float scale_log2e, float* __restrict__ z,
+                     float2* __restrict__ zstat, int z_ld, int kv_group) {
+  constexpr int NW = 8;
+  constexpr int CHK = HD / 8;
+  constexpr int KSTEPS = HD / 16;
+  constexpr int HS = HD / 32;
+  constexpr int K_TILE = ATT_BN * HD * 2;
+  constexpr int STAGE = 2 * K_TILE;
+  constexpr int ATT_BM = 32 * NW;
+  constexpr int K_INSTR = (ATT_BN * CHK / 64) / NW;
+  constexpr int V_INSTR = (HD * 8 / 64) / NW;
+  static_assert(K_INSTR >= 1 && V_INSTR >= 1, "tile copies must cover every wave");
+  static_assert(NS >= 4, "a tile is copied two steps before its first use");
+  constexpr int K_ROWS_PER_INSTR = 64 / CHK;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int group = wave >> 2;
+  const int head = blockIdx.x, b = blockIdx.z;
+  int row0, n;
+  seq_range(cu, b, n_single, row0, n);
+  const int qblocks = (n + ATT_BM - 1) / ATT_BM;
+  if ((int)blockIdx.y >= qblocks) return;
+  const int qb = qblocks - 1 - blockIdx.y;    // longest blocks first
+  const int q0 = qb * ATT_BM;
+  const int d = n_heads * HD;
+  const int kvd = d / kv_group, kvh = head / kv_group;
+  const int hi = lane >> 5, l31 = lane & 31;
+
+  const int qrow = q0 + wave * 32 + l31;
+  const int qrow_c = qrow < n ? qrow : n - 1;
+  bf16x8_t qf[KSTEPS];
+  {
+    const uint16_t* qp = q + (size_t)(row0 + qrow_c) * d + head * HD + hi * 8;
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) qf[s] = *(const bf16x8_t*)(qp + s * 16);
+  }
+
+  const int ntiles = min((n + ATT_BN - 1) / ATT_BN, (q0 + ATT_BM) / ATT_BN);
+  const uint16_t* kbase = k + (size_t)row0 * kvd + kvh * HD;
+  const uint16_t* vbase = vt + (size_t)kvh * HD * vt_ld + (cu_vt ? cu_vt[b] : 0);
+  auto issue = [&](int t) {                    // tile t into stage t mod NS
+    char* sk = lds + (t % NS) * STAGE;
+    char* sv = sk + K_TILE;
+    const int k0 = t * ATT_BN;
+#pragma unroll
+    for (int qi = 0; qi < K_INSTR; ++qi) {
+      const int slab = wave * K_INSTR + qi;
+      const int r = slab * K_ROWS_PER_INSTR + lane / CHK;
+      const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
+      int key = k0 + r;
+      key = key < n ? key : n - 1;
+      g2l16(kbase + (size_t)key * kvd + c * 8, sk + slab * 1024);
+    }
+#pragma unroll
+    for (int qi = 0; qi < V_INSTR; ++qi) {
+      const int slab = wave * V_INSTR + qi;
+      const int r = slab * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ swz64(r);
+      g2l16(vbase + (size_t)r * vt_ld + k0 + c * 8, sv + slab * 1024);
+    }
+  };
+
+  const int kperm = (l31 & 0x13) | ((l31 & 4) << 1) | ((l31 & 8) >> 1);   // swap bits 2 and 3
+  uint32_t k_addr[2];
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) k_addr[sub] = (uint32_t)((sub * 32 + kperm) * HD * 2);
+  const int kx = CHK == 16 ? swz128(kperm) : swz64(kperm);
+  const uint32_t v_addr = (uint32_t)(K_TILE + l31 * 128);
+  const int vx = swz64(l31);
+
+  floatx16_t oacc[HS];
+#pragma unroll
+  for (int h = 0; h < HS; ++h)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[h][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int q_lo = q0 + wave * 32, q_hi = q_lo + 31;
+  const bool score_wave = z != nullptr && q_lo <= n - 1 && n - 1 <= q_hi;
+  // steps in which this wave has anything to do: keys 64 i .. up to its last query
+  const int n_act = q_lo < n ? min(ntiles, q_hi / ATT_BN + 1) : 0;
+
+#define LZ_ATT_INTERLEAVE()                                  \
+  _Pragma("unroll") for (int g = 0; g < KSTEPS; ++g) {        \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
+  }
+#define LZ_PHASE_END()                                       \
+  do {                                                       \
+    __builtin_amdgcn_sched_barrier(0);                       \
+    asm volatile("s_barrier" ::: "memory");                  \
+    __builtin_amdgcn_sched_barrier(0);                       \
+  } while (0)
+  constexpr int PER_STEP = K_INSTR + V_INSTR;
+  constexpr int SCORE_STORES = 8;
+  static_assert((NS - 3) * PER_STEP + SCORE_STORES < 64, "vmcnt is 6 bits");
+  bf16x8_t fa[KSTEPS], fb[KSTEPS];
+  auto kread = [&](const char* st, int sub, int s) {
+    return *(const bf16x8_t*)(st + k_addr[sub] + (((s * 2 + hi) ^ kx) * 16));
+  };
+  auto vread = [&](const char* st, int i) {          // i = 4 * h + 2 * sub + t
+    const int chunk = ((i >> 1) & 1) * 4 + (i & 1) * 2 + hi;
+    return *(const bf16x8_t*)(st + v_addr + (i >> 2) * 32 * 128 + ((chunk ^ vx) * 16));
+  };
+
+  floatx16_t sacc[2];
+  bf16x8_t pf[2][2];
+
+  // ---- the matrix half steps.  Operand fragments alternate between fa and fb; each group of reads
+  // rides under the MFMAs of the group before it.  Consecutive MFMAs go to DIFFERENT accumulators:
+  // an MFMA that adds to the result of the one just before it waits for that result (about two
+  // issue slots), and in this schedule no second wave is there to fill the gap.  So a fragment
+  // buffer holds half the k-steps of BOTH 32-key blocks of the first product (slot u: block u & 1,
+  // k-step (u >> 1) + 4 * buffer), and of the second product the Vt rows of two output blocks,
+  // interleaved (slot u: operand pv_op(u)).
+  constexpr int HK = KSTEPS / 2;                     // k-steps per buffer and block
+  auto k_frag = [&](const char* st, int buf, int u) { return kread(st, u & 1, (u >> 1) + HK * buf); };
+  auto pv_op = [](int u) { return (u & 1) * (KSTEPS / 2) + (u >> 1); };   // 0,4,1,5,... : alternates output blocks
+  // first product of step i (on entry fa holds the first buffer of tile i's K; leaves Vt half 0 of tile i in fa)
+  auto first_product = [&](int i) {
+    const char* st = lds + (i % NS) * STAGE;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) fb[u] = k_frag(st, 1, u);
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u)
+      sacc[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], qf[u >> 1], sacc[u & 1], 0, 0, 0);
+    LZ_ATT_INTERLEAVE();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) fa[u] = vread(st, pv_op(u));
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u)
+      sacc[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u], qf[(u >> 1) + HK], sacc[u & 1], 0, 0, 0);
+    LZ_ATT_INTERLEAVE();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // second product of step i (fa holds Vt half 0 of tile i); with `next`, the first K buffer of tile
+  // i+1 is fetched into fa under its last MFMAs
+  auto second_product = [&](int i, bool next) {
+    const char* st = lds + (i % NS) * STAGE;
+    const char* st_next = lds + ((i + 1) % NS) * STAGE;
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) fb[u] = vread(st, KSTEPS + pv_op(u));
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) {
+      const int op = pv_op(u);
+      oacc[op >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], pf[(op >> 1) & 1][op & 1], oacc[op >> 2], 0, 0, 0);
+    }
+    LZ_ATT_INTERLEAVE();
+    __builtin_amdgcn_sched_barrier(0);
+    if (next) {
+#pragma unroll
+      for (int u = 0; u < KSTEPS; ++u) fa[u] = k_frag(st_next, 0, u);
+    }
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) {
+      const int op = pv_op(u);
+      oacc[HS / 2 + (op >> 2)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u], pf[(op >> 1) & 1][op & 1],
+                                                                         oacc[HS / 2 + (op >> 2)], 0, 0, 0);
+    }
+    if (next) { LZ_ATT_INTERLEAVE(); }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // ---- vector half step i: softmax of the 64 keys of step i (sacc -> pf, running statistics).
+  // Register r of block sub is key k0 + 32*sub + 16*(r/8) + 8*hi + r%8.
+  auto vector_half = [&](int i) {
+    if (i >= n_act) return;
+    const int k0 = i * ATT_BN;
+    if ((k0 + ATT_BN - 1) > q_lo) {
+      asm volatile("; causal mask" ::: "memory");   // keeps this a real branch
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * sub + 16 * (r / 8) + 8 * hi + (r % 8);
+          if (key > qrow) sacc[sub][r] = -INFINITY;
+        }
+    }
+    if (score_wave) {
+      asm volatile("; last-query logits" ::: "memory");
+      if (qrow == n - 1) {
+        float* zr = z + (size_t)head * z_ld + (cu_vt ? cu_vt[b] : 0) + k0 + 8 * hi;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            float4 v4;
+            v4.x = sacc[sub][4 * g] * scale_log2e;     v4.y = sacc[sub][4 * g + 1] * scale_log2e;
+            v4.z = sacc[sub][4 * g + 2] * scale_log2e; v4.w = sacc[sub][4 * g + 3] * scale_log2e;
+            *(float4*)(zr + 32 * sub + 16 * (g >> 1) + 4 * (g & 1)) = v4;
+          }
+      }
+    }
+    float mraw = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mraw = fmaxf(mraw, sacc[sub][r]);
+    float mloc = mraw * scale_log2e;
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.0f) != 0) {
+      const float m_new = fmaxf(m_run, mloc);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+      asm volatile("; raise the running maximum" ::: "memory");
+#pragma unroll
+      for (int h = 0; h < HS; ++h) oacc[h] *= alpha;
+    }
+    const float neg_m = -m_run;
+    float psum = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float p[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][8 * t + j], scale_log2e, neg_m));
+          psum += p[j];
+        }
+        uint4 packed = pack8(p);
+        pf[sub][t] = *reinterpret_cast<bf16x8_t*>(&packed);
+      }
+    l_run += psum;
+  };
+  // own copies of tile t have landed (tile t+1 may still be in flight; the wave that stores the
+  // last query's logits has up to SCORE_STORES more operations behind the copies)
+  auto wait_tile = [&](int t, bool stores_behind = true) {
+    if (t >= ntiles) return;
+    if (t + NS - 3 < ntiles) {                       // tiles t+1 .. t+NS-3 are in flight behind it
+      if (score_wave && stores_behind) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * PER_STEP + SCORE_STORES) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 3) * PER_STEP) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+  };
+
+  // ---- prologue: tiles 0 .. NS-2 on their way, tile 0 landed
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < ntiles) issue(t);
+  if (ntiles >= NS - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  LZ_PHASE_END();
+  if (n_act > 0) {
+#pragma unroll
+    for (int u = 0; u < KSTEPS; ++u) fa[u] = k_frag(lds, 0, u);
+  }
+
+  // One instruction stream for both halves of the workgroup; waves 4-7 run it one phase later.
+  //   waves 0-3: M(0) in phase 0, then V(i) in phase 2i+1 and M(i+1) in phase 2i+2
+  //   waves 4-7: M(0) in phase 1, then V(i) in phase 2i+2 and M(i+1) in phase 2i+3
+  // where M(0) is the first product of step 0 and M(i+1) the second product of step i followed by the
+  // first product of step i+1.  Tile i+NS-1 is issued at the start of phase 2i+2; tile i+1 is waited
+  // for before the barrier that ends phase 2i+1.
+  if (group == 1) LZ_PHASE_END();
+  if (n_act > 0) {
+    __builtin_amdgcn_s_setprio(1);
+    first_product(0);
+    __builtin_amdgcn_s_setprio(0);
+  }
+  if (group == 1) wait_tile(1, false);            // (no logit stores issued yet)
+  LZ_PHASE_END();
+  for (int i = 0; i < ntiles; ++i) {
+    if (group == 1 && i + NS - 1 < ntiles) issue(i + NS - 1);
+    vector_half(i);
+    __builtin_amdgcn_sched_barrier(0);
+    if (group == 0) wait_tile(i + 1);
+    LZ_PHASE_END();
+    if (group == 0 && i + NS - 1 < ntiles) issue(i + NS - 1);
+    if (i < n_act) {
+      const bool next = i + 1 < n_act;
+      __builtin_amdgcn_s_setprio(1);
+      second_product(i, next);
+      if (next) first_product(i + 1);
+      __builtin_amdgcn_s_setprio(0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (group == 1) wait_tile(i + 2);
+    LZ_PHASE_END();
+  }
+  if (group == 0) LZ_PHASE_END();
+#undef LZ_ATT_INTERLEAVE
+#undef LZ_PHASE_END
+
+  // ---- normalise and store.  Register r of block h is dim 32h + 8*(r/4) + 4*hi + r%4.
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  if (score_wave && qrow == n - 1 && hi == 0)
+    zstat[(size_t)b * n_heads + head] = make_float2(m_run, inv);
+  if (qrow < n) {
+    uint16_t* op = o + (size_t)(row0 + qrow) * d + head * HD + 4 * hi;
+#pragma unroll
+    for (int h = 0; h < HS; ++h)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w2;
+        w2.x = pack_bf16(oacc[h][4 * g] * inv, oacc[h][4 * g + 1] * inv);
+        w2.y = pack_bf16(oacc[h][4 * g + 2] * inv, oacc[h][4 * g + 3] * inv);
+        *(uint2*)(op + h * 32 + 8 * g) = w2;
+      }
+  }
+}
+
 hipError_t launch_attention(const void* q, const void* k, const void* vt, void* o, const int32_t* cu,
                             const int32_t* cu_vt, int n_single, int batch, int max_rows, int vt_ld,
                             int n_heads, int head_dim, hipStream_t st, float* z, void* zstat,
@@ -343,6 +682,29 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
                        scale_log2e, z, (float2*)zstat, z_ld, kv_group);                          \
   } while (0)
   if (head_dim != 128 && head_dim != 64) return hipErrorInvalidValue;
+  static const int pp_form = [] { const char* e = getenv("LAZYLLM_ATT_PP"); return e ? atoi(e) : 1; }();
+#define LZ_ATT_PP(HD, NS)                                                                          \
+  do {                                                                                           \
+    constexpr int LDS_BYTES = NS * 2 * ATT_BN * HD * 2;                                          \
+    auto kern = flash_attn_pp_kernel<HD, NS>;                                                     \
+    static bool attr_set = false;                                                                \
+    if (!attr_set) {                                                                             \
+      hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
+      if (e != hipSuccess) return e;                                                             \
+      attr_set = true;                                                                           \
+    }                                                                                            \
+    dim3 grid(n_heads, (max_rows + 255) / 256, batch), block(512);                               \
+    hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)q, (const uint16_t*)k, \
+                       (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
+                       scale_log2e, z, (float2*)zstat, z_ld, kv_group);                          \
+  } while (0)
+  if (nw == 8 && pp_form) {
+    if (head_dim == 128) LZ_ATT_PP(128, 4);
+    else LZ_ATT_PP(64, 4);
+#undef LZ_ATT_PP
+    return hipGetLastError();
+  }
   if (head_dim == 128 && nw == 8) LZ_ATT(128, 8, 4);
   else if (head_dim == 128) LZ_ATT(128, 4, 3);
   else if (nw == 8) LZ_ATT(64, 8, 4);

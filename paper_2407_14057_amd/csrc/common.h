@@ -240,6 +240,9 @@ hipError_t launch_final_norm(const void* h, const int32_t* cu, int n_single, int
                              const void* gain, float* xf, int d, float eps, hipStream_t st);
 hipError_t launch_lm_head(const float* xf, const void* w_lm, float* logits, int batch, int d,
                           int vocab, hipStream_t st);
+bool lm_head_fused_fits(int batch, int d);
+hipError_t launch_lm_head_fused(const void* h, const int32_t* cu, int n_single, int batch, const void* gain,
+                                const void* w_lm, float* logits, int d, int vocab, float eps, hipStream_t st);
 
 // ---- decoding steps (position-indexed generation state; see decode.hip) -----------------
 // Bits of the device status word (the public header's LAZYLLM_ST_* values).

@@ -363,6 +363,116 @@ hipError_t launch_lm_head(const float* xf, const void* w_lm, float* logits, int 
   return hipGetLastError();
 }
 
+// Final norm and LM head in one launch.  Every workgroup first normalises the `batch` last rows
+// itself (8 KB each, from the L2; the 500 or so workgroups all need them and a launch of its own
+// for this costs more than the repetition) into LDS as fp32, then streams its 64 vocabulary rows:
+// a wave takes four rows at a time, 16-byte loads of all four in flight before the first use
+// (eight per lane), x from LDS.  Reads V*d*2 bytes once: HBM-bound.
+constexpr int LMH_ROWS_PER_WAVE = 16, LMH_ROWS_PER_WG = 4 * LMH_ROWS_PER_WAVE;
+template <int BATCH_MAX>
+__global__ void __launch_bounds__(256)
+lm_head_fused_kernel(const uint16_t* __restrict__ h, const int32_t* __restrict__ cu, int n_single,
+                     const uint16_t* __restrict__ gain, const uint4* __restrict__ w,
+                     float* __restrict__ logits, int batch, int d, int vocab, float eps) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];     // [batch][d]
+  __shared__ float red[4];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int b = 0; b < batch; ++b) {
+    int row0, n;
+    seq_range(cu, b, n_single, row0, n);
+    const uint16_t* row = h + (size_t)(row0 + n - 1) * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+      const float f = bf16_to_float(row[i]);
+      ss += f * f;
+    }
+    ss = wave_sum(ss);
+    __syncthreads();                                   // (red is reused from the sequence before)
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    const float r = rsqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256)
+      xs[(size_t)b * d + i] = bf16_to_float(row[i]) * r * bf16_to_float(gain[i]);
+  }
+  __syncthreads();
+  const int vpr = d / 8;
+  const int first = blockIdx.x * LMH_ROWS_PER_WG + wave * LMH_ROWS_PER_WAVE;
+  for (int r0 = first; r0 < first + LMH_ROWS_PER_WAVE && r0 < vocab; r0 += 4) {
+    float acc[4][BATCH_MAX];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int b = 0; b < BATCH_MAX; ++b) acc[r][b] = 0.f;
+    const uint4* src[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) src[r] = w + (size_t)min(r0 + r, vocab - 1) * vpr;   // (rows past the end: repeated, not stored)
+    for (int v = lane; v < vpr; v += 128) {
+      uint4 wv[4][2];
+      const int v1 = v + 64 < vpr ? v + 64 : v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) { wv[r][0] = src[r][v]; wv[r][1] = src[r][v1]; }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        if (u == 1 && v + 64 >= vpr) break;
+        const int vv = u == 0 ? v : v1;
+#pragma unroll
+        for (int b = 0; b < BATCH_MAX; ++b) {
+          if (b >= batch) break;
+          const float4 x0 = *(const float4*)(xs + (size_t)b * d + vv * 8);
+          const float4 x1 = *(const float4*)(xs + (size_t)b * d + vv * 8 + 4);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float f[8];
+            unpack8(wv[r][u], f);
+            acc[r][b] += f[0] * x0.x + f[1] * x0.y + f[2] * x0.z + f[3] * x0.w + f[4] * x1.x + f[5] * x1.y +
+                         f[6] * x1.z + f[7] * x1.w;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int b = 0; b < BATCH_MAX; ++b) {
+        if (b >= batch) break;
+        const float t = wave_sum(acc[r][b]);
+        if (lane == 0 && r0 + r < vocab) logits[(size_t)b * vocab + r0 + r] = t;
+      }
+  }
+}
+
+// logits[b] = rmsnorm(last row of sequence b) . W_lm^T; false if the shape does not fit this form
+// (then the caller uses launch_final_norm + launch_lm_head).
+bool lm_head_fused_fits(int batch, int d) {
+  return batch >= 1 && batch <= 8 && d % 8 == 0 && (size_t)batch * d * 4 <= 128 * 1024;
+}
+
+hipError_t launch_lm_head_fused(const void* h, const int32_t* cu, int n_single, int batch, const void* gain,
+                                const void* w_lm, float* logits, int d, int vocab, float eps, hipStream_t st) {
+  if (!lm_head_fused_fits(batch, d)) return hipErrorInvalidValue;
+  const size_t lds = (size_t)batch * d * 4;
+  const dim3 grid((vocab + LMH_ROWS_PER_WG - 1) / LMH_ROWS_PER_WG), block(256);
+#define LZ_LMH(BM)                                                                                 \
+  do {                                                                                             \
+    auto kern = lm_head_fused_kernel<BM>;                                                          \
+    static bool attr_set = false;                                                                  \
+    if (!attr_set) {                                                                               \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                         128 * 1024);                                              \
+      if (e != hipSuccess) return e;                                                               \
+      attr_set = true;                                                                             \
+    }                                                                                              \
+    hipLaunchKernelGGL(kern, grid, block, lds, st, (const uint16_t*)h, cu, n_single,               \
+                       (const uint16_t*)gain, (const uint4*)w_lm, logits, batch, d, vocab, eps);   \
+  } while (0)
+  if (batch == 1) LZ_LMH(1);
+  else if (batch <= 4) LZ_LMH(4);
+  else LZ_LMH(8);
+#undef LZ_LMH
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------
 // Weight repack (model creation only).
 // ------------------------------------------------------------------------------------------
