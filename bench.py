@@ -228,6 +228,47 @@ def decode_bench(args, wl, shape, model, ids, sched, n_tokens, torch, B) -> int:
     return 0
 
 
+def band_height_sweep(args, torch, B) -> int:
+    """The dominant GEMM alone (gate/up projection of the 7B shape at 3376 rows, 256x256 ping-pong tiles)
+    against the height of the tile-walk band: the number of tile rows that share a run of W column blocks in
+    one XCD's L2.  Under `rocprofv3 --pmc FETCH_SIZE` the launches of one band height are told apart by their
+    order, which the lines printed here give.  The weights rotate over 8 copies, so none is L2-resident from
+    the launch before."""
+    dev = "cuda:0"
+    N, K, M = 22016, 4096, 3376
+    n_w, reps, warm = 8, max(args.steps, 4), 4
+    ws = []
+    for _ in range(n_w):
+        w = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+        wb = torch.empty_like(w)
+        B.lazyllm_op_pack_weight_ksteps(w, N, K, K, wb)
+        ws.append(wb)
+        del w
+    a = torch.randn(M, K, device=dev).to(torch.bfloat16)
+    c = torch.zeros(M, N // 2, device=dev, dtype=torch.bfloat16)
+    rows = []
+    for gm in (1, 2, 4, 7, 14):
+        e = B.EPI_SWIGLU | (5 << 8) | (gm << 16) | (1 << 29)     # forced: 256x256 ping-pong tiles, band height gm
+        for i in range(warm):
+            B.lazyllm_op_gemm(a, ws[i % n_w], c, None, M, N, K, K, K, N // 2, e)
+        torch.cuda.synchronize()
+        t0 = torch.cuda.Event(enable_timing=True)
+        t1 = torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for i in range(reps):
+            B.lazyllm_op_gemm(a, ws[i % n_w], c, None, M, N, K, K, K, N // 2, e)
+        t1.record()
+        torch.cuda.synchronize()
+        us = t0.elapsed_time(t1) / reps * 1e3
+        rows.append({"band_height": gm, "launches": warm + reps, "us_per_launch": round(us, 1),
+                     "tflops": round(2.0 * M * N * K / us / 1e6, 1)})
+        print("band height %2d: %d launches (%d warm-up + %d timed), %.1f us per launch, %.0f TFLOP/s" % (
+            gm, warm + reps, warm, reps, us, rows[-1]["tflops"]), file=sys.stderr, flush=True)
+    print(json.dumps({"study": "tile-walk band height, gate/up projection", "M": M, "N": N, "K": K,
+                      "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +286,9 @@ def main() -> int:
     ap.add_argument("--kernels", action="store_true",
                     help="instead of the prefill, time the bandwidth-bound steps (scoring, selection, "
                          "compaction, LM head) alone over a sweep of token counts with cold caches")
+    ap.add_argument("--band-heights", action="store_true",
+                    help="instead of the prefill, time the dominant GEMM alone under tile-walk bands of 1, 2, 4, 7 "
+                         "and 14 tile rows (--steps launches each)")
     ap.add_argument("--schedules", action="store_true",
                     help="instead of the headline line, time the prefill under a grid of keep schedules: one "
                          "pruning layer at varying depth and keep ratio (the paper's drop-rate study), pruning "
@@ -266,6 +310,8 @@ def main() -> int:
 
     if args.kernels:
         return kernel_sweep(args, torch, B)
+    if args.band_heights:
+        return band_height_sweep(args, torch, B)
 
     wl = synth.WORKLOADS[args.workload]
     shape = wl.shape

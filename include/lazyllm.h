@@ -43,7 +43,8 @@ typedef enum lazyllm_status {
   LAZYLLM_EINVAL = -1, /* bad argument (null pointer, size, schedule, shape) */
   LAZYLLM_ENOSPC = -2, /* workspace or output buffer too small */
   LAZYLLM_EHIP = -3,   /* HIP runtime failure; see lazyllm_last_hip_error() */
-  LAZYLLM_ENOMEM = -4  /* host or device allocation failed in model_create */
+  LAZYLLM_ENOMEM = -4, /* host or device allocation failed in model_create */
+  LAZYLLM_EFAILED = -5 /* the generation handle is unusable: an earlier step failed part-way */
 } lazyllm_status;
 
 /* Decoder shape (Sec. 3.1: a stack of layers, each multi-head self-attention
@@ -199,7 +200,10 @@ int lazyllm_prefill(const lazyllm_model* m, const int32_t* token_ids, const floa
 
 /* `batch` independent prompts packed back to back; each is pruned on its own
  * with the same schedule.  cu_seqlens_host: host int32[batch+1], starting at 0,
- * strictly increasing.  cu_seqlens_dev: the same values in device memory. */
+ * strictly increasing.  cu_seqlens_dev: the same values in device memory (may be NULL when
+ * batch == 1).  Every buffer, launch and row table follows the host copy; the device copy is only
+ * compared with it on the GPU, and a difference sets LAZYLLM_ST_BAD_CU in *status (the result is
+ * then the one the host copy describes). */
 int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                            const float* embed_scale, const int32_t* cu_seqlens_host,
                            const int32_t* cu_seqlens_dev, int32_t batch, const lazyllm_keep* sched,
@@ -281,8 +285,11 @@ int lazyllm_generation_get_view(const lazyllm_generation* g, lazyllm_generation_
  * aligned, >= lazyllm_decode_workspace_bytes.  Unlike the prefill this call SYNCHRONISES
  * hip_stream once per pruning layer: the number of revived tokens is data-dependent and sets
  * the shape of every launch that follows.  The layers after the last pruning layer are
- * still in flight at return.  ENOSPC when the capacity is used up.  A failing step leaves
- * the state undefined. */
+ * still in flight at return.  ENOSPC when the capacity is used up (the state is untouched and
+ * stays usable, as after EINVAL).  A step that fails after its first launch (EHIP) has already
+ * changed the state without advancing the token count: the handle is marked failed, every
+ * later step returns LAZYLLM_EFAILED, and the only valid call left is
+ * lazyllm_generation_destroy. */
 int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* workspace,
                         size_t ws_bytes, void* hip_stream, lazyllm_step_result* res);
 

@@ -258,6 +258,7 @@ const char* lazyllm_strerror(int status) {
     case LAZYLLM_ENOSPC: return "workspace or output buffer too small";
     case LAZYLLM_EHIP: return "HIP runtime failure";
     case LAZYLLM_ENOMEM: return "allocation failed";
+    case LAZYLLM_EFAILED: return "generation handle unusable: an earlier decoding step failed part-way";
     default: return "unknown status";
   }
 }
@@ -512,14 +513,14 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   // tickets and flags of the GEMM forms that exchange partial tiles between workgroups
   LZ_HIP(launch_gemm_counters_clear(W + ws.gemm_ws, st));
   LZ_RUN(LAZYLLM_STEP_PLAN, -1, T, 0.0,
-         launch_plan(cu_dev, seqlens[0], B, T, plan, cu_stage, cu_aux, cu_vt, res->status, st));
+         launch_plan(cu_dev, seqlens.data(), B, T, plan, cu_stage, cu_aux, cu_vt, res->status, st));
   float2* rope = (float2*)(W + ws.rope);
   LZ_RUN(LAZYLLM_STEP_ROPE_TABLE, -1, max_seqlen, (double)max_seqlen * (hd / 2) * 8.0,
          launch_rope_table(rope, max_seqlen, hd, c->rope_theta, st));
   char* hbuf[2] = {W + ws.h0, W + ws.h1};
   int cur = 0;
   LZ_RUN(LAZYLLM_STEP_EMBED, -1, T, 2.0 * T * rowb,
-         launch_embed(m->embed, token_ids, embed_scale, cu_dev, B, T, d, c->vocab, hbuf[0],
+         launch_embed(m->embed, token_ids, embed_scale, cu_stage, B, T, d, c->vocab, hbuf[0],
                       res->kept_pos[0], res->status, st, (unsigned long long*)(W + ws.ssq0)));
   const int fp = m->f_pad;
   // RMSNorm is folded into the projections that consume it (no launch, no normalised copy of
@@ -747,6 +748,10 @@ struct lazyllm_generation {
   char* state;
   int capacity, n_prompt, n_tokens;
   int32_t* host_counts;     // pinned host memory, [n_stages][4]
+  // set while a step is being enqueued and cleared when it has been enqueued completely: a step
+  // that returns an error after its first launch has already changed has_kv / has_aux / live_row
+  // without advancing n_tokens, so every later step is refused
+  bool failed;
 };
 
 extern "C" {
@@ -804,7 +809,7 @@ int lazyllm_generation_create(const lazyllm_model* m, const lazyllm_keep* sched,
   lazyllm_generation* g = new (std::nothrow) lazyllm_generation();
   if (g == nullptr) return LAZYLLM_ENOMEM;
   g->m = m; g->stg = stg; g->gl = gl; g->state = (char*)state;
-  g->capacity = capacity; g->n_prompt = n_prompt; g->n_tokens = n_prompt;
+  g->capacity = capacity; g->n_prompt = n_prompt; g->n_tokens = n_prompt; g->failed = false;
   g->host_counts = nullptr;
   hipError_t e = hipHostMalloc((void**)&g->host_counts, (size_t)stg.n_stages * 16, hipHostMallocDefault);
   if (e != hipSuccess) {
@@ -871,6 +876,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
   if (g == nullptr || token_id == nullptr || workspace == nullptr || res == nullptr)
     return LAZYLLM_EINVAL;
   if (((uintptr_t)workspace & 255) != 0) return LAZYLLM_EINVAL;
+  if (g->failed) return LAZYLLM_EFAILED;
   if (g->n_tokens >= g->capacity) return LAZYLLM_ENOSPC;
   const lazyllm_model* m = g->m;
   const lazyllm_config* c = &m->cfg;
@@ -913,6 +919,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
   char* hbuf[2] = {W + ws.h0, W + ws.h1};
   int cur = 0, M = 1;
 
+  g->failed = true;                  // until the whole step is enqueued (cleared at the end)
   LZ_HIP(launch_gemm_counters_clear(W + ws.gemm_ws, st));
   LZ_HIP(launch_decode_attention_counters_clear(W + ws.att_ws, decode_attention_workspace_bytes(d, H), st));
   LZ_RUN(LAZYLLM_STEP_EMBED, -1, 1, 2.0 * rowb,
@@ -1003,6 +1010,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
            launch_lm_head((const float*)(W + ws.xf), m->lm_head, res->logits, 1, d, c->vocab, st));
   }
   g->n_tokens = n_tot;
+  g->failed = false;
   return LAZYLLM_OK;
 }
 

@@ -159,7 +159,6 @@ struct EpiArgs {
   // workspace) zeroed likewise: launches whose tile count leaves the last round of the chip partly
   // idle may take that kernel
   int psk_ready;
-  int psk_xmode;                     // filled in by the launcher: how partial tiles are exchanged
   // the W argument is in the weight-streaming kernel's own layout (launch_pack_stream); only that
   // kernel can read it, so the launch fails where another kernel would be chosen
   int w_packed;
@@ -279,7 +278,13 @@ struct PlanArgs {
   int32_t permille[128];                // keep ratio entering stage s+1
 };
 // cu_stage[(n_stages+1)][batch+1], cu_aux[n_stages][batch+1], cu_vt[(n_stages+1)][batch+1]
-hipError_t launch_plan(const int32_t* cu_dev, int n_single, int batch, int expect_total,
+// seqlens_host[batch]: the lengths every buffer was sized from; they reach the device by value,
+// LENS_PER_LAUNCH per launch.  cu_dev (may be null when batch == 1) is only checked against them.
+constexpr int LENS_PER_LAUNCH = 960;
+struct LensChunk {
+  int32_t n[LENS_PER_LAUNCH];
+};
+hipError_t launch_plan(const int32_t* cu_dev, const int32_t* seqlens_host, int batch, int expect_total,
                        const PlanArgs& plan, int32_t* cu_stage, int32_t* cu_aux, int32_t* cu_vt,
                        int32_t* status, hipStream_t st);
 

@@ -11,18 +11,31 @@ namespace lz {
 // (Sec. 3.2: top-k percentile of the surviving tokens).  Counts do not depend on the data,
 // so the whole table is known before the first layer runs.
 // ------------------------------------------------------------------------------------------
+// The caller sizes every buffer and launch from its host copy of the sequence lengths, so the
+// tables must come from those same lengths: they arrive by value (kernel arguments, LENS_PER_LAUNCH
+// at a time) in row 0 of cu_stage before plan_kernel runs.  The device copy of the offsets is only
+// compared against them: any difference raises ST_BAD_CU, and the tables stay those of the host's
+// lengths, inside the buffers it laid out.
+__global__ void put_lens_kernel(LensChunk chunk, int offset, int count, int32_t* __restrict__ cu_stage) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) cu_stage[offset + i + 1] = chunk.n[i];
+}
+
 __global__ void plan_kernel(const int32_t* __restrict__ cu_dev, int n_single, int batch,
                             int expect_total, PlanArgs plan, int32_t* __restrict__ cu_stage,
                             int32_t* __restrict__ cu_aux, int32_t* __restrict__ cu_vt,
                             int32_t* __restrict__ status) {
   const int S = plan.n_stages + 1, W = batch + 1;
+  __shared__ int bad;
   if (threadIdx.x == 0) {
-    *status = 0;
-    if (cu_dev != nullptr && (cu_dev[0] != 0 || cu_dev[batch] != expect_total)) *status = 2;
+    bad = 0;
+    if (cu_dev != nullptr && (cu_dev[0] != 0 || cu_dev[batch] != expect_total)) bad = 1;
   }
+  __syncthreads();
   for (int b = threadIdx.x; b < batch; b += blockDim.x) {
-    int n = cu_dev ? (cu_dev[b + 1] - cu_dev[b]) : n_single;
+    int n = batch == 1 ? n_single : cu_stage[0 * W + b + 1];     // the host's length of sequence b
     if (n < 1) n = 1;
+    if (cu_dev != nullptr && cu_dev[b + 1] - cu_dev[b] != n) bad = 1;   // (benign race: all write 1)
     cu_stage[0 * W + b + 1] = n;
     for (int s = 1; s < S; ++s) {
       long long k = ((long long)n * plan.permille[s - 1] + 999) / 1000;
@@ -33,6 +46,7 @@ __global__ void plan_kernel(const int32_t* __restrict__ cu_dev, int n_single, in
     }
   }
   __syncthreads();
+  if (threadIdx.x == 0) *status = bad ? ST_BAD_CU : 0;
   // prefix sums over the batch, one stage per thread
   for (int s = threadIdx.x; s < S; s += blockDim.x) {
     int acc = 0, accv = 0;
@@ -56,10 +70,20 @@ __global__ void plan_kernel(const int32_t* __restrict__ cu_dev, int n_single, in
   }
 }
 
-hipError_t launch_plan(const int32_t* cu_dev, int n_single, int batch, int expect_total,
+hipError_t launch_plan(const int32_t* cu_dev, const int32_t* seqlens_host, int batch, int expect_total,
                        const PlanArgs& plan, int32_t* cu_stage, int32_t* cu_aux, int32_t* cu_vt,
                        int32_t* status, hipStream_t st) {
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, st, cu_dev, n_single, batch, expect_total,
+  if (batch > 1) {
+    for (int off = 0; off < batch; off += LENS_PER_LAUNCH) {
+      LensChunk chunk;
+      const int count = batch - off < LENS_PER_LAUNCH ? batch - off : LENS_PER_LAUNCH;
+      for (int i = 0; i < count; ++i) chunk.n[i] = seqlens_host[off + i];
+      for (int i = count; i < LENS_PER_LAUNCH; ++i) chunk.n[i] = 0;
+      hipLaunchKernelGGL(put_lens_kernel, dim3((count + 255) / 256), dim3(256), 0, st, chunk, off, count,
+                         cu_stage);
+    }
+  }
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(64), 0, st, cu_dev, seqlens_host[0], batch, expect_total,
                      plan, cu_stage, cu_aux, cu_vt, status);
   return hipGetLastError();
 }

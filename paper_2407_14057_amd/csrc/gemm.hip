@@ -738,7 +738,7 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
       // release fence per wave would be eight write-backs of the same cache
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      if (wave == 0 && ra.psk_xmode != 2) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     }
     if (threadIdx.x == 0)
       __hip_atomic_store(flags + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -768,7 +768,7 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
         wait_failed = failed;
         if (failed) atomicAdd(flags + 1023, 1u);              // (the last word counts give-ups)
       }
-      if (ra.psk_xmode < 2 && wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       __syncthreads();
       LZ_FRESH_LANE();
       if (wait_failed == 0) {
@@ -849,8 +849,6 @@ static hipError_t launch_psk(const void* A, const void* W, void* C, const void* 
   const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
   float* part = (float*)ws;
   unsigned* flags = (unsigned*)((char*)ws + SK_PART_BYTES + SK_TICKET_BYTES);
-  static const int xmode = [] { const char* e = getenv("LAZYLLM_PSK_XMODE"); return e ? atoi(e) : 0; }();
-  ea.psk_xmode = xmode;
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
     auto kern = gemm_psk_kernel<WM, WN, TM, TN, E>;                                              \

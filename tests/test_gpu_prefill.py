@@ -245,6 +245,34 @@ def test_bad_token_id_sets_status_and_is_clamped(tiny):
     assert out2.status == 0 and torch.equal(out2.logits, out2_logits)
 
 
+def test_device_offsets_that_disagree_with_the_host_set_status_and_stay_in_bounds(tiny_gains):
+    """Buffers and launches are sized from the host's offsets; a device copy whose interior entries
+    differ (same total) raises ST_BAD_CU, and the row tables still follow the host's lengths: the
+    result is the one the host's offsets describe, bit for bit."""
+    shape, wb, model = tiny_gains
+    lens = [70, 513, 1, 260]
+    sched = [(1, 800), (3, 400)]
+    ids = np.concatenate([synth.make_prompt(n, shape.vocab, 500 + i) for i, n in enumerate(lens)])
+    cu = [int(x) for x in np.concatenate([[0], np.cumsum(lens)])]
+    good = _run(model, ids, sched, cu=cu)
+    assert good.status == 0
+    want = (good.logits.clone(), [good.kept_pos(l).clone() for l in range(4)], [good.k(l).clone() for l in range(4)])
+    t = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(DEV)
+    ws, ob = model.buffers(lens, sched)
+    for bad_cu in ([0, 300, 583, 584, 844], [0, 1, 2, 3, 844], [0, 70, 583, 584, 843], [1, 70, 583, 584, 844]):
+        cu_dev = torch.tensor(bad_cu, dtype=torch.int32, device=DEV)
+        res = B.lazyllm_prefill_varlen(model.handle, t, None, cu, cu_dev, sched, 0, ws, ob)
+        out = B.PrefillOutput(res, ob, model.cfg)
+        torch.cuda.synchronize()
+        assert out.status & B.LAZYLLM_ST_BAD_CU, bad_cu
+        assert torch.equal(out.logits, want[0])
+        assert all(torch.equal(out.kept_pos(l), want[1][l]) and torch.equal(out.k(l), want[2][l]) for l in range(4))
+    cu_dev = torch.tensor(cu, dtype=torch.int32, device=DEV)
+    res = B.lazyllm_prefill_varlen(model.handle, t, None, cu, cu_dev, sched, 0, ws, ob)
+    torch.cuda.synchronize()
+    assert B.PrefillOutput(res, ob, model.cfg).status == 0
+
+
 def test_too_small_buffers_are_refused(tiny):
     shape, wb, model = tiny
     ids = torch.zeros(256, dtype=torch.int32, device=DEV)

@@ -30,6 +30,7 @@ def test_library_exports_every_declared_symbol():
     assert lib.lazyllm_abi_version() == 3
     assert lib.lazyllm_strerror(-1) == b"invalid argument"
     assert lib.lazyllm_strerror(-2) == b"workspace or output buffer too small"
+    assert lib.lazyllm_strerror(-5).startswith(b"generation handle unusable")
 
 
 def test_keep_counts_match_checker():
