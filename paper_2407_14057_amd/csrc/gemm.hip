@@ -1497,12 +1497,19 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
   }
   if (group_m == 0) {
     // Band height of the tile walk (tile rows that share a run of W column blocks in an XCD's L2).
-    // Measured with cold K-step-major weights at 3376 / 2364 / 1182 rows: the QKV shape (48 column
-    // blocks) is best walked column by column over all tile rows (299 / 202 / 106 us against 303 /
-    // 212 / 109 with bands of 4), the gate/up shape (86 column blocks) in bands of 2 (521 / 392 us
-    // against 526 / 400), of 1 below 8 tile rows (203 against 213); 4 elsewhere (within 1 %).
+    // Measured with cold K-step-major weights, 256x256 tiles, us per launch by band height:
+    //   gate/up (86 column blocks)  3376 rows: 2: 536-550, 5: 533, 7: 526-528, 14: 556-561
+    //                               2364 rows: 2: 408-410, 5: 402;  1182 rows: 1: 206-209, 2..5: 211-222
+    //                               8192 rows: 2: 1269-1277, 3: 1229-1234, 5: 1254, 32: 1527
+    //                               4916 rows: 2: 750, 5: 730-734;  1967 rows: 2: 331, 5: 326
+    //   QKV (48 column blocks)      3376 rows: 7: 298-303, 14: 308-312;  2364 rows: 5: 206, 10: 207-208
+    //                               8192 rows: 3 or 5: 662, 16: 718, 32: 805;  4916 rows: 5: 411-413, 20: 456
+    //   O and down projections: within 1 % from 2 to 7 (4 kept).
+    // So: about half the tile rows up to 16 of them, 5 from there, 3 for the tallest; below 8 tile rows
+    // the gate/up shape is best walked row by row and the QKV shape column by column.
     const int tm256 = (M + 255) / 256;
-    group_m = epilogue == EPI_QKV_ROPE ? (tm256 < 63 ? tm256 : 63) : epilogue == EPI_SWIGLU ? (tm256 >= 8 ? 2 : 1) : 4;
+    const int tall = tm256 <= 11 ? 5 : tm256 <= 16 ? 7 : tm256 <= 24 ? 5 : 3;
+    group_m = epilogue == EPI_QKV_ROPE ? (tm256 < 8 ? tm256 : tall) : epilogue == EPI_SWIGLU ? (tm256 < 8 ? 1 : tall) : 4;
   }
   if (cfg == 0) {
     // 256x256 tiles on 8 waves in ping-pong phases have the best reuse and keep the matrix pipe
