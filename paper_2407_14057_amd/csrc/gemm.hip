@@ -1505,11 +1505,15 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     //   QKV (48 column blocks)      3376 rows: 7: 298-303, 14: 308-312;  2364 rows: 5: 206, 10: 207-208
     //                               8192 rows: 3 or 5: 662, 16: 718, 32: 805;  4916 rows: 5: 411-413, 20: 456
     //   O and down projections: within 1 % from 2 to 7 (4 kept).
-    // So: about half the tile rows up to 16 of them, 5 from there, 3 for the tallest; below 8 tile rows
-    // the gate/up shape is best walked row by row and the QKV shape column by column.
+    //   packed batches              gate/up 41499 rows: 2: 6181, 3: 6353, 5: 6332;  29053 rows: 2: 4276, 3: 4302, 5: 4500
+    //                               QKV 41499 rows: 2: 3439, 3: 3302, 5: 3543;  14528 rows: 3: 1184, 5: 1177
+    // So: about half the tile rows up to 16 of them, 5 from there, 3 for the tallest (2 for the
+    // gate/up shape beyond 40 tile rows); below 8 tile rows the gate/up shape is best walked row by
+    // row and the QKV shape column by column.
     const int tm256 = (M + 255) / 256;
     const int tall = tm256 <= 11 ? 5 : tm256 <= 16 ? 7 : tm256 <= 24 ? 5 : 3;
-    group_m = epilogue == EPI_QKV_ROPE ? (tm256 < 8 ? tm256 : tall) : epilogue == EPI_SWIGLU ? (tm256 < 8 ? 1 : tall) : 4;
+    group_m = epilogue == EPI_QKV_ROPE ? (tm256 < 8 ? tm256 : tall)
+              : epilogue == EPI_SWIGLU ? (tm256 < 8 ? 1 : tm256 > 40 ? 2 : tall) : 4;
   }
   if (cfg == 0) {
     // 256x256 tiles on 8 waves in ping-pong phases have the best reuse and keep the matrix pipe
