@@ -620,7 +620,11 @@ def test_gather_bit_exact(m, k, d):
 
 # ------------------------------------------------------------------------------------ LM head
 
-@pytest.mark.parametrize("d,V", [(256, 1024), (4096, 32000), (256, 1001)])
+# (rows of 32, 192 and 130 16-byte chunks: a wave's two-chunk step with idle lanes, with a tail, with
+#  both; vocabularies that are no multiple of the 4 rows a wave takes at a time or the 64 of a
+#  workgroup; a row wider than the fused form takes, which goes through the two-launch form)
+@pytest.mark.parametrize("d,V", [(256, 1024), (4096, 32000), (256, 1001), (1536, 1003), (1040, 67), (8, 5),
+                                 (40960, 130)])
 def test_lm_head(d, V):
     rng = np.random.default_rng(d + V)
     h = _rand_bf16(rng, (d,), 1.5)
