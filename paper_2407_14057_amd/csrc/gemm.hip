@@ -1123,7 +1123,16 @@ static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R
   if (w_blocked) ldw = BK;
   const int tiles_m = (M + SK_BM - 1) / SK_BM, tiles_n = N / SK_BN, KT = K / BK;
   const long long U = (long long)tiles_m * tiles_n * KT;
-  const int G = SK_GRID;
+  // Workgroups: as many as are resident at once (two per CU), unless a whole number S of them per
+  // tile, with S dividing the K steps, comes close to that: then every range is exactly 1/S of
+  // one tile, a workgroup leaves one partial tile instead of two, and the fix-up reads that much
+  // less (96 tiles at 355 rows: 384 workgroups, O projection 40.9 -> 36.2 us, down 70.4 -> 61.2).
+  int G = SK_GRID;
+  for (int S = SK_GRID / (tiles_m * tiles_n); S >= 2; --S)
+    if (KT % S == 0) {
+      if (tiles_m * tiles_n * S * 10 >= SK_GRID * 7) G = tiles_m * tiles_n * S;
+      break;
+    }
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
     auto kern = gemm_sk_kernel<E>;                                                               \
