@@ -1568,9 +1568,15 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
       const double slack = (double)rounds - (double)big_tiles / 256.0;
       if (slack >= (K >= 8192 ? 0.3 : 0.45)) cfg = 9;
     }
+    // The same trade with two rounds of 256-row tiles: 192-row tiles run at about 0.82 of a
+    // 256-row tile's time each, so they win when their rounds are fewer by more than that
+    // (gate/up at 844 rows: 344 tiles = 2 rounds, 195 us; 430 tiles of 192 rows = 2 shorter
+    // rounds, 183 us; at 1182 rows 430 against 602 tiles: 215 against 264 us, not taken).
+    const long rounds256 = (big_tiles + 255) / 256, rounds192 = (tiles192 + 255) / 256;
     if (cfg != 0) {}
-    else if (N % 256 == 0 && big_tiles >= 150 && big_tiles <= 205 && tiles192 <= 256 &&
-             epilogue != EPI_QKV_ROPE) cfg = 7;
+    else if (N % 256 == 0 && big_tiles >= 150 && epilogue != EPI_QKV_ROPE &&
+             (rounds256 == 1 ? (big_tiles <= 205 && tiles192 <= 256)
+                             : (rounds256 == 2 && 0.82 * (double)rounds192 < (double)rounds256))) cfg = 7;
     else if (N % 256 == 0 && big_tiles >= 150) cfg = 5;
     // rotary epilogue with 128-wide heads: a wave must hold whole heads (128 columns), so the
     // 128x128 tile is cut into 4 waves of 32x128 (QKV at 229 rows: 46 us against 67 us for the
