@@ -13,8 +13,8 @@ def pytest_configure(config):
 
 
 def progress(msg: str) -> None:
-    """A line in gpurun_out/test_progress.log (pytest captures stdout): long checker computations
-    inside one test leave a trace of where they are."""
+    """Appends a line to a progress log in the run-output folder (pytest captures stdout): long
+    checker computations inside one test leave a trace of where they are."""
     try:
         d = os.path.join(ROOT, "gpurun_out")
         os.makedirs(d, exist_ok=True)
