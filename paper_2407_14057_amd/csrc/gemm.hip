@@ -296,12 +296,17 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     for (int q = 0; q < W_INSTR; ++q) g2l16(gw + w_off[q], sw + q * 1024);
   };
   // one of the wave's copies of a K step (q < A_INSTR: A rows, else W rows)
+  // (uniform base + 32-bit lane offset: the K step's share of the address then lives in scalar
+  // registers and a copy costs the MFMA stream a load and an M0 update, no vector arithmetic --
+  // 0.5-3 % per launch against 64-bit lane addresses; the launcher checks that both operands span
+  // less than 4 GB)
+  const uint32_t wstep32 = (uint32_t)wstep;
   auto issue_one = [&](int stage, int k0, int q) {
     if (q < A_INSTR)
-      g2l16((const char*)A + (size_t)k0 * 2 + a_off[q],
+      g2l16((const char*)A + (uint32_t)(a_off[q] + (uint32_t)k0 * 2u),
             lds + stage * STAGE_BYTES + (wave * A_INSTR + q) * 1024);
     else
-      g2l16((const char*)W + (size_t)(k0 / BK) * wstep + w_off[q - A_INSTR],
+      g2l16((const char*)W + (uint32_t)(w_off[q - A_INSTR] + (uint32_t)(k0 / BK) * wstep32),
             lds + stage * STAGE_BYTES + BM * ROW_BYTES + (wave * W_INSTR + q - A_INSTR) * 1024);
   };
 
@@ -422,6 +427,12 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   staged_tile_out<TM, TN, EPI, BM, BN, NWAVES>(acc, C, R, M, ldc, m0, n0, wm, wn, wave, lane, ra, rs, lds);
 }
 
+// The ping-pong kernels address both operands with 32-bit byte offsets from a uniform base.
+static bool pp_operands_fit_32bit(int M, int N, int K, int lda, int ldw, bool w_blocked) {
+  return (unsigned long long)M * lda * 2 < (1ull << 32) &&
+         (unsigned long long)N * (w_blocked ? K : ldw) * 2 < (1ull << 32);
+}
+
 template <int WM, int WN, int TM, int TN>
 static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R, int M, int N,
                             int K, int lda, int ldw, int ldc, int epi, int group_m,
@@ -429,6 +440,7 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
   if (N % BN != 0) return hipErrorInvalidValue;
+  if (!pp_operands_fit_32bit(M, N, K, lda, ldw, ra.w_blocked != 0)) return hipErrorInvalidValue;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   EpiArgs ea = ra;
   ea.w_step_bytes = ra.w_blocked ? (unsigned long long)N * ROW_BYTES : (unsigned long long)ROW_BYTES;
@@ -1528,7 +1540,9 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // 256x256 tiles on 8 waves in ping-pong phases have the best reuse and keep the matrix pipe
     // fed; when they would leave much of the 256 CUs idle, smaller tiles on 4 waves win.  The
     // rotary epilogue needs a wave to span a whole head (128 columns for head_dim 128).
-    const long big_tiles = (long)((M + 255) / 256) * (N / 256);
+    // (operands of 4 GB and more: only the 4-wave kernels, which address with 64-bit offsets)
+    const bool fits32 = pp_operands_fit_32bit(M, N, K, lda, ldw, ra.w_blocked != 0);
+    const long big_tiles = fits32 ? (long)((M + 255) / 256) * (N / 256) : 0;
     // Stream-K pays when the data-parallel grid would leave most CUs idle through a long K
     // loop (measured at M = 355: O projection 46 -> 40 us, down projection 114 -> 70 us); with
     // more tiles the 128x128 partial-sum traffic eats the gain (M = 1182: +-5 %).
