@@ -384,26 +384,46 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
   const int ntiles = min((n + ATT_BN - 1) / ATT_BN, (q0 + ATT_BM) / ATT_BN);
   const uint16_t* kbase = k + (size_t)row0 * kvd + kvh * HD;
   const uint16_t* vbase = vt + (size_t)kvh * HD * vt_ld + (cu_vt ? cu_vt[b] : 0);
+  // Lane offsets of this wave's copies inside a tile (bytes, 32 bits): a whole tile is then copied
+  // from a uniform base that advances by scalar arithmetic, with no vector work per copy.  Only the
+  // sequence's last, partial tile clamps its key rows lane by lane.
+  uint32_t k_off[K_INSTR], v_off[V_INSTR];
+#pragma unroll
+  for (int qi = 0; qi < K_INSTR; ++qi) {
+    const int slab = wave * K_INSTR + qi;
+    const int r = slab * K_ROWS_PER_INSTR + lane / CHK;
+    const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
+    k_off[qi] = (uint32_t)(((size_t)r * kvd + c * 8) * 2);
+  }
+#pragma unroll
+  for (int qi = 0; qi < V_INSTR; ++qi) {
+    const int slab = wave * V_INSTR + qi;
+    const int r = slab * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ swz64(r);
+    v_off[qi] = (uint32_t)(((size_t)r * vt_ld + c * 8) * 2);
+  }
   auto issue = [&](int t) {                    // tile t into stage t mod NS
     char* sk = lds + (t % NS) * STAGE;
     char* sv = sk + K_TILE;
     const int k0 = t * ATT_BN;
+    if (k0 + ATT_BN <= n) {
+      const char* kt = (const char*)(kbase + (size_t)k0 * kvd);
 #pragma unroll
-    for (int qi = 0; qi < K_INSTR; ++qi) {
-      const int slab = wave * K_INSTR + qi;
-      const int r = slab * K_ROWS_PER_INSTR + lane / CHK;
-      const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
-      int key = k0 + r;
-      key = key < n ? key : n - 1;
-      g2l16(kbase + (size_t)key * kvd + c * 8, sk + slab * 1024);
-    }
+      for (int qi = 0; qi < K_INSTR; ++qi) g2l16(kt + k_off[qi], sk + (wave * K_INSTR + qi) * 1024);
+    } else {
 #pragma unroll
-    for (int qi = 0; qi < V_INSTR; ++qi) {
-      const int slab = wave * V_INSTR + qi;
-      const int r = slab * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ swz64(r);
-      g2l16(vbase + (size_t)r * vt_ld + k0 + c * 8, sv + slab * 1024);
+      for (int qi = 0; qi < K_INSTR; ++qi) {
+        const int slab = wave * K_INSTR + qi;
+        const int r = slab * K_ROWS_PER_INSTR + lane / CHK;
+        const int c = (lane % CHK) ^ (CHK == 16 ? swz128(r) : swz64(r));
+        int key = k0 + r;
+        key = key < n ? key : n - 1;
+        g2l16(kbase + (size_t)key * kvd + c * 8, sk + slab * 1024);
+      }
     }
+    const char* vt0 = (const char*)(vbase + k0);
+#pragma unroll
+    for (int qi = 0; qi < V_INSTR; ++qi) g2l16(vt0 + v_off[qi], sv + (wave * V_INSTR + qi) * 1024);
   };
 
   const int kperm = (l31 & 0x13) | ((l31 & 4) << 1) | ((l31 & 8) >> 1);   // swap bits 2 and 3
@@ -542,13 +562,20 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
           }
       }
     }
-    float mraw = -INFINITY;
+    // (two independent chains; the two lanes of a query, l and l ^ 32, exchange their maxima with
+    // v_permlane32_swap: __shfl_xor would be an LDS round trip in the middle of the half step)
+    float mraw0 = -INFINITY, mraw1 = -INFINITY;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mraw = fmaxf(mraw, sacc[sub][r]);
-    float mloc = mraw * scale_log2e;
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    for (int r = 0; r < 16; ++r) {
+      mraw0 = fmaxf(mraw0, sacc[0][r]);
+      mraw1 = fmaxf(mraw1, sacc[1][r]);
+    }
+    float mloc = fmaxf(mraw0, mraw1) * scale_log2e;
+    {
+      const unsigned mbits = __float_as_uint(mloc);
+      const auto sw = __builtin_amdgcn_permlane32_swap(mbits, mbits, false, false);
+      mloc = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
     if (__builtin_amdgcn_ballot_w64(mloc > m_run + 8.0f) != 0) {
       const float m_new = fmaxf(m_run, mloc);
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -559,7 +586,7 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
       for (int h = 0; h < HS; ++h) oacc[h] *= alpha;
     }
     const float neg_m = -m_run;
-    float psum = 0.f;
+    float psum[4] = {0.f, 0.f, 0.f, 0.f};          // (four chains; added in a fixed order)
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -568,12 +595,12 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[sub][8 * t + j], scale_log2e, neg_m));
-          psum += p[j];
+          psum[2 * sub + t] += p[j];
         }
         uint4 packed = pack8(p);
         pf[sub][t] = *reinterpret_cast<bf16x8_t*>(&packed);
       }
-    l_run += psum;
+    l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
   };
   // own copies of tile t have landed (tile t+1 may still be in flight; the wave that stores the
   // last query's logits has up to SCORE_STORES more operations behind the copies)
@@ -701,7 +728,8 @@ hipError_t launch_attention(const void* q, const void* k, const void* vt, void* 
                        (const uint16_t*)vt, (uint16_t*)o, cu, cu_vt, n_single, vt_ld, n_heads,   \
                        scale_log2e, z, (float2*)zstat, z_ld, kv_group);                          \
   } while (0)
-  if (nw == 8 && pp_form) {
+  // (the ping-pong form addresses a Vt tile with 32-bit lane offsets: head_dim rows of vt_ld columns)
+  if (nw == 8 && pp_form && (unsigned long long)head_dim * (unsigned long long)vt_ld * 2 < (1ull << 32)) {
     if (head_dim == 128) LZ_ATT_PP(128, 4);
     else LZ_ATT_PP(64, 4);
 #undef LZ_ATT_PP
