@@ -460,76 +460,81 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
   constexpr int PER_STEP = K_INSTR + V_INSTR;
   constexpr int SCORE_STORES = 8;
   static_assert((NS - 3) * PER_STEP + SCORE_STORES < 64, "vmcnt is 6 bits");
-  bf16x8_t fa[KSTEPS], fb[KSTEPS];
-  auto kread = [&](const char* st, int sub, int s) {
-    return *(const bf16x8_t*)(st + k_addr[sub] + (((s * 2 + hi) ^ kx) * 16));
+  // ---- operand fragments.  One product is NF = 2 * KSTEPS MFMAs, each with its own 16-byte-per-lane
+  // fragment from LDS, and the fragments live in ONE ring of NF registers: right after MFMA u has
+  // taken slot u, the read of the fragment that the MFMA NF places later needs goes into the same
+  // slot -- the first product's MFMAs fetch the Vt fragments of the second product, the second
+  // product's the K fragments of the next step's first product.  Every read thus has NF MFMAs
+  // (512 cycles at head_dim 128) to come back, and since LDS returns in order the wait in front of
+  // an MFMA is always "all but the NF - 1 youngest reads": s_waitcnt lgkmcnt(NF - 1).  The reads
+  // and waits are written as asm so that they are exactly these: left to the compiler, a group of
+  // reads was followed by a wait for ALL of them (the youngest issued 32 cycles earlier), and a
+  // branch in between made it wait for everything outstanding.
+  constexpr int NF = 2 * KSTEPS;
+  static_assert(NF - 1 <= 15, "lgkmcnt has 4 bits");
+  bf16x8_t fr[NF];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  // lane parts of the fragment addresses (K: k-step s of key block `sub`; Vt: see vread)
+  uint32_t k_lane[KSTEPS], v_lane[4];
+#pragma unroll
+  for (int sidx = 0; sidx < KSTEPS; ++sidx) k_lane[sidx] = lds0 + k_addr[0] + (uint32_t)((((sidx * 2 + hi) ^ kx)) * 16);
+#pragma unroll
+  for (int c4 = 0; c4 < 4; ++c4) {                     // c4 = 2 * sub + t of vread's index
+    const int chunk = ((c4 >> 1) & 1) * 4 + (c4 & 1) * 2 + hi;
+    v_lane[c4] = lds0 + v_addr + (uint32_t)((chunk ^ vx) * 16);
+  }
+#define LZ_LDS_READ(dst, addr, OFF) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF))
+#define LZ_FRAG_READY(f) asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(NF - 1))
+  // slot u of the first product: key block u & 1, k-step (u >> 1) % (KSTEPS / 2) + (KSTEPS / 2) * (u / KSTEPS)
+  constexpr int HK = KSTEPS / 2;
+  auto k_step_of = [](int u) { return ((u % KSTEPS) >> 1) + HK * (u / KSTEPS); };
+  // slot u of the second product: Vt operand pv(u) = 4 h + 2 sub + t, alternating output blocks
+  auto pv_op = [](int u) { return (u & 1) * (KSTEPS / 2) + (u >> 1); };   // 0,4,1,5,...
+  auto v_index_of = [&](int u) { return (u / KSTEPS) * KSTEPS + pv_op(u % KSTEPS); };
+  auto read_k_slot = [&](uint32_t stage_off, int u) {  // K fragment of slot u from the stage at stage_off
+    const uint32_t addr = k_lane[k_step_of(u)] + stage_off;
+    if (u & 1) LZ_LDS_READ(fr[u], addr, 32 * HD * 2);
+    else LZ_LDS_READ(fr[u], addr, 0);
   };
-  auto vread = [&](const char* st, int i) {          // i = 4 * h + 2 * sub + t
-    const int chunk = ((i >> 1) & 1) * 4 + (i & 1) * 2 + hi;
-    return *(const bf16x8_t*)(st + v_addr + (i >> 2) * 32 * 128 + ((chunk ^ vx) * 16));
+  auto read_v_slot = [&](uint32_t stage_off, int u) {  // Vt fragment of slot u
+    const int vi = v_index_of(u);
+    const uint32_t addr = v_lane[vi & 3] + stage_off;
+    switch (vi >> 2) {
+      case 0: LZ_LDS_READ(fr[u], addr, 0); break;
+      case 1: LZ_LDS_READ(fr[u], addr, 32 * 128); break;
+      case 2: LZ_LDS_READ(fr[u], addr, 2 * 32 * 128); break;
+      default: LZ_LDS_READ(fr[u], addr, 3 * 32 * 128); break;
+    }
   };
 
   floatx16_t sacc[2];
   bf16x8_t pf[2][2];
 
-  // ---- the matrix half steps.  Operand fragments alternate between fa and fb; each group of reads
-  // rides under the MFMAs of the group before it.  Consecutive MFMAs go to DIFFERENT accumulators:
-  // an MFMA that adds to the result of the one just before it waits for that result (about two
-  // issue slots), and in this schedule no second wave is there to fill the gap.  So a fragment
-  // buffer holds half the k-steps of BOTH 32-key blocks of the first product (slot u: block u & 1,
-  // k-step (u >> 1) + 4 * buffer), and of the second product the Vt rows of two output blocks,
-  // interleaved (slot u: operand pv_op(u)).
-  constexpr int HK = KSTEPS / 2;                     // k-steps per buffer and block
-  auto k_frag = [&](const char* st, int buf, int u) { return kread(st, u & 1, (u >> 1) + HK * buf); };
-  auto pv_op = [](int u) { return (u & 1) * (KSTEPS / 2) + (u >> 1); };   // 0,4,1,5,... : alternates output blocks
-  // first product of step i (on entry fa holds the first buffer of tile i's K; leaves Vt half 0 of tile i in fa)
+  // first product of step i (the ring holds tile i's K fragments; leaves tile i's Vt fragments in it)
   auto first_product = [&](int i) {
-    const char* st = lds + (i % NS) * STAGE;
+    const uint32_t st = (uint32_t)((i % NS) * STAGE);
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
 #pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) fb[u] = k_frag(st, 1, u);
-#pragma unroll
-    for (int u = 0; u < KSTEPS; ++u)
-      sacc[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], qf[u >> 1], sacc[u & 1], 0, 0, 0);
-    LZ_ATT_INTERLEAVE();
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) fa[u] = vread(st, pv_op(u));
-#pragma unroll
-    for (int u = 0; u < KSTEPS; ++u)
-      sacc[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u], qf[(u >> 1) + HK], sacc[u & 1], 0, 0, 0);
-    LZ_ATT_INTERLEAVE();
-    __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < NF; ++u) {
+      LZ_FRAG_READY(fr[u]);
+      sacc[u & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[u], qf[k_step_of(u)], sacc[u & 1], 0, 0, 0);
+      read_v_slot(st, u);
+    }
   };
-  // second product of step i (fa holds Vt half 0 of tile i); with `next`, the first K buffer of tile
-  // i+1 is fetched into fa under its last MFMAs
-  auto second_product = [&](int i, bool next) {
-    const char* st = lds + (i % NS) * STAGE;
-    const char* st_next = lds + ((i + 1) % NS) * STAGE;
+  // second product of step i (the ring holds tile i's Vt fragments; leaves the K fragments of the
+  // stage of tile i + 1 in it -- stale bytes of a valid stage after the last tile, never used)
+  auto second_product = [&](int i) {
+    const uint32_t st_next = (uint32_t)(((i + 1) % NS) * STAGE);
 #pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) fb[u] = vread(st, KSTEPS + pv_op(u));
-#pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) {
-      const int op = pv_op(u);
-      oacc[op >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], pf[(op >> 1) & 1][op & 1], oacc[op >> 2], 0, 0, 0);
+    for (int u = 0; u < NF; ++u) {
+      const int op = pv_op(u % KSTEPS), ob = (u / KSTEPS) * (HS / 2) + (op >> 2);
+      LZ_FRAG_READY(fr[u]);
+      oacc[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[u], pf[(op >> 1) & 1][op & 1], oacc[ob], 0, 0, 0);
+      read_k_slot(st_next, u);
     }
-    LZ_ATT_INTERLEAVE();
-    __builtin_amdgcn_sched_barrier(0);
-    if (next) {
-#pragma unroll
-      for (int u = 0; u < KSTEPS; ++u) fa[u] = k_frag(st_next, 0, u);
-    }
-#pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) {
-      const int op = pv_op(u);
-      oacc[HS / 2 + (op >> 2)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u], pf[(op >> 1) & 1][op & 1],
-                                                                         oacc[HS / 2 + (op >> 2)], 0, 0, 0);
-    }
-    if (next) { LZ_ATT_INTERLEAVE(); }
-    __builtin_amdgcn_sched_barrier(0);
   };
 
   // ---- vector half step i: softmax of the 64 keys of step i (sacc -> pf, running statistics).
@@ -621,10 +626,8 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
   if (ntiles >= NS - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * PER_STEP) : "memory");
   else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   LZ_PHASE_END();
-  if (n_act > 0) {
 #pragma unroll
-    for (int u = 0; u < KSTEPS; ++u) fa[u] = k_frag(lds, 0, u);
-  }
+  for (int u = 0; u < NF; ++u) read_k_slot(0u, u);   // tile 0's K fragments
 
   // One instruction stream for both halves of the workgroup; waves 4-7 run it one phase later.
   //   waves 0-3: M(0) in phase 0, then V(i) in phase 2i+1 and M(i+1) in phase 2i+2
@@ -648,10 +651,9 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     LZ_PHASE_END();
     if (group == 0 && i + NS - 1 < ntiles) issue(i + NS - 1);
     if (i < n_act) {
-      const bool next = i + 1 < n_act;
       __builtin_amdgcn_s_setprio(1);
-      second_product(i, next);
-      if (next) first_product(i + 1);
+      second_product(i);
+      if (i + 1 < n_act) first_product(i + 1);
       __builtin_amdgcn_s_setprio(0);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -659,6 +661,8 @@ flash_attn_pp_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     LZ_PHASE_END();
   }
   if (group == 0) LZ_PHASE_END();
+#undef LZ_LDS_READ
+#undef LZ_FRAG_READY
 #undef LZ_ATT_INTERLEAVE
 #undef LZ_PHASE_END
 
