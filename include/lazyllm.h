@@ -336,7 +336,8 @@ int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* 
  * library chooses): 2 = 128x128, 3 = 128x128 in waves of 32x128, 4 = 128x256, 5 = 256x256 ping-pong, 7 = 192x256
  * ping-pong, 6 = 128x128 stream-K (needs the workspace), 8 = the weight-streaming
  * kernel of the decoding steps (M <= 32, needs the workspace), 9 / 10 = the 256x256 / 192x256
- * ping-pong tiles under the persistent stream-K schedule (need the workspace).  EINVAL where a
+ * ping-pong tiles under the persistent stream-K schedule (need the workspace), 13 = 128x256 on
+ * 8 waves of 32x128 with three stages.  EINVAL where a
  * configuration does not fit the shape. */
 size_t lazyllm_op_gemm_workspace_bytes(void);
 int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,

@@ -26,7 +26,7 @@ constexpr int SK_GRID = 512;
 constexpr size_t SK_PART_BYTES = (size_t)SK_GRID * 2 * 128 * 128 * sizeof(float);
 constexpr size_t SK_TICKET_BYTES = 4096, PSK_FLAG_BYTES = 4096;
 
-template <int WM, int WN, int TM, int TN, int EPI>
+template <int WM, int WN, int TM, int TN, int EPI, int NS = 2>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
             uint16_t* __restrict__ C, const uint16_t* __restrict__ R, int M, int N, int K, int lda,
@@ -141,17 +141,27 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     __builtin_amdgcn_sched_group_barrier(0x008, NM - NG, 0);                                  \
   } while (0)
 
+  // NS stages: K step kt lives in stage kt mod NS; steps 0 .. NS-1 are copied up front, step
+  // kt + NS in iteration kt, right after the barrier that frees step kt's stage.  With more than
+  // two stages the barrier waits only for the copies of step kt + 1 (everything but the newest
+  // NS - 2 steps' worth): a copy then has NS - 3/4 iterations to arrive instead of 1 1/4.
+  static_assert(NS == 2 || NS == 3, "two or three stages");
   const int KT = K / BK;
-  issue(0, 0);
-  if (KT > 1) issue(1, BK);
+#pragma unroll
+  for (int t = 0; t < NS; ++t)
+    if (t < KT) issue(t, t * BK);
   float rs[TM];
   load_row_scales<TM>(rs, ra, M, m0, wm, lane);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // (three steps in flight: only the first has to be there; the row scales fetched last are needed in the epilogue)
+  if (NS == 3 && KT >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * (A_INSTR + W_INSTR)) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   LZ_LOAD_FRAGS(0, lds, 0);
+  int st_cur = 0;                                   // kt mod NS
   for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = lds + (kt & 1) * STAGE_BYTES;
-    const char* nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
+    const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;
+    const char* cur = lds + st_cur * STAGE_BYTES;
+    const char* nxt = lds + st_nxt * STAGE_BYTES;
     LZ_LOAD_FRAGS(1, cur, 1);
     LZ_MFMAS(0);
     LZ_SCHED();
@@ -161,12 +171,16 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     LZ_LOAD_FRAGS(1, cur, 3);
     LZ_MFMAS(0);
     LZ_SCHED();
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // step kt + 1 must have landed; with three stages step kt + 2 (issued an iteration ago) may
+    // still be on its way, unless it does not exist
+    if (NS == 3 && kt + 2 < KT) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(A_INSTR + W_INSTR) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
-    if (kt + 2 < KT) issue(kt & 1, (kt + 2) * BK);
+    if (kt + NS < KT) issue(st_cur, (kt + NS) * BK);
     if (kt + 1 < KT) LZ_LOAD_FRAGS(0, nxt, 0);
     LZ_MFMAS(1);
     LZ_SCHED();
+    st_cur = st_nxt;
   }
 #undef LZ_LOAD_FRAGS
 #undef LZ_MFMAS
@@ -175,12 +189,14 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
 }
 
-template <int WM, int WN, int TM, int TN>
+template <int WM, int WN, int TM, int TN, int NS = 2>
 static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* R, int M, int N,
                              int K, int lda, int ldw, int ldc, int epi, int group_m,
                              const EpiArgs& ra, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  constexpr int LDS_BYTES = NS * (BM + BN) * ROW_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS of a CU");
+  if (N % BN != 0) return hipErrorInvalidValue;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   const int threads = WM * WN * 64;
   EpiArgs ea = ra;
@@ -191,7 +207,7 @@ static hipError_t launch_cfg(const void* A, const void* W, void* C, const void* 
   dim3 grid(tiles_m * tiles_n + side), block(threads);
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
-    auto kern = gemm_kernel<WM, WN, TM, TN, E>;                                                  \
+    auto kern = gemm_kernel<WM, WN, TM, TN, E, NS>;                                              \
     static bool attr_set = false;                                                                \
     if (!attr_set) {                                                                             \
       hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
@@ -1595,7 +1611,10 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // rotary epilogue with 128-wide heads: a wave must hold whole heads (128 columns), so the
     // 128x128 tile is cut into 4 waves of 32x128 (QKV at 229 rows: 46 us against 67 us for the
     // 128x256 tile of 64x128 waves, which makes half as many workgroups; level from 1000 rows on)
-    else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128) cfg = 3;
+    // while they fit one round, the same waves as one 8-wave workgroup per CU on a 128x256 tile with
+    // three stages (288 KB of LDS would not hold two of those): QKV at 355 / 394 rows 76 -> 70, 71 -> 67 us
+    else if (epilogue == EPI_QKV_ROPE && ra.head_dim == 128)
+      cfg = (N % 256 == 0 && (long)((M + 127) / 128) * (N / 256) <= 256) ? 13 : 3;
     else cfg = 2;
     if (cfg == 0) return hipErrorInvalidValue;
   }
@@ -1606,6 +1625,8 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_cfg<2, 2, 2, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 3:                                             // 128x128, 4 waves of 32x128 (whole heads per wave)
             return launch_cfg<4, 1, 1, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 13: if (N % 256) return hipErrorInvalidValue;  // 128x256, 8 waves of 32x128 (whole heads), three stages
+            return launch_cfg<4, 2, 1, 4, 3>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 5:                                             // 256x256, 8 waves of 64x128, ping-pong

@@ -100,16 +100,17 @@ def test_gemm_skinny(M, N, K, epi):
     assert torch.equal(outs[0], outs[1])
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (229, 768, 256), (700, 1536, 704)])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (229, 768, 256), (700, 1536, 704), (355, 512, 128), (130, 256, 1408)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
 def test_gemm_tile_of_32_row_waves(M, N, K, epi):
-    """The 128x128 tile cut into four waves of 32x128 (forced; the form the rotary epilogue with
-    128-wide heads uses below the large-tile threshold) gives the bits of the 64x64-wave tile."""
+    """The 128x128 tile cut into four waves of 32x128, and the 128x256 tile on eight such waves with three
+    stages (both forced; the forms the rotary epilogue with 128-wide heads uses below the large-tile
+    threshold; K of one, two, four and more steps) give the bits of the 64x64-wave tile."""
     rng = np.random.default_rng(M * 3 + N + K + epi)
     A = _rand_bf16(rng, (M, K)); W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
     R = _rand_bf16(rng, (M, N))
     outs = []
-    for cfg in (2, 3):
+    for cfg in (2, 3, 13):
         if epi == B.EPI_SWIGLU:
             Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
             B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, epi | (cfg << 8))
@@ -118,7 +119,7 @@ def test_gemm_tile_of_32_row_waves(M, N, K, epi):
             B.lazyllm_op_gemm(A, W, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N, epi | (cfg << 8))
         torch.cuda.synchronize()
         outs.append(Cout)
-    assert torch.equal(outs[0], outs[1])
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     acc = _f64(A) @ _f64(W).T
     if epi == B.EPI_SWIGLU:
         blocks = acc.reshape(M, N // 64, 2, 32)
@@ -164,7 +165,8 @@ def test_gemm_skinny_streamed_weight_layout(M, N, K, epi):
 
 
 @pytest.mark.parametrize("cfg,M,N,K", [(2, 300, 768, 256), (3, 229, 1536, 704), (4, 130, 512, 192), (5, 513, 1536, 704),
-                                       (7, 700, 768, 1408), (6, 355, 4096, 1408), (0, 2100, 6144, 512), (0, 37, 256, 128)])
+                                       (7, 700, 768, 1408), (6, 355, 4096, 1408), (0, 2100, 6144, 512), (0, 37, 256, 128),
+                                       (13, 229, 1536, 704), (13, 77, 512, 128), (13, 300, 768, 64), (13, 640, 1024, 192)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
 def test_gemm_k_step_major_weight_layout(cfg, M, N, K, epi):
     """The weight stored K-step-major (lazyllm_op_pack_weight_ksteps, the form the model keeps) must
