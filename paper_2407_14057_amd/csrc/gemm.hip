@@ -856,6 +856,17 @@ static int psk_resident_workgroups(KernT kern, int lds_bytes) {
   return per_cu >= 1 ? cus : 0;
 }
 
+// Fewer tiles than workgroups, the same number on every XCD: a whole number S of workgroups per
+// tile makes every range an exact 1/S of ONE tile, so that a workgroup has one piece, S - 1 of S
+// leave a partial tile and the owner reads S - 1 (80 tiles: 240 workgroups, three per tile,
+// instead of 256 ranges of which most straddle two tiles).  Taken when it keeps 3/4 of the CUs.
+static int psk_aligned_grid(int G, int tiles) {
+  if (tiles >= G || tiles % 8 != 0) return G;
+  const int per_xcd = tiles / 8, S = (G / 8) / per_xcd;
+  if (S >= 2 && S * per_xcd * 4 >= (G / 8) * 3) return 8 * S * per_xcd;
+  return G;
+}
+
 template <int WM, int WN, int TM, int TN>
 static hipError_t launch_psk(const void* A, const void* W, void* C, const void* R, int M, int N,
                              int K, int lda, int ldw, int ldc, int epi, int group_m,
@@ -889,6 +900,7 @@ static hipError_t launch_psk(const void* A, const void* W, void* C, const void* 
     }                                                                                            \
     int G = resident < 256 ? resident : 256;                                                     \
     G &= ~7;                                         /* whole rounds over the 8 XCDs */          \
+    G = psk_aligned_grid(G, tiles_m * tiles_n);                                                  \
     if (G < 8 || (size_t)G * BM * BN * sizeof(float) > SK_PART_BYTES || G > 1016)                \
       return hipErrorInvalidConfiguration;                                                       \
     hipLaunchKernelGGL(kern, dim3(G + side), dim3(512), LDS_BYTES, st, (const uint16_t*)A,       \
@@ -1562,7 +1574,17 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // Stream-K pays when the data-parallel grid would leave most CUs idle through a long K
     // loop (measured at M = 355: O projection 46 -> 40 us, down projection 114 -> 70 us); with
     // more tiles the 128x128 partial-sum traffic eats the gain (M = 1182: +-5 %).
-    if ((epilogue == EPI_STORE || epilogue == EPI_RESIDUAL) && sk_ws != nullptr &&
+    // Fewer 256x256 tiles than CUs, but a whole number (>= 2) of workgroups per tile on every XCD:
+    // the persistent stream-K schedule then gives each workgroup one piece of one tile (see
+    // psk_aligned_grid).  Measured, cold weights, against the best other form: down projection at
+    // 600 / 844 / 1182 / 1400 rows 106 -> 87, 107 -> 100, 153 -> 124, 166 -> 138 us; O projection at
+    // 1182 / 1400 rows 68.5 -> 63, 68.7 -> 66.6 (but 50 -> 56 at 600 rows, and at 355 rows the 128x128
+    // stream-K form below stays ahead: 62 against 79 us).
+    if ((epilogue == EPI_STORE || epilogue == EPI_RESIDUAL) && ra.psk_ready && sk_ws != nullptr &&
+        sk_ws_bytes >= gemm_workspace_bytes() && N % 256 == 0 && big_tiles < 128 &&
+        psk_aligned_grid(256, (int)big_tiles) != 256 && ((K >= 8192 && big_tiles >= 48) || big_tiles >= 80))
+      cfg = 9;
+    if (cfg == 0 && (epilogue == EPI_STORE || epilogue == EPI_RESIDUAL) && sk_ws != nullptr &&
         sk_ws_bytes >= gemm_workspace_bytes()) {
       const long t128 = (long)((M + 127) / 128) * (N / 128);
       if (t128 <= 160 && K / BK >= 32) cfg = 6;
