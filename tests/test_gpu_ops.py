@@ -455,11 +455,13 @@ def test_attention_sharp_rows():
     assert np.abs(_f64(o) - o_ref.reshape(rows, d)).max() < 3e-2
 
 
-@pytest.mark.parametrize("rows", [1793, 2364, 3376])
-def test_attention_headline_form(rows):
-    """The kernel form the 7B workloads launch: 32 heads of 128, more than 1792 rows (8 waves per
-    workgroup, 4 stages), element by element against the checker's full attention maps."""
-    got, ref = _attention_case(rows, 32, 128, rows + 11)
+@pytest.mark.parametrize("rows,H,hd", [(2049, 32, 128), (2364, 32, 128), (3376, 32, 128), (1100, 64, 64), (1281, 64, 64)])
+def test_attention_headline_form(rows, H, hd):
+    """The kernel form the 7B workloads launch (more than 256 query blocks of 256 rows over all heads:
+    8 waves per workgroup in two half-step groups, 4 stages, fragment ring), with 128-wide heads and
+    with 64-wide ones (a ring of 8 fragments), element by element against the checker's full
+    attention maps."""
+    got, ref = _attention_case(rows, H, hd, rows + 11)
     err = np.abs(got - ref)
     assert err.max() < 2e-2, "worst %.3g" % err.max()
     assert np.sqrt((err ** 2).mean()) < 3e-3
@@ -471,7 +473,7 @@ def test_attention_headline_form_sharp_rows():
     """Large, uneven logits at the headline shape: late keys that exceed the running maximum by
     far more than the lazy-rescale threshold, so the accumulator rescale path runs in the 8-wave
     form too."""
-    rows, H, hd = 2048, 32, 128
+    rows, H, hd = 2100, 32, 128
     rng = np.random.default_rng(78)
     d = H * hd
     q = _rand_bf16(rng, (rows, d), 3.0); k = _rand_bf16(rng, (rows, d), 3.0); v = _rand_bf16(rng, (rows, d))
