@@ -230,11 +230,13 @@ def test_gemm_stream_k(M, N, K, epi):
 
 @pytest.mark.parametrize("cfg", [9, 10])
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (300, 768, 256), (2364, 4096, 1024), (1182, 4096, 4096),
-                                   (3376, 2048, 512), (700, 22016, 256), (5000, 256, 128), (8192, 8192, 128)])
+                                   (3376, 2048, 512), (700, 22016, 256), (5000, 256, 128), (8192, 8192, 128),
+                                   (600, 4096, 512), (1000, 4096, 704), (1536, 4096, 256)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
 def test_gemm_persistent_stream_k(cfg, M, N, K, epi):
     """The persistent stream-K schedule of the ping-pong tiles (forced): shapes with fewer tiles than
-    CUs (every tile cut into several K pieces), with whole data-parallel rounds plus a cut remainder,
+    CUs (every tile cut into several K pieces; 48, 64, 80 and 96 tiles of 256 rows take a grid of five,
+    four, three and two workgroups per tile), with whole data-parallel rounds plus a cut remainder,
     with exactly whole rounds, and a single K step.  Same result as the plain product up to the order
     of the fp32 partial sums, the same bits on every run, flags left at zero, no wait given up."""
     rng = np.random.default_rng(M + N + K + epi + cfg)

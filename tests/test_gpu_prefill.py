@@ -224,6 +224,31 @@ def test_batch_of_ragged_prompts(tiny_gains):
         assert all(torch.equal(single.kept_pos(l), snap[b][1][l]) for l in range(4))
 
 
+def test_batch_of_a_thousand_short_prompts(tiny_gains):
+    """More sequences than one launch carries lengths for (they reach the device by value, 960 per
+    launch): the row tables of sequences on both sides of that boundary are right, and a packed
+    sequence has the bits of the same prompt run alone."""
+    shape, wb, model = tiny_gains
+    rng = np.random.default_rng(909)
+    lens = [int(x) for x in rng.integers(1, 6, 1000)]
+    lens[959], lens[960], lens[999] = 5, 3, 4
+    sched = [(1, 800), (3, 400)]
+    ids = np.concatenate([synth.make_prompt(n, shape.vocab, 7000 + i) for i, n in enumerate(lens)])
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    out = _run(model, ids, sched, cu=[int(x) for x in cu])
+    assert out.status == 0
+    for l in range(4):
+        want = [O.keep_counts(n, 4, sched)[l] for n in lens]
+        got = np.diff(out.cu_kept(l).cpu().numpy().astype(np.int64))
+        assert np.array_equal(got, np.asarray(want)), l
+    snap = {b: (out.logits[b].clone(), [out.kept_pos(l)[int(out.cu_kept(l)[b]):int(out.cu_kept(l)[b + 1])].clone()
+                                        for l in range(4)]) for b in (0, 500, 959, 960, 999)}
+    for b, (logits, kept) in snap.items():
+        single = _run(model, ids[cu[b]:cu[b + 1]], sched)
+        assert torch.equal(single.logits[0], logits), b
+        assert all(torch.equal(single.kept_pos(l), kept[l]) for l in range(4)), b
+
+
 def test_needle_scale(tiny):
     shape, wb, model = tiny
     n = 384
