@@ -331,7 +331,8 @@ int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* 
  * Requires N % 128 == 0, K % 64 == 0, 16-byte aligned rows.
  * workspace: optional device scratch of lazyllm_op_gemm_workspace_bytes() (256-byte
  * aligned) that lets epilogues 0 and 1 use the stream-K schedule for shapes whose tile
- * count does not divide over the CUs; NULL = never.
+ * count does not divide over the CUs, and epilogue 2 walk its tiles with one workgroup per
+ * CU when there are more tiles than CUs (same bits either way); NULL = never.
  * Bits 8..15 of `epilogue` force a tile configuration (measurement hook; 0 = the
  * library chooses): 2 = 128x128, 3 = 128x128 in waves of 32x128, 4 = 128x256, 5 = 256x256 ping-pong, 7 = 192x256
  * ping-pong, 6 = 128x128 stream-K (needs the workspace), 8 = the weight-streaming

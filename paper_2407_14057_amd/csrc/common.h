@@ -159,6 +159,10 @@ struct EpiArgs {
   // workspace) zeroed likewise: launches whose tile count leaves the last round of the chip partly
   // idle may take that kernel
   int psk_ready;
+  // filled in by the launcher: workgroups that walk the tiles of the ping-pong kernel's SiLU*mul
+  // form, and their ticket counters (inside the flag area above; null: one workgroup per tile)
+  int pp_walkers;
+  unsigned* walk_tickets;
   // the W argument is in the weight-streaming kernel's own layout (launch_pack_stream); only that
   // kernel can read it, so the launch fails where another kernel would be chosen
   int w_packed;

@@ -20,11 +20,13 @@ namespace lz {
 
 // Workspace of the forms that exchange partial sums between workgroups.  Layout: fp32 partial tiles
 // (64 MB) | 4 KB of tickets of the skinny kernel (see gemm_skinny_kernel) | 4 KB of flags of the
-// persistent stream-K kernel (see gemm_psk_kernel).  Tickets and flags must be zero before the
-// first launch that uses them; every launch leaves them zero again.
+// persistent stream-K kernel (see gemm_psk_kernel), of which words 1008..1016 are the tile
+// counters of the ping-pong kernel's tile walk (see gemm_pp_kernel).  Tickets, flags and counters
+// must be zero before the first launch that uses them; every launch leaves them zero again.
 constexpr int SK_GRID = 512;
 constexpr size_t SK_PART_BYTES = (size_t)SK_GRID * 2 * 128 * 128 * sizeof(float);
 constexpr size_t SK_TICKET_BYTES = 4096, PSK_FLAG_BYTES = 4096;
+constexpr int PSK_FLAG_WORDS_MAX = 1000, WALK_TICKET_WORD = 1008;      // (word 1023 counts the stream-K give-ups)
 
 template <int WM, int WN, int TM, int TN, int EPI, int NS = 2>
 __global__ void __launch_bounds__(WM * WN * 64)
@@ -265,8 +267,23 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   static_assert(BM % 64 == 0 && BN % 64 == 0 && NCOPY <= 2 * TM * TN, "tile/wave mismatch");
   constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  if ((int)blockIdx.x >= tiles_m * tiles_n) {     // side job (see EpiArgs): Eq. 1 scores
-    const int sb = (int)blockIdx.x - tiles_m * tiles_n;
+  // The SiLU*mul form walks its tiles when there are more tiles than compute units: `ra.pp_walkers`
+  // workgroups, one per CU, start on tiles 0 .. walkers-1 and then draw further tiles from a
+  // counter of their XCD (tiles walkers + x + 8n for XCD x, in order: the CUs of an XCD keep
+  // working on neighbouring tiles, as under the dispatcher, and a CU that runs ahead takes more).
+  // A tile's last K step copies step 0 of the NEXT tile (in the slot where a tile of its own
+  // launch re-copies its last step for nothing), so the next tile starts without a first-load
+  // latency, and the tile's stores drain behind the next tile's K loop instead of in front of the
+  // next workgroup's start.  The ticket for the next tile is drawn when a tile starts, handed to
+  // the other waves through LDS at the end of the first K step and read in the last (so K spans
+  // at least two steps); the last workgroup to leave zeroes the counters for the next launch.
+  // (The other epilogues need both LDS stages for the tile and stay one tile per workgroup.)
+  constexpr bool PERSIST = (EPI == EPI_SWIGLU);
+  const int T = tiles_m * tiles_n;
+  const int walkers = PERSIST ? ra.pp_walkers : T;
+  unsigned* const tk = PERSIST ? ra.walk_tickets : nullptr;   // 8 counters + 1 of leavers; null: no walk
+  if ((int)blockIdx.x >= walkers) {               // side job (see EpiArgs): Eq. 1 scores
+    const int sb = (int)blockIdx.x - walkers;
     score_finish_block<true>(ra.sf_z, ra.sf_stat, ra.sf_s, ra.sf_cu, ra.sf_n_single, ra.sf_heads,
                              ra.sf_z_ld, ra.sf_cu_z, true, sb / ra.sf_blocks_per_seq,
                              (sb % ra.sf_blocks_per_seq) * (int)blockDim.x, (float2*)lds);
@@ -280,26 +297,29 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 
   int tile_m, tile_n;
   workgroup_tile((int)blockIdx.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int crow = lane >> 3;
   uint32_t a_off[A_INSTR], w_off[W_INSTR];
+  auto set_offsets = [&](int m0_, int n0_) {
 #pragma unroll
-  for (int q = 0; q < A_INSTR; ++q) {
-    const int tr = (wave * A_INSTR + q) * 8 + crow;
-    const int cchunk = (lane & 7) ^ swz64(tr);
-    int r = m0 + tr;
-    r = r < M ? r : M - 1;
-    a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
-  }
+    for (int q = 0; q < A_INSTR; ++q) {
+      const int tr = (wave * A_INSTR + q) * 8 + crow;
+      const int cchunk = (lane & 7) ^ swz64(tr);
+      int r = m0_ + tr;
+      r = r < M ? r : M - 1;
+      a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
+    }
 #pragma unroll
-  for (int q = 0; q < W_INSTR; ++q) {
-    const int tr = (wave * W_INSTR + q) * 8 + crow;
-    const int cchunk = (lane & 7) ^ swz64(tr);
-    int r = n0 + tr;
-    r = r < N ? r : N - 1;
-    w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
-  }
+    for (int q = 0; q < W_INSTR; ++q) {
+      const int tr = (wave * W_INSTR + q) * 8 + crow;
+      const int cchunk = (lane & 7) ^ swz64(tr);
+      int r = n0_ + tr;
+      r = r < N ? r : N - 1;
+      w_off[q] = (uint32_t)(((size_t)r * ldw + cchunk * 8) * 2);
+    }
+  };
+  set_offsets(m0, n0);
   const size_t wstep = (size_t)ra.w_step_bytes;     // 128, or N * 128 for the K-step-major weight
   auto issue = [&](int stage, int k0) {
     char* sa = lds + stage * STAGE_BYTES + (wave * A_INSTR) * 1024;
@@ -334,12 +354,6 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   const uint32_t w_row = (uint32_t)(BM * ROW_BYTES + (wn * TN * 32 + (lane & 31)) * ROW_BYTES);
 
   floatx16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   bf16x8_t af[2][TM], wf[2][TN];
 
   // 2*TM*TN MFMAs with one copy behind each of the first NCOPY
@@ -390,57 +404,152 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     __builtin_amdgcn_sched_barrier(0);                                                         \
   } while (0)
 
+  // thread 0 (first group: its wait for the copies, just before, has also brought the ticket in)
+  // leaves the drawn ticket in LDS for everybody, a barrier before anyone reads it
+  // (instructions written out: the atomic's return must not be waited for where it is issued --
+  // the compiler would turn it into a wave-wide reduction with a wait -- and the slot is plain LDS)
+  const uint32_t ticket_slot =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds + 2u * STAGE_BYTES;
+#define LZ_HAND_TICKET()                                                                       \
+  do {                                                                                         \
+    if (PERSIST && tk != nullptr && kt == 0 && threadIdx.x == 0)                               \
+      asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(ticket_slot), "v"(ticket) : "memory"); \
+  } while (0)
+
   const int KT = K / BK;
   issue(0, 0);
   float rs[TM];
   load_row_scales<TM>(rs, ra, M, m0, wm, lane);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (group == 1) LZ_PHASE_END();                 // the second group starts one phase later
-  const bool idle_wave = m0 + wm * TM * 32 >= M;
-  for (int kt = 0; kt < KT; ++kt) {
-    const char* cur = lds + (kt & 1) * STAGE_BYTES;
-    // The last step copies itself again into the stage nobody reads any more: no branch in
-    // the MFMA stream, and the copy is drained by the waits below like any other.
-    const int k_next = (kt + 1 < KT ? kt + 1 : kt) * BK;
-    if (idle_wave) {
-      // all of this wave's rows are past M (last tile row): it still copies its share of the
-      // stages and keeps the barriers, but runs no MFMA -- the part is power-limited, and the
-      // matrix work on padding rows would only lower the clock for everybody else
-      LZ_PHASE_END();
+  int par = 0;                                    // stage that holds step 0 of the current tile
+  for (;;) {
 #pragma unroll
-      for (int q = 0; q < NCOPY; ++q) issue_one((kt + 1) & 1, k_next, q);
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    unsigned ticket = 0;
+    if (PERSIST && tk != nullptr && threadIdx.x == 0)
+      asm volatile("global_atomic_add %0, %1, %2, off sc0"
+                   : "=&v"(ticket) : "v"(tk + ((int)blockIdx.x & 7)), "v"(1u) : "memory");
+    bool has_next = false;
+    int m0_next = 0, n0_next = 0;
+    unsigned long long ssq_next[TM];              // row scales of the next tile, as loaded
+#pragma unroll
+    for (int i = 0; i < TM; ++i) ssq_next[i] = 0;
+    if (group == 1) LZ_PHASE_END();               // the second group starts one phase later
+    const bool idle_wave = m0 + wm * TM * 32 >= M;
+    for (int kt = 0; kt < KT; ++kt) {
+      const char* cur = lds + ((kt + par) & 1) * STAGE_BYTES;
+      const int st_next = (kt + 1 + par) & 1;
+      // The last step copies itself again into the stage nobody reads any more (no branch in
+      // the MFMA stream, and the copy is drained by the waits below like any other) -- or, when
+      // the workgroup has another tile, that tile's step 0.
+      int k_next = (kt + 1 < KT ? kt + 1 : kt) * BK;
+      if (PERSIST && tk != nullptr && kt == KT - 1) {
+        int drawn;
+        asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(drawn) : "v"(ticket_slot) : "memory");
+        drawn = __builtin_amdgcn_readfirstlane(drawn);
+        const int pid_next = walkers + ((int)blockIdx.x & 7) + 8 * drawn;
+        has_next = pid_next < T;
+        if (has_next) {
+          workgroup_tile(pid_next, tiles_m, tiles_n, group_m, tile_m, tile_n);
+          m0_next = tile_m * BM;
+          n0_next = tile_n * BN;
+          set_offsets(m0_next, n0_next);
+          k_next = 0;
+          if (ra.ssq_in != nullptr) {             // (used after the loop: nobody waits for it here)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+              const int row = m0_next + (wm * TM + i) * 32 + (lane & 31);
+              ssq_next[i] = ra.ssq_in[row < M ? row : M - 1];
+            }
+          }
+        }
+      }
+      if (idle_wave) {
+        // all of this wave's rows are past M (last tile row): it still copies its share of the
+        // stages and keeps the barriers, but runs no MFMA -- the part is power-limited, and the
+        // matrix work on padding rows would only lower the clock for everybody else
+        LZ_PHASE_END();
+#pragma unroll
+        for (int q = 0; q < NCOPY; ++q) issue_one(st_next, k_next, q);
+        LZ_PHASE_END();
+        if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        LZ_PHASE_END();
+        if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        LZ_HAND_TICKET();
+        LZ_PHASE_END();
+        continue;
+      }
+      LZ_MEM_PHASE(cur, 0);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       LZ_PHASE_END();
+      LZ_COMPUTE_COPY_PHASE(st_next, k_next);
+      LZ_PHASE_END();
+      LZ_MEM_PHASE(cur, 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       LZ_PHASE_END();
+      LZ_COMPUTE_PHASE();
       if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      LZ_HAND_TICKET();
       LZ_PHASE_END();
-      continue;
     }
-    LZ_MEM_PHASE(cur, 0);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    LZ_PHASE_END();
-    LZ_COMPUTE_COPY_PHASE((kt + 1) & 1, k_next);
-    LZ_PHASE_END();
-    LZ_MEM_PHASE(cur, 1);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (group == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    LZ_PHASE_END();
-    LZ_COMPUTE_PHASE();
-    if (group == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    LZ_PHASE_END();
+    if (group == 0) LZ_PHASE_END();
+    if (!PERSIST) break;
+    // One stage already holds the next tile's step 0; the other one -- the last step's, which
+    // nobody reads any more and which step 1 of the next tile overwrites only after that tile's
+    // first barrier -- is exactly the size of the SiLU*mul tile (half as wide as the product),
+    // so the tile still goes out through LDS in whole rows.
+    if (ra.stage_out) {
+      static_assert(BM * (BN / 2) * 2 <= STAGE_BYTES, "the SiLU*mul tile must fit one stage");
+      staged_tile_out<TM, TN, EPI, BM, BN, NWAVES>(acc, C, R, M, ldc, m0, n0, wm, wn, wave, lane, ra, rs,
+                                                   lds + ((KT - 1 + par) & 1) * STAGE_BYTES);
+    } else {
+      gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
+    }
+    if (!has_next) {
+      if (tk != nullptr && threadIdx.x == 0) {
+        const unsigned left = __hip_atomic_fetch_add(tk + 8, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left == (unsigned)walkers - 1u)         // everybody else has drawn their last ticket
+          for (int x = 0; x < 9; ++x) __hip_atomic_store(tk + x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      return;
+    }
+    m0 = m0_next;
+    n0 = n0_next;
+    par = (par + KT) & 1;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      rs[i] = (ra.ssq_in != nullptr && m0 + (wm * TM + i) * 32 + (lane & 31) < M)
+                  ? rsqrtf((float)ssq_next[i] * ra.ssq_mul + ra.eps) : 0.f;
   }
-  if (group == 0) LZ_PHASE_END();
 #undef LZ_MEM_PHASE
 #undef LZ_COMPUTE_PHASE
 #undef LZ_COMPUTE_COPY_PHASE
 #undef LZ_PHASE_END
-  if (EPI == EPI_SWIGLU || !ra.stage_out) {        // (the launcher never stages the SiLU*mul form)
+#undef LZ_HAND_TICKET
+  if (!ra.stage_out) {
     gemm_epilogue<TM, TN, EPI>(acc, C, R, M, ldc, m0, n0, wm, wn, lane, ra, rs);
     return;
   }
-  static_assert(BM * ((EPI == EPI_SWIGLU) ? BN / 2 : BN) * 2 <= 2 * STAGE_BYTES, "staged tile must fit the stages");
+  static_assert(BM * BN * 2 <= 2 * STAGE_BYTES, "staged tile must fit the stages");
   staged_tile_out<TM, TN, EPI, BM, BN, NWAVES>(acc, C, R, M, ldc, m0, n0, wm, wn, wave, lane, ra, rs, lds);
+}
+
+// Workgroups of a persistent kernel that are resident at once (one per CU when the device is
+// otherwise idle); 0 if the runtime cannot tell.
+template <typename KernT>
+static int psk_resident_workgroups(KernT kern, int lds_bytes) {
+  int dev = 0, per_cu = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, 512, (size_t)lds_bytes) != hipSuccess)
+    return 0;
+  return per_cu >= 1 ? cus : 0;
 }
 
 // The ping-pong kernels address both operands with 32-bit byte offsets from a uniform base.
@@ -454,7 +563,7 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
                             int K, int lda, int ldw, int ldc, int epi, int group_m,
                             const EpiArgs& ra, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+  constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES + 16;      // two stages and the ticket slot
   if (N % BN != 0) return hipErrorInvalidValue;
   if (!pp_operands_fit_32bit(M, N, K, lda, ldw, ra.w_blocked != 0)) return hipErrorInvalidValue;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
@@ -463,22 +572,30 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
   if (ra.w_blocked) ldw = BK;                       // rows of one K step are 128 bytes apart
   ea.sf_blocks_per_seq = (ea.sf_max_rows + 511) / 512;
   // the tile goes out through LDS when whole 16-byte chunks of every row are addressable
-  // (not for the SiLU*mul epilogue: its tile is half as wide, its GEMM runs several rounds whose
-  // stores already spread out in time, and staging measured 1.6 % slower there)
   ea.stage_out = (epi == EPI_QKV_ROPE) ? (ra.d_model % BN == 0 && (ra.kv_dim > 0 ? ra.kv_dim : ra.d_model) % BN == 0)
-                 : (epi != EPI_SWIGLU && ldc % 8 == 0 && ((uintptr_t)C & 15) == 0);
+                 : (ldc % 8 == 0 && ((uintptr_t)C & 15) == 0);
   const int side = ea.sf_z != nullptr ? ea.sf_blocks_per_seq * ea.sf_batch : 0;
-  dim3 grid(tiles_m * tiles_n + side), block(512);
+  dim3 block(512);
 #define LZ_GEMM(E)                                                                               \
   do {                                                                                           \
     auto kern = gemm_pp_kernel<WM, WN, TM, TN, E>;                                               \
     static bool attr_set = false;                                                                \
+    static int resident = 0;                                                                     \
     if (!attr_set) {                                                                             \
       hipError_t e = hipFuncSetAttribute((const void*)kern,                                      \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES); \
       if (e != hipSuccess) return e;                                                             \
+      resident = psk_resident_workgroups(kern, LDS_BYTES);                                       \
       attr_set = true;                                                                           \
     }                                                                                            \
+    /* the SiLU*mul form walks its tiles with one workgroup per CU (a whole number per XCD) when \
+       it has the ticket counters; every other form: one workgroup per tile */                   \
+    const int cus = resident & ~7;                                                               \
+    const bool walk = E == EPI_SWIGLU && ra.walk_tickets != nullptr && cus >= 8 &&               \
+                      cus < tiles_m * tiles_n && K >= 2 * BK;                                    \
+    ea.pp_walkers = walk ? cus : tiles_m * tiles_n;                                              \
+    if (!walk) ea.walk_tickets = nullptr;                                                        \
+    dim3 grid(ea.pp_walkers + side);                                                             \
     hipLaunchKernelGGL(kern, grid, block, LDS_BYTES, st, (const uint16_t*)A, (const uint16_t*)W, \
                        (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw, ldc, tiles_m,        \
                        tiles_n, group_m, ea);                                                    \
@@ -844,18 +961,6 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #undef LZ_FRESH_LANE
 }
 
-// Workgroups of the persistent kernel that are resident at once (one per CU when the device is
-// otherwise idle); 0 if the runtime cannot tell.
-template <typename KernT>
-static int psk_resident_workgroups(KernT kern, int lds_bytes) {
-  int dev = 0, per_cu = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)kern, 512, (size_t)lds_bytes) != hipSuccess)
-    return 0;
-  return per_cu >= 1 ? cus : 0;
-}
-
 // Fewer tiles than workgroups, the same number on every XCD: a whole number S of workgroups per
 // tile makes every range an exact 1/S of ONE tile, so that a workgroup has one piece, S - 1 of S
 // leave a partial tile and the owner reads S - 1 (80 tiles: 240 workgroups, three per tile,
@@ -901,7 +1006,7 @@ static hipError_t launch_psk(const void* A, const void* W, void* C, const void* 
     int G = resident < 256 ? resident : 256;                                                     \
     G &= ~7;                                         /* whole rounds over the 8 XCDs */          \
     G = psk_aligned_grid(G, tiles_m * tiles_n);                                                  \
-    if (G < 8 || (size_t)G * BM * BN * sizeof(float) > SK_PART_BYTES || G > 1016)                \
+    if (G < 8 || (size_t)G * BM * BN * sizeof(float) > SK_PART_BYTES || G > PSK_FLAG_WORDS_MAX)  \
       return hipErrorInvalidConfiguration;                                                       \
     hipLaunchKernelGGL(kern, dim3(G + side), dim3(512), LDS_BYTES, st, (const uint16_t*)A,       \
                        (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, M, N, K, lda, ldw,  \
@@ -1652,9 +1757,14 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 5:                                             // 256x256, 8 waves of 64x128, ping-pong
-            return launch_pp<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
-    case 7:                                             // 192x256, 8 waves of 96x64, ping-pong
-            return launch_pp<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 7: {                                           // 192x256, 8 waves of 96x64, ping-pong
+            EpiArgs rw = ra;                            // (the tile walk's counters live among the flags)
+            rw.walk_tickets = (sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() && ra.psk_ready)
+                                  ? (unsigned*)((char*)sk_ws + SK_PART_BYTES + SK_TICKET_BYTES) + WALK_TICKET_WORD
+                                  : nullptr;
+            return cfg == 5 ? launch_pp<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, rw, st)
+                            : launch_pp<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, rw, st);
+    }
     case 9:                                             // 256x256 ping-pong, persistent stream-K
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes() || !ra.psk_ready) return hipErrorInvalidValue;
             return launch_psk<4, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, sk_ws, st);

@@ -100,6 +100,46 @@ def test_gemm_skinny(M, N, K, epi):
     assert torch.equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(5, 1100, 22016, 192), (5, 2100, 22016, 64), (5, 1300, 16384, 128),
+                                       (7, 1100, 22016, 192), (7, 1000, 16384, 64), (7, 2100, 22016, 256)])
+def test_gemm_swiglu_walks_several_tiles_per_workgroup(cfg, M, N, K):
+    """More tiles than compute units: with a workspace (its ticket counters) the SiLU*mul form of
+    the ping-pong kernel walks them, a workgroup drawing two to four tiles in turn with the next
+    tile's first K step copied during the last step of the current one.  Odd and even numbers of K
+    steps (the stage that holds step 0 alternates or not), a single K step (no walk: one workgroup
+    per tile), a ragged last tile row; every element against the definition, twice in a row (the
+    first launch must leave the counters zero), and the same bits without a workspace."""
+    rng = np.random.default_rng(cfg * 1000 + M + N + K)
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    A = _rand_bf16(rng, (M, K))
+    W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    acc = _f64(A) @ _f64(W).T
+    blocks = acc.reshape(M, N // 64, 2, 32)
+    ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+    Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, B.EPI_SWIGLU | (cfg << 8), workspace=ws)
+    torch.cuda.synchronize()
+    _assert_bf16_close(_f64(Cout), ref, 1.0, "gemm swiglu, tile walk")
+    assert int(ws[-4096:].view(torch.int32).abs().sum()) == 0        # flags and counters back at zero
+    # again; the K-step-major weight; an output whose rows are not 16-byte aligned (direct stores);
+    # no workspace (one workgroup per tile)
+    Wb = torch.empty_like(W)
+    B.lazyllm_op_pack_weight_ksteps(W, N, K, K, Wb)
+    outs = []
+    for w, flag, kw in ((W, 0, {"workspace": ws}), (Wb, 1 << 29, {"workspace": ws}), (W, 0, {})):
+        C2 = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm(A, w, C2, None, M, N, K, K, K, N // 2, B.EPI_SWIGLU | (cfg << 8) | flag, **kw)
+        outs.append(C2)
+    wide = torch.full((M, N // 2 + 4), 7.0, dtype=torch.bfloat16, device=DEV)
+    B.lazyllm_op_gemm(A, W, wide, None, M, N, K, K, K, N // 2 + 4, B.EPI_SWIGLU | (cfg << 8), workspace=ws)
+    torch.cuda.synchronize()
+    for C2 in outs:
+        assert torch.equal(C2, Cout)
+    assert torch.equal(wide[:, :N // 2], Cout)
+    assert bool((wide[:, N // 2:] == 7.0).all())
+    assert int(ws[-4096:].view(torch.int32).abs().sum()) == 0
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (229, 768, 256), (700, 1536, 704), (355, 512, 128), (130, 256, 1408)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
 def test_gemm_tile_of_32_row_waves(M, N, K, epi):
