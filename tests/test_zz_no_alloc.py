@@ -1,6 +1,8 @@
 """The allocation-free Eq. 1 entry point (lazyllm_op_score_static): same results as
 lazyllm_op_score, bit for bit, on two calls in a row, the second with a smaller input; the CPU
 checker's Eq. 1 bounds both; sizes beyond the static scratch are refused."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -23,17 +25,24 @@ def _f64(t):
 def test_static_scratch_scoring_matches_the_buffer_form_on_two_calls_in_a_row():
     rng = np.random.default_rng(77)
     H, hd = 32, 128
-    for rows in (3376, 1182):                      # the second call is smaller than the first
+    for call, rows in enumerate((3376, 1182)):     # the second call is smaller than the first
         k = _rand_bf16(rng, (rows, H * hd))
         q_last = _rand_bf16(rng, (H * hd,), 1.5)
         s_ref = torch.full((rows,), -1.0, dtype=torch.float32, device=DEV)
         scratch = torch.empty(B.lazyllm_op_score_scratch_bytes(rows, H), dtype=torch.uint8, device=DEV)
         B.lazyllm_op_score(q_last, k, s_ref, scratch, rows, H, hd)
         s = torch.full((rows,), -2.0, dtype=torch.float32, device=DEV)
-        before = torch.cuda.memory_allocated()
+        # nothing allocated, neither through torch nor from the device behind its back (garbage of
+        # earlier tests is collected first, so that nothing of theirs is freed in between)
+        gc.collect()
+        torch.cuda.synchronize()
+        before, free_before = torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]
         B.lazyllm_op_score_static(q_last, k, s, rows, H, hd)
         assert torch.cuda.memory_allocated() == before
         torch.cuda.synchronize()
+        # (a scratch buffer would be megabytes.  Not on the first call of the process: the runtime
+        # loads the code object that holds the static array then, and the array with it)
+        assert call == 0 or free_before - torch.cuda.mem_get_info()[0] < (1 << 20)
         assert torch.equal(s, s_ref), rows           # same kernels, same order of operations
         want = O.last_row_scores(_f64(q_last).reshape(H, hd), _f64(k).reshape(rows, H, hd))
         got = s.cpu().numpy().astype(np.float64)
