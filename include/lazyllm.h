@@ -119,6 +119,10 @@ typedef struct lazyllm_model lazyllm_model;
 #define LAZYLLM_ST_BAD_CU 2          /* device cu_seqlens disagrees with the host copy */
 #define LAZYLLM_ST_NO_STATE 4        /* decoding: a selected token had neither K,V nor an Aux Cache
                                         entry at a layer (the state buffer was damaged) */
+#define LAZYLLM_ST_EXCHANGE 8        /* a matrix product whose workgroups hand partial sums to each
+                                        other gave up on a hand-over (a workgroup was not resident,
+                                        or not on the XCD it was expected on): the outputs of this
+                                        call are not to be used */
 
 /* Where the results of one prefill live.  Every pointer is device memory
  * inside the caller's output buffer and stays valid as long as that buffer.

@@ -643,6 +643,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     LZ_HIP(hipMemcpyAsync(res->hidden_out, hbuf[cur], (size_t)stg.total[s_last] * d * 2,
                           hipMemcpyDeviceToDevice, st));
   }
+  LZ_HIP(launch_gemm_exchange_check(W + ws.gemm_ws, res->status, st));
   if (lm_head_fused_fits(B, d)) {
     LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, B, (double)c->vocab * rowb,
            launch_lm_head_fused(hbuf[cur], cu_stage + s_last * BW, 0, B, m->final_norm, m->lm_head,
@@ -674,7 +675,7 @@ int lazyllm_prefill(const lazyllm_model* m, const int32_t* token_ids, const floa
 namespace {
 
 static_assert(ST_BAD_TOKEN == LAZYLLM_ST_BAD_TOKEN && ST_BAD_CU == LAZYLLM_ST_BAD_CU &&
-              ST_NO_STATE == LAZYLLM_ST_NO_STATE, "status bits");
+              ST_NO_STATE == LAZYLLM_ST_NO_STATE && ST_EXCHANGE == LAZYLLM_ST_EXCHANGE, "status bits");
 
 inline int round_up64(int x) { return (x + 63) / 64 * 64; }
 
@@ -998,6 +999,7 @@ int lazyllm_decode_step(lazyllm_generation* g, const int32_t* token_id, void* wo
            launch_gemm(W + ws.act, m->wdown[l], h, h, M, d, fp, fp, fp, d, EPI_RESIDUAL, st, &ed,
                        W + ws.gemm_ws, gemm_workspace_bytes()));
   }
+  LZ_HIP(launch_gemm_exchange_check(W + ws.gemm_ws, res->status, st));
   if (lm_head_fused_fits(1, d)) {
     LZ_RUN(LAZYLLM_STEP_LM_HEAD, -1, 1, (double)c->vocab * rowb,
            launch_lm_head_fused(hbuf[cur], nullptr, M, 1, m->final_norm, m->lm_head, res->logits, d, c->vocab,

@@ -190,6 +190,10 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
                        const EpiArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
 
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st);
+// ORs ST_EXCHANGE into *status if a GEMM since the last clear gave up on an exchange of partial
+// tiles between its workgroups (a flag that never came, or came from another XCD): its output,
+// and everything computed from it, is then not to be used.
+hipError_t launch_gemm_exchange_check(const void* sk_ws, int32_t* status, hipStream_t st);
 hipError_t launch_pack_stream(const void* W, int N, int K, int ldw, void* Wp, hipStream_t st);
 hipError_t launch_pack_kblock(const void* W, int N, int K, int ldw, void* Wb, hipStream_t st);
 
@@ -249,7 +253,7 @@ hipError_t launch_lm_head_fused(const void* h, const int32_t* cu, int n_single, 
 
 // ---- decoding steps (position-indexed generation state; see decode.hip) -----------------
 // Bits of the device status word (the public header's LAZYLLM_ST_* values).
-constexpr int ST_BAD_TOKEN = 1, ST_BAD_CU = 2, ST_NO_STATE = 4;
+constexpr int ST_BAD_TOKEN = 1, ST_BAD_CU = 2, ST_NO_STATE = 4, ST_EXCHANGE = 8;
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_scatter_rows(const void* src, const int32_t* pos, int n, void* dst, uint8_t* flag,
                                int d, hipStream_t st);

@@ -628,12 +628,17 @@ static hipError_t launch_pp(const void* A, const void* W, void* C, const void* R
 // step and share operand slabs through the L2, which a head start of a few K steps would undo),
 // then the piece it does not own -- a tile's first K steps, so these start together at K = 0;
 // the fp32 partial sums go to the workspace, lane-major, 16 bytes per lane and store, followed by
-// a release fence and a flag -- and its own piece LAST: these end together at K = KT, and the
-// other pieces of the tile were finished before the owner is (every workgroup gives its piece
-// away before it starts its own).  The owner adds them in ascending K order (a fixed order:
-// results do not depend on timing) and runs the normal epilogue.  Waits are bounded: if a flag
-// never comes (it cannot, unless fewer than G workgroups fit on the device, which the launcher
-// checks), the owner gives up, counts the failure in the workspace and finishes.
+// a flag once they have reached the L2 -- and its own piece LAST: these end together at K = KT,
+// and the other pieces of the tile were finished before the owner is (every workgroup gives its
+// piece away before it starts its own).  The owner adds them in ascending K order (a fixed order:
+// results do not depend on timing) and runs the normal epilogue.  The pieces of a tile belong to
+// workgroups of one XCD (ids x, x + 8, ...), which share an L2, so the exchange needs no cache
+// write-back or invalidation; that the dispatcher did put them on one XCD is checked, not
+// assumed: the flag's value is 1 + the writer's XCC id (hardware register XCC_ID) and the owner
+// compares it with its own.  Waits are bounded: if a flag never comes (it cannot, unless fewer
+// than G workgroups fit on the device, which the launcher checks) or comes from another XCD,
+// the owner gives up, counts the failure in the last word of the flag area -- the prefill and the
+// decoding step turn a count into LAZYLLM_ST_EXCHANGE of their status word -- and finishes.
 // Flags are zero on entry; the owner resets the flags it consumed.
 // ------------------------------------------------------------------------------------------
 constexpr unsigned PSK_SPIN_LIMIT = 1u << 22;      // about a second of polling
@@ -654,6 +659,8 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   constexpr int TILE_FLOATS = BM * BN;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   __shared__ unsigned wait_failed;
+  // the XCC (XCD) this workgroup runs on: hardware register XCC_ID, bits 3:0
+  const unsigned my_xcc = __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20);
   if ((int)blockIdx.x >= G) {                     // side job (see EpiArgs): Eq. 1 scores
     const int sb = (int)blockIdx.x - G;
     score_finish_block<true>(ra.sf_z, ra.sf_stat, ra.sf_s, ra.sf_cu, ra.sf_n_single, ra.sf_heads,
@@ -879,14 +886,16 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                 make_float4(acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2],
                             acc[i][j][4 * q4 + 3]);
         }
-      // every wave's stores have reached the L2 (vmcnt), then ONE wave writes the L2 back: a
-      // release fence per wave would be eight write-backs of the same cache
+      // Every wave's stores have reached the L2 (vmcnt), then the flag goes up.  The reader sits
+      // on the same XCD, behind the same L2, so there is nothing to write back or to invalidate
+      // (a release fence writes the whole L2 back and an acquire fence empties it for everybody
+      // on the XCD, 4-8 us per launch); the flag carries this workgroup's XCC id, and the reader
+      // checks that it is its own.
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     }
     if (threadIdx.x == 0)
-      __hip_atomic_store(flags + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(flags + g, 1u + my_xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // ---- 3. the end of the tile this workgroup owns, plus the pieces the others left
@@ -904,16 +913,16 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
         for (int ip = i_first; ip < gi; ++ip) {
           if (ubegin(ip + 1) <= ubegin(ip)) continue;         // an empty range wrote nothing
           const int gp = xcd + 8 * ip;
-          unsigned spins = 0;
-          while (__hip_atomic_load(flags + gp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+          unsigned spins = 0, seen;
+          while ((seen = __hip_atomic_load(flags + gp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
             __builtin_amdgcn_s_sleep(8);
             if (++spins >= PSK_SPIN_LIMIT) { failed = 1; break; }
           }
+          if (seen != 0u && seen != 1u + my_xcc) failed = 1;  // written behind another L2: not visible here
         }
         wait_failed = failed;
         if (failed) atomicAdd(flags + 1023, 1u);              // (the last word counts give-ups)
       }
-      if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       __syncthreads();
       LZ_FRESH_LANE();
       if (wait_failed == 0) {
@@ -1627,6 +1636,16 @@ static hipError_t launch_skinny(const void* A, const void* W, void* C, const voi
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st) {
   static_assert(SKN_COUNTER_BYTES == SK_TICKET_BYTES, "ticket area");
   return launch_fill_zero((char*)sk_ws + SK_PART_BYTES, SK_TICKET_BYTES + PSK_FLAG_BYTES, st);
+}
+
+__global__ void exchange_check_kernel(const unsigned* __restrict__ give_ups, int32_t* __restrict__ status) {
+  if (*give_ups != 0u) atomicOr(status, ST_EXCHANGE);
+}
+
+hipError_t launch_gemm_exchange_check(const void* sk_ws, int32_t* status, hipStream_t st) {
+  const unsigned* flags = (const unsigned*)((const char*)sk_ws + SK_PART_BYTES + SK_TICKET_BYTES);
+  hipLaunchKernelGGL(exchange_check_kernel, dim3(1), dim3(1), 0, st, flags + 1023, status);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
