@@ -974,11 +974,13 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 // tile makes every range an exact 1/S of ONE tile, so that a workgroup has one piece, S - 1 of S
 // leave a partial tile and the owner reads S - 1 (80 tiles: 240 workgroups, three per tile,
 // instead of 256 ranges of which most straddle two tiles).  Taken when it keeps 3/4 of the CUs.
-static int psk_aligned_grid(int G, int tiles) {
-  if (tiles >= G || tiles % 8 != 0) return G;
+static bool psk_pieces_align(int G, int tiles) {
+  if (tiles >= G || tiles % 8 != 0) return false;
   const int per_xcd = tiles / 8, S = (G / 8) / per_xcd;
-  if (S >= 2 && S * per_xcd * 4 >= (G / 8) * 3) return 8 * S * per_xcd;
-  return G;
+  return S >= 2 && S * per_xcd * 4 >= (G / 8) * 3;
+}
+static int psk_aligned_grid(int G, int tiles) {
+  return psk_pieces_align(G, tiles) ? 8 * ((G / 8) / (tiles / 8)) * (tiles / 8) : G;
 }
 
 template <int WM, int WN, int TM, int TN>
@@ -1704,10 +1706,20 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // 600 / 844 / 1182 / 1400 rows 106 -> 87, 107 -> 100, 153 -> 124, 166 -> 138 us; O projection at
     // 1182 / 1400 rows 68.5 -> 63, 68.7 -> 66.6 (but 50 -> 56 at 600 rows, and at 355 rows the 128x128
     // stream-K form below stays ahead: 62 against 79 us).
+    // With the exchange free of cache-wide fences it also pays from 64 tiles on with a short K; there
+    // the 192-row tile is taken when its count aligns too and it pads fewer rows (O projection at
+    // 600 / 768 / 861 / 1000 rows: 49 -> 46, 56 -> 49, 57 -> 50, 59 -> 57 us; down projection at
+    // 861 / 1000 rows, 64 tiles of 256 rows in four pieces each: 111 -> 95, 122 -> 106).
     if ((epilogue == EPI_STORE || epilogue == EPI_RESIDUAL) && ra.psk_ready && sk_ws != nullptr &&
-        sk_ws_bytes >= gemm_workspace_bytes() && N % 256 == 0 && big_tiles < 128 &&
-        psk_aligned_grid(256, (int)big_tiles) != 256 && ((K >= 8192 && big_tiles >= 48) || big_tiles >= 80))
-      cfg = 9;
+        sk_ws_bytes >= gemm_workspace_bytes() && N % 256 == 0 && fits32) {
+      const long t192 = (long)((M + 191) / 192) * (N / 256);
+      const long least = K >= 8192 ? 48 : 64;
+      const bool ok256 = big_tiles < 128 && big_tiles >= least && psk_pieces_align(256, (int)big_tiles);
+      const bool ok192 = K < 8192 && t192 < 128 && t192 >= least && psk_pieces_align(256, (int)t192);
+      const long pad256 = (M + 255) / 256 * 256 - M, pad192 = (M + 191) / 192 * 192 - M;
+      if (ok192 && (!ok256 || pad192 < pad256)) cfg = 10;
+      else if (ok256) cfg = 9;
+    }
     if (cfg == 0 && (epilogue == EPI_STORE || epilogue == EPI_RESIDUAL) && sk_ws != nullptr &&
         sk_ws_bytes >= gemm_workspace_bytes()) {
       const long t128 = (long)((M + 127) / 128) * (N / 128);
@@ -1739,10 +1751,29 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
     // rows 206 -> 182 us, O at 4916 rows 183 -> 174 us; gate/up at 3376 rows (4.7 rounds) 517 -> 534:
     // not taken.
     if (cfg == 0 && ra.psk_ready && sk_ws != nullptr && sk_ws_bytes >= gemm_workspace_bytes() &&
-        N % 256 == 0 && big_tiles >= 128 && epilogue != EPI_SWIGLU) {     // (gate/up at 2364 rows, 3.36 rounds: 389 -> 388 us, not worth it)
+        N % 256 == 0 && big_tiles >= 128 && epilogue != EPI_SWIGLU) {     // (gate/up: its own rule below)
       const long rounds = (big_tiles + 255) / 256;
       const double slack = (double)rounds - (double)big_tiles / 256.0;
-      if (slack >= (K >= 8192 ? 0.3 : 0.45)) cfg = 9;
+      if (slack >= (K >= 8192 ? 0.3 : 0.4)) cfg = 9;
+    }
+    // Gate/up with a last round that is two thirds empty (a single round of 150 - 205 tiles, or
+    // 320 - 384 tiles: 1.25 - 1.5 rounds, 64 - 128 remainder tiles of two to four pieces each): the
+    // persistent stream-K schedule, on the tile height that fits such a count (both: the one with
+    // fewer padding rows).  N = 22016 makes 86 column blocks, so 2 or 4 tile rows qualify.
+    // Measured, cold weights, against the best data-parallel form: 300 / 355 rows (2 x 86 tiles of
+    // 192 rows) 96 -> 89, 101 -> 93 us; 450 / 512 rows (2 x 86 of 256) 110 -> 108, 115 -> 108;
+    // 600 / 700 / 768 rows (4 x 86 of 192) 181 -> 151, 190 -> 165, 198 -> 175; 861 / 1000 rows
+    // (4 x 86 of 256) 186 -> 179, 224 -> 196.  Not at 430 tiles (1100 / 1182 rows: 216 -> 222) nor
+    // with more rounds (the data-parallel form's tile walk has no counterpart there).
+    if (cfg == 0 && epilogue == EPI_SWIGLU && ra.psk_ready && sk_ws != nullptr &&
+        sk_ws_bytes >= gemm_workspace_bytes() && N % 256 == 0 && fits32) {
+      const long t256 = big_tiles, t192 = (long)((M + 191) / 192) * (N / 256);
+      const bool ok256 = (t256 >= 150 && t256 <= 205) || (t256 >= 320 && t256 <= 384);
+      const bool ok192 = (t192 >= 150 && t192 <= 205) || (t192 >= 320 && t192 <= 384 && t256 > 256);
+      const long pad256 = (M + 255) / 256 * 256 - M, pad192 = (M + 191) / 192 * 192 - M;
+      if (ok256 && ok192) cfg = pad192 < pad256 ? 10 : 9;
+      else if (ok192) cfg = 10;
+      else if (ok256) cfg = 9;
     }
     // The same trade with two rounds of 256-row tiles: 192-row tiles run at about 0.82 of a
     // 256-row tile's time each, so they win when their rounds are fewer by more than that

@@ -268,6 +268,41 @@ def test_gemm_stream_k(M, N, K, epi):
     assert torch.equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("epi,M,N,K", [(B.EPI_SWIGLU, 355, 22016, 256), (B.EPI_SWIGLU, 450, 22016, 128),
+                                       (B.EPI_SWIGLU, 600, 22016, 192), (B.EPI_SWIGLU, 1000, 22016, 128),
+                                       (B.EPI_RESIDUAL, 600, 4096, 512), (B.EPI_RESIDUAL, 861, 4096, 512),
+                                       (B.EPI_RESIDUAL, 861, 4096, 8192), (B.EPI_STORE, 700, 12288, 256)])
+def test_gemm_library_choice_with_a_workspace(epi, M, N, K):
+    """With a workspace the library may choose the persistent stream-K schedule on its own: gate/up
+    with a last round two thirds empty (172 or 344 tiles of either height), the O and down
+    projections at 64 - 127 aligned tiles, a last round 0.4 or more empty.  Every element against the
+    definition, the same bits twice, flags back at zero."""
+    rng = np.random.default_rng(epi * 977 + M + N + K)
+    A = _rand_bf16(rng, (M, K))
+    W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    acc = _f64(A) @ _f64(W).T
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    outs = []
+    for _ in range(2):
+        if epi == B.EPI_SWIGLU:
+            blocks = acc.reshape(M, N // 64, 2, 32)
+            ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+            Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+            B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, epi, workspace=ws)
+        else:
+            if not outs:
+                R = _rand_bf16(rng, (M, N))
+            ref = acc + (_f64(R) if epi == B.EPI_RESIDUAL else 0.0)
+            Cout = R.clone()
+            B.lazyllm_op_gemm(A, W, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N, epi,
+                              workspace=ws)
+        torch.cuda.synchronize()
+        assert int(ws[-4096:].view(torch.int32).abs().sum()) == 0
+        outs.append(Cout)
+    _assert_bf16_close(_f64(outs[0]), ref, 1.0, "gemm, library's choice")
+    assert torch.equal(outs[0], outs[1])
+
+
 @pytest.mark.parametrize("cfg", [9, 10])
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (300, 768, 256), (2364, 4096, 1024), (1182, 4096, 4096),
                                    (3376, 2048, 512), (700, 22016, 256), (5000, 256, 128), (8192, 8192, 128),
