@@ -33,7 +33,8 @@ def gate_up_traffic_bytes():
     return float(m.group(1)) * 1e6 if m else None
 
 
-STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<4,2,2,4,EPI_SWIGLU> (RMSNorm scale + gate/up projection + SiLU*mul)",
+STEP_KERNEL = {"gemm_gate_up": "gemm_pp_kernel<4,2,2,4,EPI_SWIGLU> (RMSNorm scale + gate/up projection + SiLU*mul; at 355 rows "
+                               "the same epilogue under gemm_psk_kernel<2,4,3,2,EPI_SWIGLU>)",
                "gemm_qkv": "gemm_pp_kernel<4,2,2,4,EPI_QKV_ROPE128> (RMSNorm scale + QKV projection + RoPE + V^T)",
                "gemm_down": "gemm_pp_kernel<4,2,2,4,EPI_RESIDUAL> (down projection + residual + row sums of squares)",
                "gemm_o": "gemm_pp_kernel<4,2,2,4,EPI_RESIDUAL> (O projection + residual + row sums of squares)"}
