@@ -1744,9 +1744,9 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
         N % 128 == 0 && lda % 8 == 0 && ldw % 8 == 0)
       cfg = 8;
     // Persistent stream-K over the 256x256 tiles when the last data-parallel round would leave
-    // much of the chip idle.  The exchange of partial tiles costs about 25 us per launch (write,
-    // L2 write-back, read) and the cut tiles share less in the L2, so it pays only from about half
-    // an empty round on (a third with the long K of the down projection).  Measured, cold weights:
+    // much of the chip idle.  The exchange of partial tiles costs about 20 us per launch (256 KB
+    // per workgroup out and back through the L2) and the cut tiles share less in the L2, so it pays
+    // only from 0.4 of an empty round on (0.3 with the long K of the down projection).  Measured, cold weights:
     // down projection at 4916 / 2364 / 1967 rows 466 -> 401, 228 -> 209, 194 -> 163 us, QKV at 1967
     // rows 206 -> 182 us, O at 4916 rows 183 -> 174 us; gate/up at 3376 rows (4.7 rounds) 517 -> 534:
     // not taken.
