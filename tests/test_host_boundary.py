@@ -33,6 +33,23 @@ def test_library_exports_every_declared_symbol():
     assert lib.lazyllm_strerror(-5).startswith(b"generation handle unusable")
 
 
+def test_binding_constants_are_the_headers():
+    """Every status code, flag and status bit the header defines has the same value in the binding."""
+    text = open(os.path.join(ROOT, "include", "lazyllm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    found = {n: int(v.rstrip("u")) for n, v in re.findall(r"#define\s+(LAZYLLM_\w+)\s+(-?\d+u?)\b", text)}
+    found.update({n: int(v) for n, v in re.findall(r"\b(LAZYLLM_E?\w+)\s*=\s*(-?\d+)", text)})
+    for name in ("LAZYLLM_OK", "LAZYLLM_EINVAL", "LAZYLLM_ENOSPC", "LAZYLLM_EHIP", "LAZYLLM_ENOMEM", "LAZYLLM_EFAILED",
+                 "LAZYLLM_SCORE_ONLY_USED", "LAZYLLM_KEEP_HIDDEN", "LAZYLLM_ST_BAD_TOKEN", "LAZYLLM_ST_BAD_CU",
+                 "LAZYLLM_ST_NO_STATE", "LAZYLLM_ST_EXCHANGE"):
+        assert name in found, name
+        assert getattr(B, name) == found[name], name
+    assert found["LAZYLLM_MAX_LAYERS"] == B.MAX_LAYERS
+    # the status bits are distinct single bits
+    bits = [found[n] for n in found if n.startswith("LAZYLLM_ST_")]
+    assert len(bits) == 4 and all(b & (b - 1) == 0 for b in bits) and len(set(bits)) == 4
+
+
 def test_keep_counts_match_checker():
     cases = [(512, 4, [(2, 700), (3, 500)]), (3376, 32, [(8, 700), (16, 500), (24, 300)]),
              (8192, 32, [(8, 600), (16, 400), (24, 200)]), (3376, 32, [(4, 500), (12, 500), (20, 500)]),
