@@ -358,7 +358,8 @@ int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_
  *    ssq_out[t] by integer atomics (order-independent); the caller zeroes it beforehand, or
  *    passes the same buffer as another call's ssq_clear.
  *  - ssq_clear: rows 0..M-1 of this buffer are set to zero.
- * Any of the three may be NULL. */
+ * Any of the three may be NULL.  workspace as for lazyllm_op_gemm; with ssq_in or ssq_clear it
+ * is used by epilogue 2 only (the schedules open to the other two do not scale or clear rows). */
 int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R, int32_t M,
                             int32_t N, int32_t K, int32_t lda, int32_t ldw, int32_t ldc,
                             int32_t epilogue, const uint64_t* ssq_in, float eps, uint64_t* ssq_out,

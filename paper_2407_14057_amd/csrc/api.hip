@@ -1099,10 +1099,17 @@ int lazyllm_op_gemm_rmsnorm(const void* A, const void* W, void* C, const void* R
   ea.eps = eps;
   ea.ssq_out = (unsigned long long*)ssq_out;
   ea.ssq_clear = (unsigned long long*)ssq_clear;
-  // the stream-K schedule has no row scaling or clearing: only the plain residual form may use it
-  const bool sk_ok = !ssq_in && !ssq_clear;
+  // the 128x128 stream-K schedule has no row scaling or clearing: of the forms it may be chosen
+  // for, only the plain residual one gets the workspace; the SiLU*mul form (tile walk, persistent
+  // stream-K: both scale rows) always may
+  const bool sk_ok = (!ssq_in && !ssq_clear) || epi == EPI_SWIGLU;
+  const bool use_ws = sk_ok && workspace != nullptr && ws_bytes >= gemm_workspace_bytes();
+  if (use_ws) {
+    LZ_HIP(launch_gemm_counters_clear(workspace, (hipStream_t)hip_stream));
+    ea.psk_ready = 1;
+  }
   LZ_HIP(launch_gemm(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, (hipStream_t)hip_stream, &ea,
-                     sk_ok ? workspace : nullptr, sk_ok ? ws_bytes : 0));
+                     use_ws ? workspace : nullptr, use_ws ? ws_bytes : 0));
   return LAZYLLM_OK;
 }
 

@@ -377,6 +377,36 @@ def test_gemm_with_rmsnorm_folded_in(M, N, K, epi):
     assert np.all(c[:M] == 0) and np.all(c[M:] == 77)      # exactly rows 0..M-1 are zeroed
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(5, 1100, 22016, 192), (5, 2100, 22016, 128), (7, 1000, 22016, 192),
+                                       (0, 1182, 22016, 256), (0, 355, 22016, 128)])
+def test_gemm_swiglu_tile_walk_with_rmsnorm_folded_in(cfg, M, N, K):
+    """The SiLU*mul GEMM in the form the prefill launches it -- RMSNorm's row scale folded into the
+    epilogue, a workspace, more tiles than compute units -- where a workgroup fetches the row
+    scales of its NEXT tile during the last K step of the current one (and, at 355 rows, under the
+    persistent stream-K schedule).  Every element against the definition, same bits twice."""
+    rng = np.random.default_rng(cfg * 31 + M + N + K)
+    A = _rand_bf16(rng, (M, K), 0.7)
+    A[: M // 2] *= 3.0                                    # row scales that differ from tile to tile
+    W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
+    a, w = _f64(A), _f64(W)
+    eps = 1e-5
+    acc = O.rmsnorm(a, np.ones(K), eps) @ w.T
+    blocks = acc.reshape(M, N // 64, 2, 32)
+    ref = (O.silu(blocks[:, :, 0, :]) * blocks[:, :, 1, :]).reshape(M, N // 2)
+    ssq = _ssq_fixed(a)
+    ws = torch.empty(B.lazyllm_op_gemm_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    outs = []
+    for _ in range(2):
+        Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
+        B.lazyllm_op_gemm_rmsnorm(A, W, Cout, None, M, N, K, K, K, N // 2, B.EPI_SWIGLU | (cfg << 8),
+                                  ssq_in=ssq, eps=eps, workspace=ws)
+        torch.cuda.synchronize()
+        assert int(ws[-4096:].view(torch.int32).abs().sum()) == 0
+        outs.append(Cout)
+    _assert_bf16_close(_f64(outs[0]), ref, 1.0, "gemm+rmsnorm, tile walk")
+    assert torch.equal(outs[0], outs[1])
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 128, 64), (37, 256, 128), (355, 4096, 4096), (1182, 4096, 1408),
                                    (2364, 4096, 512), (3376, 4096, 256)])
 def test_gemm_residual_leaves_row_sums_of_squares(M, N, K):
