@@ -229,6 +229,41 @@ def decode_bench(args, wl, shape, model, ids, sched, n_tokens, torch, B) -> int:
     return 0
 
 
+def fused_compaction_study(args, wl, model, ids, sched, cu, scale, torch, B) -> int:
+    """Sec. 3.2's gather as a kernel of its own (kept rows copied into a compact buffer) against the form
+    that leaves them in place and lets the next layer's QKV and O projections read them through the index.
+    The two forms alternate (three rounds of `steps` prefills each); a profiled pass of each gives the
+    times of the steps that differ, at the pruning layers only."""
+    prune_layers = [l for l, p in sched if p < 1000]
+    res = {}
+    for rnd in range(3):
+        for name, flags in (("separate", 0), ("fused", B.LAZYLLM_FUSE_COMPACTION)):
+            for _ in range(3):
+                model.prefill(ids, sched, cu_seqlens=cu, embed_scale=scale, flags=flags)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                out = model.prefill(ids, sched, cu_seqlens=cu, embed_scale=scale, flags=flags)
+            torch.cuda.synchronize()
+            assert out.status == 0
+            res.setdefault(name, []).append(round((time.perf_counter() - t0) * 1e3 / args.steps, 4))
+    steps = {}
+    for name, flags in (("separate", 0), ("fused", B.LAZYLLM_FUSE_COMPACTION)):
+        B.lazyllm_profile_begin()
+        for _ in range(args.steps):
+            model.prefill(ids, sched, cu_seqlens=cu, embed_scale=scale, flags=flags)
+        recs = B.lazyllm_profile_end(1 << 20)
+        by = {}
+        for r in recs:
+            if r["layer"] in prune_layers and r["step"] in ("gather", "gemm_qkv", "gemm_o"):
+                by[(r["layer"], r["step"])] = by.get((r["layer"], r["step"]), 0.0) + r["ms"] / args.steps
+        steps[name] = {"layer %d %s" % k: round(v * 1e3, 2) for k, v in sorted(by.items())}
+    print(json.dumps({"study": "compaction as a kernel vs folded into the next layer's operand loads",
+                      "workload": wl.name, "steps": args.steps, "ttft_ms": res,
+                      "us_per_step_at_pruning_layers": steps}))
+    return 0
+
+
 def band_height_sweep(args, torch, B) -> int:
     """The dominant GEMM alone (gate/up projection of the 7B shape at 3376 rows, 256x256 ping-pong tiles)
     against the height of the tile-walk band: the number of tile rows that share a run of W column blocks in
@@ -294,6 +329,12 @@ def main() -> int:
                     help="instead of the headline line, time the prefill under a grid of keep schedules: one "
                          "pruning layer at varying depth and keep ratio (the paper's drop-rate study), pruning "
                          "all at once after the first few layers (its static-pruning baseline), progressive")
+    ap.add_argument("--prefill-flags", type=int, default=0, metavar="BITS",
+                    help="LAZYLLM_* flag bits for the timed prefills (4 = compaction folded into the next layer)")
+    ap.add_argument("--fused-compaction", action="store_true",
+                    help="study: the prefill with the compaction folded into the next layer's operand loads "
+                         "(LAZYLLM_FUSE_COMPACTION) against the copying form, alternating, with the times of the "
+                         "steps involved at the three pruning layers")
     ap.add_argument("--decode", type=int, default=0, metavar="STEPS",
                     help="instead of the headline line, run the prefill and then this many decoding steps "
                          "with Aux Cache revival (greedy tokens), and the same with no pruning; prints the time "
@@ -355,7 +396,7 @@ def main() -> int:
     n_tokens = int(ids.numel())
 
     def step(schedule):
-        return model.prefill(ids, schedule, cu_seqlens=cu, embed_scale=scale)
+        return model.prefill(ids, schedule, cu_seqlens=cu, embed_scale=scale, flags=args.prefill_flags)
 
     def timed(schedule, steps, warmup):
         for _ in range(warmup):
@@ -367,6 +408,8 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps, out
 
+    if args.fused_compaction:
+        return fused_compaction_study(args, wl, model, ids, sched, cu, scale, torch, B)
     if args.schedules:
         return schedule_sweep(args, wl, shape, n_tokens, timed, B)
     if args.decode:
@@ -549,7 +592,8 @@ def main() -> int:
                        shape.vocab),
                    "prompt_tokens": n_tokens, "batch": len(cu) - 1,
                    "keep_schedule_permille_of_survivors": sched,
-                   "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True)},
+                   "tokens_per_layer_stage": sorted(set(out.n_tokens), reverse=True),
+                   **({"prefill_flags": args.prefill_flags} if args.prefill_flags else {})},
         "ttft_ms": round(ms, 4), "ttft_ms_median": round(ttft_median, 4), "ttft_ms_min": round(ttft_min, 4),
         "ttft_ms_host_synced_median": round(synced[len(synced) // 2], 4),
         "ttft_runs": len(each), "dense_ttft_ms": None if dense_ms is None else round(dense_ms, 4),

@@ -113,6 +113,12 @@ typedef struct lazyllm_model lazyllm_model;
                                          result.scores of other layers is NULL */
 #define LAZYLLM_KEEP_HIDDEN 2u        /* also return every layer's input hidden states and the
                                          last layer's output (verification aid; adds copies) */
+#define LAZYLLM_FUSE_COMPACTION 4u    /* Sec. 3.2's gather folded into the next layer: the kept rows
+                                         are not copied; the layer after a selection reads them
+                                         through the index of kept rows (A operand and row scales
+                                         of its QKV projection, residual of its O projection).
+                                         Same bits as without.  Ignored with LAZYLLM_KEEP_HIDDEN
+                                         and with gemm_dtype 1. */
 
 /* Bits of *lazyllm_result.status (device int32, read after stream sync). */
 #define LAZYLLM_ST_BAD_TOKEN 1       /* a token id was outside [0, vocab); clamped */

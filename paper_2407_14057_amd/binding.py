@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblazyllm.so")
 MAX_LAYERS = 128
 
 LAZYLLM_OK, LAZYLLM_EINVAL, LAZYLLM_ENOSPC, LAZYLLM_EHIP, LAZYLLM_ENOMEM, LAZYLLM_EFAILED = 0, -1, -2, -3, -4, -5
-LAZYLLM_SCORE_ALL_LAYERS, LAZYLLM_SCORE_ONLY_USED, LAZYLLM_KEEP_HIDDEN = 0, 1, 2
+LAZYLLM_SCORE_ALL_LAYERS, LAZYLLM_SCORE_ONLY_USED, LAZYLLM_KEEP_HIDDEN, LAZYLLM_FUSE_COMPACTION = 0, 1, 2, 4
 LAZYLLM_ST_BAD_TOKEN, LAZYLLM_ST_BAD_CU, LAZYLLM_ST_NO_STATE, LAZYLLM_ST_EXCHANGE = 1, 2, 4, 8
 EPI_STORE, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2
 

@@ -290,7 +290,7 @@ size_t lazyllm_workspace_bytes(const lazyllm_config* cfg, int32_t total_tokens, 
 
 size_t lazyllm_output_bytes(const lazyllm_config* cfg, const int32_t* seqlens, int32_t batch,
                             const lazyllm_keep* sched, int32_t n_sched, uint32_t flags) {
-  if (!config_ok(cfg) || seqlens == nullptr || batch <= 0 || (flags & ~3u) != 0) return 0;
+  if (!config_ok(cfg) || seqlens == nullptr || batch <= 0 || (flags & ~7u) != 0) return 0;
   if (!schedule_ok(cfg->n_layers, sched, n_sched)) return 0;
   long long total = 0;
   for (int b = 0; b < batch; ++b) {
@@ -449,7 +449,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       out_buf == nullptr || res == nullptr || batch <= 0)
     return LAZYLLM_EINVAL;
   if (batch > 1 && cu_dev == nullptr) return LAZYLLM_EINVAL;
-  if ((flags & ~3u) != 0) return LAZYLLM_EINVAL;
+  if ((flags & ~7u) != 0) return LAZYLLM_EINVAL;
   if (((uintptr_t)workspace & 255) != 0 || ((uintptr_t)out_buf & 255) != 0) return LAZYLLM_EINVAL;
   const lazyllm_config* c = &m->cfg;
   if (!schedule_ok(c->n_layers, sched, n_sched)) return LAZYLLM_EINVAL;
@@ -532,10 +532,16 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
   unsigned long long* ssq_attn = (unsigned long long*)(W + ws.ssq0);
   unsigned long long* ssq_ffn = (unsigned long long*)(W + ws.ssq1);
   const float ssq_mul = 1.0f / (4294967296.0f * (float)d);
+  // Compaction folded into the operand loads of the layer that follows a selection: not with the
+  // 8-bit projections (their row quantiser reads A itself) nor when the caller wants every layer's
+  // input rows copied out.
+  const bool fuse_compaction = (flags & LAZYLLM_FUSE_COMPACTION) != 0 && c->gemm_dtype == 0 &&
+                               (flags & LAZYLLM_KEEP_HIDDEN) == 0;
   for (int l = 0; l < L; ++l) {
     const int s = stg.stage_of_layer[l];
     const int n = (int)stg.total[s];
     const int32_t* cu = cu_stage + s * BW;
+    const int32_t* rows_of_h = nullptr;             // set: row t of this layer's input is row rows_of_h[t] of h
     if (s > 0 && stg.first_layer[s] == l) {
       // Sec. 3.2: the scores of layer l-1 pick the tokens that enter layer l; the others'
       // hidden states go to this layer's Aux Cache.
@@ -545,13 +551,26 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
       LZ_RUN(LAZYLLM_STEP_SELECT, l, n_prev, 8.0 * n_prev,
              launch_select(res->scores[l - 1], cu_stage + (s - 1) * BW, cu, 0, 0, B, keep_idx,
                            prune_idx, st));
-      LZ_RUN(LAZYLLM_STEP_GATHER, l, n_prev, 2.0 * n_prev * rowb,
-             launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
-                           hbuf[cur ^ 1], res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st,
-                           ssq_attn));
-      cur ^= 1;
+      if (fuse_compaction) {
+        // only the dropped rows move (to the Aux Cache) and the positions are compacted; the kept
+        // rows stay where they are (read once, for the same sums of squares as the copying form
+        // leaves) and this layer's QKV projection (A operand, row scales) and O projection
+        // (residual) read them through keep_idx, the O projection writing the compact hidden
+        // states into the other buffer
+        LZ_RUN(LAZYLLM_STEP_GATHER, l, n_prev, 2.0 * (n_prev - n) * rowb,
+               launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
+                             nullptr, res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st,
+                             ssq_attn));
+        rows_of_h = keep_idx;
+      } else {
+        LZ_RUN(LAZYLLM_STEP_GATHER, l, n_prev, 2.0 * n_prev * rowb,
+               launch_gather(hbuf[cur], res->kept_pos[l - 1], keep_idx, n, prune_idx, n_prev - n,
+                             hbuf[cur ^ 1], res->kept_pos[l], res->aux_h[l], res->aux_pos[l], d, st,
+                             ssq_attn));
+        cur ^= 1;
+      }
     }
-    char* h = hbuf[cur];
+    char* h = hbuf[cur];                            // the layer's input (rows through rows_of_h, if set)
     // One projection: the 16-bit GEMM, or in the 8-bit variant the row quantiser on the operand
     // followed by the 8-bit GEMM with the same epilogue (both in the step's timing).
     auto project = [&](const void* A, int K, const void* w16, const void* w8, const float* sw8,
@@ -594,6 +613,7 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
     ra.vt = (uint16_t*)(W + ws.vt); ra.vt_ld = (int)stg.vt_ld[s];
     ra.vt_col = B > 1 ? (const int32_t*)(W + ws.vt_col) : nullptr;
     ra.ssq_in = ssq_attn; ra.ssq_mul = ssq_mul; ra.eps = c->rms_eps; ra.ssq_clear = ssq_ffn;
+    ra.a_rows = rows_of_h;
     if (stg.first_layer[s] == l)
       LZ_RUN(LAZYLLM_STEP_V_TRANSPOSE, l, n, 0.0,
              launch_vt_stage_setup(W + ws.vt, B > 1 ? (int32_t*)(W + ws.vt_col) : nullptr, cu,
@@ -613,9 +633,17 @@ int lazyllm_prefill_varlen(const lazyllm_model* m, const int32_t* token_ids,
                             (int)stg.vt_ld[s], kv_group));
     EpiArgs eo{};
     eo.ssq_out = ssq_ffn;
-    LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
-           project(W + ws.o, d, m->wo[l], f8 ? m->wo8[l] : nullptr, f8 ? m->so[l] : nullptr, h, h, d, d,
-                   EPI_RESIDUAL, &eo, true));
+    eo.r_rows = rows_of_h;
+    if (rows_of_h != nullptr) {                     // residual rows through the index, output compact
+      LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
+             project(W + ws.o, d, m->wo[l], nullptr, nullptr, hbuf[cur ^ 1], h, d, d, EPI_RESIDUAL, &eo, true));
+      cur ^= 1;
+      h = hbuf[cur];
+    } else {
+      LZ_RUN(LAZYLLM_STEP_GEMM_O, l, n, 2.0 * n * dd * dd,
+             project(W + ws.o, d, m->wo[l], f8 ? m->wo8[l] : nullptr, f8 ? m->so[l] : nullptr, h, h, d, d,
+                     EPI_RESIDUAL, &eo, true));
+    }
     EpiArgs eg{};
     eg.ssq_in = ssq_ffn; eg.ssq_mul = ssq_mul; eg.eps = c->rms_eps; eg.ssq_clear = ssq_attn;
     if (scored) {

@@ -141,6 +141,12 @@ struct EpiArgs {
   float ssq_mul, eps;
   unsigned long long* ssq_out;
   unsigned long long* ssq_clear;
+  // Row indirection (compaction folded into the operand loads, Sec. 3.2's gather): row t of the A
+  // operand, and of ssq_in, is row a_rows[t] of the buffers passed (rope epilogue's GEMMs); row
+  // t of the residual R is row r_rows[t] (residual epilogue; C is then another buffer than R).
+  // Null: the identity.
+  const int32_t* a_rows;
+  const int32_t* r_rows;
   // Side job for workgroups past the last tile (independent of the GEMM; it rides in this launch
   // because a launch of its own would cost more than the work): Eq. 1 from the logits the
   // attention kernel left, see score_finish_block.  sf_z == nullptr: none.

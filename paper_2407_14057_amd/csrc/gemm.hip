@@ -70,6 +70,7 @@ gemm_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
     const int cchunk = (lane & 7) ^ swz64(tr);
     int r = m0 + tr;
     r = r < M ? r : M - 1;                       // rows past the edge: re-read the last row
+    if (ra.a_rows != nullptr) r = ra.a_rows[r];
     a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
   }
 #pragma unroll
@@ -308,6 +309,7 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
       const int cchunk = (lane & 7) ^ swz64(tr);
       int r = m0_ + tr;
       r = r < M ? r : M - 1;
+      if (ra.a_rows != nullptr) r = ra.a_rows[r];
       a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
     }
 #pragma unroll
@@ -464,7 +466,8 @@ gemm_pp_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
               const int row = m0_next + (wm * TM + i) * 32 + (lane & 31);
-              ssq_next[i] = ra.ssq_in[row < M ? row : M - 1];
+              const int rc = row < M ? row : M - 1;
+              ssq_next[i] = ra.ssq_in[ra.a_rows != nullptr ? ra.a_rows[rc] : rc];
             }
           }
         }
@@ -728,6 +731,7 @@ gemm_psk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
       const int cchunk = (lane & 7) ^ swz64(tr);
       int r = m0 + tr;
       r = r < M ? r : M - 1;
+      if (ra.a_rows != nullptr) r = ra.a_rows[r];
       a_off[q] = (uint32_t)(((size_t)r * lda + cchunk * 8) * 2);
     }
 #pragma unroll
@@ -1054,7 +1058,8 @@ __global__ void __launch_bounds__(256)
 gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
                uint16_t* __restrict__ C, const uint16_t* __restrict__ R, float* __restrict__ partial,
                int M, int N, int K, int lda, int ldw, int ldc, int tiles_m, int tiles_n, int G,
-               unsigned long long* __restrict__ ssq_out, size_t wstep) {
+               unsigned long long* __restrict__ ssq_out, size_t wstep,
+               const int32_t* __restrict__ r_rows) {
   constexpr int WM = 2, WN = 2, TM = 2, TN = 2, NWAVES = 4;
   constexpr int BM = SK_BM, BN = SK_BN;
   constexpr int A_INSTR = BM / 8 / NWAVES, W_INSTR = BN / 8 / NWAVES;
@@ -1081,6 +1086,7 @@ gemm_sk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W,
   const int crow = lane >> 3;
   EpiArgs ra{};
   ra.ssq_out = ssq_out;
+  ra.r_rows = r_rows;
 
   long long u = u0;
   while (u < u1) {
@@ -1192,7 +1198,8 @@ template <int EPI>
 __global__ void __launch_bounds__(256)
 gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C,
                      const uint16_t* __restrict__ R, int M, int ldc, int tiles_m, int KT,
-                     long long U, int G, unsigned long long* __restrict__ ssq_out) {
+                     long long U, int G, unsigned long long* __restrict__ ssq_out,
+                     const int32_t* __restrict__ r_rows) {
   const int tile = blockIdx.x;
   const long long ua = (long long)tile * KT, ub = ua + KT - 1;
   // owner(u) = largest g with sk_begin(g) <= u
@@ -1249,7 +1256,7 @@ gemm_sk_fixup_kernel(const float* __restrict__ partial, uint16_t* __restrict__ C
   if (row < M) {
     const size_t off = (size_t)row * ldc + n0 + c4;
     if (EPI == EPI_RESIDUAL) {
-      const uint2 r2 = *(const uint2*)(R + off);
+      const uint2 r2 = *(const uint2*)(R + (size_t)(r_rows != nullptr ? r_rows[row] : row) * ldc + n0 + c4);
       acc.x += bf16_lo(r2.x); acc.y += bf16_hi(r2.x);
       acc.z += bf16_lo(r2.y); acc.w += bf16_hi(r2.y);
     }
@@ -1273,7 +1280,8 @@ size_t gemm_workspace_bytes() { return SK_PART_BYTES + SK_TICKET_BYTES + PSK_FLA
 
 static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R, float* partial,
                             int M, int N, int K, int lda, int ldw, int ldc, int epi,
-                            unsigned long long* ssq_out, bool w_blocked, hipStream_t st) {
+                            unsigned long long* ssq_out, bool w_blocked, const int32_t* r_rows,
+                            hipStream_t st) {
   constexpr int LDS_BYTES = 2 * (SK_BM + SK_BN) * ROW_BYTES;
   const size_t wstep = w_blocked ? (size_t)N * ROW_BYTES : (size_t)ROW_BYTES;   // bytes from one K step of a row to the next
   if (w_blocked) ldw = BK;
@@ -1301,12 +1309,12 @@ static hipError_t launch_sk(const void* A, const void* W, void* C, const void* R
     }                                                                                            \
     hipLaunchKernelGGL(kern, dim3(G), dim3(256), LDS_BYTES, st, (const uint16_t*)A,              \
                        (const uint16_t*)W, (uint16_t*)C, (const uint16_t*)R, partial, M, N, K,   \
-                       lda, ldw, ldc, tiles_m, tiles_n, G, ssq_out, wstep);                      \
+                       lda, ldw, ldc, tiles_m, tiles_n, G, ssq_out, wstep, r_rows);              \
     hipError_t e = hipGetLastError();                                                            \
     if (e != hipSuccess) return e;                                                               \
     hipLaunchKernelGGL(gemm_sk_fixup_kernel<E>, dim3(tiles_m * tiles_n, 16), dim3(256), 0, st,   \
                        partial, (uint16_t*)C, (const uint16_t*)R, M, ldc, tiles_m, KT, U, G,     \
-                       ssq_out);                                                                 \
+                       ssq_out, r_rows);                                                         \
   } while (0)
   if (epi == EPI_STORE) LZ_GEMM(EPI_STORE);
   else if (epi == EPI_RESIDUAL) LZ_GEMM(EPI_RESIDUAL);
@@ -1823,8 +1831,9 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_psk<2, 4, 3, 2>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, sk_ws, st);
     case 6:                                             // 128x128 stream-K + fix-up
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
+            if (ra.a_rows != nullptr) return hipErrorInvalidValue;   // (no row indirection on its A operand)
             return launch_sk(A, W, C, R, (float*)sk_ws, M, N, K, lda, ldw, ldc, epilogue, ra.ssq_out,
-                             ra.w_blocked != 0, st);
+                             ra.w_blocked != 0, ra.r_rows, st);
     case 8:                                             // M <= 32: weight streaming
             if (sk_ws == nullptr || sk_ws_bytes < gemm_workspace_bytes()) return hipErrorInvalidValue;
             if (ra.w_stream != nullptr && !ra.w_packed) {

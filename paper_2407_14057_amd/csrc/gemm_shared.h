@@ -25,7 +25,8 @@ __device__ __forceinline__ void load_row_scales(float (&rs)[TM], const EpiArgs& 
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + (wm * TM + i) * 32 + (lane & 31);
     rs[i] = (ra.ssq_in != nullptr && row < M)
-                ? rsqrtf((float)ra.ssq_in[row] * ra.ssq_mul + ra.eps) : 0.f;
+                ? rsqrtf((float)ra.ssq_in[ra.a_rows != nullptr ? ra.a_rows[row] : row] * ra.ssq_mul + ra.eps)
+                : 0.f;
   }
 }
 
@@ -55,7 +56,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
     if (EPI != EPI_RESIDUAL && ra.ssq_in != nullptr) {
       // RMSNorm of the A operand's row, applied to the product
       const float rs = rs_pre != nullptr ? rs_pre[i]
-                       : valid ? rsqrtf((float)ra.ssq_in[row] * ra.ssq_mul + ra.eps) : 0.f;
+                       : valid ? rsqrtf((float)ra.ssq_in[ra.a_rows != nullptr ? ra.a_rows[row] : row] *
+                                            ra.ssq_mul + ra.eps) : 0.f;
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[i][j] *= rs;
     }
@@ -185,6 +187,9 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
       }
     } else {
       float ss = 0.f;
+      // the residual row: the output row, or the one the index names (compaction folded in)
+      const size_t r_shift = (EPI == EPI_RESIDUAL && !STAGED && ra.r_rows != nullptr)
+                                 ? ((size_t)ra.r_rows[row] - (size_t)row) * ldc : 0;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const size_t off = (size_t)row * ldc + n0 + (wn * TN + j) * 32 + feat_l;
@@ -197,7 +202,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16_t (&acc)[TM][TN], uint16_
                                                   (wn * TN + j) * 32 + 8 * g + feat_l) : nullptr;
           if (EPI == EPI_RESIDUAL) {
             // staged: the residual tile was copied into the same LDS slots beforehand
-            const uint2 r2 = STAGED ? *(const uint2*)sp : *(const uint2*)(R + off + 8 * g);
+            const uint2 r2 = STAGED ? *(const uint2*)sp : *(const uint2*)(R + off + r_shift + 8 * g);
             v[0] += bf16_lo(r2.x); v[1] += bf16_hi(r2.x);
             v[2] += bf16_lo(r2.y); v[3] += bf16_hi(r2.y);
           }
@@ -265,6 +270,7 @@ __device__ __forceinline__ void staged_tile_out(floatx16_t (&acc)[TM][TN], uint1
       const int chunk = (lane % NCH) ^ (rr & (NCH - 1));
       int gr = m0 + rr;
       gr = gr < M ? gr : M - 1;
+      if (ra.r_rows != nullptr) gr = ra.r_rows[gr];
       g2l16(R + (size_t)gr * ldc + n0 + chunk * 8, lds + instr * 1024);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

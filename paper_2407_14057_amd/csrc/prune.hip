@@ -509,6 +509,8 @@ hipError_t launch_gen_stage(const float* s, const uint8_t* member_prev, int n_to
 // ------------------------------------------------------------------------------------------
 // Compaction + Aux Cache write: every input row is read once and written once, either to
 // the compacted hidden states or to the Aux Cache of this pruning layer.  One wave per row.
+// h_out == nullptr: the kept rows are read (for their sums of squares, which then go to ssq at the
+// row's OLD index) but not copied: the caller's next projections read them through keep_idx.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
@@ -523,8 +525,8 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
   uint4* dst;
   if (r < n_keep) {
     src_row = keep_idx[r];
-    dst = h_out + (size_t)r * vpr;
     if (lane == 0) pos_out[r] = pos[src_row];
+    dst = h_out != nullptr ? h_out + (size_t)r * vpr : nullptr;
   } else {
     const int ra = r - n_keep;
     src_row = prune_idx[ra];
@@ -539,8 +541,10 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
     uint4 t[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) t[i] = src[v + 64 * i];
+    if (dst != nullptr) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dst[v + 64 * i] = t[i];
+      for (int i = 0; i < 8; ++i) dst[v + 64 * i] = t[i];
+    }
     if (want_ssq) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -553,7 +557,7 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
   }
   for (; v < vpr; v += 64) {
     const uint4 x = src[v];
-    dst[v] = x;
+    if (dst != nullptr) dst[v] = x;
     if (want_ssq) {
       float f[8];
       unpack8(x, f);
@@ -563,7 +567,7 @@ gather_kernel(const uint4* __restrict__ h, const int32_t* __restrict__ pos,
   }
   if (want_ssq) {
     ss = wave_sum(ss);
-    if (lane == 0) ssq[r] = ssq_to_fixed(ss);
+    if (lane == 0) ssq[h_out != nullptr ? r : src_row] = ssq_to_fixed(ss);
   }
 }
 

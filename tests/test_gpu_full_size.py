@@ -170,6 +170,17 @@ def test_headline_3376(model7b):
     _, out2 = _run(model, wl, flags=0)
     assert torch.equal(snap[0], out2.logits) and torch.equal(snap[1], out2.kept_pos(31))
     assert torch.equal(snap[2], out2.k(31))
+    # ... and so does the form that reads the kept rows of layers 8 / 16 / 24 through the index
+    # instead of compacting them (2364, 1182 and 355 rows: the ping-pong, persistent stream-K,
+    # three-stage and 128x128 stream-K kernels each take an indirect operand or residual there)
+    snap = snap + tuple(out2.v(l).clone() for l in (8, 16, 24)) + tuple(out2.aux_h(l).clone() for l in (8, 16, 24)) + \
+        tuple(out2.scores(l).clone() for l in (8, 23, 31))
+    _, out3 = _run(model, wl, flags=B.LAZYLLM_FUSE_COMPACTION)
+    assert out3.status == 0
+    got = (out3.logits, out3.kept_pos(31), out3.k(31)) + tuple(out3.v(l) for l in (8, 16, 24)) + \
+        tuple(out3.aux_h(l) for l in (8, 16, 24)) + tuple(out3.scores(l) for l in (8, 23, 31))
+    for x, y in zip(snap, got):
+        assert torch.equal(x, y)
 
 
 def test_headline_3376_end_to_end_from_token_ids(model7b):

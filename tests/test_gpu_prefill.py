@@ -205,6 +205,47 @@ def test_score_only_used_flag_gives_same_result(tiny):
     assert b.scores(0) is None and b.scores(3) is None and b.scores(1) is not None and b.scores(2) is not None
 
 
+def _snapshot(out, n_layers):
+    snap = [out.logits.clone()]
+    for l in range(n_layers):
+        for t in (out.kept_pos(l), out.k(l), out.v(l), out.scores(l), out.aux_h(l), out.aux_pos(l)):
+            snap.append(None if t is None else t.clone())
+    return snap
+
+
+@pytest.mark.parametrize("n,sched", [(65, [(1, 900), (2, 500), (3, 100)]), (300, [(3, 1)]), (777, [(1, 300)]),
+                                     (1030, [(2, 1000), (3, 250)]), (512, [(2, 700), (3, 500)])])
+def test_compaction_folded_into_the_next_layer_gives_the_same_bits(tiny_gains, n, sched):
+    """LAZYLLM_FUSE_COMPACTION: the layer after a selection reads the kept rows through the index
+    (QKV operand and row scales, residual of the O projection) instead of a compacted copy.  Same
+    arithmetic on the same rows: logits, K, V, scores, kept positions and the Aux Cache of every
+    layer are bit-equal to the copying form's, and the oracle bounds both."""
+    shape, wb, model = tiny_gains
+    ids = synth.make_prompt(n, shape.vocab, 300 + n)
+    a = _run(model, ids, sched)
+    assert a.status == 0
+    want = _snapshot(a, shape.n_layers)
+    b = _run(model, ids, sched, flags=B.LAZYLLM_FUSE_COMPACTION)
+    assert b.status == 0
+    got = _snapshot(b, shape.n_layers)
+    for x, y in zip(want, got):
+        assert (x is None and y is None) or torch.equal(x, y)
+    check_against_checker(shape, wb, ids, sched, b, verbose="fused compaction n=%d %s" % (n, sched))
+
+
+def test_compaction_folded_in_on_a_ragged_batch(tiny_gains):
+    shape, wb, model = tiny_gains
+    lens = [70, 513, 1, 260]
+    sched = [(1, 800), (3, 400)]
+    ids = np.concatenate([synth.make_prompt(n, shape.vocab, 500 + i) for i, n in enumerate(lens)])
+    cu = list(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32))
+    want = _snapshot(_run(model, ids, sched, cu=cu), shape.n_layers)
+    b = _run(model, ids, sched, cu=cu, flags=B.LAZYLLM_FUSE_COMPACTION)
+    assert b.status == 0
+    for x, y in zip(want, _snapshot(b, shape.n_layers)):
+        assert (x is None and y is None) or torch.equal(x, y)
+
+
 def test_batch_of_ragged_prompts(tiny_gains):
     shape, wb, model = tiny_gains
     lens = [70, 513, 1, 260]
