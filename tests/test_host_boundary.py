@@ -40,7 +40,7 @@ def test_binding_constants_are_the_headers():
     found = {n: int(v.rstrip("u")) for n, v in re.findall(r"#define\s+(LAZYLLM_\w+)\s+(-?\d+u?)\b", text)}
     found.update({n: int(v) for n, v in re.findall(r"\b(LAZYLLM_E?\w+)\s*=\s*(-?\d+)", text)})
     for name in ("LAZYLLM_OK", "LAZYLLM_EINVAL", "LAZYLLM_ENOSPC", "LAZYLLM_EHIP", "LAZYLLM_ENOMEM", "LAZYLLM_EFAILED",
-                 "LAZYLLM_SCORE_ONLY_USED", "LAZYLLM_KEEP_HIDDEN", "LAZYLLM_ST_BAD_TOKEN", "LAZYLLM_ST_BAD_CU",
+                 "LAZYLLM_SCORE_ONLY_USED", "LAZYLLM_KEEP_HIDDEN", "LAZYLLM_FUSE_COMPACTION", "LAZYLLM_ST_BAD_TOKEN", "LAZYLLM_ST_BAD_CU",
                  "LAZYLLM_ST_NO_STATE", "LAZYLLM_ST_EXCHANGE"):
         assert name in found, name
         assert getattr(B, name) == found[name], name
