@@ -348,7 +348,7 @@ int lazyllm_profile_end(lazyllm_profile_record* out, int32_t capacity, int32_t* 
  * ping-pong, 6 = 128x128 stream-K (needs the workspace), 8 = the weight-streaming
  * kernel of the decoding steps (M <= 32, needs the workspace), 9 / 10 = the 256x256 / 192x256
  * ping-pong tiles under the persistent stream-K schedule (need the workspace), 13 = 128x256 on
- * 8 waves of 32x128 with three stages.  EINVAL where a
+ * 8 waves of 32x128 with three stages, 14 = 256x256 on four waves of 128x128 (one per SIMD).  EINVAL where a
  * configuration does not fit the shape. */
 size_t lazyllm_op_gemm_workspace_bytes(void);
 int lazyllm_op_gemm(const void* A, const void* W, void* C, const void* R, int32_t M, int32_t N,

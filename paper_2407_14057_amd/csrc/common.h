@@ -195,6 +195,10 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
                        int lda, int ldw, int ldc, int epilogue, hipStream_t st,
                        const EpiArgs* rope = nullptr, void* sk_ws = nullptr, size_t sk_ws_bytes = 0);
 
+// The 256x256 tile on four waves of 128x128, one per SIMD (gemm_w4.hip); N % 256 == 0.
+hipError_t launch_gemm_w4(const void* A, const void* W, void* C, const void* R, int M, int N, int K,
+                          int lda, int ldw, int ldc, int epi, int group_m, const EpiArgs& ra,
+                          hipStream_t st);
 hipError_t launch_gemm_counters_clear(void* sk_ws, hipStream_t st);
 // ORs ST_EXCHANGE into *status if a GEMM since the last clear gave up on an exchange of partial
 // tiles between its workgroups (a flag that never came, or came from another XCD): its output,

@@ -1812,6 +1812,8 @@ hipError_t launch_gemm(const void* A, const void* W, void* C, const void* R, int
             return launch_cfg<4, 1, 1, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 13: if (N % 256) return hipErrorInvalidValue;  // 128x256, 8 waves of 32x128 (whole heads), three stages
             return launch_cfg<4, 2, 1, 4, 3>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
+    case 14: if (N % 256) return hipErrorInvalidValue;  // 256x256, 4 waves of 128x128 (one per SIMD)
+            return launch_gemm_w4(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 4: if (N % 256) return hipErrorInvalidValue;   // 128x256, 4 waves of 64x128
             return launch_cfg<2, 2, 2, 4>(A, W, C, R, M, N, K, lda, ldw, ldc, epilogue, group_m, ra, st);
     case 5:                                             // 256x256, 8 waves of 64x128, ping-pong

@@ -150,7 +150,7 @@ def test_gemm_tile_of_32_row_waves(M, N, K, epi):
     A = _rand_bf16(rng, (M, K)); W = _rand_bf16(rng, (N, K), 1.0 / math.sqrt(K))
     R = _rand_bf16(rng, (M, N))
     outs = []
-    for cfg in (2, 3, 13):
+    for cfg in (2, 3, 13, 14):                     # (14: the 256x256 tile on four waves of 128x128)
         if epi == B.EPI_SWIGLU:
             Cout = torch.full((M, N // 2), 7.0, dtype=torch.bfloat16, device=DEV)
             B.lazyllm_op_gemm(A, W, Cout, None, M, N, K, K, K, N // 2, epi | (cfg << 8))
@@ -159,7 +159,7 @@ def test_gemm_tile_of_32_row_waves(M, N, K, epi):
             B.lazyllm_op_gemm(A, W, Cout, Cout if epi == B.EPI_RESIDUAL else None, M, N, K, K, K, N, epi | (cfg << 8))
         torch.cuda.synchronize()
         outs.append(Cout)
-    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert all(torch.equal(outs[0], o) for o in outs[1:])
     acc = _f64(A) @ _f64(W).T
     if epi == B.EPI_SWIGLU:
         blocks = acc.reshape(M, N // 64, 2, 32)
@@ -206,7 +206,8 @@ def test_gemm_skinny_streamed_weight_layout(M, N, K, epi):
 
 @pytest.mark.parametrize("cfg,M,N,K", [(2, 300, 768, 256), (3, 229, 1536, 704), (4, 130, 512, 192), (5, 513, 1536, 704),
                                        (7, 700, 768, 1408), (6, 355, 4096, 1408), (0, 2100, 6144, 512), (0, 37, 256, 128),
-                                       (13, 229, 1536, 704), (13, 77, 512, 128), (13, 300, 768, 64), (13, 640, 1024, 192)])
+                                       (13, 229, 1536, 704), (13, 77, 512, 128), (13, 300, 768, 64), (13, 640, 1024, 192),
+                                       (14, 513, 1536, 704), (14, 300, 768, 64), (14, 1, 256, 128), (14, 700, 2048, 1408)])
 @pytest.mark.parametrize("epi", [B.EPI_STORE, B.EPI_RESIDUAL, B.EPI_SWIGLU])
 def test_gemm_k_step_major_weight_layout(cfg, M, N, K, epi):
     """The weight stored K-step-major (lazyllm_op_pack_weight_ksteps, the form the model keeps) must
