@@ -168,6 +168,13 @@ def test_shared_kv_heads(heads, hd, kv, n, sched):
     assert out.status == 0 and out.k(0).shape == (n, kv, hd)
     check_against_checker(shape, synth.weights_to_host_bits(w), ids, sched, out,
                           verbose="gqa H=%d hd=%d kv=%d n=%d" % (heads, hd, kv, n))
+    # the same bits with the compaction folded into the next layer's operand loads
+    want = (out.logits.clone(), [out.k(l).clone() for l in range(shape.n_layers)],
+            [out.kept_pos(l).clone() for l in range(shape.n_layers)])
+    fused = _run(model, ids, sched, flags=B.LAZYLLM_FUSE_COMPACTION)
+    assert fused.status == 0 and torch.equal(fused.logits, want[0])
+    assert all(torch.equal(fused.k(l), want[1][l]) and torch.equal(fused.kept_pos(l), want[2][l])
+               for l in range(shape.n_layers))
     model.close()
 
 
