@@ -306,6 +306,21 @@ def test_needles_3376(model7b):
         print("needles layer %d: top-64 mass %.3f, max/median %.1f" % (l, s[:64].sum(), s[0] / np.median(s)), flush=True)
 
 
+def _fused_compaction_gives_the_same_bits(model, wl):
+    """flags 0 against LAZYLLM_FUSE_COMPACTION at full size: logits, last layer's kept rows and K, and
+    the Aux Cache of every pruning layer."""
+    _, a = _run(model, wl, flags=0)
+    prune = [l for l, p in wl.schedule if p < 1000]
+    want = [a.logits.clone(), a.kept_pos(wl.shape.n_layers - 1).clone(), a.k(wl.shape.n_layers - 1).clone()] + \
+        [a.aux_h(l).clone() for l in prune] + [a.v(l).clone() for l in prune]
+    _, b = _run(model, wl, flags=B.LAZYLLM_FUSE_COMPACTION)
+    assert b.status == 0
+    got = [b.logits, b.kept_pos(wl.shape.n_layers - 1), b.k(wl.shape.n_layers - 1)] + \
+        [b.aux_h(l) for l in prune] + [b.v(l) for l in prune]
+    for x, y in zip(want, got):
+        assert torch.equal(x, y)
+
+
 def test_long_8192(model7b):
     w, model = model7b
     wl = synth.WORKLOADS["7b_8192"]
@@ -317,6 +332,8 @@ def test_long_8192(model7b):
     for l in (0, 7, 15, 23, 31):
         _check_layer(w, out, l, wl.schedule, tag="7b_8192")
     _check_logits(w, out)
+    del out
+    _fused_compaction_gives_the_same_bits(model, wl)
 
 
 def test_batch8(model7b):
@@ -335,6 +352,8 @@ def test_batch8(model7b):
             _check_layer(w, out, l, wl.schedule, lo=lo, hi=hi, tag="batch8 seq %d" % b, seq=b)
     for bb in range(8):
         _check_logits(w, out, bb)
+    del out
+    _fused_compaction_gives_the_same_bits(model, wl)
 
 
 def test_second_model_shape_xgen7b():
