@@ -166,3 +166,13 @@ def test_static_scratch_scoring_validates_before_any_hip_call():
     # the limit is the scratch size the buffer form would ask for
     assert B.lazyllm_op_score_scratch_bytes(39000, 32) <= 6 * 1024 * 1024 < B.lazyllm_op_score_scratch_bytes(40000, 32)
     assert lib.lazyllm_op_score_static(one, one, one, 40000, 32, 128, None) == B.LAZYLLM_ENOSPC
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is the whole target: `bench.py --gpus N` with N above 1 says so and exits non-zero,
+    before anything touches a device."""
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
